@@ -1,0 +1,150 @@
+/*
+ * rrm.h - C ABI of the MI355X (gfx950) Recurrent Residual Module library.
+ *
+ * The library keeps, for one linear layer (convolution or fully connected) of a CNN that runs
+ * on video, the previous frame's input I_{t-1} and projection P_{t-1} = W (*) I_{t-1} + b on
+ * the device and advances them with the paper's delta update (Eq. 5; Algorithm 1, inner loop)
+ *
+ *      P_t = P_{t-1} + W (*) (I_t - I_{t-1}),
+ *
+ * doing work only where the input changed.  Everything is asynchronous on the HIP stream the
+ * caller passes; no call in the per-frame path synchronises with the host or allocates.
+ *
+ * Layouts (all row-major, innermost index last)
+ *   activations  x  [n][h][w][c_in]            (FC: [n][c_in])
+ *   conv weights    [c_out][kh][kw][c_in/groups]   cross-correlation, no kernel flip
+ *   FC weights      [c_out][c_in]
+ *   outputs      y  [n][h_out][w_out][c_out]   (FC: [n][c_out])
+ *   n is the number of independent video streams (chunks of a video processed in parallel,
+ *   Sec. 3.2 last paragraph); each has its own snapshots, weights are shared.
+ *
+ * Element types (rrm_dtype)
+ *   RRM_I8_I32    x, weights int8; bias, y int32.  Exact.  The difference of two inputs must
+ *                 fit int8 (true whenever inputs are post-ReLU values in [0,127]); a violation
+ *                 raises the sticky RRM_ERR_RANGE reported by rrm_get_stats.
+ *   RRM_BF16_F32  x, weights bfloat16 (16-bit patterns); bias, y float32.  Inputs must be
+ *                 finite.
+ *   RRM_BIN_I32   x, weights are +1/-1 values bit-packed along the channel axis into 32-bit
+ *                 words, LSB first, bit 1 = +1 (c_in must be a multiple of 32; x is
+ *                 [n][h][w][c_in/32] words, weights [c_out][kh][kw][c_in/groups/32] words);
+ *                 bias, y int32.  Exact.  Convolution only; taps outside the image contribute 0.
+ *
+ * Pointers: `weights` and `bias` given to rrm_layer_create may be host or device memory and are
+ * copied (the caller may free them on return).  x / y arguments of rrm_step and rrm_dense are
+ * DEVICE pointers, 16-byte aligned, borrowed until the work enqueued on `hip_stream` has run.
+ * `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *
+ * Errors: every call returns an rrm_status (never throws, never aborts).  rrm_last_error()
+ * gives a human-readable description of the last failure on the calling thread.
+ *
+ * Threading: one handle is used from one stream at a time; distinct handles are independent.
+ */
+#ifndef RRM_H
+#define RRM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rrm_layer rrm_layer; /* opaque: device copies of W, b, snapshots, scratch */
+
+typedef enum {
+    RRM_OK = 0,
+    RRM_ERR_NULL = -1,   /* a required pointer is NULL */
+    RRM_ERR_SHAPE = -2,  /* shape not representable / not supported */
+    RRM_ERR_DTYPE = -3,  /* unknown dtype, or dtype not valid for this kind */
+    RRM_ERR_ALLOC = -4,  /* device or host allocation failed */
+    RRM_ERR_HIP = -5,    /* a HIP runtime call failed */
+    RRM_ERR_STATE = -6,  /* call not valid in the handle's current state */
+    RRM_ERR_RANGE = -7,  /* an int8 difference did not fit int8 (sticky, see rrm_get_stats) */
+    RRM_ERR_OPTION = -8, /* unknown option key or value */
+    RRM_ERR_ALIGN = -9   /* a device pointer is not 16-byte aligned */
+} rrm_status;
+
+typedef enum { RRM_CONV = 0, RRM_FC = 1 } rrm_kind;
+typedef enum { RRM_I8_I32 = 0, RRM_BF16_F32 = 1, RRM_BIN_I32 = 2 } rrm_dtype;
+
+/* Layer description.  FC layers use n, c_in, c_out (h = w = kh = kw = stride = groups = 1,
+ * pad = 0).  h_out = (h + 2*pad - kh)/stride + 1, likewise w_out. */
+typedef struct {
+    int kind; /* rrm_kind */
+    int n, h, w, c_in, c_out, kh, kw, stride, pad, groups;
+} rrm_shape;
+
+/* Counters of a handle.  All are totals since creation or the last rrm_reset. */
+typedef struct {
+    uint64_t steps;           /* rrm_step calls enqueued */
+    uint64_t delta_steps;     /* of those, steps that took the sparse delta path */
+    uint64_t changed_elems;   /* input elements (binary: bits) that differed from the snapshot */
+    uint64_t changed_units;   /* 16-byte input units with any difference (FC: = changed_elems) */
+    uint64_t active_tiles;    /* conv: 8x8 output tiles recomputed; FC: columns streamed */
+    uint64_t total_tiles;     /* conv: tiles a dense step would compute, summed over delta steps;
+                                 FC: c_in summed over delta steps */
+    int32_t range_error;      /* non-zero once an int8 difference overflowed */
+    int32_t reserved;
+} rrm_stats;
+
+/* Create a layer handle (Eq. 3 defines the layer; Sec. 3.2 the state it keeps).
+ *   weights  layout and element type as above; host or device; copied and repacked.
+ *   bias     c_out values (int32 or float32), host or device, may be NULL (= 0); copied.
+ *   shape    validated; unsupported combinations give RRM_ERR_SHAPE.
+ *   out      receives the handle.  The initial state is I_0 = 0 (Algorithm 1, first line) and
+ *            P_0 = b, so the first rrm_step yields the dense result of its frame. */
+rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_shape* shape, int dtype,
+                            rrm_layer** out);
+
+/* One (layer, frame) iteration of Algorithm 1: difference with the stored input, weights times
+ * the non-zero part of the difference, sum into the stored projection, snapshot of the input.
+ *   x_t    device, this frame's input for all n streams.
+ *   y_out  device, may be NULL; when given it receives a full copy of P_t (n*h_out*w_out*c_out
+ *          values).  Without it, read the projection through rrm_snapshot.
+ * After the enqueued work has run: y_snap == b + W (*) x_t (exactly for I8/BIN; to fp32
+ * accumulation accuracy for BF16) and x_snap == x_t bitwise. */
+rrm_status rrm_step(rrm_layer* layer, const void* x_t, void* y_out, void* hip_stream);
+
+/* The standard (dense) layer of Eq. 3: y = b + W (*) x.  Stateless: snapshots are untouched. */
+rrm_status rrm_dense(rrm_layer* layer, const void* x, void* y, void* hip_stream);
+
+/* Forget the stream history: I <- 0, P <- b, counters cleared (the "new precise inference"
+ * of Sec. 3.4 starts from here: the next rrm_step recomputes its frame in full). */
+rrm_status rrm_reset(rrm_layer* layer, void* hip_stream);
+
+/* Borrowed device pointers to the stored input and projection (valid until destroy). */
+rrm_status rrm_snapshot(rrm_layer* layer, const void** x_snap, const void** y_snap);
+
+/* Copy the stored input and/or projection into caller-owned device buffers (either may be NULL),
+ * enqueued on hip_stream: x_dst receives the bytes of x_snap (same format as x_t), y_dst the
+ * n*h_out*w_out*c_out values of y_snap. */
+rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* hip_stream);
+
+/* Options (value semantics per key):
+ *   "path"        0 auto, 1 sparse delta path always, 2 recompute densely every step
+ *   "cout_block"  conv: output channels per workgroup, 16 / 32 / 64 (0 = heuristic)
+ *   "fc_splits"   FC: number of workgroups the changed-column list is split over (0 = heuristic)
+ *   "bf16_terms"  BF16 conv: 2 = difference carried as hi+lo bf16 pair (default), 1 = hi only
+ *   "bin_cout_per_wave"  binary conv: output channels per wavefront, 8 / 16 (0 = heuristic) */
+rrm_status rrm_set_option(rrm_layer* layer, const char* key, long value);
+
+/* Read the counters.  Synchronises with the device (copies a small block back); call it after
+ * the stream has been synchronised, outside timed regions.  Returns RRM_ERR_RANGE (with *out
+ * filled) if the sticky range flag is set. */
+rrm_status rrm_get_stats(rrm_layer* layer, rrm_stats* out);
+
+void rrm_layer_destroy(rrm_layer* layer);
+
+const char* rrm_status_string(int status);
+const char* rrm_last_error(void);
+
+/* Harness helper, NOT part of the paper's linear-layer path: the nonlinear map f that the int8
+ * conv-stack benchmark places between layers.  out = maxpool3x3/2( min(127, max(0, y) >> shift) )
+ * (pooling only if pool != 0), y NHWC int32 -> out NHWC int8, both device pointers. */
+rrm_status rrm_aux_relu_requant_pool_i8(const void* y, void* out, int n, int h, int w, int c, int shift,
+                                        int pool, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RRM_H */

@@ -1,0 +1,528 @@
+// Host dispatcher and C ABI of the RRM library (see include/rrm.h for the contract).
+//
+// A handle owns: the layer's weights repacked for the kernels that read them, the bias, the two
+// snapshots of Sec. 3.2 (stored input I_{t-1}, stored projection P_{t-1}) and the scratch of the
+// change map (difference buffer, bitmap, tile stamps, FC column list).  rrm_step enqueues
+//   convolution   scan (delta + change map + commit)  ->  tile kernel on stamped tiles
+//   FC            scan + ordered compaction           ->  column scatter
+// and never touches the host side of the stream.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "rrm_internal.h"
+
+using namespace rrm;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+rrm_status fail(rrm_status st, const std::string& msg) {
+    g_last_error = msg;
+    return st;
+}
+
+#define RRM_HIP(expr)                                                                                       \
+    do {                                                                                                    \
+        hipError_t e_ = (expr);                                                                             \
+        if (e_ != hipSuccess)                                                                               \
+            return fail(RRM_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));                    \
+    } while (0)
+
+size_t round16(size_t b) { return (b + 15) & ~size_t(15); }
+
+}  // namespace
+
+struct rrm_layer {
+    rrm_shape shape{};
+    int dtype = 0;
+    int esize = 1;          // bytes per input element (binary: per 32-bit word)
+    long long x_elems = 0;  // elements of x (binary: words)
+    long long y_elems = 0;
+    size_t x_bytes = 0, y_bytes = 0;
+    ScanGeom sg{};
+    ConvGeom cg{};
+    BinGeom bg{};
+    FcGeom fg{};
+    // device memory
+    void* wpack = nullptr;   // conv: MFMA fragment order; FC: W^T; binary: scalar-load order
+    int* offtab = nullptr;   // conv: LDS offsets of the K pairs, per slab
+    void* bias = nullptr;
+    void* x_snap = nullptr;
+    void* y_snap = nullptr;
+    void* d0 = nullptr;      // difference (bf16: head; binary: flip mask)
+    void* d1 = nullptr;      // bf16: tail of the difference
+    unsigned long long* bitmap = nullptr;
+    unsigned int* tileflag = nullptr;
+    int* fc_idx = nullptr;
+    void* fc_val = nullptr;
+    int* fc_count = nullptr;
+    DevStats* stats = nullptr;
+    // state
+    unsigned int epoch = 0;
+    bool has_snapshot = false;
+    unsigned long long steps = 0, delta_steps = 0, total_tiles = 0;
+    // options
+    int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0;
+
+    ~rrm_layer() {
+        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, bitmap, tileflag, fc_idx, fc_val, fc_count, stats};
+        for (void* p : ptrs)
+            if (p) (void)hipFree(p);
+    }
+};
+
+namespace {
+
+rrm_status validate(const rrm_shape* s, int dtype) {
+    if (dtype != RRM_I8_I32 && dtype != RRM_BF16_F32 && dtype != RRM_BIN_I32)
+        return fail(RRM_ERR_DTYPE, "unknown dtype");
+    if (s->kind != RRM_CONV && s->kind != RRM_FC) return fail(RRM_ERR_SHAPE, "kind must be RRM_CONV or RRM_FC");
+    if (s->n < 1 || s->c_in < 1 || s->c_out < 1) return fail(RRM_ERR_SHAPE, "n, c_in, c_out must be positive");
+    if (s->kind == RRM_FC) {
+        if (dtype == RRM_BIN_I32) return fail(RRM_ERR_DTYPE, "binary layers are convolutions only");
+        if ((long long)s->n * s->c_in > (1ll << 30) || (long long)s->c_in * s->c_out > (1ll << 32))
+            return fail(RRM_ERR_SHAPE, "FC layer too large");
+        return RRM_OK;
+    }
+    if (s->h < 1 || s->w < 1 || s->kh < 1 || s->kw < 1 || s->stride < 1 || s->pad < 0 || s->groups < 1)
+        return fail(RRM_ERR_SHAPE, "h, w, kh, kw, stride, groups must be positive and pad non-negative");
+    if (s->c_in % s->groups || s->c_out % s->groups) return fail(RRM_ERR_SHAPE, "groups must divide c_in and c_out");
+    if (s->h + 2 * s->pad < s->kh || s->w + 2 * s->pad < s->kw)
+        return fail(RRM_ERR_SHAPE, "filter window larger than the padded input");
+    if (dtype == RRM_BIN_I32 && ((s->c_in / s->groups) % 32))
+        return fail(RRM_ERR_SHAPE, "binary layers need c_in/groups to be a multiple of 32");
+    const long long ho = (s->h + 2 * s->pad - s->kh) / s->stride + 1, wo = (s->w + 2 * s->pad - s->kw) / s->stride + 1;
+    if ((long long)s->n * s->h * s->w * s->c_in > (1ll << 31) || (long long)s->n * ho * wo * s->c_out > (1ll << 31))
+        return fail(RRM_ERR_SHAPE, "tensor too large");
+    if ((long long)s->kh * s->kw > 4096) return fail(RRM_ERR_SHAPE, "filter window too large");
+    return RRM_OK;
+}
+
+// copy `bytes` from a host-or-device pointer into a host vector
+rrm_status fetch(const void* src, size_t bytes, std::vector<unsigned char>& out) {
+    out.resize(bytes);
+    if (!bytes) return RRM_OK;
+    RRM_HIP(hipMemcpy(out.data(), src, bytes, hipMemcpyDefault));
+    return RRM_OK;
+}
+
+rrm_status upload(const void* host, size_t bytes, void** dev) {
+    const size_t alloc = round16(bytes ? bytes : 16);
+    if (hipMalloc(dev, alloc) != hipSuccess) {
+        *dev = nullptr;
+        return fail(RRM_ERR_ALLOC, "hipMalloc failed");
+    }
+    RRM_HIP(hipMemset(*dev, 0, alloc));
+    if (bytes) RRM_HIP(hipMemcpy(*dev, host, bytes, hipMemcpyHostToDevice));
+    return RRM_OK;
+}
+
+rrm_status dalloc(size_t bytes, void** dev) {
+    const size_t alloc = round16(bytes ? bytes : 16);
+    if (hipMalloc(dev, alloc) != hipSuccess) {
+        *dev = nullptr;
+        return fail(RRM_ERR_ALLOC, "hipMalloc failed");
+    }
+    RRM_HIP(hipMemset(*dev, 0, alloc));
+    return RRM_OK;
+}
+
+int pitch_for(int sc) { return sc * 16 + ((sc % 2 == 0) ? 16 : 0); }
+
+rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
+    const rrm_shape& s = L->shape;
+    ConvGeom& g = L->cg;
+    g.n = s.n; g.h = s.h; g.w = s.w; g.c_in = s.c_in; g.c_out = s.c_out;
+    g.kh = s.kh; g.kw = s.kw; g.stride = s.stride; g.pad = s.pad; g.groups = s.groups;
+    g.ho = (s.h + 2 * s.pad - s.kh) / s.stride + 1;
+    g.wo = (s.w + 2 * s.pad - s.kw) / s.stride + 1;
+    g.cg = s.c_in / s.groups;
+    g.og = s.c_out / s.groups;
+    g.tiles_y = (g.ho + TILE - 1) / TILE;
+    g.tiles_x = (g.wo + TILE - 1) / TILE;
+    g.th_in = (TILE - 1) * s.stride + s.kh;
+    g.tw_in = (TILE - 1) * s.stride + s.kw;
+    g.per_vec = 16 / L->esize;
+    g.chunks = (g.cg + g.per_vec - 1) / g.per_vec;
+    const int ntaps = s.kh * s.kw;
+    const int terms = L->dtype == RRM_BF16_F32 ? 2 : 1;
+    const long long npos = (long long)g.th_in * g.tw_in;
+    int sc = g.chunks < 8 ? g.chunks : 8;
+    auto lds_need = [&](int c) { return (long long)terms * npos * pitch_for(c) + (long long)((ntaps * c + 3) / 4) * 16; };
+    while (sc > 1 && lds_need(sc) > 60 * 1024) --sc;
+    if (lds_need(sc) > 64 * 1024) return fail(RRM_ERR_SHAPE, "input window of one output tile does not fit LDS");
+    g.sc = sc;
+    g.nslab = (g.chunks + sc - 1) / sc;
+    g.pitch = pitch_for(sc);
+    g.nq = (ntaps * sc + 3) / 4;
+    g.ncb = (g.og + 15) / 16;
+    g.fast_stage = ((s.c_in * L->esize) % 16 == 0) && ((g.cg * L->esize) % 16 == 0);
+    g.vec_store = (s.c_out % 4 == 0) && (g.og % 4 == 0);
+    g.lds_tile_bytes = (int)(npos * g.pitch);
+
+    // LDS offsets of the K pairs (tap, chunk), per slab; padded pairs point at offset 0 and carry
+    // zero weights.
+    std::vector<int> tab((size_t)g.nslab * g.nq * 4, 0);
+    for (int slab = 0; slab < g.nslab; ++slab) {
+        const int sc_eff = std::min(g.sc, g.chunks - slab * g.sc);
+        for (int e = 0; e < ntaps * sc_eff; ++e) {
+            const int tap = e / sc_eff, cc = e % sc_eff;
+            const int ky = tap / s.kw, kx = tap % s.kw;
+            tab[(size_t)slab * g.nq * 4 + e] = (ky * g.tw_in + kx) * g.pitch + cc * 16;
+        }
+    }
+    rrm_status st = upload(tab.data(), tab.size() * sizeof(int), (void**)&L->offtab);
+    if (st != RRM_OK) return st;
+
+    // weights in per-lane MFMA operand order: [group][16-block][slab][K step][lane] x 16 bytes,
+    // lane l -> output channel 16*block + l%16, K pair 4*step + l/16
+    const size_t nfrag = (size_t)s.groups * g.ncb * g.nslab * g.nq * 64;
+    std::vector<unsigned char> pack(nfrag * 16, 0);
+    const int es = L->esize;
+    for (int grp = 0; grp < s.groups; ++grp)
+        for (int cb = 0; cb < g.ncb; ++cb)
+            for (int slab = 0; slab < g.nslab; ++slab) {
+                const int sc_eff = std::min(g.sc, g.chunks - slab * g.sc);
+                for (int q = 0; q < g.nq; ++q)
+                    for (int lane = 0; lane < 64; ++lane) {
+                        const int co = cb * 16 + (lane & 15);
+                        const int e = 4 * q + (lane >> 4);
+                        if (co >= g.og || e >= ntaps * sc_eff) continue;
+                        const int tap = e / sc_eff, cc = e % sc_eff;
+                        const int c0 = (slab * g.sc + cc) * g.per_vec;
+                        unsigned char* dst =
+                            pack.data() + ((((size_t)grp * g.ncb + cb) * g.nslab + slab) * g.nq + q) * 64 * 16 + (size_t)lane * 16;
+                        const size_t wbase = (((size_t)(grp * g.og + co)) * ntaps + tap) * g.cg;
+                        for (int k = 0; k < g.per_vec && c0 + k < g.cg; ++k)
+                            std::memcpy(dst + (size_t)k * es, w.data() + (wbase + c0 + k) * es, es);
+                    }
+            }
+    return upload(pack.data(), pack.size(), &L->wpack);
+}
+
+rrm_status setup_bin(rrm_layer* L, const std::vector<unsigned char>& w) {
+    const rrm_shape& s = L->shape;
+    BinGeom& g = L->bg;
+    g.n = s.n; g.h = s.h; g.w = s.w; g.c_out = s.c_out; g.kh = s.kh; g.kw = s.kw;
+    g.stride = s.stride; g.pad = s.pad; g.groups = s.groups;
+    g.wpp = s.c_in / 32;
+    g.wg = g.wpp / s.groups;
+    g.og = s.c_out / s.groups;
+    g.ho = (s.h + 2 * s.pad - s.kh) / s.stride + 1;
+    g.wo = (s.w + 2 * s.pad - s.kw) / s.stride + 1;
+    g.tiles_y = (g.ho + TILE - 1) / TILE;
+    g.tiles_x = (g.wo + TILE - 1) / TILE;
+    g.th_in = (TILE - 1) * s.stride + s.kh;
+    g.tw_in = (TILE - 1) * s.stride + s.kw;
+    g.nslab = (g.wg + 3) / 4;
+    g.pitch = g.nslab * 4 + 4;
+    g.nob8 = 2 * ((g.og + 15) / 16);
+    if ((long long)2 * g.th_in * g.tw_in * g.pitch * 4 > 64 * 1024)
+        return fail(RRM_ERR_SHAPE, "input window of one output tile does not fit LDS");
+    const int ntaps = s.kh * s.kw;
+    // filter words: [group][co/8][slab][tap][co%8][4 words]
+    std::vector<unsigned int> pack((size_t)s.groups * g.nob8 * g.nslab * ntaps * 8 * 4, 0u);
+    const unsigned int* ww = reinterpret_cast<const unsigned int*>(w.data());
+    for (int grp = 0; grp < s.groups; ++grp)
+        for (int co = 0; co < g.og; ++co)
+            for (int tap = 0; tap < ntaps; ++tap)
+                for (int wd = 0; wd < g.wg; ++wd) {
+                    const int slab = wd / 4;
+                    const size_t dst = (((((size_t)grp * g.nob8 + co / 8) * g.nslab + slab) * ntaps + tap) * 8 + co % 8) * 4 + wd % 4;
+                    pack[dst] = ww[(((size_t)(grp * g.og + co)) * ntaps + tap) * g.wg + wd];
+                }
+    return upload(pack.data(), pack.size() * 4, &L->wpack);
+}
+
+rrm_status setup_fc(rrm_layer* L, const std::vector<unsigned char>& w) {
+    const rrm_shape& s = L->shape;
+    FcGeom& g = L->fg;
+    g.n = s.n; g.c_in = s.c_in; g.c_out = s.c_out;
+    g.per_vec = 16 / L->esize;
+    g.c_out_p = (s.c_out + g.per_vec - 1) / g.per_vec * g.per_vec;
+    g.slices = (g.c_out_p + 256 * g.per_vec - 1) / (256 * g.per_vec);
+    g.vec_ok = (s.c_in % g.per_vec) == 0;
+    // input-major copy: W^T [c_in][c_out_p], every column of W contiguous
+    const int es = L->esize;
+    std::vector<unsigned char> t((size_t)s.c_in * g.c_out_p * es, 0);
+    for (int o = 0; o < s.c_out; ++o)
+        for (int j = 0; j < s.c_in; ++j)
+            std::memcpy(t.data() + ((size_t)j * g.c_out_p + o) * es, w.data() + ((size_t)o * s.c_in + j) * es, es);
+    rrm_status st = upload(t.data(), t.size(), &L->wpack);
+    if (st != RRM_OK) return st;
+    if ((st = dalloc((size_t)s.n * s.c_in * sizeof(int), (void**)&L->fc_idx)) != RRM_OK) return st;
+    if ((st = dalloc((size_t)s.n * s.c_in * 4, &L->fc_val)) != RRM_OK) return st;
+    return dalloc((size_t)s.n * sizeof(int), (void**)&L->fc_count);
+}
+
+int conv_wm(const rrm_layer* L) {
+    const ConvGeom& g = L->cg;
+    if (L->opt_wm) return L->opt_wm;
+    int wm = g.og <= 16 ? 1 : (g.og <= 32 ? 2 : 4);
+    while (wm > 1 && (long long)g.n * g.tiles_y * g.tiles_x * g.groups * ((g.ncb + wm - 1) / wm) < 256) wm /= 2;
+    return wm;
+}
+
+int bin_cw(const rrm_layer* L) {
+    if (L->opt_bin_cw) return L->opt_bin_cw;
+    const BinGeom& g = L->bg;
+    return ((long long)g.n * g.tiles_y * g.tiles_x * g.groups * ((g.og + 63) / 64) >= 512) ? 16 : 8;
+}
+
+int fc_splits(const rrm_layer* L) {
+    if (L->opt_fc_splits) return L->opt_fc_splits;
+    int s = 1024 / (L->fg.slices * L->fg.n);
+    if (s < 1) s = 1;
+    if (s > 256) s = 256;
+    return s;
+}
+
+rrm_status check_ptr(const void* p, const char* what) {
+    if (!p) return fail(RRM_ERR_NULL, std::string(what) + " is NULL");
+    if (reinterpret_cast<uintptr_t>(p) & 15) return fail(RRM_ERR_ALIGN, std::string(what) + " is not 16-byte aligned");
+    return RRM_OK;
+}
+
+// dense layer of Eq. 3 from x into y
+rrm_status enqueue_dense(rrm_layer* L, const void* x, void* y, hipStream_t st) {
+    if (L->shape.kind == RRM_FC) {
+        RRM_HIP(launch_fill_bias(L->dtype == RRM_BF16_F32, y, L->bias, L->shape.n, L->shape.c_out, st));
+        RRM_HIP(launch_fc_scatter(L->dtype, 1, fc_splits(L), L->wpack, nullptr, nullptr, nullptr, x, y, L->fg, L->stats, st));
+    } else if (L->dtype == RRM_BIN_I32) {
+        RRM_HIP(launch_bin_conv(MODE_DENSE, bin_cw(L), x, nullptr, nullptr, nullptr, 0, L->wpack, L->bias, y, L->bg, L->stats, st));
+    } else {
+        RRM_HIP(launch_conv(L->dtype, MODE_DENSE, conv_wm(L), 1, x, nullptr, nullptr, nullptr, 0, L->wpack, L->offtab,
+                            L->bias, y, L->cg, L->stats, st));
+    }
+    return RRM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_shape* shape, int dtype, rrm_layer** out) {
+    if (!out) return fail(RRM_ERR_NULL, "out is NULL");
+    *out = nullptr;
+    if (!weights) return fail(RRM_ERR_NULL, "weights is NULL");
+    if (!shape) return fail(RRM_ERR_NULL, "shape is NULL");
+    rrm_status st = validate(shape, dtype);
+    if (st != RRM_OK) return st;
+    rrm_layer* L = new (std::nothrow) rrm_layer();
+    if (!L) return fail(RRM_ERR_ALLOC, "out of host memory");
+    L->shape = *shape;
+    if (shape->kind == RRM_FC) {
+        L->shape.h = L->shape.w = L->shape.kh = L->shape.kw = L->shape.stride = L->shape.groups = 1;
+        L->shape.pad = 0;
+    }
+    const rrm_shape& s = L->shape;
+    L->dtype = dtype;
+    L->esize = dtype == RRM_I8_I32 ? 1 : (dtype == RRM_BF16_F32 ? 2 : 4);
+    const long long ho = (s.h + 2 * s.pad - s.kh) / s.stride + 1, wo = (s.w + 2 * s.pad - s.kw) / s.stride + 1;
+    const long long cin_units = dtype == RRM_BIN_I32 ? s.c_in / 32 : s.c_in;
+    L->x_elems = (long long)s.n * s.h * s.w * cin_units;
+    L->y_elems = (long long)s.n * ho * wo * s.c_out;
+    L->x_bytes = (size_t)L->x_elems * L->esize;
+    L->y_bytes = (size_t)L->y_elems * 4;
+
+    const long long w_units = (long long)s.c_out * s.kh * s.kw * (cin_units / s.groups);
+    std::vector<unsigned char> hw, hb;
+    auto bail = [&](rrm_status e) {
+        delete L;
+        return e;
+    };
+    if ((st = fetch(weights, (size_t)w_units * L->esize, hw)) != RRM_OK) return bail(st);
+    if (bias) {
+        if ((st = fetch(bias, (size_t)s.c_out * 4, hb)) != RRM_OK) return bail(st);
+        if ((st = upload(hb.data(), hb.size(), &L->bias)) != RRM_OK) return bail(st);
+    }
+    if (s.kind == RRM_FC)
+        st = setup_fc(L, hw);
+    else if (dtype == RRM_BIN_I32)
+        st = setup_bin(L, hw);
+    else
+        st = setup_conv(L, hw);
+    if (st != RRM_OK) return bail(st);
+
+    if ((st = dalloc(L->x_bytes, &L->x_snap)) != RRM_OK) return bail(st);
+    if ((st = dalloc(L->y_bytes, &L->y_snap)) != RRM_OK) return bail(st);
+    if ((st = dalloc(sizeof(DevStats), (void**)&L->stats)) != RRM_OK) return bail(st);
+    if (s.kind == RRM_CONV) {
+        ScanGeom& sg = L->sg;
+        sg.total_elems = L->x_elems;
+        sg.c = (int)cin_units;
+        sg.h = s.h; sg.w = s.w; sg.kh = s.kh; sg.kw = s.kw; sg.stride = s.stride; sg.pad = s.pad;
+        sg.ho = (int)ho; sg.wo = (int)wo;
+        sg.tiles_y = (int)((ho + TILE - 1) / TILE);
+        sg.tiles_x = (int)((wo + TILE - 1) / TILE);
+        sg.per_vec = 16 / L->esize;
+        const size_t nvec = round16(L->x_bytes) / 16;
+        if ((st = dalloc(L->x_bytes, &L->d0)) != RRM_OK) return bail(st);
+        if (dtype == RRM_BF16_F32 && (st = dalloc(L->x_bytes, &L->d1)) != RRM_OK) return bail(st);
+        if ((st = dalloc(((nvec + 63) / 64) * 8, (void**)&L->bitmap)) != RRM_OK) return bail(st);
+        if ((st = dalloc((size_t)s.n * sg.tiles_y * sg.tiles_x * 4, (void**)&L->tileflag)) != RRM_OK) return bail(st);
+    }
+    // P_0 = b (Eq. 3 at I_0 = 0); I_0 = 0 comes from the zeroed allocation
+    hipError_t e = launch_fill_bias(dtype == RRM_BF16_F32, L->y_snap, L->bias, L->y_elems / s.c_out, s.c_out, nullptr);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        delete L;
+        return fail(RRM_ERR_HIP, std::string("initialising the projection: ") + hipGetErrorString(e));
+    }
+    *out = L;
+    return RRM_OK;
+}
+
+rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream) {
+    if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
+    rrm_status st = check_ptr(x_t, "x_t");
+    if (st != RRM_OK) return st;
+    if (y_out && (reinterpret_cast<uintptr_t>(y_out) & 15)) return fail(RRM_ERR_ALIGN, "y_out is not 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const bool first_bin = L->dtype == RRM_BIN_I32 && !L->has_snapshot;
+    if (L->opt_path == 2 || first_bin) {
+        // full recomputation: P <- b + W (*) x_t, I <- x_t
+        if ((st = enqueue_dense(L, x_t, L->y_snap, s)) != RRM_OK) return st;
+        RRM_HIP(launch_copy(L->x_snap, x_t, L->x_bytes, s));
+    } else if (L->shape.kind == RRM_FC) {
+        RRM_HIP(launch_fc_scan(L->dtype, x_t, L->x_snap, L->fc_idx, L->fc_val, L->fc_count, L->fg, L->stats, s));
+        RRM_HIP(launch_fc_scatter(L->dtype, 0, fc_splits(L), L->wpack, L->fc_idx, L->fc_val, L->fc_count, nullptr,
+                                  L->y_snap, L->fg, L->stats, s));
+        ++L->delta_steps;
+        L->total_tiles += (unsigned long long)L->shape.n * L->shape.c_in;
+    } else {
+        if (++L->epoch == 0) {  // stamp counter wrapped: old stamps could alias, clear them
+            RRM_HIP(launch_fill_zero(L->tileflag, round16((size_t)L->shape.n * L->sg.tiles_y * L->sg.tiles_x * 4), s));
+            L->epoch = 1;
+        }
+        RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag, L->epoch, L->sg, L->stats, s));
+        if (L->dtype == RRM_BIN_I32)
+            RRM_HIP(launch_bin_conv(MODE_DELTA, bin_cw(L), L->x_snap, L->d0, L->bitmap, L->tileflag, L->epoch, L->wpack,
+                                    nullptr, L->y_snap, L->bg, L->stats, s));
+        else
+            RRM_HIP(launch_conv(L->dtype, MODE_DELTA, conv_wm(L), L->dtype == RRM_BF16_F32 ? L->opt_terms : 1, L->d0, L->d1,
+                                L->bitmap, L->tileflag, L->epoch, L->wpack, L->offtab, nullptr, L->y_snap, L->cg, L->stats, s));
+        ++L->delta_steps;
+        L->total_tiles += (unsigned long long)L->shape.n * L->sg.tiles_y * L->sg.tiles_x;
+    }
+    L->has_snapshot = true;
+    ++L->steps;
+    if (y_out) RRM_HIP(launch_copy(y_out, L->y_snap, L->y_bytes, s));
+    return RRM_OK;
+}
+
+rrm_status rrm_dense(rrm_layer* L, const void* x, void* y, void* hip_stream) {
+    if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
+    rrm_status st = check_ptr(x, "x");
+    if (st != RRM_OK) return st;
+    if ((st = check_ptr(y, "y")) != RRM_OK) return st;
+    return enqueue_dense(L, x, y, static_cast<hipStream_t>(hip_stream));
+}
+
+rrm_status rrm_reset(rrm_layer* L, void* hip_stream) {
+    if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    RRM_HIP(launch_fill_zero(L->x_snap, round16(L->x_bytes), s));
+    RRM_HIP(launch_fill_bias(L->dtype == RRM_BF16_F32, L->y_snap, L->bias, L->y_elems / L->shape.c_out, L->shape.c_out, s));
+    RRM_HIP(launch_fill_zero(L->stats, round16(sizeof(DevStats)), s));
+    L->has_snapshot = false;
+    L->steps = L->delta_steps = L->total_tiles = 0;
+    return RRM_OK;
+}
+
+rrm_status rrm_snapshot(rrm_layer* L, const void** x_snap, const void** y_snap) {
+    if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
+    if (x_snap) *x_snap = L->x_snap;
+    if (y_snap) *y_snap = L->y_snap;
+    return RRM_OK;
+}
+
+rrm_status rrm_read_snapshot(rrm_layer* L, void* x_dst, void* y_dst, void* hip_stream) {
+    if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (x_dst) RRM_HIP(hipMemcpyAsync(x_dst, L->x_snap, L->x_bytes, hipMemcpyDeviceToDevice, s));
+    if (y_dst) RRM_HIP(hipMemcpyAsync(y_dst, L->y_snap, L->y_bytes, hipMemcpyDeviceToDevice, s));
+    return RRM_OK;
+}
+
+rrm_status rrm_set_option(rrm_layer* L, const char* key, long value) {
+    if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
+    if (!key) return fail(RRM_ERR_NULL, "key is NULL");
+    const std::string k(key);
+    if (k == "path") {
+        if (value < 0 || value > 2) return fail(RRM_ERR_OPTION, "path must be 0, 1 or 2");
+        L->opt_path = (int)value;
+    } else if (k == "cout_block") {
+        if (value != 0 && value != 16 && value != 32 && value != 64) return fail(RRM_ERR_OPTION, "cout_block must be 0, 16, 32 or 64");
+        L->opt_wm = (int)value / 16;
+    } else if (k == "fc_splits") {
+        if (value < 0 || value > 4096) return fail(RRM_ERR_OPTION, "fc_splits must be in [0, 4096]");
+        L->opt_fc_splits = (int)value;
+    } else if (k == "bf16_terms") {
+        if (value != 1 && value != 2) return fail(RRM_ERR_OPTION, "bf16_terms must be 1 or 2");
+        L->opt_terms = (int)value;
+    } else if (k == "bin_cout_per_wave") {
+        if (value != 0 && value != 8 && value != 16) return fail(RRM_ERR_OPTION, "bin_cout_per_wave must be 0, 8 or 16");
+        L->opt_bin_cw = (int)value;
+    } else {
+        return fail(RRM_ERR_OPTION, "unknown option key: " + k);
+    }
+    return RRM_OK;
+}
+
+rrm_status rrm_get_stats(rrm_layer* L, rrm_stats* out) {
+    if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
+    if (!out) return fail(RRM_ERR_NULL, "out is NULL");
+    DevStats d{};
+    RRM_HIP(hipMemcpy(&d, L->stats, sizeof(d), hipMemcpyDeviceToHost));
+    out->steps = L->steps;
+    out->delta_steps = L->delta_steps;
+    out->changed_elems = d.changed_elems;
+    out->changed_units = d.changed_units;
+    out->active_tiles = d.active_tiles;
+    out->total_tiles = L->total_tiles;
+    out->range_error = (int32_t)d.range_error;
+    out->reserved = 0;
+    if (d.range_error) return fail(RRM_ERR_RANGE, "an int8 input difference did not fit int8");
+    return RRM_OK;
+}
+
+void rrm_layer_destroy(rrm_layer* L) { delete L; }
+
+const char* rrm_status_string(int status) {
+    switch (status) {
+        case RRM_OK: return "ok";
+        case RRM_ERR_NULL: return "null pointer";
+        case RRM_ERR_SHAPE: return "unsupported shape";
+        case RRM_ERR_DTYPE: return "unsupported dtype";
+        case RRM_ERR_ALLOC: return "allocation failed";
+        case RRM_ERR_HIP: return "HIP runtime error";
+        case RRM_ERR_STATE: return "invalid state";
+        case RRM_ERR_RANGE: return "int8 difference out of range";
+        case RRM_ERR_OPTION: return "unknown option";
+        case RRM_ERR_ALIGN: return "misaligned pointer";
+        default: return "unknown status";
+    }
+}
+
+const char* rrm_last_error(void) { return g_last_error.c_str(); }
+
+rrm_status rrm_aux_relu_requant_pool_i8(const void* y, void* out, int n, int h, int w, int c, int shift, int pool,
+                                        void* hip_stream) {
+    if (!y || !out) return fail(RRM_ERR_NULL, "y / out is NULL");
+    if (n < 1 || h < 1 || w < 1 || c < 1 || shift < 0 || shift > 31 || (pool && (h < 3 || w < 3)))
+        return fail(RRM_ERR_SHAPE, "bad shape for relu_requant_pool");
+    RRM_HIP(launch_relu_requant_pool(y, out, n, h, w, c, shift, pool, static_cast<hipStream_t>(hip_stream)));
+    return RRM_OK;
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

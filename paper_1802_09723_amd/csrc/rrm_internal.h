@@ -1,0 +1,103 @@
+// Internal declarations shared by the host dispatcher and the gfx950 kernels of the RRM
+// library.  Nothing here is part of the public ABI (see include/rrm.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rrm.h"
+
+namespace rrm {
+
+constexpr int TILE = 8;          // output tile side (positions); 4 MFMA sub-tiles of 4x4
+constexpr int WAVE = 64;
+constexpr int CONV_THREADS = 256;
+
+enum Mode : int { MODE_DELTA = 0, MODE_DENSE = 1 };
+
+// Device-side counters (totals).  64-bit, updated with atomics by the kernels.
+struct DevStats {
+    unsigned long long changed_elems;
+    unsigned long long changed_units;
+    unsigned long long active_tiles;
+    unsigned int range_error;
+    unsigned int pad_;
+};
+
+// Geometry of the flat scan over x (delta + change map), one element = int8 / bf16 / u32 word.
+struct ScanGeom {
+    long long total_elems;   // n*h*w*c (binary: words)
+    int c;                   // elements per position
+    int h, w;                // input map
+    int kh, kw, stride, pad;
+    int ho, wo;
+    int tiles_y, tiles_x;
+    int per_vec;             // elements per 16-byte unit: 16 / 8 / 4
+};
+
+// Geometry of the tiled implicit-GEMM convolution (int8 / bf16 MFMA path).
+struct ConvGeom {
+    int n, h, w, c_in, c_out, kh, kw, stride, pad, groups;
+    int ho, wo, cg, og;
+    int tiles_y, tiles_x;
+    int th_in, tw_in;    // input window of one 8x8 output tile
+    int per_vec;         // elements per 16-byte K chunk (16 int8 / 8 bf16)
+    int chunks;          // 16-byte chunks per (position, group): ceil(cg / per_vec)
+    int sc;              // chunks per LDS slab
+    int nslab;           // ceil(chunks / sc)
+    int pitch;           // LDS bytes per staged position
+    int nq;              // MFMA K-steps per slab: ceil(kh*kw*sc / 4)
+    int ncb;             // 16-wide output-channel blocks per group
+    int fast_stage;      // 1: 16-byte aligned channel runs, vector staging
+    int vec_store;       // 1: y rows allow 16-byte read-modify-write
+    int lds_tile_bytes;  // th_in*tw_in*pitch
+};
+
+// Geometry of the binary (XNOR / popcount) convolution.
+struct BinGeom {
+    int n, h, w, c_out, kh, kw, stride, pad, groups;
+    int wpp;             // 32-bit words per input position (all groups)
+    int wg;              // words per position per group
+    int og;              // output channels per group
+    int ho, wo, tiles_y, tiles_x;
+    int th_in, tw_in;
+    int pitch;           // LDS words per staged position
+    int nslab;           // word slabs of 4 per group
+    int nob8;            // packed 8-channel filter blocks per group (og padded to 16)
+};
+
+struct FcGeom {
+    int n, c_in, c_out;
+    int c_out_p;         // row pitch of the transposed weights (elements), multiple of per_vec
+    int per_vec;         // output channels per lane per 16-byte load: 16 / 8
+    int slices;          // ceil(c_out_p / (256 * per_vec))
+    int vec_ok;          // 1: x rows are 16-byte aligned multiples
+};
+
+// ---- launchers implemented in the kernel translation units ------------------------------------
+hipError_t launch_scan(int dtype, const void* x_t, void* x_snap, void* d0, void* d1, unsigned long long* bitmap,
+                       unsigned int* tileflag, unsigned int epoch, const ScanGeom& g, DevStats* stats,
+                       hipStream_t s);
+
+hipError_t launch_conv(int dtype, int mode, int wm, int terms, const void* src0, const void* src1,
+                       const unsigned long long* bitmap, const unsigned int* tileflag, unsigned int epoch,
+                       const void* wpack, const int* offtab, const void* bias, void* y, const ConvGeom& g,
+                       DevStats* stats, hipStream_t s);
+
+hipError_t launch_fc_scan(int dtype, const void* x_t, void* x_snap, int* idx, void* val, int* count,
+                          const FcGeom& g, DevStats* stats, hipStream_t s);
+
+hipError_t launch_fc_scatter(int dtype, int dense, int splits, const void* wT, const int* idx, const void* val,
+                             const int* count, const void* x, void* y, const FcGeom& g, DevStats* stats,
+                             hipStream_t s);
+
+hipError_t launch_bin_conv(int mode, int cw, const void* xsrc, const void* flip, const unsigned long long* bitmap,
+                           const unsigned int* tileflag, unsigned int epoch, const void* wpack, const void* bias,
+                           void* y, const BinGeom& g, DevStats* stats, hipStream_t s);
+
+hipError_t launch_fill_bias(int is_float, void* y, const void* bias, long long rows, int c_out, hipStream_t s);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+hipError_t launch_relu_requant_pool(const void* y, void* out, int n, int h, int w, int c, int shift, int pool,
+                                    hipStream_t s);
+
+}  // namespace rrm

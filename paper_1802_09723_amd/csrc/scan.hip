@@ -1,0 +1,161 @@
+// Fused delta + change-map kernel for convolution layers (int8, bf16, binary).
+//
+// Algorithm 1, first statement of the inner loop: the difference of this frame's input with the
+// stored input.  The GPU form of "skip the zero elements" (Sec. 3.1, Sec. 3.5: the engine scans
+// the activation vector for its non-zero entries) is a change map: x is scanned once as a flat
+// array of 16-byte units; each wavefront turns its 64 compare results into one 64-bit mask
+// (ballot), which is the bitmap word of those units; changed units write their difference, are
+// committed to the snapshot, and stamp every 8x8 output tile whose receptive field contains them.
+//
+// HBM traffic per step: 2|x| read, plus (difference + snapshot) written only where x changed.
+#include "rrm_internal.h"
+
+namespace rrm {
+
+namespace {
+
+__device__ __forceinline__ float bf16_to_f32(unsigned int h) { return __uint_as_float(h << 16); }
+
+// round-to-nearest-even float -> bf16 pattern (finite inputs)
+__device__ __forceinline__ unsigned int f32_to_bf16(float f) {
+    unsigned int u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ uint4 load_x_guarded(const unsigned char* x, long long off, long long total_bytes) {
+    if (off + 16 <= total_bytes) return *reinterpret_cast<const uint4*>(x + off);
+    unsigned int w[4] = {0u, 0u, 0u, 0u};
+    for (int i = 0; i < 16; ++i)
+        if (off + i < total_bytes) w[i >> 2] |= (unsigned int)x[off + i] << (8 * (i & 3));
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+__device__ __forceinline__ void mark_tiles(const ScanGeom& g, long long pos, unsigned int* tileflag,
+                                           unsigned int epoch) {
+    const int hw = g.h * g.w;
+    const int b = (int)(pos / hw);
+    const int r = (int)(pos - (long long)b * hw);
+    const int iy = r / g.w, ix = r - iy * g.w;
+    const int ty0 = iy + g.pad - (g.kh - 1), tx0 = ix + g.pad - (g.kw - 1);
+    const int oy_lo = ty0 <= 0 ? 0 : (ty0 + g.stride - 1) / g.stride;
+    const int ox_lo = tx0 <= 0 ? 0 : (tx0 + g.stride - 1) / g.stride;
+    int oy_hi = (iy + g.pad) / g.stride, ox_hi = (ix + g.pad) / g.stride;
+    if (oy_hi > g.ho - 1) oy_hi = g.ho - 1;
+    if (ox_hi > g.wo - 1) ox_hi = g.wo - 1;
+    if (oy_lo > oy_hi || ox_lo > ox_hi) return;
+    for (int ty = oy_lo / TILE; ty <= oy_hi / TILE; ++ty)
+        for (int tx = ox_lo / TILE; tx <= ox_hi / TILE; ++tx)
+            tileflag[((long long)b * g.tiles_y + ty) * g.tiles_x + tx] = epoch;
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restrict__ x_t, uint4* __restrict__ x_snap,
+                                                   uint4* __restrict__ d0, uint4* __restrict__ d1,
+                                                   unsigned long long* __restrict__ bitmap,
+                                                   unsigned int* __restrict__ tileflag, unsigned int epoch,
+                                                   ScanGeom g, long long nvec, long long total_bytes,
+                                                   DevStats* __restrict__ stats) {
+    const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    bool changed = false;
+    unsigned int nelem = 0;
+    uint4 a = make_uint4(0, 0, 0, 0);
+    if (v < nvec) {
+        a = load_x_guarded(x_t, v * 16, total_bytes);
+        const uint4 b = x_snap[v];
+        const unsigned int za = a.x ^ b.x, zb = a.y ^ b.y, zc = a.z ^ b.z, zd = a.w ^ b.w;
+        changed = (za | zb | zc | zd) != 0u;
+        if (changed) {
+            const unsigned int aw[4] = {a.x, a.y, a.z, a.w};
+            const unsigned int bw[4] = {b.x, b.y, b.z, b.w};
+            unsigned int dw[4], lw[4] = {0u, 0u, 0u, 0u};
+            if (DT == RRM_I8_I32) {
+                const unsigned int H = 0x80808080u;
+                unsigned int ovf = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    // byte-wise wrapping subtraction and its signed-overflow mask
+                    const unsigned int d = ((aw[i] | H) - (bw[i] & ~H)) ^ ((aw[i] ^ ~bw[i]) & H);
+                    ovf |= (aw[i] ^ bw[i]) & (aw[i] ^ d) & H;
+                    dw[i] = d;
+                    const unsigned int z = aw[i] ^ bw[i];
+                    nelem += __popc((((z & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | z) & H);
+                }
+                if (ovf) atomicOr(&stats->range_error, 1u);
+            } else if (DT == RRM_BF16_F32) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    unsigned int hi2 = 0, lo2 = 0;
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) {
+                        const unsigned int xa = (aw[i] >> (16 * k)) & 0xFFFFu, xb = (bw[i] >> (16 * k)) & 0xFFFFu;
+                        unsigned int hi = 0, lo = 0;
+                        if (xa != xb) {
+                            ++nelem;
+                            // difference in fp32 (exact unless the operands are > 2^15 apart in
+                            // magnitude), then split into a bf16 head and a bf16 tail
+                            const float d = bf16_to_f32(xa) - bf16_to_f32(xb);
+                            hi = f32_to_bf16(d);
+                            lo = f32_to_bf16(d - bf16_to_f32(hi));
+                        }
+                        hi2 |= hi << (16 * k);
+                        lo2 |= lo << (16 * k);
+                    }
+                    dw[i] = hi2;
+                    lw[i] = lo2;
+                }
+                d1[v] = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+            } else {  // binary: the flip mask
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    dw[i] = aw[i] ^ bw[i];
+                    nelem += __popc(dw[i]);
+                }
+            }
+            d0[v] = make_uint4(dw[0], dw[1], dw[2], dw[3]);
+            x_snap[v] = a;  // snapshot of the input, only where it changed
+            // stamp the output tiles that see this unit
+            const long long e0 = v * g.per_vec;
+            long long e1 = e0 + g.per_vec - 1;
+            if (e1 > g.total_elems - 1) e1 = g.total_elems - 1;
+            const long long p0 = e0 / g.c, p1 = e1 / g.c;
+            for (long long p = p0; p <= p1; ++p) mark_tiles(g, p, tileflag, epoch);
+        }
+    }
+    const unsigned long long mask = __ballot(changed);
+    if ((threadIdx.x & 63) == 0 && (v >> 6) < ((nvec + 63) >> 6)) bitmap[v >> 6] = mask;
+    if (mask) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) nelem += __shfl_xor(nelem, o);
+        if ((threadIdx.x & 63) == 0) {
+            atomicAdd(&stats->changed_elems, (unsigned long long)nelem);
+            atomicAdd(&stats->changed_units, (unsigned long long)__popcll(mask));
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_scan(int dtype, const void* x_t, void* x_snap, void* d0, void* d1, unsigned long long* bitmap,
+                       unsigned int* tileflag, unsigned int epoch, const ScanGeom& g, DevStats* stats,
+                       hipStream_t s) {
+    const int esize = dtype == RRM_I8_I32 ? 1 : (dtype == RRM_BF16_F32 ? 2 : 4);
+    const long long total_bytes = g.total_elems * esize;
+    const long long nvec = (total_bytes + 15) / 16;
+    const long long blocks = (nvec + 255) / 256;
+    if (blocks <= 0) return hipSuccess;
+    dim3 grid((unsigned int)blocks), block(256);
+    const unsigned char* xt = static_cast<const unsigned char*>(x_t);
+    if (dtype == RRM_I8_I32)
+        hipLaunchKernelGGL(scan_kernel<RRM_I8_I32>, grid, block, 0, s, xt, (uint4*)x_snap, (uint4*)d0, (uint4*)d1,
+                           bitmap, tileflag, epoch, g, nvec, total_bytes, stats);
+    else if (dtype == RRM_BF16_F32)
+        hipLaunchKernelGGL(scan_kernel<RRM_BF16_F32>, grid, block, 0, s, xt, (uint4*)x_snap, (uint4*)d0, (uint4*)d1,
+                           bitmap, tileflag, epoch, g, nvec, total_bytes, stats);
+    else
+        hipLaunchKernelGGL(scan_kernel<RRM_BIN_I32>, grid, block, 0, s, xt, (uint4*)x_snap, (uint4*)d0, (uint4*)d1,
+                           bitmap, tileflag, epoch, g, nvec, total_bytes, stats);
+    return hipGetLastError();
+}
+
+}  // namespace rrm
