@@ -22,19 +22,28 @@ namespace {
 template <int MODE, int CW>
 __global__ __launch_bounds__(256) void bin_conv_kernel(const unsigned int* __restrict__ xsrc,
                                                        const unsigned int* __restrict__ flip,
-                                                       const unsigned long long* __restrict__ bitmap,
-                                                       const unsigned int* __restrict__ tileflag, unsigned int epoch,
+                                                       unsigned int* tileflag,
                                                        const uint4* __restrict__ wpack, const int* __restrict__ bias,
-                                                       int* __restrict__ y, BinGeom g, DevStats* __restrict__ stats) {
+                                                       int* y, BinGeom g, DevStats* __restrict__ stats) {
     extern __shared__ uint4 smem[];
     unsigned int* A = reinterpret_cast<unsigned int*>(smem);
     const int npos = g.th_in * g.tw_in;
     unsigned int* B = A + npos * g.pitch;
+    __shared__ unsigned int s_flag;
 
     const int tile = blockIdx.x;
     if (MODE == MODE_DELTA) {
-        if (tileflag[tile] != epoch) return;
-        if (blockIdx.y == 0 && threadIdx.x == 0) atomicAdd(&stats->active_tiles, 1ull);
+        // the stamp counts the workgroups that still have to consume this tile (see scan.hip)
+        if (threadIdx.x == 0) {
+            const unsigned int f = tileflag[tile];
+            if (f) {
+                atomicSub(&tileflag[tile], 1u);
+                if (blockIdx.y == 0) atomicAdd(&stats[tile & (STAT_SLOTS - 1)].active_tiles, 1ull);
+            }
+            s_flag = f;
+        }
+        __syncthreads();
+        if (s_flag == 0) return;
     }
     const int tiles_per_img = g.tiles_y * g.tiles_x;
     const int b = tile / tiles_per_img;
@@ -51,18 +60,13 @@ __global__ __launch_bounds__(256) void bin_conv_kernel(const unsigned int* __res
     // ---- stage A = m & x and B = m & ~x of the input window -------------------------------------
     const int units = npos * wg4;
     for (int u = tid; u < units; u += 256) {
-        const int hp = u / wg4, wd = u - hp * wg4;
-        const int hy = hp / g.tw_in, hx = hp - hy * g.tw_in;
+        const int hp = (int)(g.magic_wg4 ? __umulhi((unsigned int)u, g.magic_wg4) : (unsigned int)u), wd = u - hp * wg4;
+        const int hy = (int)(g.magic_tw ? __umulhi((unsigned int)hp, g.magic_tw) : (unsigned int)hp), hx = hp - hy * g.tw_in;
         const int iy = iy0 + hy, ix = ix0 + hx;
         unsigned int m = 0, xv = 0;
         if (wd < g.wg && iy >= 0 && iy < g.h && ix >= 0 && ix < g.w) {
             const long long wi = (((long long)b * g.h + iy) * g.w + ix) * g.wpp + (long long)grp * g.wg + wd;
-            if (MODE == MODE_DELTA) {
-                const long long vi = wi >> 2;
-                if ((bitmap[vi >> 6] >> (vi & 63)) & 1ull) m = flip[wi];
-            } else {
-                m = 0xFFFFFFFFu;
-            }
+            m = MODE == MODE_DELTA ? flip[wi] : 0xFFFFFFFFu;  // the flip buffer is zero where nothing changed
             if (m) xv = xsrc[wi];
         }
         A[hp * g.pitch + wd] = m & xv;
@@ -148,14 +152,13 @@ __global__ __launch_bounds__(256) void bin_conv_kernel(const unsigned int* __res
 }
 
 template <int MODE, int CW>
-hipError_t launch_one(const void* xsrc, const void* flip, const unsigned long long* bitmap,
-                      const unsigned int* tileflag, unsigned int epoch, const void* wpack, const void* bias, void* y,
-                      const BinGeom& g, DevStats* stats, hipStream_t s) {
+hipError_t launch_one(const void* xsrc, const void* flip, unsigned int* tileflag, const void* wpack,
+                      const void* bias, void* y, const BinGeom& g, DevStats* stats, hipStream_t s) {
     const int nblk = (g.og + 4 * CW - 1) / (4 * CW);
     dim3 grid((unsigned int)(g.n * g.tiles_y * g.tiles_x), (unsigned int)(g.groups * nblk));
     const size_t lds = (size_t)2 * g.th_in * g.tw_in * g.pitch * sizeof(unsigned int);
     hipLaunchKernelGGL((bin_conv_kernel<MODE, CW>), grid, dim3(256), lds, s, static_cast<const unsigned int*>(xsrc),
-                       static_cast<const unsigned int*>(flip), bitmap, tileflag, epoch,
+                       static_cast<const unsigned int*>(flip), tileflag,
                        static_cast<const uint4*>(wpack), static_cast<const int*>(bias), static_cast<int*>(y), g,
                        stats);
     return hipGetLastError();
@@ -163,15 +166,17 @@ hipError_t launch_one(const void* xsrc, const void* flip, const unsigned long lo
 
 }  // namespace
 
-hipError_t launch_bin_conv(int mode, int cw, const void* xsrc, const void* flip, const unsigned long long* bitmap,
-                           const unsigned int* tileflag, unsigned int epoch, const void* wpack, const void* bias,
-                           void* y, const BinGeom& g, DevStats* stats, hipStream_t s) {
+int bin_consumers(int cw, const BinGeom& g) { return g.groups * ((g.og + 4 * cw - 1) / (4 * cw)); }
+
+hipError_t launch_bin_conv(int mode, int cw, const void* xsrc, const void* flip, unsigned int* tileflag,
+                           const void* wpack, const void* bias, void* y, const BinGeom& g, DevStats* stats,
+                           hipStream_t s) {
     if (mode == MODE_DELTA) {
-        if (cw == 16) return launch_one<MODE_DELTA, 16>(xsrc, flip, bitmap, tileflag, epoch, wpack, bias, y, g, stats, s);
-        return launch_one<MODE_DELTA, 8>(xsrc, flip, bitmap, tileflag, epoch, wpack, bias, y, g, stats, s);
+        if (cw == 16) return launch_one<MODE_DELTA, 16>(xsrc, flip, tileflag, wpack, bias, y, g, stats, s);
+        return launch_one<MODE_DELTA, 8>(xsrc, flip, tileflag, wpack, bias, y, g, stats, s);
     }
-    if (cw == 16) return launch_one<MODE_DENSE, 16>(xsrc, flip, bitmap, tileflag, epoch, wpack, bias, y, g, stats, s);
-    return launch_one<MODE_DENSE, 8>(xsrc, flip, bitmap, tileflag, epoch, wpack, bias, y, g, stats, s);
+    if (cw == 16) return launch_one<MODE_DENSE, 16>(xsrc, flip, tileflag, wpack, bias, y, g, stats, s);
+    return launch_one<MODE_DENSE, 8>(xsrc, flip, tileflag, wpack, bias, y, g, stats, s);
 }
 
 }  // namespace rrm

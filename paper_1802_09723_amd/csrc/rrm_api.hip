@@ -65,7 +65,6 @@ struct rrm_layer {
     int* fc_count = nullptr;
     DevStats* stats = nullptr;
     // state
-    unsigned int epoch = 0;
     bool has_snapshot = false;
     unsigned long long steps = 0, delta_steps = 0, total_tiles = 0;
     // options
@@ -136,6 +135,12 @@ rrm_status dalloc(size_t bytes, void** dev) {
 
 int pitch_for(int sc) { return sc * 16 + ((sc % 2 == 0) ? 16 : 0); }
 
+// reciprocal for the kernels' u / d on small u (0 encodes d == 1)
+unsigned int magic_for(int d) { return d <= 1 ? 0u : (unsigned int)((1ull << 32) / (unsigned long long)d + 1ull); }
+
+constexpr int kPF = 4;  // K steps per slab are padded to the tile kernel's prefetch depth
+int nq_for(int ntaps, int sc) { return ((ntaps * sc + 3) / 4 + kPF - 1) / kPF * kPF; }
+
 rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     const rrm_shape& s = L->shape;
     ConvGeom& g = L->cg;
@@ -155,13 +160,16 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     const int terms = L->dtype == RRM_BF16_F32 ? 2 : 1;
     const long long npos = (long long)g.th_in * g.tw_in;
     int sc = g.chunks < 8 ? g.chunks : 8;
-    auto lds_need = [&](int c) { return (long long)terms * npos * pitch_for(c) + (long long)((ntaps * c + 3) / 4) * 16; };
+    auto lds_need = [&](int c) { return (long long)terms * npos * pitch_for(c) + (long long)nq_for(ntaps, c) * 16; };
     while (sc > 1 && lds_need(sc) > 60 * 1024) --sc;
     if (lds_need(sc) > 64 * 1024) return fail(RRM_ERR_SHAPE, "input window of one output tile does not fit LDS");
     g.sc = sc;
     g.nslab = (g.chunks + sc - 1) / sc;
     g.pitch = pitch_for(sc);
-    g.nq = (ntaps * sc + 3) / 4;
+    g.nq = nq_for(ntaps, sc);
+    g.magic_sc[0] = magic_for(sc);
+    g.magic_sc[1] = magic_for(g.chunks - (g.nslab - 1) * sc);
+    g.magic_tw = magic_for(g.tw_in);
     g.ncb = (g.og + 15) / 16;
     g.fast_stage = ((s.c_in * L->esize) % 16 == 0) && ((g.cg * L->esize) % 16 == 0);
     g.vec_store = (s.c_out % 4 == 0) && (g.og % 4 == 0);
@@ -224,6 +232,8 @@ rrm_status setup_bin(rrm_layer* L, const std::vector<unsigned char>& w) {
     g.nslab = (g.wg + 3) / 4;
     g.pitch = g.nslab * 4 + 4;
     g.nob8 = 2 * ((g.og + 15) / 16);
+    g.magic_wg4 = magic_for(g.nslab * 4);
+    g.magic_tw = magic_for(g.tw_in);
     if ((long long)2 * g.th_in * g.tw_in * g.pitch * 4 > 64 * 1024)
         return fail(RRM_ERR_SHAPE, "input window of one output tile does not fit LDS");
     const int ntaps = s.kh * s.kw;
@@ -296,10 +306,10 @@ rrm_status enqueue_dense(rrm_layer* L, const void* x, void* y, hipStream_t st) {
         RRM_HIP(launch_fill_bias(L->dtype == RRM_BF16_F32, y, L->bias, L->shape.n, L->shape.c_out, st));
         RRM_HIP(launch_fc_scatter(L->dtype, 1, fc_splits(L), L->wpack, nullptr, nullptr, nullptr, x, y, L->fg, L->stats, st));
     } else if (L->dtype == RRM_BIN_I32) {
-        RRM_HIP(launch_bin_conv(MODE_DENSE, bin_cw(L), x, nullptr, nullptr, nullptr, 0, L->wpack, L->bias, y, L->bg, L->stats, st));
+        RRM_HIP(launch_bin_conv(MODE_DENSE, bin_cw(L), x, nullptr, nullptr, L->wpack, L->bias, y, L->bg, L->stats, st));
     } else {
-        RRM_HIP(launch_conv(L->dtype, MODE_DENSE, conv_wm(L), 1, x, nullptr, nullptr, nullptr, 0, L->wpack, L->offtab,
-                            L->bias, y, L->cg, L->stats, st));
+        RRM_HIP(launch_conv(L->dtype, MODE_DENSE, conv_wm(L), 1, x, nullptr, nullptr, L->wpack, L->offtab, L->bias, y,
+                            L->cg, L->stats, st));
     }
     return RRM_OK;
 }
@@ -354,7 +364,7 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
 
     if ((st = dalloc(L->x_bytes, &L->x_snap)) != RRM_OK) return bail(st);
     if ((st = dalloc(L->y_bytes, &L->y_snap)) != RRM_OK) return bail(st);
-    if ((st = dalloc(sizeof(DevStats), (void**)&L->stats)) != RRM_OK) return bail(st);
+    if ((st = dalloc(sizeof(DevStats) * STAT_SLOTS, (void**)&L->stats)) != RRM_OK) return bail(st);
     if (s.kind == RRM_CONV) {
         ScanGeom& sg = L->sg;
         sg.total_elems = L->x_elems;
@@ -399,17 +409,19 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
         ++L->delta_steps;
         L->total_tiles += (unsigned long long)L->shape.n * L->shape.c_in;
     } else {
-        if (++L->epoch == 0) {  // stamp counter wrapped: old stamps could alias, clear them
-            RRM_HIP(launch_fill_zero(L->tileflag, round16((size_t)L->shape.n * L->sg.tiles_y * L->sg.tiles_x * 4), s));
-            L->epoch = 1;
+        if (L->dtype == RRM_BIN_I32) {
+            const int cw = bin_cw(L);
+            RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag,
+                                (unsigned int)bin_consumers(cw, L->bg), L->sg, L->stats, s));
+            RRM_HIP(launch_bin_conv(MODE_DELTA, cw, L->x_snap, L->d0, L->tileflag, L->wpack, nullptr, L->y_snap, L->bg,
+                                    L->stats, s));
+        } else {
+            const int wm = conv_wm(L);
+            RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag,
+                                (unsigned int)conv_consumers(wm, L->cg), L->sg, L->stats, s));
+            RRM_HIP(launch_conv(L->dtype, MODE_DELTA, wm, L->dtype == RRM_BF16_F32 ? L->opt_terms : 1, L->d0, L->d1,
+                                L->tileflag, L->wpack, L->offtab, nullptr, L->y_snap, L->cg, L->stats, s));
         }
-        RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag, L->epoch, L->sg, L->stats, s));
-        if (L->dtype == RRM_BIN_I32)
-            RRM_HIP(launch_bin_conv(MODE_DELTA, bin_cw(L), L->x_snap, L->d0, L->bitmap, L->tileflag, L->epoch, L->wpack,
-                                    nullptr, L->y_snap, L->bg, L->stats, s));
-        else
-            RRM_HIP(launch_conv(L->dtype, MODE_DELTA, conv_wm(L), L->dtype == RRM_BF16_F32 ? L->opt_terms : 1, L->d0, L->d1,
-                                L->bitmap, L->tileflag, L->epoch, L->wpack, L->offtab, nullptr, L->y_snap, L->cg, L->stats, s));
         ++L->delta_steps;
         L->total_tiles += (unsigned long long)L->shape.n * L->sg.tiles_y * L->sg.tiles_x;
     }
@@ -432,7 +444,14 @@ rrm_status rrm_reset(rrm_layer* L, void* hip_stream) {
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     RRM_HIP(launch_fill_zero(L->x_snap, round16(L->x_bytes), s));
     RRM_HIP(launch_fill_bias(L->dtype == RRM_BF16_F32, L->y_snap, L->bias, L->y_elems / L->shape.c_out, L->shape.c_out, s));
-    RRM_HIP(launch_fill_zero(L->stats, round16(sizeof(DevStats)), s));
+    RRM_HIP(launch_fill_zero(L->stats, sizeof(DevStats) * STAT_SLOTS, s));
+    if (L->shape.kind == RRM_CONV) {
+        // the difference buffer is zero wherever the bitmap is clear, and no tile is stamped
+        RRM_HIP(launch_fill_zero(L->d0, round16(L->x_bytes), s));
+        if (L->d1) RRM_HIP(launch_fill_zero(L->d1, round16(L->x_bytes), s));
+        RRM_HIP(launch_fill_zero(L->bitmap, round16(((round16(L->x_bytes) / 16 + 63) / 64) * 8), s));
+        RRM_HIP(launch_fill_zero(L->tileflag, round16((size_t)L->shape.n * L->sg.tiles_y * L->sg.tiles_x * 4), s));
+    }
     L->has_snapshot = false;
     L->steps = L->delta_steps = L->total_tiles = 0;
     return RRM_OK;
@@ -481,8 +500,15 @@ rrm_status rrm_set_option(rrm_layer* L, const char* key, long value) {
 rrm_status rrm_get_stats(rrm_layer* L, rrm_stats* out) {
     if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
     if (!out) return fail(RRM_ERR_NULL, "out is NULL");
+    DevStats slots[STAT_SLOTS];
+    RRM_HIP(hipMemcpy(slots, L->stats, sizeof(slots), hipMemcpyDeviceToHost));
     DevStats d{};
-    RRM_HIP(hipMemcpy(&d, L->stats, sizeof(d), hipMemcpyDeviceToHost));
+    for (const DevStats& t : slots) {
+        d.changed_elems += t.changed_elems;
+        d.changed_units += t.changed_units;
+        d.active_tiles += t.active_tiles;
+        d.range_error |= t.range_error;
+    }
     out->steps = L->steps;
     out->delta_steps = L->delta_steps;
     out->changed_elems = d.changed_elems;

@@ -14,7 +14,10 @@ constexpr int CONV_THREADS = 256;
 
 enum Mode : int { MODE_DELTA = 0, MODE_DENSE = 1 };
 
-// Device-side counters (totals).  64-bit, updated with atomics by the kernels.
+// Device-side counters (totals), updated with atomics by the kernels.  There are STAT_SLOTS copies
+// (a workgroup uses slot blockIdx.x % STAT_SLOTS) so that same-address atomics do not serialise
+// the scan; rrm_get_stats sums them.
+constexpr int STAT_SLOTS = 64;
 struct DevStats {
     unsigned long long changed_elems;
     unsigned long long changed_units;
@@ -46,6 +49,8 @@ struct ConvGeom {
     int nslab;           // ceil(chunks / sc)
     int pitch;           // LDS bytes per staged position
     int nq;              // MFMA K-steps per slab: ceil(kh*kw*sc / 4)
+    unsigned int magic_sc[2];  // floor(2^32/d)+1 for d = sc (full slab) and d = last slab's chunk count
+    unsigned int magic_tw;     // same for d = tw_in
     int ncb;             // 16-wide output-channel blocks per group
     int fast_stage;      // 1: 16-byte aligned channel runs, vector staging
     int vec_store;       // 1: y rows allow 16-byte read-modify-write
@@ -63,6 +68,8 @@ struct BinGeom {
     int pitch;           // LDS words per staged position
     int nslab;           // word slabs of 4 per group
     int nob8;            // packed 8-channel filter blocks per group (og padded to 16)
+    unsigned int magic_wg4;    // floor(2^32/d)+1 for d = 4*nslab
+    unsigned int magic_tw;     // same for d = tw_in
 };
 
 struct FcGeom {
@@ -75,13 +82,12 @@ struct FcGeom {
 
 // ---- launchers implemented in the kernel translation units ------------------------------------
 hipError_t launch_scan(int dtype, const void* x_t, void* x_snap, void* d0, void* d1, unsigned long long* bitmap,
-                       unsigned int* tileflag, unsigned int epoch, const ScanGeom& g, DevStats* stats,
+                       unsigned int* tileflag, unsigned int stamp, const ScanGeom& g, DevStats* stats,
                        hipStream_t s);
 
 hipError_t launch_conv(int dtype, int mode, int wm, int terms, const void* src0, const void* src1,
-                       const unsigned long long* bitmap, const unsigned int* tileflag, unsigned int epoch,
-                       const void* wpack, const int* offtab, const void* bias, void* y, const ConvGeom& g,
-                       DevStats* stats, hipStream_t s);
+                       unsigned int* tileflag, const void* wpack, const int* offtab, const void* bias, void* y,
+                       const ConvGeom& g, DevStats* stats, hipStream_t s);
 
 hipError_t launch_fc_scan(int dtype, const void* x_t, void* x_snap, int* idx, void* val, int* count,
                           const FcGeom& g, DevStats* stats, hipStream_t s);
@@ -90,9 +96,11 @@ hipError_t launch_fc_scatter(int dtype, int dense, int splits, const void* wT, c
                              const int* count, const void* x, void* y, const FcGeom& g, DevStats* stats,
                              hipStream_t s);
 
-hipError_t launch_bin_conv(int mode, int cw, const void* xsrc, const void* flip, const unsigned long long* bitmap,
-                           const unsigned int* tileflag, unsigned int epoch, const void* wpack, const void* bias,
-                           void* y, const BinGeom& g, DevStats* stats, hipStream_t s);
+hipError_t launch_bin_conv(int mode, int cw, const void* xsrc, const void* flip, unsigned int* tileflag,
+                           const void* wpack, const void* bias, void* y, const BinGeom& g, DevStats* stats,
+                           hipStream_t s);
+int conv_consumers(int wm, const ConvGeom& g);   // workgroups per tile of the MFMA tile kernel
+int bin_consumers(int cw, const BinGeom& g);     // workgroups per tile of the binary kernel
 
 hipError_t launch_fill_bias(int is_float, void* y, const void* bias, long long rows, int c_out, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);

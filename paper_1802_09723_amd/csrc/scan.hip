@@ -7,6 +7,12 @@
 // (ballot), which is the bitmap word of those units; changed units write their difference, are
 // committed to the snapshot, and stamp every 8x8 output tile whose receptive field contains them.
 //
+// The difference buffer keeps the invariant "zero wherever the bitmap bit is clear": a unit that
+// changed in the previous step but not in this one is written back to zero, so the tile kernel can
+// stage its input window with plain loads.  A stamped tile holds the number of workgroups that will
+// consume it; each consumer takes one off when it is done, so the stamps are all zero again after
+// the tile kernel and nothing on the host has to change between steps (graph replay safe).
+//
 // HBM traffic per step: 2|x| read, plus (difference + snapshot) written only where x changed.
 #include "rrm_internal.h"
 
@@ -32,7 +38,7 @@ __device__ __forceinline__ uint4 load_x_guarded(const unsigned char* x, long lon
 }
 
 __device__ __forceinline__ void mark_tiles(const ScanGeom& g, long long pos, unsigned int* tileflag,
-                                           unsigned int epoch) {
+                                           unsigned int stamp) {
     const int hw = g.h * g.w;
     const int b = (int)(pos / hw);
     const int r = (int)(pos - (long long)b * hw);
@@ -46,17 +52,19 @@ __device__ __forceinline__ void mark_tiles(const ScanGeom& g, long long pos, uns
     if (oy_lo > oy_hi || ox_lo > ox_hi) return;
     for (int ty = oy_lo / TILE; ty <= oy_hi / TILE; ++ty)
         for (int tx = ox_lo / TILE; tx <= ox_hi / TILE; ++tx)
-            tileflag[((long long)b * g.tiles_y + ty) * g.tiles_x + tx] = epoch;
+            tileflag[((long long)b * g.tiles_y + ty) * g.tiles_x + tx] = stamp;
 }
 
 template <int DT>
 __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restrict__ x_t, uint4* __restrict__ x_snap,
                                                    uint4* __restrict__ d0, uint4* __restrict__ d1,
                                                    unsigned long long* __restrict__ bitmap,
-                                                   unsigned int* __restrict__ tileflag, unsigned int epoch,
+                                                   unsigned int* __restrict__ tileflag, unsigned int stamp,
                                                    ScanGeom g, long long nvec, long long total_bytes,
-                                                   DevStats* __restrict__ stats) {
+                                                   DevStats* __restrict__ stats_base) {
     const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    DevStats* __restrict__ stats = stats_base + (blockIdx.x & (STAT_SLOTS - 1));
+    const unsigned long long prev_mask = v < nvec ? bitmap[v >> 6] : 0ull;  // wave-uniform word
     bool changed = false;
     unsigned int nelem = 0;
     uint4 a = make_uint4(0, 0, 0, 0);
@@ -119,11 +127,15 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
             long long e1 = e0 + g.per_vec - 1;
             if (e1 > g.total_elems - 1) e1 = g.total_elems - 1;
             const long long p0 = e0 / g.c, p1 = e1 / g.c;
-            for (long long p = p0; p <= p1; ++p) mark_tiles(g, p, tileflag, epoch);
+            for (long long p = p0; p <= p1; ++p) mark_tiles(g, p, tileflag, stamp);
+        } else if ((prev_mask >> (threadIdx.x & 63)) & 1ull) {
+            // changed last step, unchanged now: restore the zero of the difference buffer
+            d0[v] = make_uint4(0, 0, 0, 0);
+            if (DT == RRM_BF16_F32) d1[v] = make_uint4(0, 0, 0, 0);
         }
     }
     const unsigned long long mask = __ballot(changed);
-    if ((threadIdx.x & 63) == 0 && (v >> 6) < ((nvec + 63) >> 6)) bitmap[v >> 6] = mask;
+    if ((threadIdx.x & 63) == 0 && v < nvec) bitmap[v >> 6] = mask;
     if (mask) {
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) nelem += __shfl_xor(nelem, o);
@@ -137,7 +149,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
 }  // namespace
 
 hipError_t launch_scan(int dtype, const void* x_t, void* x_snap, void* d0, void* d1, unsigned long long* bitmap,
-                       unsigned int* tileflag, unsigned int epoch, const ScanGeom& g, DevStats* stats,
+                       unsigned int* tileflag, unsigned int stamp, const ScanGeom& g, DevStats* stats,
                        hipStream_t s) {
     const int esize = dtype == RRM_I8_I32 ? 1 : (dtype == RRM_BF16_F32 ? 2 : 4);
     const long long total_bytes = g.total_elems * esize;
@@ -148,13 +160,13 @@ hipError_t launch_scan(int dtype, const void* x_t, void* x_snap, void* d0, void*
     const unsigned char* xt = static_cast<const unsigned char*>(x_t);
     if (dtype == RRM_I8_I32)
         hipLaunchKernelGGL(scan_kernel<RRM_I8_I32>, grid, block, 0, s, xt, (uint4*)x_snap, (uint4*)d0, (uint4*)d1,
-                           bitmap, tileflag, epoch, g, nvec, total_bytes, stats);
+                           bitmap, tileflag, stamp, g, nvec, total_bytes, stats);
     else if (dtype == RRM_BF16_F32)
         hipLaunchKernelGGL(scan_kernel<RRM_BF16_F32>, grid, block, 0, s, xt, (uint4*)x_snap, (uint4*)d0, (uint4*)d1,
-                           bitmap, tileflag, epoch, g, nvec, total_bytes, stats);
+                           bitmap, tileflag, stamp, g, nvec, total_bytes, stats);
     else
         hipLaunchKernelGGL(scan_kernel<RRM_BIN_I32>, grid, block, 0, s, xt, (uint4*)x_snap, (uint4*)d0, (uint4*)d1,
-                           bitmap, tileflag, epoch, g, nvec, total_bytes, stats);
+                           bitmap, tileflag, stamp, g, nvec, total_bytes, stats);
     return hipGetLastError();
 }
 
