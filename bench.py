@@ -1,0 +1,460 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X Recurrent Residual Module library.
+
+Default run (the driver's contract): the AlexNet-shaped int8 conv stack of the benchmark's
+configs[1] -- five conv layers with ReLU / requantisation / max-pool between them -- over
+synthetic 32-frame moving-patch sequences for `--streams` independent video streams (chunks
+processed in parallel, Sec. 3.2 of the paper).  One "step" is one frame of every stream through
+the whole stack: per layer one rrm_step (delta + change map, then the tile kernel on changed
+tiles) followed by the harness nonlinearity.  Every 32nd step starts a new sequence, i.e. a frame
+in which everything changes.  Inputs are resident in HBM before the timed region.  Prints ONE
+JSON line; everything else goes to stderr.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--streams S] [--sweep]
+
+--sweep additionally times every layer of configs 2-4 (ResNet bf16, FC sparse-delta, binary) over
+their density grids and writes gpurun_out/sweep.jsonl plus a table on stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12          # B/s, MI355X HBM3E
+MFMA_PEAK = {0: 5.0e15, 1: 2.5e15}  # dense int8 OP/s, bf16 FLOP/s
+VALU_LANE_PEAK = 256 * 64 * 2.4e9   # lane-instructions / s: 256 CUs x 4 SIMD16 x 16 lanes x 2.4 GHz
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def macs(shape) -> int:
+    """dense multiply count of a layer (Table 1 of the paper)."""
+    if shape.kind == 1:
+        return shape.n * shape.c_in * shape.c_out
+    return shape.n * shape.h_out * shape.w_out * (shape.c_in // shape.groups) * shape.c_out * shape.kh * shape.kw
+
+
+class Timer:
+    """HIP-event timing on the current torch stream."""
+
+    def __init__(self):
+        import torch
+        self.t = torch
+        self.a = torch.cuda.Event(enable_timing=True)
+        self.b = torch.cuda.Event(enable_timing=True)
+
+    def __enter__(self):
+        self.t.cuda.synchronize()
+        self.a.record()
+        return self
+
+    def __exit__(self, *exc):
+        self.b.record()
+        self.t.cuda.synchronize()
+        self.ms = self.a.elapsed_time(self.b)
+
+
+# ------------------------------------------------------------------------------------------------
+# config 1: the AlexNet-shaped int8 stack
+# ------------------------------------------------------------------------------------------------
+class Stack:
+    def __init__(self, streams: int, T: int = 32):
+        import torch
+        import paper_1802_09723_amd as rrm
+        import rrm_synth as S
+        self.torch, self.rrm, self.S = torch, rrm, S
+        self.B, self.T = streams, T
+        seqs = [S.config1(seed=S.seed_for(1, k), n=streams, T=T) for k in range(2)]
+        self.cfg = seqs[0]
+        self.layers = [rrm.Layer(l["shape"], S.I8, l["weights"], l["bias"]) for l in self.cfg["layers"]]
+        # frames of two different sequences back to back: 0..T-1 of A, 0..T-1 of B
+        self.frames = [torch.from_numpy(f).cuda() for s in seqs for f in s["frames"]]
+        self.host_frames = [f for s in seqs for f in s["frames"]]
+        self.xin = torch.empty_like(self.frames[0])
+        self.bufs, self.meta = [], []
+        for l, L in zip(self.cfg["layers"], self.layers):
+            sh = l["shape"]
+            ho, wo = L.y_shape[1], L.y_shape[2]
+            po, qo = ((ho - 3) // 2 + 1, (wo - 3) // 2 + 1) if l["pool"] else (ho, wo)
+            self.bufs.append(torch.empty((sh.n, po, qo, sh.c_out), dtype=torch.int8, device="cuda"))
+            self.meta.append((sh.n, ho, wo, sh.c_out, bool(l["pool"])))
+        self.ysnap = [L.snapshot_ptrs()[1] for L in self.layers]
+        self.shifts = self._calibrate()
+        self.graph = None
+
+    def _calibrate(self):
+        """Per-layer right shift of the harness requantisation: smallest shift that brings the
+        99.9th percentile of ReLU(y) on the first frame to <= 127 (fixed for the whole run)."""
+        torch, rrm = self.torch, self.rrm
+        shifts = []
+        x = self.frames[0]
+        for i, L in enumerate(self.layers):
+            y = torch.empty(L.y_shape, dtype=torch.int32, device="cuda")
+            L.dense(x, y)
+            torch.cuda.synchronize()
+            v = float(np.percentile(np.maximum(y[:1].cpu().numpy(), 0), 99.9))
+            s = 0
+            while (int(v) >> s) > 127:
+                s += 1
+            shifts.append(s)
+            n, ho, wo, c, pool = self.meta[i]
+            rrm.relu_requant_pool_i8(y, self.bufs[i], n, ho, wo, c, s, pool)
+            x = self.bufs[i]
+        torch.cuda.synchronize()
+        return shifts
+
+    def set_path(self, path: int):
+        for L in self.layers:
+            L.set_option("path", path)
+        self.graph = None
+
+    def frame(self, x):
+        rrm = self.rrm
+        for i, L in enumerate(self.layers):
+            L.step(x)
+            n, ho, wo, c, pool = self.meta[i]
+            rrm.relu_requant_pool_i8(self.ysnap[i], self.bufs[i], n, ho, wo, c, self.shifts[i], pool)
+            x = self.bufs[i]
+
+    def capture(self):
+        torch = self.torch
+        self.frame(self.xin)  # make sure nothing lazy happens inside the capture
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.frame(self.xin)
+        self.graph = g
+
+    def run_steps(self, k0: int, K: int, use_graph: bool):
+        nf = len(self.frames)
+        for k in range(k0, k0 + K):
+            if use_graph:
+                self.xin.copy_(self.frames[k % nf], non_blocking=True)
+                self.graph.replay()
+            else:
+                self.frame(self.frames[k % nf])
+
+    def timed(self, K: int, W: int, use_graph: bool) -> float:
+        """ms per step over exactly K steps after W warm-up steps."""
+        if use_graph and self.graph is None:
+            self.capture()
+        self.run_steps(0, W, use_graph)
+        with Timer() as t:
+            self.run_steps(W, K, use_graph)
+        return t.ms / K
+
+    def profile_layers(self, K: int, W: int):
+        """Eager pass with every kernel of rrm_step bracketed by HIP events (the library's
+        "profile" option): per-layer average scan / compute kernel time and change statistics."""
+        self.run_steps(0, W, False)
+        self.torch.cuda.synchronize()
+        s0 = [L.stats() for L in self.layers]
+        for L in self.layers:
+            L.set_option("profile", 1)
+        self.run_steps(W, K, False)
+        self.torch.cuda.synchronize()
+        out = []
+        for L, a in zip(self.layers, s0):
+            scan_us, comp_us, n = L.kernel_times()
+            L.set_option("profile", 0)
+            b = L.stats()
+            d = {k: b[k] - a[k] for k in ("changed_elems", "changed_units", "active_tiles", "total_tiles", "delta_steps")}
+            out.append({"scan_us": scan_us / max(n, 1), "compute_us": comp_us / max(n, 1), "steps": n, **d})
+        return out
+
+
+def conv_alg_bytes(shape, esize, changed_units_per_step, active_tiles_per_step, terms=1):
+    """Algorithmic HBM bytes of one delta step of a conv layer, split by kernel.
+    scan: both copies of x are read once; changed 16-byte units write their difference (terms
+          buffers) and the snapshot.
+    tile: the changed difference units are read once, the weights once (if anything changed),
+          and the touched 8x8 output tiles are read and written once (4-byte outputs)."""
+    xb = shape.n * shape.h * shape.w * shape.c_in * esize
+    wb = shape.c_out * shape.kh * shape.kw * (shape.c_in // shape.groups) * esize
+    tile_y = 64 * shape.c_out * 4
+    scan = 2 * xb + changed_units_per_step * 16 * (1 + terms)
+    tile = changed_units_per_step * 16 * terms + 2 * active_tiles_per_step * tile_y + (wb if active_tiles_per_step > 0 else 0)
+    return scan, tile
+
+
+def run_stack(args):
+    import torch
+    st = Stack(args.streams)
+    B = st.B
+    shapes = [l["shape"] for l in st.cfg["layers"]]
+    names = [l["name"] for l in st.cfg["layers"]]
+    log(f"[bench] AlexNet int8 conv stack, streams={B}, shifts={st.shifts}")
+
+    # ---- headline: K steps of the delta path (graph replay unless --no-graph) --------------------
+    st.set_path(0)
+    ms_delta = st.timed(args.steps, args.warmup, not args.no_graph)
+    # ---- same steps with every layer recomputed densely (the library's own dense path) -----------
+    st.set_path(2)
+    ms_dense = st.timed(args.steps, args.warmup, not args.no_graph)
+    st.set_path(0)
+    # ---- per-kernel times and change statistics (eager, event-bracketed) -------------------------
+    prof = st.profile_layers(args.steps, args.warmup)
+    st.set_path(2)
+    prof_dense = st.profile_layers(min(args.steps, 64), 4)
+    st.set_path(0)
+
+    frames_per_s = B * 1e3 / ms_delta
+    total_macs = sum(macs(s) for s in shapes)  # for all B streams, one frame each
+    layers = []
+    dom = None
+    for nm, sh, p, pd in zip(names, shapes, prof, prof_dense):
+        n = max(p["steps"], 1)
+        cu, at = p["changed_units"] / n, p["active_tiles"] / n
+        scan_b, tile_b = conv_alg_bytes(sh, 1, cu, at)
+        rho_elem = p["changed_elems"] / n / (sh.n * sh.h * sh.w * sh.c_in)
+        rho_tile = p["active_tiles"] / max(p["total_tiles"], 1)
+        ops_alg = 2 * rho_elem * macs(sh)
+        t_step = p["scan_us"] + p["compute_us"]
+        t_roof_hbm = (scan_b + tile_b) / HBM_PEAK * 1e6
+        t_roof_mfma = ops_alg / MFMA_PEAK[0] * 1e6
+        rec = {
+            "layer": nm, "rho_elem": round(rho_elem, 4), "rho_tile": round(rho_tile, 4),
+            "scan_us": round(p["scan_us"], 2), "tile_us": round(p["compute_us"], 2),
+            "dense_us": round(pd["compute_us"], 2),
+            "frames_per_s": round(B * 1e6 / t_step, 1),
+            "dense_equiv_gops": round(2 * macs(sh) / t_step * 1e-3, 1),
+            "speedup_vs_dense_kernel": round((pd["compute_us"] + pd["scan_us"]) / t_step, 3),
+            "alg_bytes": int(scan_b + tile_b), "roof_us": round(max(t_roof_hbm, t_roof_mfma), 3),
+            "roof_bound": "hbm" if t_roof_hbm >= t_roof_mfma else "mfma",
+            "roof_frac": round(max(t_roof_hbm, t_roof_mfma) / t_step, 4),
+        }
+        layers.append(rec)
+        log("[layer]", json.dumps(rec))
+        for kind, us, byts in (("scan", p["scan_us"], scan_b), ("tile", p["compute_us"], tile_b)):
+            if dom is None or us > dom["us"]:
+                dom = {"kernel": f"{kind}:{nm}", "us": us, "bytes": byts,
+                       "ops": ops_alg if kind == "tile" else 0.0}
+
+    achieved = dom["bytes"] / (dom["us"] * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                "frac": round(achieved * 1e9 / HBM_PEAK, 4), "traffic": None,
+                "kernel": dom["kernel"], "avg_us": round(dom["us"], 2), "alg_bytes_per_launch": int(dom["bytes"]),
+                "mfma_frac": round(dom["ops"] / (dom["us"] * 1e-6) / MFMA_PEAK[0], 5)}
+
+    floor_us = launch_floor(st)
+    cpu = None if args.skip_cpu else cpu_baseline_stack(st)
+    out = {
+        "metric": "frames_per_s", "value": round(frames_per_s, 1), "unit": "frames/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_delta, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "cfg1_alexnet_conv_stack_int8", "streams": B, "frames_per_sequence": st.T,
+                   "graph_replay": not args.no_graph},
+        "dense_equiv_gops": round(2 * total_macs / (ms_delta * 1e-3) * 1e-9, 1),
+        "ms_per_step_dense_path": round(ms_dense, 5),
+        "speedup_vs_dense_path": round(ms_dense / ms_delta, 3),
+        "launch_floor_us": round(floor_us, 2),
+        "layers": layers, "roofline": roofline, "cpu_baseline": cpu,
+    }
+    return out
+
+
+def launch_floor(st) -> float:
+    """us per launch of a one-thread kernel replayed back to back in a graph (the floor under
+    every per-kernel time quoted here)."""
+    import torch
+    rrm = st.rrm
+    y = torch.zeros((1, 3, 3, 1), dtype=torch.int32, device="cuda")
+    o = torch.zeros((1, 1, 1, 1), dtype=torch.int8, device="cuda")
+    rrm.relu_requant_pool_i8(y, o, 1, 3, 3, 1, 0, True)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(100):
+            rrm.relu_requant_pool_i8(y, o, 1, 3, 3, 1, 0, True)
+    g.replay()
+    with Timer() as t:
+        for _ in range(10):
+            g.replay()
+    return t.ms * 1e3 / 1000
+
+
+def cpu_baseline_stack(st, budget_s: float = 12.0):
+    """The CPU oracle (dense projection of every layer, its own nonlinearity in between) on one
+    stream's frames, on this host's cores, for a bounded number of frames."""
+    import oracle
+    S = st.S
+    cfg = st.cfg
+    frames_done, t0 = 0, time.perf_counter()
+    layers1 = [(l["shape"].with_n(1), l) for l in cfg["layers"]]
+    while frames_done < st.T and (time.perf_counter() - t0) < budget_s:
+        x = np.ascontiguousarray(st.host_frames[frames_done][:1])
+        for i, (sh, l) in enumerate(layers1):
+            y = oracle.dense(sh, S.I8, l["weights"], l["bias"], x)
+            x = oracle.relu_requant_pool(y, st.shifts[i], l["pool"])
+        frames_done += 1
+    dt = time.perf_counter() - t0
+    return {"value": round(frames_done / dt, 3), "unit": "frames/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{frames_done} frames of one stream through the 5-layer stack (dense oracle per layer), {dt:.1f} s"}
+
+
+# ------------------------------------------------------------------------------------------------
+# sweep over configs 2-4 (one layer at a time)
+# ------------------------------------------------------------------------------------------------
+def time_layer(seq, to_dev, weights, reps: int = 5):
+    """Per-step wall time (graph of one whole sequence, delta and dense path) and event-bracketed
+    kernel times of one layer over its frame sequence."""
+    import torch
+    import paper_1802_09723_amd as rrm
+    L = rrm.Layer(seq.shape, seq.dtype, weights, seq.bias)
+    xs = [to_dev(f) for f in seq.frames]
+    T = len(xs)
+    res = {}
+    for tag, path in (("delta", 0), ("dense", 2)):
+        L.set_option("path", path)
+        for x in xs:  # warm-up pass, leaves the snapshot at the last frame
+            L.step(x)
+        torch.cuda.synchronize()
+        # ping-pong through the sequence: T-2, ..., 0, 1, ..., T-1.  Every step is a genuine
+        # consecutive-frame difference and the replay ends where it starts.
+        order = xs[-2::-1] + xs[1:]
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for x in order:
+                L.step(x)
+        g.replay()
+        with Timer() as t:
+            for _ in range(reps):
+                g.replay()
+        res[f"{tag}_us"] = t.ms * 1e3 / (reps * len(order))
+        # event-bracketed kernels (eager)
+        s0 = L.stats()
+        L.set_option("profile", 1)
+        for x in order:
+            L.step(x)
+        torch.cuda.synchronize()
+        a, c, n = L.kernel_times()
+        L.set_option("profile", 0)
+        s1 = L.stats()
+        res[f"{tag}_scan_us"], res[f"{tag}_compute_us"] = a / max(n, 1), c / max(n, 1)
+        if path == 0:
+            res["stats"] = {k: (s1[k] - s0[k]) / max(n, 1) for k in ("changed_elems", "changed_units", "active_tiles", "total_tiles")}
+    L.destroy()
+    return res
+
+
+def run_sweep(args):
+    import torch
+    import rrm_synth as S
+    from paper_1802_09723_amd import binding  # noqa: F401
+    rows = []
+
+    def dev_i8(f):
+        return torch.from_numpy(np.ascontiguousarray(f)).cuda()
+
+    def dev_bf16(f):
+        return torch.from_numpy(np.ascontiguousarray(f).view(np.int16)).cuda()
+
+    def dev_bin(f):
+        return torch.from_numpy(S.pack_pm1(f).view(np.int32)).cuda()
+
+    # config 2: ResNet-18-shaped bf16 3x3 convs
+    for layer, hw, c in S.RESNET_LAYERS:
+        for frac in S.RESNET_DENSITIES:
+            seq = S.config2(layer, frac)
+            r = time_layer(seq, dev_bf16, seq.weights)
+            sh, stt = seq.shape, r["stats"]
+            scan_b, tile_b = conv_alg_bytes(sh, 2, stt["changed_units"], stt["active_tiles"], terms=2)
+            rho_elem = stt["changed_elems"] / (hw * hw * c)
+            ops = 2 * rho_elem * macs(sh)
+            kt = r["delta_scan_us"] + r["delta_compute_us"]
+            roof = max((scan_b + tile_b) / HBM_PEAK, ops / MFMA_PEAK[1]) * 1e6
+            rows.append({"config": 2, "case": seq.name, "rho_elem": rho_elem, "rho_tile": stt["active_tiles"] / max(stt["total_tiles"], 1),
+                         "step_us": r["delta_us"], "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"],
+                         "compute_us": r["delta_compute_us"], "dense_kernel_us": r["dense_compute_us"],
+                         "frames_per_s": 1e6 / r["delta_us"], "dense_equiv_gops": 2 * macs(sh) / r["delta_us"] * 1e-3,
+                         "speedup_vs_dense": r["dense_us"] / r["delta_us"], "alg_bytes": scan_b + tile_b, "roof_us": roof,
+                         "roof_bound": "hbm" if (scan_b + tile_b) / HBM_PEAK >= ops / MFMA_PEAK[1] else "mfma",
+                         "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]})
+            log("[sweep]", json.dumps(rows[-1]))
+    # config 3: FC sparse-delta mat-vec
+    for layer, ci, co in S.FC_LAYERS:
+        for dt, es in ((S.I8, 1), (S.BF16, 2)):
+            for frac in S.FC_DENSITIES:
+                seq = S.config3(layer, dt, frac)
+                r = time_layer(seq, dev_i8 if dt == S.I8 else dev_bf16, seq.weights)
+                nnz = r["stats"]["changed_elems"]
+                byts = nnz * co * es + 2 * ci * es + 2 * co * 4
+                kt = r["delta_scan_us"] + r["delta_compute_us"]
+                roof = byts / HBM_PEAK * 1e6
+                rows.append({"config": 3, "case": seq.name, "rho_elem": nnz / ci, "step_us": r["delta_us"],
+                             "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"], "compute_us": r["delta_compute_us"],
+                             "dense_kernel_us": r["dense_compute_us"], "frames_per_s": 1e6 / r["delta_us"],
+                             "dense_equiv_gops": 2 * ci * co / r["delta_us"] * 1e-3, "speedup_vs_dense": r["dense_us"] / r["delta_us"],
+                             "alg_bytes": byts, "roof_us": roof, "roof_bound": "hbm",
+                             "scatter_GBps": nnz * co * es / (r["delta_compute_us"] * 1e-6) / 1e9,
+                             "dense_GBps": ci * co * es / (r["dense_compute_us"] * 1e-6) / 1e9,
+                             "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]})
+                log("[sweep]", json.dumps(rows[-1]))
+    # config 4: binary conv
+    for layer, hw, c in S.XNOR_LAYERS:
+        for frac in S.XNOR_FLIPS:
+            seq = S.config4(layer, frac)
+            r = time_layer(seq, dev_bin, S.pack_pm1(seq.weights))
+            sh, stt = seq.shape, r["stats"]
+            words = stt["changed_units"] * 4  # upper bound on 32-bit words holding a flipped bit
+            lane_instr = 2 * words * c * 9
+            roof = max(lane_instr / VALU_LANE_PEAK, (2 * hw * hw * c / 8 + 2 * stt["active_tiles"] * 64 * c * 4) / HBM_PEAK) * 1e6
+            kt = r["delta_scan_us"] + r["delta_compute_us"]
+            rows.append({"config": 4, "case": seq.name, "rho_elem": stt["changed_elems"] / (hw * hw * c),
+                         "rho_tile": stt["active_tiles"] / max(stt["total_tiles"], 1), "step_us": r["delta_us"],
+                         "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"], "compute_us": r["delta_compute_us"],
+                         "dense_kernel_us": r["dense_compute_us"], "frames_per_s": 1e6 / r["delta_us"],
+                         "dense_equiv_gops": 2 * macs(sh) / r["delta_us"] * 1e-3, "speedup_vs_dense": r["dense_us"] / r["delta_us"],
+                         "roof_us": roof, "roof_bound": "alu", "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]})
+            log("[sweep]", json.dumps(rows[-1]))
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    with open(os.path.join(ROOT, "gpurun_out", "sweep.jsonl"), "w") as f:
+        for r in rows:
+            f.write(json.dumps(r) + "\n")
+    log("| case | rho_elem | step us | dense us | speedup | scan us | compute us | roof us | frac (kernels) |")
+    log("|---|---|---|---|---|---|---|---|---|")
+    for r in rows:
+        log(f"| {r['case']} | {r['rho_elem']:.3f} | {r['step_us']:.2f} | {r['dense_step_us']:.2f} | {r['speedup_vs_dense']:.2f} | "
+            f"{r['scan_us']:.2f} | {r['compute_us']:.2f} | {r['roof_us']:.3f} | {r['roof_frac_kernels']:.3f} |")
+    return rows
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=320)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--streams", type=int, default=int(os.environ.get("RRM_BENCH_STREAMS", "1")))
+    ap.add_argument("--no-graph", action="store_true", help="issue every launch from Python instead of replaying a HIP graph")
+    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--sweep", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (video streams are independent and would shard without any "
+              "collective); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    out = run_stack(args)
+    if args.sweep:
+        run_sweep(args)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

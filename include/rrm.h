@@ -125,13 +125,21 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
  *   "cout_block"  conv: output channels per workgroup, 16 / 32 / 64 (0 = heuristic)
  *   "fc_splits"   FC: number of workgroups the changed-column list is split over (0 = heuristic)
  *   "bf16_terms"  BF16 conv: 2 = difference carried as hi+lo bf16 pair (default), 1 = hi only
- *   "bin_cout_per_wave"  binary conv: output channels per wavefront, 8 / 16 (0 = heuristic) */
+ *   "bin_cout_per_wave"  binary conv: output channels per wavefront, 8 / 16 (0 = heuristic)
+ *   "profile"     1 = bracket every kernel of the following rrm_step calls with HIP events on the
+ *                 caller's stream (see rrm_get_kernel_times; not for use under graph capture), 0 = off */
 rrm_status rrm_set_option(rrm_layer* layer, const char* key, long value);
 
 /* Read the counters.  Synchronises with the device (copies a small block back); call it after
  * the stream has been synchronised, outside timed regions.  Returns RRM_ERR_RANGE (with *out
  * filled) if the sticky range flag is set. */
 rrm_status rrm_get_stats(rrm_layer* layer, rrm_stats* out);
+
+/* Kernel times of the rrm_step calls made since "profile" was switched on (or since the last call
+ * of this function): sums, in microseconds, of the event-bracketed durations of the scan kernel
+ * (delta + change map) and of the compute kernel (tile conv / column scatter / popcount conv), and
+ * the number of steps summed.  Synchronises with the recorded events.  At most 1024 steps are kept. */
+rrm_status rrm_get_kernel_times(rrm_layer* layer, double* scan_us, double* compute_us, int* steps);
 
 void rrm_layer_destroy(rrm_layer* layer);
 

@@ -71,6 +71,8 @@ def lib():
         L.rrm_read_snapshot.argtypes = [P, P, P, P]
         L.rrm_set_option.argtypes = [P, ctypes.c_char_p, ctypes.c_long]
         L.rrm_get_stats.argtypes = [P, ctypes.POINTER(Stats)]
+        L.rrm_get_kernel_times.argtypes = [P, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                           ctypes.POINTER(I)]
         L.rrm_layer_destroy.argtypes = [P]
         L.rrm_layer_destroy.restype = None
         L.rrm_status_string.argtypes = [I]
@@ -78,7 +80,7 @@ def lib():
         L.rrm_last_error.restype = ctypes.c_char_p
         L.rrm_aux_relu_requant_pool_i8.argtypes = [P, P, I, I, I, I, I, I, P]
         for f in ("rrm_layer_create", "rrm_step", "rrm_dense", "rrm_reset", "rrm_snapshot", "rrm_read_snapshot", "rrm_set_option",
-                  "rrm_get_stats", "rrm_aux_relu_requant_pool_i8"):
+                  "rrm_get_stats", "rrm_get_kernel_times", "rrm_aux_relu_requant_pool_i8"):
             getattr(L, f).restype = I
         _lib = L
     return _lib
@@ -160,6 +162,12 @@ class Layer:
         s = Stats()
         _check(lib().rrm_get_stats(self._h, ctypes.byref(s)), allow_range=allow_range_error)
         return s.as_dict()
+
+    def kernel_times(self):
+        """(scan_us, compute_us, steps) summed since "profile" was switched on / last read."""
+        a, c, n = ctypes.c_double(), ctypes.c_double(), ctypes.c_int()
+        _check(lib().rrm_get_kernel_times(self._h, ctypes.byref(a), ctypes.byref(c), ctypes.byref(n)))
+        return a.value, c.value, n.value
 
     def destroy(self) -> None:
         if getattr(self, "_h", None):

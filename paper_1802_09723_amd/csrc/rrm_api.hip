@@ -67,6 +67,10 @@ struct rrm_layer {
     // state
     bool has_snapshot = false;
     unsigned long long steps = 0, delta_steps = 0, total_tiles = 0;
+    // event brackets of the "profile" option: 3 events per step (before scan, between, after)
+    std::vector<hipEvent_t> prof_ev;
+    int prof_n = 0;
+    bool prof_on = false;
     // options
     int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0;
 
@@ -74,6 +78,7 @@ struct rrm_layer {
         void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, bitmap, tileflag, fc_idx, fc_val, fc_count, stats};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
+        for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
     }
 };
 
@@ -272,6 +277,22 @@ rrm_status setup_fc(rrm_layer* L, const std::vector<unsigned char>& w) {
     return dalloc((size_t)s.n * sizeof(int), (void**)&L->fc_count);
 }
 
+constexpr int kProfMax = 1024;
+
+// record the k-th (0..2) event of the current profiled step
+rrm_status prof_mark(rrm_layer* L, int k, hipStream_t s) {
+    if (!L->prof_on || L->prof_n >= kProfMax) return RRM_OK;
+    const size_t need = (size_t)3 * (L->prof_n + 1);
+    while (L->prof_ev.size() < need) {
+        hipEvent_t e;
+        RRM_HIP(hipEventCreate(&e));
+        L->prof_ev.push_back(e);
+    }
+    RRM_HIP(hipEventRecord(L->prof_ev[(size_t)3 * L->prof_n + k], s));
+    if (k == 2) ++L->prof_n;
+    return RRM_OK;
+}
+
 int conv_wm(const rrm_layer* L) {
     const ConvGeom& g = L->cg;
     if (L->opt_wm) return L->opt_wm;
@@ -400,28 +421,38 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
     const bool first_bin = L->dtype == RRM_BIN_I32 && !L->has_snapshot;
     if (L->opt_path == 2 || first_bin) {
         // full recomputation: P <- b + W (*) x_t, I <- x_t
-        if ((st = enqueue_dense(L, x_t, L->y_snap, s)) != RRM_OK) return st;
+        if ((st = prof_mark(L, 0, s)) != RRM_OK) return st;
         RRM_HIP(launch_copy(L->x_snap, x_t, L->x_bytes, s));
+        if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
+        if ((st = enqueue_dense(L, x_t, L->y_snap, s)) != RRM_OK) return st;
+        if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
     } else if (L->shape.kind == RRM_FC) {
+        if ((st = prof_mark(L, 0, s)) != RRM_OK) return st;
         RRM_HIP(launch_fc_scan(L->dtype, x_t, L->x_snap, L->fc_idx, L->fc_val, L->fc_count, L->fg, L->stats, s));
+        if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
         RRM_HIP(launch_fc_scatter(L->dtype, 0, fc_splits(L), L->wpack, L->fc_idx, L->fc_val, L->fc_count, nullptr,
                                   L->y_snap, L->fg, L->stats, s));
+        if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
         ++L->delta_steps;
         L->total_tiles += (unsigned long long)L->shape.n * L->shape.c_in;
     } else {
+        if ((st = prof_mark(L, 0, s)) != RRM_OK) return st;
         if (L->dtype == RRM_BIN_I32) {
             const int cw = bin_cw(L);
             RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag,
                                 (unsigned int)bin_consumers(cw, L->bg), L->sg, L->stats, s));
+            if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
             RRM_HIP(launch_bin_conv(MODE_DELTA, cw, L->x_snap, L->d0, L->tileflag, L->wpack, nullptr, L->y_snap, L->bg,
                                     L->stats, s));
         } else {
             const int wm = conv_wm(L);
             RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag,
                                 (unsigned int)conv_consumers(wm, L->cg), L->sg, L->stats, s));
+            if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
             RRM_HIP(launch_conv(L->dtype, MODE_DELTA, wm, L->dtype == RRM_BF16_F32 ? L->opt_terms : 1, L->d0, L->d1,
                                 L->tileflag, L->wpack, L->offtab, nullptr, L->y_snap, L->cg, L->stats, s));
         }
+        if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
         ++L->delta_steps;
         L->total_tiles += (unsigned long long)L->shape.n * L->sg.tiles_y * L->sg.tiles_x;
     }
@@ -488,6 +519,10 @@ rrm_status rrm_set_option(rrm_layer* L, const char* key, long value) {
     } else if (k == "bf16_terms") {
         if (value != 1 && value != 2) return fail(RRM_ERR_OPTION, "bf16_terms must be 1 or 2");
         L->opt_terms = (int)value;
+    } else if (k == "profile") {
+        if (value != 0 && value != 1) return fail(RRM_ERR_OPTION, "profile must be 0 or 1");
+        L->prof_on = value != 0;
+        L->prof_n = 0;
     } else if (k == "bin_cout_per_wave") {
         if (value != 0 && value != 8 && value != 16) return fail(RRM_ERR_OPTION, "bin_cout_per_wave must be 0, 8 or 16");
         L->opt_bin_cw = (int)value;
@@ -518,6 +553,24 @@ rrm_status rrm_get_stats(rrm_layer* L, rrm_stats* out) {
     out->range_error = (int32_t)d.range_error;
     out->reserved = 0;
     if (d.range_error) return fail(RRM_ERR_RANGE, "an int8 input difference did not fit int8");
+    return RRM_OK;
+}
+
+rrm_status rrm_get_kernel_times(rrm_layer* L, double* scan_us, double* compute_us, int* steps) {
+    if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
+    double a = 0.0, c = 0.0;
+    for (int i = 0; i < L->prof_n; ++i) {
+        float ms = 0.f;
+        RRM_HIP(hipEventSynchronize(L->prof_ev[(size_t)3 * i + 2]));
+        RRM_HIP(hipEventElapsedTime(&ms, L->prof_ev[(size_t)3 * i], L->prof_ev[(size_t)3 * i + 1]));
+        a += 1e3 * ms;
+        RRM_HIP(hipEventElapsedTime(&ms, L->prof_ev[(size_t)3 * i + 1], L->prof_ev[(size_t)3 * i + 2]));
+        c += 1e3 * ms;
+    }
+    if (scan_us) *scan_us = a;
+    if (compute_us) *compute_us = c;
+    if (steps) *steps = L->prof_n;
+    L->prof_n = 0;
     return RRM_OK;
 }
 
