@@ -80,9 +80,10 @@ typedef struct {
     uint64_t delta_steps;     /* of those, steps that took the sparse delta path */
     uint64_t changed_elems;   /* input elements (binary: bits) that differed from the snapshot */
     uint64_t changed_units;   /* 16-byte input units with any difference (FC: = changed_elems) */
-    uint64_t active_tiles;    /* conv: 8x8 output tiles recomputed; FC: columns streamed */
-    uint64_t total_tiles;     /* conv: tiles a dense step would compute, summed over delta steps;
-                                 FC: c_in summed over delta steps */
+    uint64_t active_tiles;    /* int8 / bf16 conv: 4x4 output sub-tiles recomputed; binary conv: 8x8 output
+                                 tiles recomputed; FC: columns streamed */
+    uint64_t total_tiles;     /* the same unit, counted as a dense step would, summed over delta steps
+                                 (FC: c_in per step) */
     int32_t range_error;      /* non-zero once an int8 difference overflowed */
     int32_t reserved;
 } rrm_stats;
@@ -122,7 +123,7 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
 
 /* Options (value semantics per key):
  *   "path"        0 auto, 1 sparse delta path always, 2 recompute densely every step
- *   "cout_block"  conv: output channels per workgroup, 16 / 32 / 64 (0 = heuristic)
+ *   "cout_block"  int8 / bf16 conv: output channels per workgroup, 16 or 64 (default by layer shape)
  *   "fc_splits"   FC: number of workgroups the changed-column list is split over (0 = heuristic)
  *   "bf16_terms"  BF16 conv: 2 = difference carried as hi+lo bf16 pair (default), 1 = hi only
  *   "bin_cout_per_wave"  binary conv: output channels per wavefront, 8 / 16 (0 = heuristic)

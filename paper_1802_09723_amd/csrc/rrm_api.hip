@@ -59,7 +59,9 @@ struct rrm_layer {
     void* d0 = nullptr;      // difference (bf16: head; binary: flip mask)
     void* d1 = nullptr;      // bf16: tail of the difference
     unsigned long long* bitmap = nullptr;
-    unsigned int* tileflag = nullptr;
+    unsigned int* tileflag = nullptr;  // binary: 8x8 tile stamps; int8 / bf16: 4x4 sub-tile bit array
+    size_t marks_bytes = 0;
+    unsigned int* ctrl = nullptr;      // arrival counter of the gather kernel
     int* fc_idx = nullptr;
     void* fc_val = nullptr;
     int* fc_count = nullptr;
@@ -75,7 +77,7 @@ struct rrm_layer {
     int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0;
 
     ~rrm_layer() {
-        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, bitmap, tileflag, fc_idx, fc_val, fc_count, stats};
+        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, bitmap, tileflag, ctrl, fc_idx, fc_val, fc_count, stats};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
         for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
@@ -146,40 +148,11 @@ unsigned int magic_for(int d) { return d <= 1 ? 0u : (unsigned int)((1ull << 32)
 constexpr int kPF = 4;  // K steps per slab are padded to the tile kernel's prefetch depth
 int nq_for(int ntaps, int sc) { return ((ntaps * sc + 3) / 4 + kPF - 1) / kPF * kPF; }
 
-rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
+// Pack the LDS offset table and the weights for the slab layout chosen in L->cg.
+rrm_status pack_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     const rrm_shape& s = L->shape;
     ConvGeom& g = L->cg;
-    g.n = s.n; g.h = s.h; g.w = s.w; g.c_in = s.c_in; g.c_out = s.c_out;
-    g.kh = s.kh; g.kw = s.kw; g.stride = s.stride; g.pad = s.pad; g.groups = s.groups;
-    g.ho = (s.h + 2 * s.pad - s.kh) / s.stride + 1;
-    g.wo = (s.w + 2 * s.pad - s.kw) / s.stride + 1;
-    g.cg = s.c_in / s.groups;
-    g.og = s.c_out / s.groups;
-    g.tiles_y = (g.ho + TILE - 1) / TILE;
-    g.tiles_x = (g.wo + TILE - 1) / TILE;
-    g.th_in = (TILE - 1) * s.stride + s.kh;
-    g.tw_in = (TILE - 1) * s.stride + s.kw;
-    g.per_vec = 16 / L->esize;
-    g.chunks = (g.cg + g.per_vec - 1) / g.per_vec;
     const int ntaps = s.kh * s.kw;
-    const int terms = L->dtype == RRM_BF16_F32 ? 2 : 1;
-    const long long npos = (long long)g.th_in * g.tw_in;
-    int sc = g.chunks < 8 ? g.chunks : 8;
-    auto lds_need = [&](int c) { return (long long)terms * npos * pitch_for(c) + (long long)nq_for(ntaps, c) * 16; };
-    while (sc > 1 && lds_need(sc) > 60 * 1024) --sc;
-    if (lds_need(sc) > 64 * 1024) return fail(RRM_ERR_SHAPE, "input window of one output tile does not fit LDS");
-    g.sc = sc;
-    g.nslab = (g.chunks + sc - 1) / sc;
-    g.pitch = pitch_for(sc);
-    g.nq = nq_for(ntaps, sc);
-    g.magic_sc[0] = magic_for(sc);
-    g.magic_sc[1] = magic_for(g.chunks - (g.nslab - 1) * sc);
-    g.magic_tw = magic_for(g.tw_in);
-    g.ncb = (g.og + 15) / 16;
-    g.fast_stage = ((s.c_in * L->esize) % 16 == 0) && ((g.cg * L->esize) % 16 == 0);
-    g.vec_store = (s.c_out % 4 == 0) && (g.og % 4 == 0);
-    g.lds_tile_bytes = (int)(npos * g.pitch);
-
     // LDS offsets of the K pairs (tap, chunk), per slab; padded pairs point at offset 0 and carry
     // zero weights.
     std::vector<int> tab((size_t)g.nslab * g.nq * 4, 0);
@@ -188,7 +161,7 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
         for (int e = 0; e < ntaps * sc_eff; ++e) {
             const int tap = e / sc_eff, cc = e % sc_eff;
             const int ky = tap / s.kw, kx = tap % s.kw;
-            tab[(size_t)slab * g.nq * 4 + e] = (ky * g.tw_in + kx) * g.pitch + cc * 16;
+            tab[(size_t)slab * g.nq * 4 + e] = (ky * g.ww + kx) * g.pitch + cc * 16;
         }
     }
     rrm_status st = upload(tab.data(), tab.size() * sizeof(int), (void**)&L->offtab);
@@ -218,6 +191,82 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
                     }
             }
     return upload(pack.data(), pack.size(), &L->wpack);
+}
+
+
+// LDS bytes of the gather kernel for a (sub-tiles per workgroup, chunks per slab) choice
+long long conv_lds_need(const ConvGeom& g, int terms, int nt, int sc, int ntaps) {
+    return (long long)terms * nt * g.wpos * pitch_for(sc) + (long long)nq_for(ntaps, sc) * 16;
+}
+
+// Fill the slab-dependent fields for a workgroup shape; false if it does not fit.
+bool conv_try_shape(ConvGeom& g, int terms, int nt, int ntaps) {
+    const int max_units = (terms == 2 ? CONV_MAX_STAGE_UNITS / 2 : CONV_MAX_STAGE_UNITS) * CONV_THREADS;
+    int sc = g.chunks < 16 ? g.chunks : 16;
+    // prefer slabs the kernel can stage through registers; a single chunk may exceed that (then the
+    // kernel stages it directly)
+    while (sc > 1 && (conv_lds_need(g, terms, nt, sc, ntaps) > 60 * 1024 || (long long)nt * g.wpos * sc > max_units)) --sc;
+    if (conv_lds_need(g, terms, nt, sc, ntaps) > 60 * 1024) sc = 0;
+    if (sc < 1) return false;
+    g.nt = nt;
+    g.sc = sc;
+    g.nslab = (g.chunks + sc - 1) / sc;
+    g.pitch = pitch_for(sc);
+    g.slot_bytes = g.wpos * g.pitch;
+    g.nq = nq_for(ntaps, sc);
+    const int last = g.chunks - (g.nslab - 1) * sc;
+    g.magic_sc[0] = magic_for(sc);
+    g.magic_sc[1] = magic_for(last);
+    g.magic_wsc[0] = magic_for(g.wpos * sc);
+    g.magic_wsc[1] = magic_for(g.wpos * last);
+    return true;
+}
+
+rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
+    const rrm_shape& s = L->shape;
+    ConvGeom& g = L->cg;
+    g.n = s.n; g.h = s.h; g.w = s.w; g.c_in = s.c_in; g.c_out = s.c_out;
+    g.kh = s.kh; g.kw = s.kw; g.stride = s.stride; g.pad = s.pad; g.groups = s.groups;
+    g.ho = (s.h + 2 * s.pad - s.kh) / s.stride + 1;
+    g.wo = (s.w + 2 * s.pad - s.kw) / s.stride + 1;
+    g.cg = s.c_in / s.groups;
+    g.og = s.c_out / s.groups;
+    g.sty = (g.ho + 3) / 4;
+    g.stx = (g.wo + 3) / 4;
+    g.n_sub = s.n * g.sty * g.stx;
+    g.n_words = (g.n_sub + 31) / 32;
+    g.wh = 3 * s.stride + s.kh;
+    g.ww = 3 * s.stride + s.kw;
+    g.wpos = g.wh * g.ww;
+    g.per_vec = 16 / L->esize;
+    g.chunks = (g.cg + g.per_vec - 1) / g.per_vec;
+    g.ncb = (g.og + 15) / 16;
+    g.wm = g.ncb >= 2 ? 4 : 1;
+    g.magic_ww = magic_for(g.ww);
+    g.magic_sub = magic_for(g.sty * g.stx);
+    g.magic_stx = magic_for(g.stx);
+    g.fast_stage = ((s.c_in * L->esize) % 16 == 0) && ((g.cg * L->esize) % 16 == 0);
+    g.vec_store = (s.c_out % 4 == 0) && (g.og % 4 == 0);
+    const int ntaps = s.kh * s.kw;
+    const int terms = L->dtype == RRM_BF16_F32 ? 2 : 1;
+    // Workgroup shape: as many sub-tiles per workgroup as LDS and the staging registers allow while a
+    // slab still holds at least 4 chunks (or all of them); the packing of the weights depends on it.
+    bool ok = false;
+    for (int nt : {16, 8, 4}) {
+        ConvGeom t = g;
+        if (conv_try_shape(t, terms, nt, ntaps) && (t.sc >= 4 || t.sc == t.chunks)) {
+            g = t;
+            ok = true;
+            break;
+        }
+    }
+    if (!ok && !conv_try_shape(g, terms, 4, ntaps)) {
+        // very large windows: one or two sub-tiles per workgroup, wavefronts over output channels
+        g.wm = 4;
+        if (!conv_try_shape(g, terms, 2, ntaps) && !conv_try_shape(g, terms, 1, ntaps))
+            return fail(RRM_ERR_SHAPE, "input window of one output sub-tile does not fit LDS");
+    }
+    return pack_conv(L, w);
 }
 
 rrm_status setup_bin(rrm_layer* L, const std::vector<unsigned char>& w) {
@@ -293,14 +342,6 @@ rrm_status prof_mark(rrm_layer* L, int k, hipStream_t s) {
     return RRM_OK;
 }
 
-int conv_wm(const rrm_layer* L) {
-    const ConvGeom& g = L->cg;
-    if (L->opt_wm) return L->opt_wm;
-    int wm = g.og <= 16 ? 1 : (g.og <= 32 ? 2 : 4);
-    while (wm > 1 && (long long)g.n * g.tiles_y * g.tiles_x * g.groups * ((g.ncb + wm - 1) / wm) < 256) wm /= 2;
-    return wm;
-}
-
 int bin_cw(const rrm_layer* L) {
     if (L->opt_bin_cw) return L->opt_bin_cw;
     const BinGeom& g = L->bg;
@@ -329,8 +370,8 @@ rrm_status enqueue_dense(rrm_layer* L, const void* x, void* y, hipStream_t st) {
     } else if (L->dtype == RRM_BIN_I32) {
         RRM_HIP(launch_bin_conv(MODE_DENSE, bin_cw(L), x, nullptr, nullptr, L->wpack, L->bias, y, L->bg, L->stats, st));
     } else {
-        RRM_HIP(launch_conv(L->dtype, MODE_DENSE, conv_wm(L), 1, x, nullptr, nullptr, L->wpack, L->offtab, L->bias, y,
-                            L->cg, L->stats, st));
+        RRM_HIP(launch_conv(L->dtype, MODE_DENSE, L->cg.wm, L->cg.nt, 1, x, nullptr, nullptr, nullptr, L->wpack, L->offtab,
+                            L->bias, y, L->cg, L->stats, st));
     }
     return RRM_OK;
 }
@@ -399,7 +440,13 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
         if ((st = dalloc(L->x_bytes, &L->d0)) != RRM_OK) return bail(st);
         if (dtype == RRM_BF16_F32 && (st = dalloc(L->x_bytes, &L->d1)) != RRM_OK) return bail(st);
         if ((st = dalloc(((nvec + 63) / 64) * 8, (void**)&L->bitmap)) != RRM_OK) return bail(st);
-        if ((st = dalloc((size_t)s.n * sg.tiles_y * sg.tiles_x * 4, (void**)&L->tileflag)) != RRM_OK) return bail(st);
+        sg.sty = (int)((ho + 3) / 4);
+        sg.stx = (int)((wo + 3) / 4);
+        // binary: one stamp per 8x8 tile; int8 / bf16: one bit per 4x4 sub-tile
+        L->marks_bytes = dtype == RRM_BIN_I32 ? (size_t)s.n * sg.tiles_y * sg.tiles_x * 4
+                                              : (size_t)((s.n * sg.sty * sg.stx + 31) / 32) * 4;
+        if ((st = dalloc(L->marks_bytes, (void**)&L->tileflag)) != RRM_OK) return bail(st);
+        if ((st = dalloc(16, (void**)&L->ctrl)) != RRM_OK) return bail(st);
     }
     // P_0 = b (Eq. 3 at I_0 = 0); I_0 = 0 comes from the zeroed allocation
     hipError_t e = launch_fill_bias(dtype == RRM_BF16_F32, L->y_snap, L->bias, L->y_elems / s.c_out, s.c_out, nullptr);
@@ -445,16 +492,16 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
             RRM_HIP(launch_bin_conv(MODE_DELTA, cw, L->x_snap, L->d0, L->tileflag, L->wpack, nullptr, L->y_snap, L->bg,
                                     L->stats, s));
         } else {
-            const int wm = conv_wm(L);
-            RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag,
-                                (unsigned int)conv_consumers(wm, L->cg), L->sg, L->stats, s));
+            RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag, 0u, L->sg, L->stats, s));
             if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
-            RRM_HIP(launch_conv(L->dtype, MODE_DELTA, wm, L->dtype == RRM_BF16_F32 ? L->opt_terms : 1, L->d0, L->d1,
-                                L->tileflag, L->wpack, L->offtab, nullptr, L->y_snap, L->cg, L->stats, s));
+            RRM_HIP(launch_conv(L->dtype, MODE_DELTA, L->cg.wm, L->cg.nt, L->dtype == RRM_BF16_F32 ? L->opt_terms : 1,
+                                L->d0, L->d1, L->tileflag, L->ctrl, L->wpack, L->offtab, nullptr, L->y_snap, L->cg,
+                                L->stats, s));
         }
         if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
         ++L->delta_steps;
-        L->total_tiles += (unsigned long long)L->shape.n * L->sg.tiles_y * L->sg.tiles_x;
+        L->total_tiles += L->dtype == RRM_BIN_I32 ? (unsigned long long)L->shape.n * L->sg.tiles_y * L->sg.tiles_x
+                                                   : (unsigned long long)L->shape.n * L->sg.sty * L->sg.stx;
     }
     L->has_snapshot = true;
     ++L->steps;
@@ -481,7 +528,8 @@ rrm_status rrm_reset(rrm_layer* L, void* hip_stream) {
         RRM_HIP(launch_fill_zero(L->d0, round16(L->x_bytes), s));
         if (L->d1) RRM_HIP(launch_fill_zero(L->d1, round16(L->x_bytes), s));
         RRM_HIP(launch_fill_zero(L->bitmap, round16(((round16(L->x_bytes) / 16 + 63) / 64) * 8), s));
-        RRM_HIP(launch_fill_zero(L->tileflag, round16((size_t)L->shape.n * L->sg.tiles_y * L->sg.tiles_x * 4), s));
+        RRM_HIP(launch_fill_zero(L->tileflag, round16(L->marks_bytes), s));
+        RRM_HIP(launch_fill_zero(L->ctrl, 16, s));
     }
     L->has_snapshot = false;
     L->steps = L->delta_steps = L->total_tiles = 0;
@@ -511,8 +559,10 @@ rrm_status rrm_set_option(rrm_layer* L, const char* key, long value) {
         if (value < 0 || value > 2) return fail(RRM_ERR_OPTION, "path must be 0, 1 or 2");
         L->opt_path = (int)value;
     } else if (k == "cout_block") {
-        if (value != 0 && value != 16 && value != 32 && value != 64) return fail(RRM_ERR_OPTION, "cout_block must be 0, 16, 32 or 64");
-        L->opt_wm = (int)value / 16;
+        if (L->shape.kind != RRM_CONV || L->dtype == RRM_BIN_I32) return fail(RRM_ERR_OPTION, "cout_block is an option of int8 / bf16 convolutions");
+        if (value != 16 && value != 64) return fail(RRM_ERR_OPTION, "cout_block must be 16 or 64");
+        if (value == 16 && L->cg.nt < 4) return fail(RRM_ERR_OPTION, "this layer's windows only fit with cout_block 64");
+        L->cg.wm = (int)value / 16;
     } else if (k == "fc_splits") {
         if (value < 0 || value > 4096) return fail(RRM_ERR_OPTION, "fc_splits must be in [0, 4096]");
         L->opt_fc_splits = (int)value;

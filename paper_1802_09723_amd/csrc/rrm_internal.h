@@ -33,28 +33,38 @@ struct ScanGeom {
     int h, w;                // input map
     int kh, kw, stride, pad;
     int ho, wo;
-    int tiles_y, tiles_x;
+    int tiles_y, tiles_x;    // 8x8 output tiles (binary path: stamped words)
+    int sty, stx;            // 4x4 output sub-tiles (MFMA path: one bit each)
     int per_vec;             // elements per 16-byte unit: 16 / 8 / 4
 };
 
-// Geometry of the tiled implicit-GEMM convolution (int8 / bf16 MFMA path).
+constexpr int CONV_MAX_STAGE_UNITS = 12;  // 16-byte units a thread stages per slab (half for 2 terms)
+
+// Geometry of the gather-tile implicit-GEMM convolution (int8 / bf16 MFMA path).
 struct ConvGeom {
     int n, h, w, c_in, c_out, kh, kw, stride, pad, groups;
     int ho, wo, cg, og;
-    int tiles_y, tiles_x;
-    int th_in, tw_in;    // input window of one 8x8 output tile
+    int sty, stx;        // 4x4 output sub-tiles per image
+    int n_sub;           // n*sty*stx
+    int n_words;         // 32-bit words of the sub-tile bit array
+    int wh, ww;          // input window of one sub-tile: 3*stride + kh, 3*stride + kw
+    int wpos;            // wh*ww
     int per_vec;         // elements per 16-byte K chunk (16 int8 / 8 bf16)
     int chunks;          // 16-byte chunks per (position, group): ceil(cg / per_vec)
     int sc;              // chunks per LDS slab
     int nslab;           // ceil(chunks / sc)
     int pitch;           // LDS bytes per staged position
-    int nq;              // MFMA K-steps per slab: ceil(kh*kw*sc / 4)
-    unsigned int magic_sc[2];  // floor(2^32/d)+1 for d = sc (full slab) and d = last slab's chunk count
-    unsigned int magic_tw;     // same for d = tw_in
+    int slot_bytes;      // wpos*pitch: LDS bytes of one sub-tile's window
+    int nq;              // MFMA K steps per slab (multiple of the prefetch depth)
     int ncb;             // 16-wide output-channel blocks per group
+    int wm, nt;          // workgroup shape: 16-channel blocks (1 or 4) and sub-tiles (4, 8, 16)
+    unsigned int magic_sc[2];   // reciprocals (floor(2^32/d)+1, 0 for d = 1): d = sc / last slab's chunks
+    unsigned int magic_wsc[2];  // d = wpos*sc / wpos*(last slab's chunks)
+    unsigned int magic_ww;      // d = ww
+    unsigned int magic_sub;     // d = sty*stx
+    unsigned int magic_stx;     // d = stx
     int fast_stage;      // 1: 16-byte aligned channel runs, vector staging
     int vec_store;       // 1: y rows allow 16-byte read-modify-write
-    int lds_tile_bytes;  // th_in*tw_in*pitch
 };
 
 // Geometry of the binary (XNOR / popcount) convolution.
@@ -81,13 +91,15 @@ struct FcGeom {
 };
 
 // ---- launchers implemented in the kernel translation units ------------------------------------
+// `marks` is the 8x8-tile stamp array (binary layers, stamp = consumers per tile) or the 4x4
+// sub-tile bit array (int8 / bf16 layers, stamp ignored)
 hipError_t launch_scan(int dtype, const void* x_t, void* x_snap, void* d0, void* d1, unsigned long long* bitmap,
-                       unsigned int* tileflag, unsigned int stamp, const ScanGeom& g, DevStats* stats,
+                       unsigned int* marks, unsigned int stamp, const ScanGeom& g, DevStats* stats,
                        hipStream_t s);
 
-hipError_t launch_conv(int dtype, int mode, int wm, int terms, const void* src0, const void* src1,
-                       unsigned int* tileflag, const void* wpack, const int* offtab, const void* bias, void* y,
-                       const ConvGeom& g, DevStats* stats, hipStream_t s);
+hipError_t launch_conv(int dtype, int mode, int wm, int nt, int terms, const void* src0, const void* src1,
+                       unsigned int* subbits, unsigned int* ctrl, const void* wpack, const int* offtab,
+                       const void* bias, void* y, const ConvGeom& g, DevStats* stats, hipStream_t s);
 
 hipError_t launch_fc_scan(int dtype, const void* x_t, void* x_snap, int* idx, void* val, int* count,
                           const FcGeom& g, DevStats* stats, hipStream_t s);
@@ -99,7 +111,6 @@ hipError_t launch_fc_scatter(int dtype, int dense, int splits, const void* wT, c
 hipError_t launch_bin_conv(int mode, int cw, const void* xsrc, const void* flip, unsigned int* tileflag,
                            const void* wpack, const void* bias, void* y, const BinGeom& g, DevStats* stats,
                            hipStream_t s);
-int conv_consumers(int wm, const ConvGeom& g);   // workgroups per tile of the MFMA tile kernel
 int bin_consumers(int cw, const BinGeom& g);     // workgroups per tile of the binary kernel
 
 hipError_t launch_fill_bias(int is_float, void* y, const void* bias, long long rows, int c_out, hipStream_t s);
