@@ -123,7 +123,6 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
 
 /* Options (value semantics per key):
  *   "path"        0 auto, 1 sparse delta path always, 2 recompute densely every step
- *   "cout_block"  int8 / bf16 conv: output channels per workgroup, 16 or 64 (default by layer shape)
  *   "fc_splits"   FC: number of workgroups the changed-column list is split over (0 = heuristic)
  *   "bf16_terms"  BF16 conv: 2 = difference carried as hi+lo bf16 pair (default), 1 = hi only
  *   "bin_cout_per_wave"  binary conv: output channels per wavefront, 8 / 16 (0 = heuristic)

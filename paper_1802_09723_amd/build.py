@@ -13,7 +13,7 @@ LIB = os.path.join(LIBDIR, "librrm_hip.so")
 SOURCES = ["rrm_api.hip", "scan.hip", "conv_gather.hip", "fc.hip", "bin_conv.hip", "aux.hip"]
 
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
+    "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared", "-fvisibility=hidden",
     "-munsafe-fp-atomics",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

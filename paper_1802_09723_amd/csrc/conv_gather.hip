@@ -5,24 +5,29 @@
 // computes Eq. 3, y = b + F * x, everywhere.
 //
 // Unit of work: a 4x4 block of output positions (a "sub-tile", 16 positions = one MFMA column
-// block).  The scan kernel sets one bit per sub-tile whose receptive field contains a changed input.
-// Every workgroup of this kernel reads that bit array (a few hundred bytes), ranks the set bits with
-// a popcount prefix sum, and takes its share of the ranked list: up to NT active sub-tiles from
+// block).  The scan kernel sets one byte flag per sub-tile whose receptive field contains a changed
+// input.  Every workgroup of this kernel reads that flag array (a few KB at most), ranks the set flags
+// with a popcount prefix sum, and takes its share of the ranked list: up to NT active sub-tiles from
 // anywhere in the batch.  They become the N dimension of one GEMM per workgroup:
-//     M = output channels (WM blocks of 16, one wavefront each)
+//     M = NCB blocks of 16 output channels
 //     N = 16 x (gathered sub-tiles)
 //     K = (filter tap, 16-byte channel chunk) pairs, four per MFMA
 //         (v_mfma_i32_16x16x64_i8 / v_mfma_f32_16x16x32_bf16; lane l supplies row/column l%16 and the
 //          16 bytes of pair 4q + l/16).
-// The weight operand is read from a copy of the filters packed at create time in that per-lane order
-// (one coalesced 1 KiB read per wavefront and K step, prefetched PF steps ahead in registers) and is
-// reused for all gathered sub-tiles; the activation operand comes from the sub-tiles' input windows
-// staged in LDS (slab by slab over the channel chunks, the next slab's loads in flight during the
-// current K loop).  In delta mode the staged data is the difference buffer, zero where nothing changed.
+// Both operands go through LDS, one slab of channel chunks at a time:
+//   * weights: the filters are packed at create time in per-lane MFMA order, K pairs ordered chunk by
+//     chunk, so a slab is a contiguous run of 1 KiB fragments per channel block; wavefronts copy them
+//     with LDS-direct loads (global_load_lds_dwordx4, no registers), double-buffered across slabs;
+//   * activations: the gathered sub-tiles' input windows, gathered 16 bytes per lane with the same
+//     LDS-direct loads (chunk index XOR-swizzled by position against bank conflicts; units outside the
+//     image read a block of zeros), also double-buffered.  In delta mode the source is the difference
+//     buffer, zero where nothing changed.
+// Each wavefront owns every fourth gathered sub-tile and all NCB channel blocks (register blocking
+// NCB x NT/4), so one weight fragment read feeds NT/4 MFMAs and one window read feeds NCB MFMAs.
 // The number of sub-tiles per workgroup adapts on the device: few active sub-tiles are spread one per
-// workgroup (latency), many are packed NT per workgroup (weight reuse).
+// workgroup (latency), many are packed NT per workgroup (operand reuse).
 // Every output element has exactly one owner: no atomics on y, results reproducible run to run.
-// The last workgroup to finish clears the bit array and the arrival counter, so nothing on the host
+// The last workgroup to arrive clears the flag array and the arrival counter, so nothing on the host
 // changes between steps (HIP-graph replay safe).
 #include "rrm_internal.h"
 
@@ -33,8 +38,6 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-
-constexpr int PF = 4;        // weight fragments in flight per wavefront; nq is a multiple of PF
 
 template <int DT>
 struct Acc;
@@ -64,40 +67,85 @@ __device__ __forceinline__ int fdiv(int u, unsigned int magic) {
     return magic ? (int)__umulhi((unsigned int)u, magic) : u;
 }
 
-template <int DT, int MODE, int WM, int NT, int TERMS>
+#ifdef RRM_TRACE
+// debug build only: cycle stamps of workgroup (0,0), wavefront 0 into the spare stats slots
+#define RRM_STAMP(k)                                                                               \
+    do {                                                                                           \
+        if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)                                \
+            reinterpret_cast<unsigned long long*>(stats + 32)[k] = __builtin_readcyclecounter();   \
+    } while (0)
+#else
+#define RRM_STAMP(k) do {} while (0)
+#endif
+
+typedef const void __attribute__((address_space(1))) * gptr_t;
+typedef void __attribute__((address_space(3))) * lptr_t;
+
+template <int DT, int MODE, int NCB, int NT, int TERMS>
 __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
-    const unsigned char* __restrict__ src0, const unsigned char* __restrict__ src1, unsigned int* subbits,
-    unsigned int* ctrl, const uint4* __restrict__ wpack, const int* __restrict__ offtab,
-    const void* __restrict__ bias_v, void* y_v, ConvGeom g, DevStats* __restrict__ stats) {
+    const unsigned char* __restrict__ src0, const unsigned char* __restrict__ src1,
+    const unsigned char* __restrict__ zero16, unsigned int* flags, unsigned int* ctrl,
+    const uint4* __restrict__ wpack, const int* __restrict__ offtab, const void* __restrict__ bias_v, void* y_v,
+    ConvGeom g, DevStats* __restrict__ stats) {
     typedef typename Acc<DT>::type acc_t;
     typedef typename Acc<DT>::vec vec_t;
     typedef typename Acc<DT>::scalar sc_t;
     constexpr int ESIZE = DT == RRM_I8_I32 ? 1 : 2;
-    constexpr int WN = 4 / WM;      // wavefronts along N
-    constexpr int NA = NT / WN;     // accumulators (sub-tiles) per wavefront
-    constexpr bool PREFETCH_Y = MODE == MODE_DELTA && NA <= 8;
-    constexpr int MAXU = TERMS == 2 ? CONV_MAX_STAGE_UNITS / 2 : CONV_MAX_STAGE_UNITS;  // per thread and slab
-    static_assert(NT % WN == 0 && NA >= 1, "bad tile shape");
+    constexpr int NS = NT / 4;  // gathered sub-tiles per wavefront
+    constexpr int MAXU = CONV_MAX_STAGE_UNITS;  // staged 16-byte units per thread and slab (host guarantees)
+    static_assert(NT % 4 == 0, "NT must be a multiple of the wavefront count");
 
+    // LDS: [weights x nbuf][windows (TERMS planes) x nbuf][K-pair table]
     extern __shared__ uint4 smem[];
-    unsigned char* tile0 = reinterpret_cast<unsigned char*>(smem);
-    unsigned char* tile1 = tile0 + (size_t)NT * g.slot_bytes;
-    int* tab = reinterpret_cast<int*>(tile0 + (size_t)TERMS * NT * g.slot_bytes);
-    __shared__ int s_sub[NT];          // gathered sub-tile ids
+    unsigned char* lds = reinterpret_cast<unsigned char*>(smem);
+    const int nbuf = g.nslab > 1 ? 2 : 1;
+    const int a_bytes = NCB * g.nq * 1024;
+    const int plane_bytes = NT * g.slot_bytes;  // one term's windows
+    const int b_bytes = TERMS * plane_bytes;
+    unsigned char* bbase = lds + nbuf * a_bytes;
+    int* tab = reinterpret_cast<int*>(bbase + nbuf * b_bytes);
+    __shared__ int s_sub[NT];   // gathered sub-tile ids
+    __shared__ int s_pix[NT];   // first input position of the sub-tile's image: b*h*w
+    __shared__ int s_iy0[NT];   // window origin in the input map (may be negative: padding)
+    __shared__ int s_ix0[NT];
+    __shared__ int s_ypos[NT];  // output position index of the sub-tile's corner: (b*ho + 4sy)*wo + 4sx
     __shared__ int s_scan[CONV_THREADS / WAVE];
     __shared__ int s_last;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const int ncbg = (g.ncb + NCB - 1) / NCB;  // channel-block groups per filter group
+    const int grp = blockIdx.y / ncbg;
+    const int cbg = blockIdx.y - grp * ncbg;
+    // packed weights: [group][channel block (padded to ncbg*NCB)][K step][lane]; a slab is K steps
+    // slab*nq .. slab*nq + nq - 1 of each of this workgroup's NCB blocks
+    const int kall = g.nslab * g.nq;
+    const uint4* wbase = wpack + ((size_t)(grp * ncbg + cbg) * NCB) * kall * 64 + lane;
+    auto stage_weights = [&](int slab) {
+        unsigned char* dst = lds + (slab & (nbuf - 1)) * a_bytes;
+#pragma unroll
+        for (int c = 0; c < NCB; ++c) {
+            const uint4* src = wbase + (size_t)(c * kall + slab * g.nq) * 64;
+            for (int q = wave; q < g.nq; q += 4)
+                __builtin_amdgcn_global_load_lds((gptr_t)(src + (size_t)q * 64), (lptr_t)(dst + (c * g.nq + q) * 1024), 16,
+                                                 0, 0);
+        }
+    };
+    RRM_STAMP(0);
+    // Small grids (one stream of a small map): the first weight slab does not depend on the work
+    // list, so its copy is started before the flag scan and overlaps it.
+    if (g.early_weights) stage_weights(0);
 
     // ---- which sub-tiles does this workgroup own? ----------------------------------------------------
     int count, excl = 0;
-    const int wpt = (g.n_words + CONV_THREADS - 1) / CONV_THREADS;  // bit-array words per thread
+    const int wpt = (g.n_words + CONV_THREADS - 1) / CONV_THREADS;  // flag words (4 flags each) per thread
     const int w_lo = tid * wpt, w_hi = min(w_lo + wpt, g.n_words);
     if (MODE == MODE_DELTA) {
-        // popcount prefix sum over the bit array (every workgroup does the same small scan)
+        // popcount prefix sum over the flag array (every workgroup does the same small scan)
         int mine = 0;
-        for (int w = w_lo; w < w_hi; ++w) mine += __popc(subbits[w]);
+        for (int w = w_lo; w < w_hi; ++w) mine += __popc(flags[w] & 0x01010101u);
         int incl = mine;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -122,20 +170,20 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
 
     if (MODE == MODE_DELTA) {
         if (mycount > 0) {
-            // the rank of a set bit is the number of set bits before it; keep ranks first .. first+mycount-1
+            // the rank of a set flag is the number of set flags before it; keep ranks first .. first+mycount-1
             int rank = excl;
             for (int w = w_lo; w < w_hi; ++w) {
-                unsigned int bits = subbits[w];
+                unsigned int bits = flags[w] & 0x01010101u;
                 while (bits) {
                     const int bpos = __ffs(bits) - 1;
                     bits &= bits - 1;
                     const int r = rank - first;
-                    if (r >= 0 && r < mycount) s_sub[r] = w * 32 + bpos;
+                    if (r >= 0 && r < mycount) s_sub[r] = w * 4 + (bpos >> 3);
                     ++rank;
                 }
             }
         }
-        // arrival: after this workgroup's last read of the bit array
+        // arrival: after this workgroup's last read of the flag array
         __syncthreads();
         if (tid == 0) {
             __threadfence();
@@ -145,262 +193,342 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
         }
         __syncthreads();
         if (s_last) {
-            // every workgroup has read the bits: clear them for the next step
-            for (int w = tid; w < g.n_words; w += CONV_THREADS) subbits[w] = 0u;
+            // every workgroup has read the flags: clear them for the next step
+            for (int w = tid; w < g.n_words; w += CONV_THREADS) flags[w] = 0u;
             if (tid == 0) {
                 ctrl[0] = 0u;
                 if (count) atomicAdd(&stats[0].active_tiles, (unsigned long long)count);
             }
         }
-        if (mycount <= 0) return;
-    } else {
-        if (mycount <= 0) return;
-        if (tid < mycount) s_sub[tid] = first + tid;
-        __syncthreads();
+    } else if (tid < mycount) {
+        s_sub[tid] = first + tid;
     }
-
-    const int nbg = (g.ncb + WM - 1) / WM;
-    const int grp = blockIdx.y / nbg;
-    const int bg = blockIdx.y - grp * nbg;
-    const int j = lane & 15, kgrp = lane >> 4;
-    const int wm_i = wave % WM, wn_i = wave / WM;
-    const int cb = bg * WM + wm_i;
-    const bool has_mma = cb < g.ncb;
-    const int co0 = cb * 16 + 4 * kgrp;  // first of this lane's 4 output channels, within the group
-    const bool vec_ok = g.vec_store && co0 + 3 < g.og;
-    const int subs_per_img = g.sty * g.stx;
-
-    // lane-constant offset of its output position inside a sub-tile's input window
-    const int posbase = (((j >> 2) * g.stride) * g.ww + (j & 3) * g.stride) * g.pitch;
-
-    long long ybase[NA];
-    bool ok[NA];
-    vec_t yold[PREFETCH_Y ? NA : 1];
-    acc_t acc[NA];
-#pragma unroll
-    for (int a = 0; a < NA; ++a) {
-        const int slot = wn_i + a * WN;
-        acc[a] = acc_t{0, 0, 0, 0};
-        ok[a] = false;
-        ybase[a] = 0;
-        if (slot < mycount) {
-            const int id = s_sub[slot];
-            const int b = fdiv(id, g.magic_sub);
-            const int r = id - b * subs_per_img;
-            const int sy = fdiv(r, g.magic_stx), sx = r - sy * g.stx;
-            const int oy = 4 * sy + (j >> 2), ox = 4 * sx + (j & 3);
-            ok[a] = has_mma && oy < g.ho && ox < g.wo && co0 < g.og;
-            ybase[a] = (((long long)b * g.ho + oy) * g.wo + ox) * g.c_out + (long long)grp * g.og + co0;
-            if (PREFETCH_Y && ok[a] && vec_ok)
-                yold[PREFETCH_Y ? a : 0] = *reinterpret_cast<const vec_t*>(static_cast<const sc_t*>(y_v) + ybase[a]);
-        }
+    if (mycount <= 0) {
+        __builtin_amdgcn_s_waitcnt(0);  // let an early weight copy land before the LDS is released
+        return;
     }
-
-    const int ntab = g.nq * 4;
-    const int ktotal = g.nslab * g.nq;
-    const uint4* wp = wpack + (((long long)grp * g.ncb + (has_mma ? cb : 0)) * ktotal) * 64 + lane;
-    uint4 abuf[PF];
-#pragma unroll
-    for (int i = 0; i < PF; ++i) abuf[i] = wp[(long long)min(i, ktotal - 1) * 64];
-    int kk = 0;
-
-    // ---- staging: global -> registers -> LDS, one slab of channel chunks at a time ---------------------
-    uint4 st0[MAXU], st1[TERMS == 2 ? MAXU : 1];
-    // value(s) of staged unit u of a slab: 16 bytes of one (sub-tile, window position, chunk)
-    auto fetch_unit = [&](int u, int slab, bool last, int sc_eff, int per_slot, uint4& v0, uint4& v1, int& lds_off) {
-        const int slot = fdiv(u, g.magic_wsc[last ? 1 : 0]);
-        const int r = u - slot * per_slot;
-        const int hp = fdiv(r, g.magic_sc[last ? 1 : 0]), cc = r - hp * sc_eff;
-        lds_off = slot * g.slot_bytes + hp * g.pitch + cc * 16;
-        const int hy = fdiv(hp, g.magic_ww), hx = hp - hy * g.ww;
-        const int id = s_sub[slot];
+    __syncthreads();
+    // per-slot geometry, once
+    if (tid < mycount) {
+        const int id = s_sub[tid];
         const int b = fdiv(id, g.magic_sub);
-        const int rr = id - b * subs_per_img;
-        const int sy = fdiv(rr, g.magic_stx), sx = rr - sy * g.stx;
-        const int iy = 4 * sy * g.stride - g.pad + hy, ix = 4 * sx * g.stride - g.pad + hx;
-        v0 = make_uint4(0, 0, 0, 0);
-        v1 = make_uint4(0, 0, 0, 0);
-        if (iy >= 0 && iy < g.h && ix >= 0 && ix < g.w) {
-            const long long ebase = ((((long long)b * g.h + iy) * g.w + ix) * g.c_in) + (long long)grp * g.cg +
-                                    (long long)(slab * g.sc + cc) * g.per_vec;
-            if (g.fast_stage) {
-                v0 = *reinterpret_cast<const uint4*>(src0 + ebase * ESIZE);
-                if (TERMS == 2) v1 = *reinterpret_cast<const uint4*>(src1 + ebase * ESIZE);
-            } else {
-                unsigned int w0[4] = {0, 0, 0, 0}, w1[4] = {0, 0, 0, 0};
-                const int c0 = (slab * g.sc + cc) * g.per_vec;
-                for (int e = 0; e < g.per_vec; ++e) {
-                    if (c0 + e >= g.cg) break;
-                    const long long ei = ebase + e;
-                    if (ESIZE == 1) {
-                        w0[e >> 2] |= (unsigned int)src0[ei] << (8 * (e & 3));
-                    } else {
-                        w0[e >> 1] |= (unsigned int)reinterpret_cast<const unsigned short*>(src0)[ei] << (16 * (e & 1));
-                        if (TERMS == 2)
-                            w1[e >> 1] |= (unsigned int)reinterpret_cast<const unsigned short*>(src1)[ei] << (16 * (e & 1));
-                    }
-                }
-                v0 = make_uint4(w0[0], w0[1], w0[2], w0[3]);
-                v1 = make_uint4(w1[0], w1[1], w1[2], w1[3]);
-            }
+        const int r = id - b * (g.sty * g.stx);
+        const int sy = fdiv(r, g.magic_stx), sx = r - sy * g.stx;
+        s_pix[tid] = b * g.h * g.w;
+        s_iy0[tid] = 4 * sy * g.stride - g.pad;
+        s_ix0[tid] = 4 * sx * g.stride - g.pad;
+        s_ypos[tid] = (b * g.ho + 4 * sy) * g.wo + 4 * sx;
+    }
+    for (int e = tid; e < g.nq * 4; e += CONV_THREADS) tab[e] = offtab[e];  // the same for every slab
+    __syncthreads();
+    RRM_STAMP(1);
+
+    // ---- window staging --------------------------------------------------------------------------------
+    // A staged unit is 16 bytes of one (sub-tile, window position, chunk-in-slab).  Unit v lives at LDS
+    // byte 16*v of its plane, v = (slot*wpos + hp)*sc + cs, where the chunk is XOR-swizzled with the
+    // position, cs = cc ^ (hp & swz), so that the MFMA operand reads of neighbouring positions fall into
+    // different banks.  Consecutive lanes own consecutive units, which is what the LDS-direct gather
+    // (per-lane global address, LDS address = wave base + 16*lane) needs.  The decomposition does not
+    // depend on the slab, so each thread works out the source offsets of its units once; a slab only adds
+    // its channel offset.  Units outside the image, or whose chunk does not exist in the last slab, read
+    // a 16-byte block of zeros instead.
+    const int units = mycount * g.wpos * g.sc;
+    const int my_units = units > tid ? (units - tid + CONV_THREADS - 1) / CONV_THREADS : 0;  // this thread's share
+    unsigned int uoff[MAXU];   // source byte offset at slab 0, 0xFFFFFFFF = zeros
+    unsigned int ulast = 0;    // bit i: unit i's chunk does not exist in the last slab
+#pragma unroll
+    for (int i = 0; i < MAXU; ++i) {
+        uoff[i] = 0xFFFFFFFFu;
+        if (i < my_units) {
+            const int v = tid + i * CONV_THREADS;
+            const int r = fdiv(v, g.magic_sc[0]), cs = v - r * g.sc;
+            const int slot = fdiv(r, g.magic_wsc[0]), hp = r - slot * g.wpos;
+            const int hy = fdiv(hp, g.magic_ww), hx = hp - hy * g.ww;
+            const int cc = cs ^ (hp & g.swz);
+            const int iy = s_iy0[slot] + hy, ix = s_ix0[slot] + hx;
+            if (cc >= g.last_sc) ulast |= 1u << i;
+            if (iy >= 0 && iy < g.h && ix >= 0 && ix < g.w)
+                uoff[i] = ((unsigned int)(s_pix[slot] + iy * g.w + ix) * (unsigned int)g.c_in +
+                           (unsigned int)(grp * g.cg + cc * g.per_vec)) * (unsigned int)ESIZE;
         }
+    }
+    // element-wise fetch for channel runs that are not 16-byte aligned (e.g. 3 input channels)
+    auto fetch_slow = [&](const unsigned char* src, unsigned int goff, int c0) -> uint4 {
+        unsigned int a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+        for (int e = 0; e < g.per_vec; ++e) {
+            if (c0 + e >= g.cg) break;
+            unsigned int x0;
+            int sh, wd;
+            if (ESIZE == 1) {
+                x0 = src[goff + e];
+                sh = 8 * (e & 3);
+                wd = e >> 2;
+            } else {
+                x0 = *reinterpret_cast<const unsigned short*>(src + goff + 2 * e);
+                sh = 16 * (e & 1);
+                wd = e >> 1;
+            }
+            x0 <<= sh;
+            a0 |= wd == 0 ? x0 : 0u; a1 |= wd == 1 ? x0 : 0u; a2 |= wd == 2 ? x0 : 0u; a3 |= wd == 3 ? x0 : 0u;
+        }
+        return make_uint4(a0, a1, a2, a3);
     };
-    // Register-buffered staging (loads of the next slab overlap the current K loop) when a slab is at
-    // most MAXU units per thread; otherwise global -> LDS directly at store time.
-    const bool reg_stage = (long long)NT * g.wpos * g.sc <= (long long)MAXU * CONV_THREADS;
-    auto stage_load = [&](int slab) {
-        if (!reg_stage) return;
+    const unsigned int slab_src_bytes = (unsigned int)(g.sc * 16);  // source bytes between consecutive slabs
+    auto stage_windows = [&](int slab) {
+        unsigned char* dst = bbase + (slab & (nbuf - 1)) * b_bytes;
         const bool last = slab == g.nslab - 1;
-        const int sc_eff = last ? g.chunks - slab * g.sc : g.sc;
-        const int per_slot = g.wpos * sc_eff;
-        const int units = mycount * per_slot;
 #pragma unroll
         for (int i = 0; i < MAXU; ++i) {
-            const int u = tid + i * CONV_THREADS;
-            uint4 v0 = make_uint4(0, 0, 0, 0), v1 = make_uint4(0, 0, 0, 0);
-            int o;
-            if (u < units) fetch_unit(u, slab, last, sc_eff, per_slot, v0, v1, o);
-            st0[i] = v0;
-            if (TERMS == 2) st1[i] = v1;
-        }
-    };
-    auto stage_store = [&](int slab) {
-        const bool last = slab == g.nslab - 1;
-        const int sc_eff = last ? g.chunks - slab * g.sc : g.sc;
-        const int per_slot = g.wpos * sc_eff;
-        const int units = mycount * per_slot;
-        if (reg_stage) {
-#pragma unroll
-            for (int i = 0; i < MAXU; ++i) {
-                const int u = tid + i * CONV_THREADS;
-                if (u < units) {
-                    const int slot = fdiv(u, g.magic_wsc[last ? 1 : 0]);
-                    const int r = u - slot * per_slot;
-                    const int hp = fdiv(r, g.magic_sc[last ? 1 : 0]), cc = r - hp * sc_eff;
-                    const int o = slot * g.slot_bytes + hp * g.pitch + cc * 16;
-                    *reinterpret_cast<uint4*>(tile0 + o) = st0[i];
-                    if (TERMS == 2) *reinterpret_cast<uint4*>(tile1 + o) = st1[i];
+            if (i >= my_units) break;
+            const bool real = uoff[i] != 0xFFFFFFFFu && !(last && ((ulast >> i) & 1u));
+            const unsigned int o = uoff[i] + (unsigned int)slab * slab_src_bytes;
+            unsigned char* d = dst + (i * CONV_THREADS + wave * 64) * 16;  // wave-uniform; lane adds 16*lane
+            if (g.fast_stage) {
+                const unsigned char* p0 = real ? src0 + o : zero16;
+                __builtin_amdgcn_global_load_lds((gptr_t)p0, (lptr_t)d, 16, 0, 0);
+                if (TERMS == 2) {
+                    const unsigned char* p1 = real ? src1 + o : zero16;
+                    __builtin_amdgcn_global_load_lds((gptr_t)p1, (lptr_t)(d + plane_bytes), 16, 0, 0);
                 }
-            }
-        } else {
-            for (int u = tid; u < units; u += CONV_THREADS) {
-                uint4 v0, v1;
-                int o;
-                fetch_unit(u, slab, last, sc_eff, per_slot, v0, v1, o);
-                *reinterpret_cast<uint4*>(tile0 + o) = v0;
-                if (TERMS == 2) *reinterpret_cast<uint4*>(tile1 + o) = v1;
+            } else {
+                // slow path: compose the unit from single elements and store it
+                const int v = tid + i * CONV_THREADS;
+                const int r = fdiv(v, g.magic_sc[0]), cs = v - r * g.sc;
+                const int hp = r - fdiv(r, g.magic_wsc[0]) * g.wpos;
+                const int c0 = (slab * g.sc + (cs ^ (hp & g.swz))) * g.per_vec;
+                uint4 v0 = make_uint4(0, 0, 0, 0), v1 = make_uint4(0, 0, 0, 0);
+                if (real) {
+                    v0 = fetch_slow(src0, o, c0);
+                    if (TERMS == 2) v1 = fetch_slow(src1, o, c0);
+                }
+                *reinterpret_cast<uint4*>(d + lane * 16) = v0;
+                if (TERMS == 2) *reinterpret_cast<uint4*>(d + plane_bytes + lane * 16) = v1;
             }
         }
-        for (int e = tid; e < ntab; e += CONV_THREADS) tab[e] = offtab[slab * ntab + e];
     };
 
-    stage_load(0);
+    const int j = lane & 15, kgrp = lane >> 4;
+    // lane-constant window position of its output position (tap 0,0)
+    const int hp_lane = ((j >> 2) * g.stride) * g.ww + (j & 3) * g.stride;
+    // this wavefront's sub-tile slots are wave, wave + 4, ...: how many of them are in use
+    const int nact = mycount > wave ? (mycount - wave + 3) / 4 : 0;
+
+    acc_t acc[NCB][NS];
+#pragma unroll
+    for (int c = 0; c < NCB; ++c)
+#pragma unroll
+        for (int s = 0; s < NS; ++s) acc[c][s] = acc_t{0, 0, 0, 0};
+
+    // ---- K loop of one slab, compiled per number of sub-tiles in use by the wavefront (no per-sub-tile
+    //      branches; unused slots read stale LDS and their results are dropped) --------------------------
+    auto k_loop = [&]<int NSA>(const unsigned char* aw, const unsigned char* bw) {
+        const unsigned char* ap = aw + lane * 16;
+        const unsigned char* bp = bw + wave * g.slot_bytes;
+        const int sstride = 4 * g.slot_bytes;
+        const int* tp = tab + kgrp;
+        const int sc16 = g.sc * 16;
+        uint4 a[NCB], b0[NSA], b1[TERMS == 2 ? NSA : 1];
+        auto fetch = [&](int q, uint4(&a_)[NCB], uint4(&b0_)[NSA], uint4(&b1_)[TERMS == 2 ? NSA : 1]) {
+            const int t = tp[4 * q];                  // (window position of the tap) | chunk << 16
+            const int hp = hp_lane + (t & 0xFFFF);
+            const int off = hp * sc16 + (((t >> 16) ^ (hp & g.swz)) << 4);
+#pragma unroll
+            for (int c = 0; c < NCB; ++c) a_[c] = *reinterpret_cast<const uint4*>(ap + (c * g.nq + q) * 1024);
+#pragma unroll
+            for (int s = 0; s < NSA; ++s) {
+                b0_[s] = *reinterpret_cast<const uint4*>(bp + off + s * sstride);
+                if (TERMS == 2) b1_[s] = *reinterpret_cast<const uint4*>(bp + plane_bytes + off + s * sstride);
+            }
+        };
+        // software pipeline: the operands of K step q+1 are read from LDS while step q multiplies
+        fetch(0, a, b0, b1);
+        for (int q = 0; q < g.nq; ++q) {
+            uint4 an[NCB], b0n[NSA], b1n[TERMS == 2 ? NSA : 1];
+            fetch(min(q + 1, g.nq - 1), an, b0n, b1n);
+#pragma unroll
+            for (int c = 0; c < NCB; ++c)
+#pragma unroll
+                for (int s = 0; s < NSA; ++s) {
+                    acc[c][s] = mma(a[c], b0[s], acc[c][s]);
+                    if (TERMS == 2) acc[c][s] = mma(a[c], b1[s], acc[c][s]);
+                }
+#pragma unroll
+            for (int c = 0; c < NCB; ++c) a[c] = an[c];
+#pragma unroll
+            for (int s = 0; s < NSA; ++s) {
+                b0[s] = b0n[s];
+                if (TERMS == 2) b1[s] = b1n[s];
+            }
+        }
+    };
+
+    RRM_STAMP(2);
+    if (!g.early_weights) stage_weights(0);
+    stage_windows(0);
+    RRM_STAMP(3);
     for (int slab = 0; slab < g.nslab; ++slab) {
-        if (slab) __syncthreads();  // everyone is done reading the previous slab
-        stage_store(slab);
-        __syncthreads();
-        if (slab + 1 < g.nslab) stage_load(slab + 1);  // in flight during this slab's K loop
-        if (has_mma) {
-            for (int q = 0; q < g.nq; q += PF) {
+        if (slab < 2) RRM_STAMP(4 + 5 * slab);
+        __builtin_amdgcn_s_waitcnt(0);  // this wavefront's copies for this slab have landed in LDS
+        if (slab < 2) RRM_STAMP(5 + 5 * slab);
+        __syncthreads();  // ... and everyone else's; everyone is also done with the other buffer
+        if (slab < 2) RRM_STAMP(6 + 5 * slab);
+        if (slab + 1 < g.nslab) {  // next slab in flight during this slab's K loop
+            stage_weights(slab + 1);
+            stage_windows(slab + 1);
+        }
+        if (slab < 2) RRM_STAMP(7 + 5 * slab);
+        const unsigned char* aw = lds + (slab & (nbuf - 1)) * a_bytes;
+        const unsigned char* bw = bbase + (slab & (nbuf - 1)) * b_bytes;
+        if (nact > 2) {
+            if constexpr (NS >= 4) k_loop.template operator()<4>(aw, bw);
+        } else if (nact > 1) {
+            if constexpr (NS >= 2) k_loop.template operator()<2>(aw, bw);
+        } else if (nact > 0) {
+            k_loop.template operator()<1>(aw, bw);
+        }
+        if (slab < 2) RRM_STAMP(8 + 5 * slab);
+    }
+    RRM_STAMP(14);
+
+    // ---- epilogue: lane holds 4 consecutive output channels of one position ----------------------------
+    // Addresses first, then every load (stored projection / bias) in flight together, then the stores:
+    // a read-modify-write per accumulator would serialise one memory round trip after another.
+    sc_t* y = static_cast<sc_t*>(y_v);
+    const sc_t* bias = static_cast<const sc_t*>(bias_v);
+    unsigned int ybase[NS];
+    bool pos_ok[NS];
 #pragma unroll
-                for (int p = 0; p < PF; ++p) {
-                    const uint4 a = abuf[p];
-                    abuf[p] = wp[(long long)min(kk + PF, ktotal - 1) * 64];  // refill PF steps ahead
-                    ++kk;
-                    const int off = tab[4 * (q + p) + kgrp] + posbase;
+    for (int s = 0; s < NS; ++s) {
+        const int slot = wave + 4 * s;
+        pos_ok[s] = false;
+        ybase[s] = 0;
+        if (slot < mycount) {
+            const int yp = s_ypos[slot];               // (b*ho + 4sy)*wo + 4sx
+            const int py = j >> 2, px = j & 3;
+            const int row = fdiv(yp, g.magic_wo);      // b*ho + 4sy
+            const int col = yp - row * g.wo + px;      // 4sx + px
+            const int rin = row - fdiv(row, g.magic_ho) * g.ho + py;  // 4sy + py
+            pos_ok[s] = col < g.wo && rin < g.ho;
+            ybase[s] = (unsigned int)(yp + py * g.wo + px) * (unsigned int)g.c_out + (unsigned int)(grp * g.og);
+        }
+    }
+    const bool all_vec = g.vec_store && (cbg * NCB + NCB) * 16 <= g.og;  // every lane's 4 channels exist
+    if (all_vec) {
+        if (MODE == MODE_DELTA) {
+            vec_t old[NCB][NS];
 #pragma unroll
-                    for (int s = 0; s < NA; ++s) {
-                        const int slot = wn_i + s * WN;
-                        if (slot < mycount) {  // wave-uniform
-                            const uint4 b0 = *reinterpret_cast<const uint4*>(tile0 + slot * g.slot_bytes + off);
-                            acc[s] = mma(a, b0, acc[s]);
-                            if (TERMS == 2) {
-                                const uint4 b1 = *reinterpret_cast<const uint4*>(tile1 + slot * g.slot_bytes + off);
-                                acc[s] = mma(a, b1, acc[s]);
-                            }
-                        }
+            for (int c = 0; c < NCB; ++c)
+#pragma unroll
+                for (int s = 0; s < NS; ++s)
+                    if (pos_ok[s])
+                        old[c][s] = *reinterpret_cast<const vec_t*>(y + (ybase[s] + (unsigned int)((cbg * NCB + c) * 16 + 4 * kgrp)));
+#pragma unroll
+            for (int c = 0; c < NCB; ++c)
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    if (!pos_ok[s]) continue;
+                    const acc_t r = acc[c][s];
+                    if (r[0] == (sc_t)0 && r[1] == (sc_t)0 && r[2] == (sc_t)0 && r[3] == (sc_t)0) continue;
+                    vec_t o = old[c][s];
+                    o.x += r[0]; o.y += r[1]; o.z += r[2]; o.w += r[3];
+                    *reinterpret_cast<vec_t*>(y + (ybase[s] + (unsigned int)((cbg * NCB + c) * 16 + 4 * kgrp))) = o;
+                }
+        } else {
+            vec_t bv[NCB];
+#pragma unroll
+            for (int c = 0; c < NCB; ++c) {
+                bv[c] = vec_t{0, 0, 0, 0};
+                if (bias) bv[c] = *reinterpret_cast<const vec_t*>(bias + grp * g.og + (cbg * NCB + c) * 16 + 4 * kgrp);
+            }
+#pragma unroll
+            for (int c = 0; c < NCB; ++c)
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    if (!pos_ok[s]) continue;
+                    const acc_t r = acc[c][s];
+                    vec_t o;
+                    o.x = r[0] + bv[c].x; o.y = r[1] + bv[c].y; o.z = r[2] + bv[c].z; o.w = r[3] + bv[c].w;
+                    *reinterpret_cast<vec_t*>(y + (ybase[s] + (unsigned int)((cbg * NCB + c) * 16 + 4 * kgrp))) = o;
+                }
+        }
+    } else {
+        // ragged channel counts: element by element
+#pragma unroll
+        for (int c = 0; c < NCB; ++c) {
+            const int co0 = (cbg * NCB + c) * 16 + 4 * kgrp;  // within the filter group
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                if (!pos_ok[s] || co0 >= g.og) continue;
+                sc_t* yp4 = y + (ybase[s] + (unsigned int)co0);
+                const acc_t r = acc[c][s];
+                for (int k = 0; k < 4 && co0 + k < g.og; ++k) {
+                    if (MODE == MODE_DELTA) {
+                        if (r[k] != (sc_t)0) yp4[k] += r[k];
+                    } else {
+                        yp4[k] = r[k] + (bias ? bias[grp * g.og + co0 + k] : (sc_t)0);
                     }
                 }
             }
         }
     }
-
-    // ---- epilogue: lane holds 4 consecutive output channels of one position ----------------------------
-    sc_t* y = static_cast<sc_t*>(y_v);
-    const sc_t* bias = static_cast<const sc_t*>(bias_v);
-#pragma unroll
-    for (int a = 0; a < NA; ++a) {
-        if (!ok[a]) continue;
-        const sc_t r[4] = {acc[a][0], acc[a][1], acc[a][2], acc[a][3]};
-        if (MODE == MODE_DELTA) {
-            if (r[0] == (sc_t)0 && r[1] == (sc_t)0 && r[2] == (sc_t)0 && r[3] == (sc_t)0) continue;
-            if (vec_ok) {
-                vec_t o;
-                if (PREFETCH_Y)
-                    o = yold[PREFETCH_Y ? a : 0];
-                else
-                    o = *reinterpret_cast<const vec_t*>(y + ybase[a]);
-                o.x += r[0]; o.y += r[1]; o.z += r[2]; o.w += r[3];
-                *reinterpret_cast<vec_t*>(y + ybase[a]) = o;
-            } else {
-                for (int k = 0; k < 4 && co0 + k < g.og; ++k) y[ybase[a] + k] += r[k];
-            }
-        } else {
-            const int bo = grp * g.og + co0;
-            if (vec_ok) {
-                vec_t o;
-                o.x = r[0] + (bias ? bias[bo] : (sc_t)0);
-                o.y = r[1] + (bias ? bias[bo + 1] : (sc_t)0);
-                o.z = r[2] + (bias ? bias[bo + 2] : (sc_t)0);
-                o.w = r[3] + (bias ? bias[bo + 3] : (sc_t)0);
-                *reinterpret_cast<vec_t*>(y + ybase[a]) = o;
-            } else {
-                for (int k = 0; k < 4 && co0 + k < g.og; ++k) y[ybase[a] + k] = r[k] + (bias ? bias[bo + k] : (sc_t)0);
-            }
-        }
-    }
+    RRM_STAMP(15);
 }
 
-template <int DT, int MODE, int WM, int NT, int TERMS>
-hipError_t launch_one(const void* src0, const void* src1, unsigned int* subbits, unsigned int* ctrl,
-                      const void* wpack, const int* offtab, const void* bias, void* y, const ConvGeom& g,
-                      DevStats* stats, hipStream_t s) {
-    const int nbg = (g.ncb + WM - 1) / WM;
-    dim3 grid((unsigned int)((g.n_sub + NT - 1) / NT), (unsigned int)(g.groups * nbg));
-    const size_t lds = (size_t)TERMS * NT * g.slot_bytes + (size_t)g.nq * 4 * sizeof(int);
-    hipLaunchKernelGGL((conv_gather_kernel<DT, MODE, WM, NT, TERMS>), grid, dim3(CONV_THREADS), lds, s,
-                       static_cast<const unsigned char*>(src0), static_cast<const unsigned char*>(src1), subbits,
-                       ctrl, static_cast<const uint4*>(wpack), offtab, bias, y, g, stats);
+template <int DT, int MODE, int NCB, int NT, int TERMS>
+hipError_t launch_one(const void* src0, const void* src1, const void* zero16, unsigned int* flags,
+                      unsigned int* ctrl, const void* wpack, const int* offtab, const void* bias, void* y,
+                      const ConvGeom& g, DevStats* stats, hipStream_t s) {
+    const int ncbg = (g.ncb + NCB - 1) / NCB;
+    dim3 grid((unsigned int)((g.n_sub + NT - 1) / NT), (unsigned int)(g.groups * ncbg));
+    const size_t lds = conv_lds_bytes(g, NCB, NT, TERMS);
+    auto kern = conv_gather_kernel<DT, MODE, NCB, NT, TERMS>;
+    if (lds > 64 * 1024) {
+        static size_t granted = 0;  // one per instantiation; creation and launches of a process share it
+        if (lds > granted) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            granted = lds;
+        }
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(CONV_THREADS), lds, s, static_cast<const unsigned char*>(src0),
+                       static_cast<const unsigned char*>(src1), static_cast<const unsigned char*>(zero16), flags, ctrl,
+                       static_cast<const uint4*>(wpack), offtab, bias, y, g, stats);
     return hipGetLastError();
 }
 
 template <int DT, int MODE, int TERMS>
-hipError_t launch_shape(int wm, int nt, const void* src0, const void* src1, unsigned int* subbits,
-                        unsigned int* ctrl, const void* wpack, const int* offtab, const void* bias, void* y,
+hipError_t launch_shape(int ncb, int nt, const void* src0, const void* src1, const void* zero16,
+                        unsigned int* flags, unsigned int* ctrl, const void* wpack, const int* offtab, const void* bias, void* y,
                         const ConvGeom& g, DevStats* stats, hipStream_t s) {
-#define RRM_CASE(WMV, NTV)                                                                                          \
-    if (wm == WMV && nt == NTV)                                                                                      \
-        return launch_one<DT, MODE, WMV, NTV, TERMS>(src0, src1, subbits, ctrl, wpack, offtab, bias, y, g, stats, s);
-    RRM_CASE(4, 1) RRM_CASE(4, 2) RRM_CASE(4, 4) RRM_CASE(4, 8) RRM_CASE(4, 16) RRM_CASE(1, 4) RRM_CASE(1, 8) RRM_CASE(1, 16)
+#define RRM_CASE(CBV, NTV)                                                                                          \
+    if (ncb == CBV && nt == NTV)                                                                                     \
+        return launch_one<DT, MODE, CBV, NTV, TERMS>(src0, src1, zero16, flags, ctrl, wpack, offtab, bias, y, g, stats, s);
+    RRM_CASE(4, 4) RRM_CASE(4, 8) RRM_CASE(4, 16) RRM_CASE(1, 4) RRM_CASE(1, 8) RRM_CASE(1, 16)
 #undef RRM_CASE
     return hipErrorInvalidValue;
 }
 
 }  // namespace
 
-hipError_t launch_conv(int dtype, int mode, int wm, int nt, int terms, const void* src0, const void* src1,
-                       unsigned int* subbits, unsigned int* ctrl, const void* wpack, const int* offtab,
+size_t conv_lds_bytes(const ConvGeom& g, int ncb, int nt, int terms) {
+    return (size_t)(g.nslab > 1 ? 2 : 1) * ((size_t)ncb * g.nq * 1024 + (size_t)terms * nt * g.slot_bytes) +
+           (size_t)g.nq * 4 * sizeof(int);
+}
+
+hipError_t launch_conv(int dtype, int mode, int ncb, int nt, int terms, const void* src0, const void* src1,
+                       const void* zero16, unsigned int* flags, unsigned int* ctrl, const void* wpack, const int* offtab,
                        const void* bias, void* y, const ConvGeom& g, DevStats* stats, hipStream_t s) {
     if (dtype == RRM_I8_I32) {
         if (mode == MODE_DELTA)
-            return launch_shape<RRM_I8_I32, MODE_DELTA, 1>(wm, nt, src0, src1, subbits, ctrl, wpack, offtab, bias, y, g, stats, s);
-        return launch_shape<RRM_I8_I32, MODE_DENSE, 1>(wm, nt, src0, src1, subbits, ctrl, wpack, offtab, bias, y, g, stats, s);
+            return launch_shape<RRM_I8_I32, MODE_DELTA, 1>(ncb, nt, src0, src1, zero16, flags, ctrl, wpack, offtab, bias, y, g, stats, s);
+        return launch_shape<RRM_I8_I32, MODE_DENSE, 1>(ncb, nt, src0, src1, zero16, flags, ctrl, wpack, offtab, bias, y, g, stats, s);
     }
     if (mode == MODE_DENSE)
-        return launch_shape<RRM_BF16_F32, MODE_DENSE, 1>(wm, nt, src0, src1, subbits, ctrl, wpack, offtab, bias, y, g, stats, s);
+        return launch_shape<RRM_BF16_F32, MODE_DENSE, 1>(ncb, nt, src0, src1, zero16, flags, ctrl, wpack, offtab, bias, y, g, stats, s);
     if (terms == 2)
-        return launch_shape<RRM_BF16_F32, MODE_DELTA, 2>(wm, nt, src0, src1, subbits, ctrl, wpack, offtab, bias, y, g, stats, s);
-    return launch_shape<RRM_BF16_F32, MODE_DELTA, 1>(wm, nt, src0, src1, subbits, ctrl, wpack, offtab, bias, y, g, stats, s);
+        return launch_shape<RRM_BF16_F32, MODE_DELTA, 2>(ncb, nt, src0, src1, zero16, flags, ctrl, wpack, offtab, bias, y, g, stats, s);
+    return launch_shape<RRM_BF16_F32, MODE_DELTA, 1>(ncb, nt, src0, src1, zero16, flags, ctrl, wpack, offtab, bias, y, g, stats, s);
 }
 
 }  // namespace rrm

@@ -59,9 +59,10 @@ struct rrm_layer {
     void* d0 = nullptr;      // difference (bf16: head; binary: flip mask)
     void* d1 = nullptr;      // bf16: tail of the difference
     unsigned long long* bitmap = nullptr;
-    unsigned int* tileflag = nullptr;  // binary: 8x8 tile stamps; int8 / bf16: 4x4 sub-tile bit array
+    unsigned int* tileflag = nullptr;  // binary: 8x8 tile stamps; int8 / bf16: 4x4 sub-tile byte flags
     size_t marks_bytes = 0;
     unsigned int* ctrl = nullptr;      // arrival counter of the gather kernel
+    void* zero16 = nullptr;            // a block of zeros: source of staged units outside the image
     int* fc_idx = nullptr;
     void* fc_val = nullptr;
     int* fc_count = nullptr;
@@ -77,7 +78,7 @@ struct rrm_layer {
     int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0;
 
     ~rrm_layer() {
-        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, bitmap, tileflag, ctrl, fc_idx, fc_val, fc_count, stats};
+        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, bitmap, tileflag, ctrl, zero16, fc_idx, fc_val, fc_count, stats};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
         for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
@@ -105,7 +106,8 @@ rrm_status validate(const rrm_shape* s, int dtype) {
     if (dtype == RRM_BIN_I32 && ((s->c_in / s->groups) % 32))
         return fail(RRM_ERR_SHAPE, "binary layers need c_in/groups to be a multiple of 32");
     const long long ho = (s->h + 2 * s->pad - s->kh) / s->stride + 1, wo = (s->w + 2 * s->pad - s->kw) / s->stride + 1;
-    if ((long long)s->n * s->h * s->w * s->c_in > (1ll << 31) || (long long)s->n * ho * wo * s->c_out > (1ll << 31))
+    // 32-bit byte offsets inside the kernels
+    if ((long long)s->n * s->h * s->w * s->c_in > (1ll << 30) || (long long)s->n * ho * wo * s->c_out > (1ll << 30))
         return fail(RRM_ERR_SHAPE, "tensor too large");
     if ((long long)s->kh * s->kw > 4096) return fail(RRM_ERR_SHAPE, "filter window too large");
     return RRM_OK;
@@ -140,86 +142,85 @@ rrm_status dalloc(size_t bytes, void** dev) {
     return RRM_OK;
 }
 
-int pitch_for(int sc) { return sc * 16 + ((sc % 2 == 0) ? 16 : 0); }
+int pitch_for(int sc) { return sc * 16; }
 
 // reciprocal for the kernels' u / d on small u (0 encodes d == 1)
 unsigned int magic_for(int d) { return d <= 1 ? 0u : (unsigned int)((1ull << 32) / (unsigned long long)d + 1ull); }
 
-constexpr int kPF = 4;  // K steps per slab are padded to the tile kernel's prefetch depth
-int nq_for(int ntaps, int sc) { return ((ntaps * sc + 3) / 4 + kPF - 1) / kPF * kPF; }
 
-// Pack the LDS offset table and the weights for the slab layout chosen in L->cg.
+
+// Pack the LDS offset table and the weights for the workgroup shape chosen in L->cg.
+// K pairs are ordered chunk by chunk: pair e of a slab is (chunk slab*sc + e / ntaps, tap e % ntaps),
+// four pairs per K step, nq K steps per slab.
 rrm_status pack_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     const rrm_shape& s = L->shape;
     ConvGeom& g = L->cg;
     const int ntaps = s.kh * s.kw;
-    // LDS offsets of the K pairs (tap, chunk), per slab; padded pairs point at offset 0 and carry
-    // zero weights.
-    std::vector<int> tab((size_t)g.nslab * g.nq * 4, 0);
-    for (int slab = 0; slab < g.nslab; ++slab) {
-        const int sc_eff = std::min(g.sc, g.chunks - slab * g.sc);
-        for (int e = 0; e < ntaps * sc_eff; ++e) {
-            const int tap = e / sc_eff, cc = e % sc_eff;
-            const int ky = tap / s.kw, kx = tap % s.kw;
-            tab[(size_t)slab * g.nq * 4 + e] = (ky * g.ww + kx) * g.pitch + cc * 16;
-        }
+    // LDS offsets of a slab's K pairs (the same for every slab); padded pairs point at offset 0 and
+    // carry zero weights.
+    std::vector<int> tab((size_t)g.nq * 4, 0);
+    for (int e = 0; e < ntaps * g.sc && e < g.nq * 4; ++e) {
+        const int cc = e / ntaps, tap = e % ntaps;
+        const int ky = tap / s.kw, kx = tap % s.kw;
+        tab[e] = (ky * g.ww + kx) | (cc << 16);  // window position of the tap | chunk in slab
     }
     rrm_status st = upload(tab.data(), tab.size() * sizeof(int), (void**)&L->offtab);
     if (st != RRM_OK) return st;
 
-    // weights in per-lane MFMA operand order: [group][16-block][slab][K step][lane] x 16 bytes,
-    // lane l -> output channel 16*block + l%16, K pair 4*step + l/16
-    const size_t nfrag = (size_t)s.groups * g.ncb * g.nslab * g.nq * 64;
-    std::vector<unsigned char> pack(nfrag * 16, 0);
+    // Weights in per-lane MFMA operand order: [group][16-channel block][K step][lane] x 16 bytes, with
+    // lane l -> output channel 16*block + l%16, K pair 4*step + l/16.  The block dimension is padded to
+    // a multiple of the workgroup's block count; padded blocks, channels and pairs are zero.
+    const int NCB = g.wg_cb;
+    const int ncb_p = (g.ncb + NCB - 1) / NCB * NCB;
+    const int kall = g.nslab * g.nq;
+    const size_t nfrag = (size_t)s.groups * ncb_p * kall;
+    std::vector<unsigned char> pack(nfrag * 64 * 16, 0);
     const int es = L->esize;
     for (int grp = 0; grp < s.groups; ++grp)
         for (int cb = 0; cb < g.ncb; ++cb)
-            for (int slab = 0; slab < g.nslab; ++slab) {
-                const int sc_eff = std::min(g.sc, g.chunks - slab * g.sc);
+            for (int slab = 0; slab < g.nslab; ++slab)
                 for (int q = 0; q < g.nq; ++q)
                     for (int lane = 0; lane < 64; ++lane) {
                         const int co = cb * 16 + (lane & 15);
                         const int e = 4 * q + (lane >> 4);
-                        if (co >= g.og || e >= ntaps * sc_eff) continue;
-                        const int tap = e / sc_eff, cc = e % sc_eff;
-                        const int c0 = (slab * g.sc + cc) * g.per_vec;
-                        unsigned char* dst =
-                            pack.data() + ((((size_t)grp * g.ncb + cb) * g.nslab + slab) * g.nq + q) * 64 * 16 + (size_t)lane * 16;
+                        if (co >= g.og || e >= ntaps * g.sc) continue;
+                        const int chunk = slab * g.sc + e / ntaps, tap = e % ntaps;
+                        if (chunk >= g.chunks) continue;
+                        const int c0 = chunk * g.per_vec;
+                        const size_t frag = ((size_t)(grp * ncb_p + cb) * kall + (size_t)slab * g.nq + q);
+                        unsigned char* dst = pack.data() + (frag * 64 + lane) * 16;
                         const size_t wbase = (((size_t)(grp * g.og + co)) * ntaps + tap) * g.cg;
                         for (int k = 0; k < g.per_vec && c0 + k < g.cg; ++k)
                             std::memcpy(dst + (size_t)k * es, w.data() + (wbase + c0 + k) * es, es);
                     }
-            }
     return upload(pack.data(), pack.size(), &L->wpack);
 }
 
-
-// LDS bytes of the gather kernel for a (sub-tiles per workgroup, chunks per slab) choice
-long long conv_lds_need(const ConvGeom& g, int terms, int nt, int sc, int ntaps) {
-    return (long long)terms * nt * g.wpos * pitch_for(sc) + (long long)nq_for(ntaps, sc) * 16;
-}
-
-// Fill the slab-dependent fields for a workgroup shape; false if it does not fit.
-bool conv_try_shape(ConvGeom& g, int terms, int nt, int ntaps) {
-    const int max_units = (terms == 2 ? CONV_MAX_STAGE_UNITS / 2 : CONV_MAX_STAGE_UNITS) * CONV_THREADS;
-    int sc = g.chunks < 16 ? g.chunks : 16;
-    // prefer slabs the kernel can stage through registers; a single chunk may exceed that (then the
-    // kernel stages it directly)
-    while (sc > 1 && (conv_lds_need(g, terms, nt, sc, ntaps) > 60 * 1024 || (long long)nt * g.wpos * sc > max_units)) --sc;
-    if (conv_lds_need(g, terms, nt, sc, ntaps) > 60 * 1024) sc = 0;
-    if (sc < 1) return false;
-    g.nt = nt;
-    g.sc = sc;
-    g.nslab = (g.chunks + sc - 1) / sc;
-    g.pitch = pitch_for(sc);
-    g.slot_bytes = g.wpos * g.pitch;
-    g.nq = nq_for(ntaps, sc);
-    const int last = g.chunks - (g.nslab - 1) * sc;
-    g.magic_sc[0] = magic_for(sc);
-    g.magic_sc[1] = magic_for(last);
-    g.magic_wsc[0] = magic_for(g.wpos * sc);
-    g.magic_wsc[1] = magic_for(g.wpos * last);
-    return true;
+// Fill the slab-dependent fields for (blocks, sub-tiles) per workgroup with the largest slab that fits
+// the LDS budget; false if none does.
+bool conv_try_shape(ConvGeom& g, int terms, int wg_cb, int nt, int ntaps, long long budget) {
+    const int max_units = CONV_MAX_STAGE_UNITS * CONV_THREADS;
+    for (int sc = g.chunks; sc >= 1; --sc) {
+        // several slabs: a slab must be a whole number of K steps (4 pairs each)
+        if (sc < g.chunks && (sc * ntaps) % 4 != 0) continue;
+        ConvGeom t = g;
+        t.wg_cb = wg_cb;
+        t.nt = nt;
+        t.sc = sc;
+        t.nslab = (t.chunks + sc - 1) / sc;
+        t.pitch = pitch_for(sc);
+        t.slot_bytes = t.wpos * t.pitch;
+        t.nq = (ntaps * sc + 3) / 4;
+        if ((long long)conv_lds_bytes(t, wg_cb, nt, terms) > budget) continue;
+        if ((long long)nt * t.wpos * sc > max_units) continue;  // staged units per thread are bounded
+        t.magic_sc[0] = t.magic_sc[1] = magic_for(sc);
+        t.magic_wsc[0] = t.magic_wsc[1] = magic_for(t.wpos);
+        t.swz = (sc & -sc) - 1;
+        t.last_sc = t.chunks - (t.nslab - 1) * sc;
+        g = t;
+        return true;
+    }
+    return false;
 }
 
 rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
@@ -234,38 +235,52 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     g.sty = (g.ho + 3) / 4;
     g.stx = (g.wo + 3) / 4;
     g.n_sub = s.n * g.sty * g.stx;
-    g.n_words = (g.n_sub + 31) / 32;
+    g.n_words = (g.n_sub + 3) / 4;
     g.wh = 3 * s.stride + s.kh;
     g.ww = 3 * s.stride + s.kw;
     g.wpos = g.wh * g.ww;
     g.per_vec = 16 / L->esize;
     g.chunks = (g.cg + g.per_vec - 1) / g.per_vec;
     g.ncb = (g.og + 15) / 16;
-    g.wm = g.ncb >= 2 ? 4 : 1;
     g.magic_ww = magic_for(g.ww);
     g.magic_sub = magic_for(g.sty * g.stx);
     g.magic_stx = magic_for(g.stx);
+    g.magic_wo = magic_for(g.wo);
+    g.magic_ho = magic_for(g.ho);
     g.fast_stage = ((s.c_in * L->esize) % 16 == 0) && ((g.cg * L->esize) % 16 == 0);
     g.vec_store = (s.c_out % 4 == 0) && (g.og % 4 == 0);
     const int ntaps = s.kh * s.kw;
     const int terms = L->dtype == RRM_BF16_F32 ? 2 : 1;
-    // Workgroup shape: as many sub-tiles per workgroup as LDS and the staging registers allow while a
-    // slab still holds at least 4 chunks (or all of them); the packing of the weights depends on it.
+    // Workgroup shape.  Few sub-tiles in total (one stream of a small map): latency matters, so one
+    // channel block and up to 4 sub-tiles per workgroup, the whole K range in as few slabs as fit.
+    // Many sub-tiles (many streams): operand reuse matters, so 4 channel blocks x 16 sub-tiles.
+    struct Cand { int cb, nt; };
+    std::vector<Cand> cands;
+    const bool small = (long long)g.n_sub * g.ncb * s.groups <= 2048;
+    if (small || g.ncb < 2) {
+        cands = {{1, 4}, {1, 8}, {1, 16}};
+        if (!small) cands = {{1, 16}, {1, 8}, {1, 4}};
+    } else {
+        cands = {{4, 16}, {4, 8}, {4, 4}, {1, 16}, {1, 8}, {1, 4}};
+    }
+    g.early_weights = small ? 1 : 0;
     bool ok = false;
-    for (int nt : {16, 8, 4}) {
-        ConvGeom t = g;
-        if (conv_try_shape(t, terms, nt, ntaps) && (t.sc >= 4 || t.sc == t.chunks)) {
-            g = t;
-            ok = true;
-            break;
+    for (long long budget : {(small ? 96ll : 156ll) * 1024, 156ll * 1024}) {
+        for (const Cand& c : cands) {
+            ConvGeom t = g;
+            // a slab should hold at least 4 chunks (or all of them) to amortise its barriers
+            if (conv_try_shape(t, terms, c.cb, c.nt, ntaps, budget) && (t.sc >= 4 || t.sc == t.chunks)) {
+                g = t;
+                ok = true;
+                break;
+            }
         }
+        if (ok) break;
     }
-    if (!ok && !conv_try_shape(g, terms, 4, ntaps)) {
-        // very large windows: one or two sub-tiles per workgroup, wavefronts over output channels
-        g.wm = 4;
-        if (!conv_try_shape(g, terms, 2, ntaps) && !conv_try_shape(g, terms, 1, ntaps))
-            return fail(RRM_ERR_SHAPE, "input window of one output sub-tile does not fit LDS");
-    }
+    if (!ok)
+        for (const Cand& c : cands)
+            if (!ok) ok = conv_try_shape(g, terms, c.cb, c.nt, ntaps, 156 * 1024);
+    if (!ok) return fail(RRM_ERR_SHAPE, "input window of one output sub-tile does not fit LDS");
     return pack_conv(L, w);
 }
 
@@ -370,7 +385,7 @@ rrm_status enqueue_dense(rrm_layer* L, const void* x, void* y, hipStream_t st) {
     } else if (L->dtype == RRM_BIN_I32) {
         RRM_HIP(launch_bin_conv(MODE_DENSE, bin_cw(L), x, nullptr, nullptr, L->wpack, L->bias, y, L->bg, L->stats, st));
     } else {
-        RRM_HIP(launch_conv(L->dtype, MODE_DENSE, L->cg.wm, L->cg.nt, 1, x, nullptr, nullptr, nullptr, L->wpack, L->offtab,
+        RRM_HIP(launch_conv(L->dtype, MODE_DENSE, L->cg.wg_cb, L->cg.nt, 1, x, nullptr, L->zero16, nullptr, nullptr, L->wpack, L->offtab,
                             L->bias, y, L->cg, L->stats, st));
     }
     return RRM_OK;
@@ -442,11 +457,12 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
         if ((st = dalloc(((nvec + 63) / 64) * 8, (void**)&L->bitmap)) != RRM_OK) return bail(st);
         sg.sty = (int)((ho + 3) / 4);
         sg.stx = (int)((wo + 3) / 4);
-        // binary: one stamp per 8x8 tile; int8 / bf16: one bit per 4x4 sub-tile
+        // binary: one stamp per 8x8 tile; int8 / bf16: one byte flag per 4x4 sub-tile
         L->marks_bytes = dtype == RRM_BIN_I32 ? (size_t)s.n * sg.tiles_y * sg.tiles_x * 4
-                                              : (size_t)((s.n * sg.sty * sg.stx + 31) / 32) * 4;
+                                              : (size_t)((s.n * sg.sty * sg.stx + 3) / 4) * 4;
         if ((st = dalloc(L->marks_bytes, (void**)&L->tileflag)) != RRM_OK) return bail(st);
         if ((st = dalloc(16, (void**)&L->ctrl)) != RRM_OK) return bail(st);
+        if ((st = dalloc(256, &L->zero16)) != RRM_OK) return bail(st);
     }
     // P_0 = b (Eq. 3 at I_0 = 0); I_0 = 0 comes from the zeroed allocation
     hipError_t e = launch_fill_bias(dtype == RRM_BF16_F32, L->y_snap, L->bias, L->y_elems / s.c_out, s.c_out, nullptr);
@@ -494,8 +510,8 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
         } else {
             RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag, 0u, L->sg, L->stats, s));
             if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
-            RRM_HIP(launch_conv(L->dtype, MODE_DELTA, L->cg.wm, L->cg.nt, L->dtype == RRM_BF16_F32 ? L->opt_terms : 1,
-                                L->d0, L->d1, L->tileflag, L->ctrl, L->wpack, L->offtab, nullptr, L->y_snap, L->cg,
+            RRM_HIP(launch_conv(L->dtype, MODE_DELTA, L->cg.wg_cb, L->cg.nt, L->dtype == RRM_BF16_F32 ? L->opt_terms : 1,
+                                L->d0, L->d1, L->zero16, L->tileflag, L->ctrl, L->wpack, L->offtab, nullptr, L->y_snap, L->cg,
                                 L->stats, s));
         }
         if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
@@ -558,11 +574,6 @@ rrm_status rrm_set_option(rrm_layer* L, const char* key, long value) {
     if (k == "path") {
         if (value < 0 || value > 2) return fail(RRM_ERR_OPTION, "path must be 0, 1 or 2");
         L->opt_path = (int)value;
-    } else if (k == "cout_block") {
-        if (L->shape.kind != RRM_CONV || L->dtype == RRM_BIN_I32) return fail(RRM_ERR_OPTION, "cout_block is an option of int8 / bf16 convolutions");
-        if (value != 16 && value != 64) return fail(RRM_ERR_OPTION, "cout_block must be 16 or 64");
-        if (value == 16 && L->cg.nt < 4) return fail(RRM_ERR_OPTION, "this layer's windows only fit with cout_block 64");
-        L->cg.wm = (int)value / 16;
     } else if (k == "fc_splits") {
         if (value < 0 || value > 4096) return fail(RRM_ERR_OPTION, "fc_splits must be in [0, 4096]");
         L->opt_fc_splits = (int)value;
@@ -623,6 +634,15 @@ rrm_status rrm_get_kernel_times(rrm_layer* L, double* scan_us, double* compute_u
     L->prof_n = 0;
     return RRM_OK;
 }
+
+#ifdef RRM_TRACE
+// debug build only: raw copy of the device statistics block
+rrm_status rrm_debug_raw_stats(rrm_layer* L, void* dst, size_t bytes) {
+    RRM_HIP(hipMemcpy(dst, L->stats, bytes < sizeof(DevStats) * STAT_SLOTS ? bytes : sizeof(DevStats) * STAT_SLOTS,
+                      hipMemcpyDeviceToHost));
+    return RRM_OK;
+}
+#endif
 
 void rrm_layer_destroy(rrm_layer* L) { delete L; }
 

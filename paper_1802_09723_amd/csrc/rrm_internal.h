@@ -34,7 +34,7 @@ struct ScanGeom {
     int kh, kw, stride, pad;
     int ho, wo;
     int tiles_y, tiles_x;    // 8x8 output tiles (binary path: stamped words)
-    int sty, stx;            // 4x4 output sub-tiles (MFMA path: one bit each)
+    int sty, stx;            // 4x4 output sub-tiles (MFMA path: one byte flag each)
     int per_vec;             // elements per 16-byte unit: 16 / 8 / 4
 };
 
@@ -46,23 +46,27 @@ struct ConvGeom {
     int ho, wo, cg, og;
     int sty, stx;        // 4x4 output sub-tiles per image
     int n_sub;           // n*sty*stx
-    int n_words;         // 32-bit words of the sub-tile bit array
+    int n_words;         // 32-bit words of the sub-tile flag array (4 byte flags per word)
     int wh, ww;          // input window of one sub-tile: 3*stride + kh, 3*stride + kw
     int wpos;            // wh*ww
     int per_vec;         // elements per 16-byte K chunk (16 int8 / 8 bf16)
     int chunks;          // 16-byte chunks per (position, group): ceil(cg / per_vec)
     int sc;              // chunks per LDS slab
     int nslab;           // ceil(chunks / sc)
-    int pitch;           // LDS bytes per staged position
+    int pitch;           // LDS bytes per staged position: 16*sc
     int slot_bytes;      // wpos*pitch: LDS bytes of one sub-tile's window
-    int nq;              // MFMA K steps per slab (multiple of the prefetch depth)
+    int swz;             // XOR mask applied to the chunk index by the window position (bank spreading)
+    int last_sc;         // chunks present in the last slab
+    int nq;              // MFMA K steps per slab: ceil(kh*kw*sc / 4)
     int ncb;             // 16-wide output-channel blocks per group
-    int wm, nt;          // workgroup shape: 16-channel blocks (1 or 4) and sub-tiles (4, 8, 16)
-    unsigned int magic_sc[2];   // reciprocals (floor(2^32/d)+1, 0 for d = 1): d = sc / last slab's chunks
-    unsigned int magic_wsc[2];  // d = wpos*sc / wpos*(last slab's chunks)
+    int wg_cb, nt;       // workgroup shape: 16-channel blocks (1 or 4) and gathered sub-tiles (4, 8, 16)
+    unsigned int magic_sc[2];   // reciprocals (floor(2^32/d)+1, 0 for d = 1): [0] d = sc
+    unsigned int magic_wsc[2];  // [0] d = wpos
+    unsigned int magic_wo, magic_ho;  // d = wo, d = ho
     unsigned int magic_ww;      // d = ww
     unsigned int magic_sub;     // d = sty*stx
     unsigned int magic_stx;     // d = stx
+    int early_weights;   // 1: small grid, start the first weight slab's copy before the flag scan
     int fast_stage;      // 1: 16-byte aligned channel runs, vector staging
     int vec_store;       // 1: y rows allow 16-byte read-modify-write
 };
@@ -92,13 +96,14 @@ struct FcGeom {
 
 // ---- launchers implemented in the kernel translation units ------------------------------------
 // `marks` is the 8x8-tile stamp array (binary layers, stamp = consumers per tile) or the 4x4
-// sub-tile bit array (int8 / bf16 layers, stamp ignored)
+// sub-tile byte-flag array (int8 / bf16 layers, stamp ignored)
 hipError_t launch_scan(int dtype, const void* x_t, void* x_snap, void* d0, void* d1, unsigned long long* bitmap,
                        unsigned int* marks, unsigned int stamp, const ScanGeom& g, DevStats* stats,
                        hipStream_t s);
 
-hipError_t launch_conv(int dtype, int mode, int wm, int nt, int terms, const void* src0, const void* src1,
-                       unsigned int* subbits, unsigned int* ctrl, const void* wpack, const int* offtab,
+size_t conv_lds_bytes(const ConvGeom& g, int ncb, int nt, int terms);  // dynamic LDS of the gather kernel
+hipError_t launch_conv(int dtype, int mode, int ncb, int nt, int terms, const void* src0, const void* src1,
+                       const void* zero16, unsigned int* subbits, unsigned int* ctrl, const void* wpack, const int* offtab,
                        const void* bias, void* y, const ConvGeom& g, DevStats* stats, hipStream_t s);
 
 hipError_t launch_fc_scan(int dtype, const void* x_t, void* x_snap, int* idx, void* val, int* count,

@@ -5,15 +5,15 @@
 // the activation vector for its non-zero entries) is a change map: x is scanned once as a flat
 // array of 16-byte units; each wavefront turns its 64 compare results into one 64-bit mask
 // (ballot), which is the bitmap word of those units; changed units write their difference, are
-// committed to the snapshot, and mark the output blocks whose receptive field contains them: one bit
-// per 4x4 output sub-tile for the MFMA path (the gather kernel ranks these bits into its work list),
-// one stamp per 8x8 output tile for the binary path.
+// committed to the snapshot, and mark the output blocks whose receptive field contains them: one byte
+// flag per 4x4 output sub-tile for the MFMA path (the gather kernel ranks these flags into its work
+// list), one stamp per 8x8 output tile for the binary path.
 //
 // The difference buffer keeps the invariant "zero wherever the bitmap bit is clear": a unit that
 // changed in the previous step but not in this one is written back to zero, so the tile kernel can
 // stage its input window with plain loads.  A stamped 8x8 tile holds the number of workgroups that
 // will consume it; each consumer takes one off, so the stamps are all zero again after the binary
-// kernel; the sub-tile bits are cleared by the gather kernel's last workgroup.  Nothing on the host
+// kernel; the sub-tile flags are cleared by the gather kernel's last workgroup.  Nothing on the host
 // has to change between steps (graph replay safe).
 //
 // HBM traffic per step: 2|x| read, plus (difference + snapshot) written only where x changed.
@@ -58,47 +58,22 @@ __device__ __forceinline__ void mark_tiles(const ScanGeom& g, long long pos, uns
             tileflag[((long long)b * g.tiles_y + ty) * g.tiles_x + tx] = stamp;
 }
 
-// Mark the 4x4 output sub-tiles that see input position `pos` (valid where `has`) in the bit array.
-// Called by whole wavefronts: lanes that mark the same word are merged into one atomic.
-__device__ __forceinline__ void mark_subtiles(const ScanGeom& g, bool has, long long pos, unsigned int* bits_arr) {
-    int b = 0, sy0 = 0, sx0 = 0, rh = 0, rw = 0;
-    if (has) {
-        const int hw = g.h * g.w;
-        b = (int)(pos / hw);
-        const int r = (int)(pos - (long long)b * hw);
-        const int iy = r / g.w, ix = r - iy * g.w;
-        const int ty0 = iy + g.pad - (g.kh - 1), tx0 = ix + g.pad - (g.kw - 1);
-        const int oy_lo = ty0 <= 0 ? 0 : (ty0 + g.stride - 1) / g.stride;
-        const int ox_lo = tx0 <= 0 ? 0 : (tx0 + g.stride - 1) / g.stride;
-        int oy_hi = (iy + g.pad) / g.stride, ox_hi = (ix + g.pad) / g.stride;
-        if (oy_hi > g.ho - 1) oy_hi = g.ho - 1;
-        if (ox_hi > g.wo - 1) ox_hi = g.wo - 1;
-        if (oy_lo <= oy_hi && ox_lo <= ox_hi) {
-            sy0 = oy_lo >> 2;
-            sx0 = ox_lo >> 2;
-            rh = (oy_hi >> 2) - sy0 + 1;
-            rw = (ox_hi >> 2) - sx0 + 1;
-        }
-    }
-    const int lane = threadIdx.x & 63;
-    for (int dy = 0; __ballot(dy < rh) != 0ull; ++dy)
-        for (int dx = 0; __ballot(dy < rh && dx < rw) != 0ull; ++dx) {
-            const bool m = dy < rh && dx < rw;
-            const int id = m ? ((b * g.sty + sy0 + dy) * g.stx + sx0 + dx) : 0;
-            const int word = id >> 5;
-            const unsigned int bit = m ? (1u << (id & 31)) : 0u;
-            unsigned long long todo = __ballot(m);
-            while (todo) {
-                const int leader = __ffsll((long long)todo) - 1;
-                const int w0 = __shfl(word, leader);
-                const bool mine = m && word == w0;
-                unsigned int acc = mine ? bit : 0u;
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) acc |= __shfl_xor(acc, o);
-                if (lane == leader && (bits_arr[w0] & acc) != acc) atomicOr(&bits_arr[w0], acc);
-                todo &= ~__ballot(mine);
-            }
-        }
+// Mark the 4x4 output sub-tiles that see input position `pos`: one byte flag each, plain stores
+// (every writer stores the same value, so no atomics and no same-address serialisation).
+__device__ __forceinline__ void mark_subtiles(const ScanGeom& g, long long pos, unsigned char* flags) {
+    const int hw = g.h * g.w;
+    const int b = (int)(pos / hw);
+    const int r = (int)(pos - (long long)b * hw);
+    const int iy = r / g.w, ix = r - iy * g.w;
+    const int ty0 = iy + g.pad - (g.kh - 1), tx0 = ix + g.pad - (g.kw - 1);
+    const int oy_lo = ty0 <= 0 ? 0 : (ty0 + g.stride - 1) / g.stride;
+    const int ox_lo = tx0 <= 0 ? 0 : (tx0 + g.stride - 1) / g.stride;
+    int oy_hi = (iy + g.pad) / g.stride, ox_hi = (ix + g.pad) / g.stride;
+    if (oy_hi > g.ho - 1) oy_hi = g.ho - 1;
+    if (ox_hi > g.wo - 1) ox_hi = g.wo - 1;
+    if (oy_lo > oy_hi || ox_lo > ox_hi) return;
+    for (int sy = oy_lo >> 2; sy <= (oy_hi >> 2); ++sy)
+        for (int sx = ox_lo >> 2; sx <= (ox_hi >> 2); ++sx) flags[((long long)b * g.sty + sy) * g.stx + sx] = 1;
 }
 
 template <int DT>
@@ -181,11 +156,11 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
             if (DT == RRM_BF16_F32) d1[v] = make_uint4(0, 0, 0, 0);
         }
     }
-    // mark the output blocks that see the changed positions (whole wavefront, convergent)
+    // mark the output blocks that see the changed positions
     if (DT == RRM_BIN_I32) {
         for (long long p = p0; p <= p1; ++p) mark_tiles(g, p, tileflag, stamp);
     } else {
-        for (long long p = p0; __ballot(p <= p1) != 0ull; ++p) mark_subtiles(g, p <= p1, p, tileflag);
+        for (long long p = p0; p <= p1; ++p) mark_subtiles(g, p, reinterpret_cast<unsigned char*>(tileflag));
     }
     const unsigned long long mask = __ballot(changed);
     if ((threadIdx.x & 63) == 0 && v < nvec) bitmap[v >> 6] = mask;

@@ -21,11 +21,6 @@ def test_config0_every_frame_bit_exact():
     assert 0 < st["active_tiles"] < st["total_tiles"]
 
 
-@pytest.mark.parametrize("wm", [16, 64])
-def test_config0_all_cout_blockings(wm):
-    run_sequence(S.config0(T=3), cout_block=wm)
-
-
 def test_config0_batched_streams():
     run_sequence(S.config0(n=3, T=4))
 
