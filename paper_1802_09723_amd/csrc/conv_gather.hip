@@ -22,6 +22,10 @@
 //     LDS-direct loads (chunk index XOR-swizzled by position against bank conflicts; units outside the
 //     image read a block of zeros), also double-buffered.  In delta mode the source is the difference
 //     buffer, zero where nothing changed.
+// The source is always in a 16-byte-chunk layout [stream][row][column][group][chunk]: the caller's x
+// when its channel runs are 16-byte multiples, otherwise the padded (or column-folded) copy that the
+// scan / repack kernels write (see scan.hip); the kernel itself only sees "source positions" of
+// pos_bytes bytes with their own strides and window size.
 // Each wavefront owns every fourth gathered sub-tile and all NCB channel blocks (register blocking
 // NCB x NT/4), so one weight fragment read feeds NT/4 MFMAs and one window read feeds NCB MFMAs.
 // The number of sub-tiles per workgroup adapts on the device: few active sub-tiles are spread one per
@@ -90,7 +94,6 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
     typedef typename Acc<DT>::type acc_t;
     typedef typename Acc<DT>::vec vec_t;
     typedef typename Acc<DT>::scalar sc_t;
-    constexpr int ESIZE = DT == RRM_I8_I32 ? 1 : 2;
     constexpr int NS = NT / 4;  // gathered sub-tiles per wavefront
     constexpr int MAXU = CONV_MAX_STAGE_UNITS;  // staged 16-byte units per thread and slab (host guarantees)
     static_assert(NT % 4 == 0, "NT must be a multiple of the wavefront count");
@@ -214,9 +217,9 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
         const int b = fdiv(id, g.magic_sub);
         const int r = id - b * (g.sty * g.stx);
         const int sy = fdiv(r, g.magic_stx), sx = r - sy * g.stx;
-        s_pix[tid] = b * g.h * g.w;
-        s_iy0[tid] = 4 * sy * g.stride - g.pad;
-        s_ix0[tid] = 4 * sx * g.stride - g.pad;
+        s_pix[tid] = b * g.src_h * g.src_w;
+        s_iy0[tid] = 4 * sy * g.str_y - g.pad_y;
+        s_ix0[tid] = 4 * sx * g.str_x - g.pad_x;
         s_ypos[tid] = (b * g.ho + 4 * sy) * g.wo + 4 * sx;
     }
     for (int e = tid; e < g.nq * 4; e += CONV_THREADS) tab[e] = offtab[e];  // the same for every slab
@@ -247,32 +250,11 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
             const int cc = cs ^ (hp & g.swz);
             const int iy = s_iy0[slot] + hy, ix = s_ix0[slot] + hx;
             if (cc >= g.last_sc) ulast |= 1u << i;
-            if (iy >= 0 && iy < g.h && ix >= 0 && ix < g.w)
-                uoff[i] = ((unsigned int)(s_pix[slot] + iy * g.w + ix) * (unsigned int)g.c_in +
-                           (unsigned int)(grp * g.cg + cc * g.per_vec)) * (unsigned int)ESIZE;
+            if (iy >= 0 && iy < g.src_h && ix >= 0 && ix < g.src_w)
+                uoff[i] = (unsigned int)(s_pix[slot] + iy * g.src_w + ix) * (unsigned int)g.pos_bytes +
+                          (unsigned int)(grp * g.grp_bytes + cc * 16);
         }
     }
-    // element-wise fetch for channel runs that are not 16-byte aligned (e.g. 3 input channels)
-    auto fetch_slow = [&](const unsigned char* src, unsigned int goff, int c0) -> uint4 {
-        unsigned int a0 = 0, a1 = 0, a2 = 0, a3 = 0;
-        for (int e = 0; e < g.per_vec; ++e) {
-            if (c0 + e >= g.cg) break;
-            unsigned int x0;
-            int sh, wd;
-            if (ESIZE == 1) {
-                x0 = src[goff + e];
-                sh = 8 * (e & 3);
-                wd = e >> 2;
-            } else {
-                x0 = *reinterpret_cast<const unsigned short*>(src + goff + 2 * e);
-                sh = 16 * (e & 1);
-                wd = e >> 1;
-            }
-            x0 <<= sh;
-            a0 |= wd == 0 ? x0 : 0u; a1 |= wd == 1 ? x0 : 0u; a2 |= wd == 2 ? x0 : 0u; a3 |= wd == 3 ? x0 : 0u;
-        }
-        return make_uint4(a0, a1, a2, a3);
-    };
     const unsigned int slab_src_bytes = (unsigned int)(g.sc * 16);  // source bytes between consecutive slabs
     auto stage_windows = [&](int slab) {
         unsigned char* dst = bbase + (slab & (nbuf - 1)) * b_bytes;
@@ -283,33 +265,18 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
             const bool real = uoff[i] != 0xFFFFFFFFu && !(last && ((ulast >> i) & 1u));
             const unsigned int o = uoff[i] + (unsigned int)slab * slab_src_bytes;
             unsigned char* d = dst + (i * CONV_THREADS + wave * 64) * 16;  // wave-uniform; lane adds 16*lane
-            if (g.fast_stage) {
-                const unsigned char* p0 = real ? src0 + o : zero16;
-                __builtin_amdgcn_global_load_lds((gptr_t)p0, (lptr_t)d, 16, 0, 0);
-                if (TERMS == 2) {
-                    const unsigned char* p1 = real ? src1 + o : zero16;
-                    __builtin_amdgcn_global_load_lds((gptr_t)p1, (lptr_t)(d + plane_bytes), 16, 0, 0);
-                }
-            } else {
-                // slow path: compose the unit from single elements and store it
-                const int v = tid + i * CONV_THREADS;
-                const int r = fdiv(v, g.magic_sc[0]), cs = v - r * g.sc;
-                const int hp = r - fdiv(r, g.magic_wsc[0]) * g.wpos;
-                const int c0 = (slab * g.sc + (cs ^ (hp & g.swz))) * g.per_vec;
-                uint4 v0 = make_uint4(0, 0, 0, 0), v1 = make_uint4(0, 0, 0, 0);
-                if (real) {
-                    v0 = fetch_slow(src0, o, c0);
-                    if (TERMS == 2) v1 = fetch_slow(src1, o, c0);
-                }
-                *reinterpret_cast<uint4*>(d + lane * 16) = v0;
-                if (TERMS == 2) *reinterpret_cast<uint4*>(d + plane_bytes + lane * 16) = v1;
+            const unsigned char* p0 = real ? src0 + o : zero16;
+            __builtin_amdgcn_global_load_lds((gptr_t)p0, (lptr_t)d, 16, 0, 0);
+            if (TERMS == 2) {
+                const unsigned char* p1 = real ? src1 + o : zero16;
+                __builtin_amdgcn_global_load_lds((gptr_t)p1, (lptr_t)(d + plane_bytes), 16, 0, 0);
             }
         }
     };
 
     const int j = lane & 15, kgrp = lane >> 4;
     // lane-constant window position of its output position (tap 0,0)
-    const int hp_lane = ((j >> 2) * g.stride) * g.ww + (j & 3) * g.stride;
+    const int hp_lane = ((j >> 2) * g.str_y) * g.ww + (j & 3) * g.str_x;
     // this wavefront's sub-tile slots are wave, wave + 4, ...: how many of them are in use
     const int nact = mycount > wave ? (mycount - wave + 3) / 4 : 0;
 

@@ -46,6 +46,7 @@ struct rrm_layer {
     long long x_elems = 0;  // elements of x (binary: words)
     long long y_elems = 0;
     size_t x_bytes = 0, y_bytes = 0;
+    size_t d_bytes = 0;     // bytes of one difference buffer
     ScanGeom sg{};
     ConvGeom cg{};
     BinGeom bg{};
@@ -58,6 +59,7 @@ struct rrm_layer {
     void* y_snap = nullptr;
     void* d0 = nullptr;      // difference (bf16: head; binary: flip mask)
     void* d1 = nullptr;      // bf16: tail of the difference
+    void* xpad = nullptr;    // dense path of layers whose channel runs are not 16-byte multiples: repacked x
     unsigned long long* bitmap = nullptr;
     unsigned int* tileflag = nullptr;  // binary: 8x8 tile stamps; int8 / bf16: 4x4 sub-tile byte flags
     size_t marks_bytes = 0;
@@ -78,7 +80,7 @@ struct rrm_layer {
     int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0;
 
     ~rrm_layer() {
-        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, bitmap, tileflag, ctrl, zero16, fc_idx, fc_val, fc_count, stats};
+        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, ctrl, zero16, fc_idx, fc_val, fc_count, stats};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
         for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
@@ -151,18 +153,19 @@ unsigned int magic_for(int d) { return d <= 1 ? 0u : (unsigned int)((1ull << 32)
 
 // Pack the LDS offset table and the weights for the workgroup shape chosen in L->cg.
 // K pairs are ordered chunk by chunk: pair e of a slab is (chunk slab*sc + e / ntaps, tap e % ntaps),
-// four pairs per K step, nq K steps per slab.
+// four pairs per K step, nq K steps per slab.  A "tap" is a filter tap in source positions: in a
+// folded layer one tap covers `fold` filter columns of cp channels each.
 rrm_status pack_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     const rrm_shape& s = L->shape;
     ConvGeom& g = L->cg;
-    const int ntaps = s.kh * s.kw;
+    const int ntaps = s.kh * g.kw_eff;
     // LDS offsets of a slab's K pairs (the same for every slab); padded pairs point at offset 0 and
     // carry zero weights.
     std::vector<int> tab((size_t)g.nq * 4, 0);
     for (int e = 0; e < ntaps * g.sc && e < g.nq * 4; ++e) {
         const int cc = e / ntaps, tap = e % ntaps;
-        const int ky = tap / s.kw, kx = tap % s.kw;
-        tab[e] = (ky * g.ww + kx) | (cc << 16);  // window position of the tap | chunk in slab
+        const int ky = tap / g.kw_eff, ku = tap % g.kw_eff;
+        tab[e] = (ky * g.ww + ku) | (cc << 16);  // window position of the tap | chunk in slab
     }
     rrm_status st = upload(tab.data(), tab.size() * sizeof(int), (void**)&L->offtab);
     if (st != RRM_OK) return st;
@@ -176,6 +179,7 @@ rrm_status pack_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     const size_t nfrag = (size_t)s.groups * ncb_p * kall;
     std::vector<unsigned char> pack(nfrag * 64 * 16, 0);
     const int es = L->esize;
+    const int real_taps = s.kh * s.kw;
     for (int grp = 0; grp < s.groups; ++grp)
         for (int cb = 0; cb < g.ncb; ++cb)
             for (int slab = 0; slab < g.nslab; ++slab)
@@ -186,12 +190,23 @@ rrm_status pack_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
                         if (co >= g.og || e >= ntaps * g.sc) continue;
                         const int chunk = slab * g.sc + e / ntaps, tap = e % ntaps;
                         if (chunk >= g.chunks) continue;
-                        const int c0 = chunk * g.per_vec;
+                        const int ky = tap / g.kw_eff, ku = tap % g.kw_eff;
                         const size_t frag = ((size_t)(grp * ncb_p + cb) * kall + (size_t)slab * g.nq + q);
                         unsigned char* dst = pack.data() + (frag * 64 + lane) * 16;
-                        const size_t wbase = (((size_t)(grp * g.og + co)) * ntaps + tap) * g.cg;
-                        for (int k = 0; k < g.per_vec && c0 + k < g.cg; ++k)
-                            std::memcpy(dst + (size_t)k * es, w.data() + (wbase + c0 + k) * es, es);
+                        const size_t wrow = (size_t)(grp * g.og + co) * real_taps;
+                        for (int k = 0; k < g.per_vec; ++k) {
+                            // element k of the 16-byte chunk: filter column and channel it stands for
+                            int kx, c;
+                            if (g.fold > 1) {
+                                kx = ku * g.fold + k / g.cp;
+                                c = k % g.cp;
+                            } else {
+                                kx = ku;
+                                c = chunk * g.per_vec + k;
+                            }
+                            if (kx >= s.kw || c >= g.cg) continue;
+                            std::memcpy(dst + (size_t)k * es, w.data() + ((wrow + (size_t)ky * s.kw + kx) * g.cg + c) * es, es);
+                        }
                     }
     return upload(pack.data(), pack.size(), &L->wpack);
 }
@@ -236,20 +251,46 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     g.stx = (g.wo + 3) / 4;
     g.n_sub = s.n * g.sty * g.stx;
     g.n_words = (g.n_sub + 3) / 4;
-    g.wh = 3 * s.stride + s.kh;
-    g.ww = 3 * s.stride + s.kw;
-    g.wpos = g.wh * g.ww;
     g.per_vec = 16 / L->esize;
     g.chunks = (g.cg + g.per_vec - 1) / g.per_vec;
+    // Source layout seen by the gather kernel.
+    g.src_h = s.h;
+    g.str_y = s.stride;
+    g.pad_y = s.pad;
+    const int run_bytes = g.cg * L->esize;  // one position's channels of one group
+    g.aligned = (run_bytes % 16 == 0) ? 1 : 0;
+    g.fold = 1;
+    g.cp = g.chunks * g.per_vec;
+    g.wp = s.w;
+    if (!g.aligned && s.groups == 1 && run_bytes < 16) {
+        // few channels: 16 / cpb neighbouring columns share one chunk, if the stride and the padding
+        // keep every sub-tile's window aligned to that
+        int cpb = 4;
+        while (cpb < run_bytes) cpb *= 2;
+        const int fold = 16 / cpb;
+        if (fold > 1 && s.stride % fold == 0 && s.pad % fold == 0) {
+            g.fold = fold;
+            g.cp = cpb / L->esize;
+            g.wp = (s.w + fold - 1) / fold * fold;
+        }
+    }
+    g.kw_eff = (s.kw + g.fold - 1) / g.fold;
+    g.src_w = g.wp / g.fold;
+    g.str_x = s.stride / g.fold;
+    g.pad_x = s.pad / g.fold;
+    g.grp_bytes = g.fold > 1 ? 16 : g.chunks * 16;
+    g.pos_bytes = g.fold > 1 ? 16 : s.groups * g.chunks * 16;
+    g.wh = 3 * g.str_y + s.kh;
+    g.ww = 3 * g.str_x + g.kw_eff;
+    g.wpos = g.wh * g.ww;
     g.ncb = (g.og + 15) / 16;
     g.magic_ww = magic_for(g.ww);
     g.magic_sub = magic_for(g.sty * g.stx);
     g.magic_stx = magic_for(g.stx);
     g.magic_wo = magic_for(g.wo);
     g.magic_ho = magic_for(g.ho);
-    g.fast_stage = ((s.c_in * L->esize) % 16 == 0) && ((g.cg * L->esize) % 16 == 0);
     g.vec_store = (s.c_out % 4 == 0) && (g.og % 4 == 0);
-    const int ntaps = s.kh * s.kw;
+    const int ntaps = s.kh * g.kw_eff;
     const int terms = L->dtype == RRM_BF16_F32 ? 2 : 1;
     // Workgroup shape.  Few sub-tiles in total (one stream of a small map): latency matters, so one
     // channel block and up to 4 sub-tiles per workgroup, the whole K range in as few slabs as fit.
@@ -385,7 +426,12 @@ rrm_status enqueue_dense(rrm_layer* L, const void* x, void* y, hipStream_t st) {
     } else if (L->dtype == RRM_BIN_I32) {
         RRM_HIP(launch_bin_conv(MODE_DENSE, bin_cw(L), x, nullptr, nullptr, L->wpack, L->bias, y, L->bg, L->stats, st));
     } else {
-        RRM_HIP(launch_conv(L->dtype, MODE_DENSE, L->cg.wg_cb, L->cg.nt, 1, x, nullptr, L->zero16, nullptr, nullptr, L->wpack, L->offtab,
+        const void* src = x;
+        if (!L->cg.aligned) {  // bring x into the 16-byte-chunk layout first (its pad elements stay zero)
+            RRM_HIP(launch_repack(L->esize, x, L->xpad, L->sg, st));
+            src = L->xpad;
+        }
+        RRM_HIP(launch_conv(L->dtype, MODE_DENSE, L->cg.wg_cb, L->cg.nt, 1, src, nullptr, L->zero16, nullptr, nullptr, L->wpack, L->offtab,
                             L->bias, y, L->cg, L->stats, st));
     }
     return RRM_OK;
@@ -452,8 +498,20 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
         sg.tiles_x = (int)((wo + TILE - 1) / TILE);
         sg.per_vec = 16 / L->esize;
         const size_t nvec = round16(L->x_bytes) / 16;
-        if ((st = dalloc(L->x_bytes, &L->d0)) != RRM_OK) return bail(st);
-        if (dtype == RRM_BF16_F32 && (st = dalloc(L->x_bytes, &L->d1)) != RRM_OK) return bail(st);
+        // difference buffer: x's own layout, or the padded / folded layout of the gather kernel
+        L->d_bytes = L->x_bytes;
+        sg.scatter = 0;
+        if (dtype != RRM_BIN_I32 && !L->cg.aligned) {
+            sg.scatter = 1;
+            sg.wp = L->cg.wp;
+            sg.cp = L->cg.cp;
+            sg.cg = L->cg.cg;
+            sg.groups = s.groups;
+            L->d_bytes = (size_t)s.n * s.h * sg.wp * s.groups * sg.cp * L->esize;
+            if ((st = dalloc(L->d_bytes, &L->xpad)) != RRM_OK) return bail(st);  // dense path's repacked x
+        }
+        if ((st = dalloc(L->d_bytes, &L->d0)) != RRM_OK) return bail(st);
+        if (dtype == RRM_BF16_F32 && (st = dalloc(L->d_bytes, &L->d1)) != RRM_OK) return bail(st);
         if ((st = dalloc(((nvec + 63) / 64) * 8, (void**)&L->bitmap)) != RRM_OK) return bail(st);
         sg.sty = (int)((ho + 3) / 4);
         sg.stx = (int)((wo + 3) / 4);
@@ -541,8 +599,8 @@ rrm_status rrm_reset(rrm_layer* L, void* hip_stream) {
     RRM_HIP(launch_fill_zero(L->stats, sizeof(DevStats) * STAT_SLOTS, s));
     if (L->shape.kind == RRM_CONV) {
         // the difference buffer is zero wherever the bitmap is clear, and no tile is stamped
-        RRM_HIP(launch_fill_zero(L->d0, round16(L->x_bytes), s));
-        if (L->d1) RRM_HIP(launch_fill_zero(L->d1, round16(L->x_bytes), s));
+        RRM_HIP(launch_fill_zero(L->d0, round16(L->d_bytes), s));
+        if (L->d1) RRM_HIP(launch_fill_zero(L->d1, round16(L->d_bytes), s));
         RRM_HIP(launch_fill_zero(L->bitmap, round16(((round16(L->x_bytes) / 16 + 63) / 64) * 8), s));
         RRM_HIP(launch_fill_zero(L->tileflag, round16(L->marks_bytes), s));
         RRM_HIP(launch_fill_zero(L->ctrl, 16, s));

@@ -36,6 +36,11 @@ struct ScanGeom {
     int tiles_y, tiles_x;    // 8x8 output tiles (binary path: stamped words)
     int sty, stx;            // 4x4 output sub-tiles (MFMA path: one byte flag each)
     int per_vec;             // elements per 16-byte unit: 16 / 8 / 4
+    // Layout of the difference buffer.  scatter == 0: same as x (16-byte units map one to one).
+    // scatter == 1: element (row r = b*h + iy, column ix, channel c) goes to element
+    // ((r*wp + ix)*groups + c / cg)*cp + c % cg, i.e. rows padded to wp columns and every group's
+    // channels padded to cp, so that the gather kernel only ever sees whole 16-byte chunks.
+    int scatter, wp, cp, cg, groups;
 };
 
 constexpr int CONV_MAX_STAGE_UNITS = 12;  // 16-byte units a thread stages per slab (half for 2 terms)
@@ -44,6 +49,17 @@ constexpr int CONV_MAX_STAGE_UNITS = 12;  // 16-byte units a thread stages per s
 struct ConvGeom {
     int n, h, w, c_in, c_out, kh, kw, stride, pad, groups;
     int ho, wo, cg, og;
+    // The source as the kernel sees it: a map of src_h x src_w "source positions" of pos_bytes bytes
+    // (groups x chunks x 16), with its own strides, padding and window.  For layers with 16-byte
+    // channel runs this is x itself.  For few-channel layers `fold` neighbouring columns share one
+    // 16-byte chunk (a filter row becomes ceil(kw/fold) taps of 16 bytes).
+    int src_h, src_w, str_y, str_x, pad_y, pad_x;
+    int pos_bytes, grp_bytes;
+    int fold;            // columns per source position (1 unless folded)
+    int cp;              // channels per group and column in the source layout
+    int wp;              // columns per row in the source layout (w, or w rounded up to fold)
+    int kw_eff;          // filter taps per row in source positions: ceil(kw / fold)
+    int aligned;         // 1: the source layout is the caller's x layout
     int sty, stx;        // 4x4 output sub-tiles per image
     int n_sub;           // n*sty*stx
     int n_words;         // 32-bit words of the sub-tile flag array (4 byte flags per word)
@@ -67,7 +83,6 @@ struct ConvGeom {
     unsigned int magic_sub;     // d = sty*stx
     unsigned int magic_stx;     // d = stx
     int early_weights;   // 1: small grid, start the first weight slab's copy before the flag scan
-    int fast_stage;      // 1: 16-byte aligned channel runs, vector staging
     int vec_store;       // 1: y rows allow 16-byte read-modify-write
 };
 
@@ -121,6 +136,8 @@ int bin_consumers(int cw, const BinGeom& g);     // workgroups per tile of the b
 hipError_t launch_fill_bias(int is_float, void* y, const void* bias, long long rows, int c_out, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+// x (caller layout) -> the padded / folded source layout described by g (pad elements are left untouched)
+hipError_t launch_repack(int esize, const void* x, void* dst, const ScanGeom& g, hipStream_t s);
 hipError_t launch_relu_requant_pool(const void* y, void* out, int n, int h, int w, int c, int shift, int pool,
                                     hipStream_t s);
 

@@ -76,6 +76,48 @@ __device__ __forceinline__ void mark_subtiles(const ScanGeom& g, long long pos, 
         for (int sx = ox_lo >> 2; sx <= (ox_hi >> 2); ++sx) flags[((long long)b * g.sty + sy) * g.stx + sx] = 1;
 }
 
+// Element index of x element e in the padded / folded difference layout (see ScanGeom).
+__device__ __forceinline__ long long scatter_index(const ScanGeom& g, long long e) {
+    const long long p = e / g.c;
+    const int c = (int)(e - p * g.c);
+    const long long r = p / g.w;
+    const int ix = (int)(p - r * g.w);
+    const int grp = c / g.cg;
+    return ((r * g.wp + ix) * g.groups + grp) * g.cp + (c - grp * g.cg);
+}
+
+// Write the 16 bytes of unit v (already computed difference words) element by element into the
+// padded / folded layout.
+template <int DT>
+__device__ __forceinline__ void scatter_unit(const ScanGeom& g, long long v, const unsigned int (&w0)[4],
+                                             const unsigned int (&w1)[4], uint4* d0, uint4* d1) {
+    const long long e0 = v * g.per_vec;
+    for (int k = 0; k < g.per_vec; ++k) {
+        if (e0 + k >= g.total_elems) break;
+        const long long dst = scatter_index(g, e0 + k);
+        if (DT == RRM_I8_I32) {
+            const unsigned int word = k < 4 ? w0[0] : (k < 8 ? w0[1] : (k < 12 ? w0[2] : w0[3]));
+            reinterpret_cast<unsigned char*>(d0)[dst] = (unsigned char)(word >> (8 * (k & 3)));
+        } else if (DT == RRM_BF16_F32) {
+            const unsigned int a = k < 2 ? w0[0] : (k < 4 ? w0[1] : (k < 6 ? w0[2] : w0[3]));
+            const unsigned int b = k < 2 ? w1[0] : (k < 4 ? w1[1] : (k < 6 ? w1[2] : w1[3]));
+            reinterpret_cast<unsigned short*>(d0)[dst] = (unsigned short)(a >> (16 * (k & 1)));
+            reinterpret_cast<unsigned short*>(d1)[dst] = (unsigned short)(b >> (16 * (k & 1)));
+        }
+    }
+}
+
+template <int ESIZE>
+__global__ void repack_kernel(const unsigned char* __restrict__ x, unsigned char* __restrict__ dst, ScanGeom g) {
+    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= g.total_elems) return;
+    const long long d = scatter_index(g, e);
+    if (ESIZE == 1)
+        dst[d] = x[e];
+    else
+        reinterpret_cast<unsigned short*>(dst)[d] = reinterpret_cast<const unsigned short*>(x)[e];
+}
+
 template <int DT>
 __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restrict__ x_t, uint4* __restrict__ x_snap,
                                                    uint4* __restrict__ d0, uint4* __restrict__ d1,
@@ -134,7 +176,6 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
                     dw[i] = hi2;
                     lw[i] = lo2;
                 }
-                d1[v] = make_uint4(lw[0], lw[1], lw[2], lw[3]);
             } else {  // binary: the flip mask
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -142,7 +183,12 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
                     nelem += __popc(dw[i]);
                 }
             }
-            d0[v] = make_uint4(dw[0], dw[1], dw[2], dw[3]);
+            if (!g.scatter) {
+                d0[v] = make_uint4(dw[0], dw[1], dw[2], dw[3]);
+                if (DT == RRM_BF16_F32) d1[v] = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+            } else {
+                scatter_unit<DT>(g, v, dw, lw, d0, d1);
+            }
             x_snap[v] = a;  // snapshot of the input, only where it changed
             // input positions covered by this unit
             const long long e0 = v * g.per_vec;
@@ -152,8 +198,13 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
             p1 = e1 / g.c;
         } else if ((prev_mask >> (threadIdx.x & 63)) & 1ull) {
             // changed last step, unchanged now: restore the zero of the difference buffer
-            d0[v] = make_uint4(0, 0, 0, 0);
-            if (DT == RRM_BF16_F32) d1[v] = make_uint4(0, 0, 0, 0);
+            if (!g.scatter) {
+                d0[v] = make_uint4(0, 0, 0, 0);
+                if (DT == RRM_BF16_F32) d1[v] = make_uint4(0, 0, 0, 0);
+            } else {
+                const unsigned int z[4] = {0u, 0u, 0u, 0u};
+                scatter_unit<DT>(g, v, z, z, d0, d1);
+            }
         }
     }
     // mark the output blocks that see the changed positions
@@ -175,6 +226,18 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
 }
 
 }  // namespace
+
+hipError_t launch_repack(int esize, const void* x, void* dst, const ScanGeom& g, hipStream_t s) {
+    const long long blocks = (g.total_elems + 255) / 256;
+    if (blocks <= 0) return hipSuccess;
+    if (esize == 1)
+        hipLaunchKernelGGL(repack_kernel<1>, dim3((unsigned int)blocks), dim3(256), 0, s, (const unsigned char*)x,
+                           (unsigned char*)dst, g);
+    else
+        hipLaunchKernelGGL(repack_kernel<2>, dim3((unsigned int)blocks), dim3(256), 0, s, (const unsigned char*)x,
+                           (unsigned char*)dst, g);
+    return hipGetLastError();
+}
 
 hipError_t launch_scan(int dtype, const void* x_t, void* x_snap, void* d0, void* d1, unsigned long long* bitmap,
                        unsigned int* tileflag, unsigned int stamp, const ScanGeom& g, DevStats* stats,
