@@ -40,11 +40,11 @@ __device__ __forceinline__ uint4 load_x_guarded(const unsigned char* x, long lon
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-__device__ __forceinline__ void mark_tiles(const ScanGeom& g, long long pos, unsigned int* tileflag,
+__device__ __forceinline__ void mark_tiles(const ScanGeom& g, int pos, unsigned int* tileflag,
                                            unsigned int stamp) {
     const int hw = g.h * g.w;
-    const int b = (int)(pos / hw);
-    const int r = (int)(pos - (long long)b * hw);
+    const int b = pos / hw;
+    const int r = pos - b * hw;
     const int iy = r / g.w, ix = r - iy * g.w;
     const int ty0 = iy + g.pad - (g.kh - 1), tx0 = ix + g.pad - (g.kw - 1);
     const int oy_lo = ty0 <= 0 ? 0 : (ty0 + g.stride - 1) / g.stride;
@@ -55,15 +55,15 @@ __device__ __forceinline__ void mark_tiles(const ScanGeom& g, long long pos, uns
     if (oy_lo > oy_hi || ox_lo > ox_hi) return;
     for (int ty = oy_lo / TILE; ty <= oy_hi / TILE; ++ty)
         for (int tx = ox_lo / TILE; tx <= ox_hi / TILE; ++tx)
-            tileflag[((long long)b * g.tiles_y + ty) * g.tiles_x + tx] = stamp;
+            tileflag[(b * g.tiles_y + ty) * g.tiles_x + tx] = stamp;
 }
 
 // Mark the 4x4 output sub-tiles that see input position `pos`: one byte flag each, plain stores
 // (every writer stores the same value, so no atomics and no same-address serialisation).
-__device__ __forceinline__ void mark_subtiles(const ScanGeom& g, long long pos, unsigned char* flags) {
-    const int hw = g.h * g.w;
+__device__ __forceinline__ void mark_subtiles(const ScanGeom& g, unsigned int pos, unsigned char* flags) {
+    const unsigned int hw = (unsigned int)(g.h * g.w);
     const int b = (int)(pos / hw);
-    const int r = (int)(pos - (long long)b * hw);
+    const int r = (int)(pos - (unsigned int)b * hw);
     const int iy = r / g.w, ix = r - iy * g.w;
     const int ty0 = iy + g.pad - (g.kh - 1), tx0 = ix + g.pad - (g.kw - 1);
     const int oy_lo = ty0 <= 0 ? 0 : (ty0 + g.stride - 1) / g.stride;
@@ -73,36 +73,53 @@ __device__ __forceinline__ void mark_subtiles(const ScanGeom& g, long long pos, 
     if (ox_hi > g.wo - 1) ox_hi = g.wo - 1;
     if (oy_lo > oy_hi || ox_lo > ox_hi) return;
     for (int sy = oy_lo >> 2; sy <= (oy_hi >> 2); ++sy)
-        for (int sx = ox_lo >> 2; sx <= (ox_hi >> 2); ++sx) flags[((long long)b * g.sty + sy) * g.stx + sx] = 1;
+        for (int sx = ox_lo >> 2; sx <= (ox_hi >> 2); ++sx) flags[(b * g.sty + sy) * g.stx + sx] = 1;
 }
 
 // Element index of x element e in the padded / folded difference layout (see ScanGeom).
-__device__ __forceinline__ long long scatter_index(const ScanGeom& g, long long e) {
-    const long long p = e / g.c;
-    const int c = (int)(e - p * g.c);
-    const long long r = p / g.w;
-    const int ix = (int)(p - r * g.w);
-    const int grp = c / g.cg;
+// (tensors are below 2^30 elements, so 32-bit arithmetic is exact)
+__device__ __forceinline__ unsigned int scatter_index(const ScanGeom& g, unsigned int e) {
+    const unsigned int p = e / (unsigned int)g.c;
+    const unsigned int c = e - p * (unsigned int)g.c;
+    const unsigned int r = p / (unsigned int)g.w;
+    const unsigned int ix = p - r * (unsigned int)g.w;
+    const unsigned int grp = c / (unsigned int)g.cg;
     return ((r * g.wp + ix) * g.groups + grp) * g.cp + (c - grp * g.cg);
 }
 
 // Write the 16 bytes of unit v (already computed difference words) element by element into the
-// padded / folded layout.
+// padded / folded layout.  The (row, column, channel) of the first element is divided out once and
+// then stepped.
 template <int DT>
-__device__ __forceinline__ void scatter_unit(const ScanGeom& g, long long v, const unsigned int (&w0)[4],
-                                             const unsigned int (&w1)[4], uint4* d0, uint4* d1) {
-    const long long e0 = v * g.per_vec;
-    for (int k = 0; k < g.per_vec; ++k) {
-        if (e0 + k >= g.total_elems) break;
-        const long long dst = scatter_index(g, e0 + k);
+__device__ __forceinline__ void scatter_unit(const ScanGeom& g, long long v, uint4 w0, uint4 w1, uint4* d0, uint4* d1) {
+    constexpr int PV = DT == RRM_I8_I32 ? 16 : 8;
+    const unsigned int e0 = (unsigned int)v * PV;
+    const unsigned int total = (unsigned int)g.total_elems;
+    const unsigned int p = e0 / (unsigned int)g.c;
+    int c = (int)(e0 - p * (unsigned int)g.c);
+    const unsigned int r0 = p / (unsigned int)g.w;
+    int ix = (int)(p - r0 * (unsigned int)g.w);
+    unsigned int rowbase = r0 * (unsigned int)g.wp;
+#pragma unroll
+    for (int k = 0; k < PV; ++k) {
+        if (e0 + k >= total) break;
+        const int grp = g.groups == 1 ? 0 : c / g.cg;
+        const unsigned int dst = ((rowbase + ix) * g.groups + grp) * g.cp + (c - grp * g.cg);
         if (DT == RRM_I8_I32) {
-            const unsigned int word = k < 4 ? w0[0] : (k < 8 ? w0[1] : (k < 12 ? w0[2] : w0[3]));
+            const unsigned int word = k < 4 ? w0.x : (k < 8 ? w0.y : (k < 12 ? w0.z : w0.w));
             reinterpret_cast<unsigned char*>(d0)[dst] = (unsigned char)(word >> (8 * (k & 3)));
         } else if (DT == RRM_BF16_F32) {
-            const unsigned int a = k < 2 ? w0[0] : (k < 4 ? w0[1] : (k < 6 ? w0[2] : w0[3]));
-            const unsigned int b = k < 2 ? w1[0] : (k < 4 ? w1[1] : (k < 6 ? w1[2] : w1[3]));
+            const unsigned int a = k < 2 ? w0.x : (k < 4 ? w0.y : (k < 6 ? w0.z : w0.w));
+            const unsigned int b = k < 2 ? w1.x : (k < 4 ? w1.y : (k < 6 ? w1.z : w1.w));
             reinterpret_cast<unsigned short*>(d0)[dst] = (unsigned short)(a >> (16 * (k & 1)));
             reinterpret_cast<unsigned short*>(d1)[dst] = (unsigned short)(b >> (16 * (k & 1)));
+        }
+        if (++c == g.c) {
+            c = 0;
+            if (++ix == g.w) {
+                ix = 0;
+                rowbase += (unsigned int)g.wp;
+            }
         }
     }
 }
@@ -111,14 +128,14 @@ template <int ESIZE>
 __global__ void repack_kernel(const unsigned char* __restrict__ x, unsigned char* __restrict__ dst, ScanGeom g) {
     const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= g.total_elems) return;
-    const long long d = scatter_index(g, e);
+    const unsigned int d = scatter_index(g, (unsigned int)e);
     if (ESIZE == 1)
         dst[d] = x[e];
     else
         reinterpret_cast<unsigned short*>(dst)[d] = reinterpret_cast<const unsigned short*>(x)[e];
 }
 
-template <int DT>
+template <int DT, bool SCATTER>
 __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restrict__ x_t, uint4* __restrict__ x_snap,
                                                    uint4* __restrict__ d0, uint4* __restrict__ d1,
                                                    unsigned long long* __restrict__ bitmap,
@@ -129,7 +146,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
     DevStats* __restrict__ stats = stats_base + (blockIdx.x & (STAT_SLOTS - 1));
     const unsigned long long prev_mask = v < nvec ? bitmap[v >> 6] : 0ull;  // wave-uniform word
     bool changed = false;
-    long long p0 = 0, p1 = -1;  // input positions of this unit, when it changed
+    int p0 = 0, p1 = -1;  // input positions of this unit, when it changed
     unsigned int nelem = 0;
     uint4 a = make_uint4(0, 0, 0, 0);
     if (v < nvec) {
@@ -183,35 +200,34 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
                     nelem += __popc(dw[i]);
                 }
             }
-            if (!g.scatter) {
+            if (!SCATTER) {
                 d0[v] = make_uint4(dw[0], dw[1], dw[2], dw[3]);
                 if (DT == RRM_BF16_F32) d1[v] = make_uint4(lw[0], lw[1], lw[2], lw[3]);
             } else {
-                scatter_unit<DT>(g, v, dw, lw, d0, d1);
+                scatter_unit<DT>(g, v, make_uint4(dw[0], dw[1], dw[2], dw[3]), make_uint4(lw[0], lw[1], lw[2], lw[3]), d0, d1);
             }
             x_snap[v] = a;  // snapshot of the input, only where it changed
             // input positions covered by this unit
-            const long long e0 = v * g.per_vec;
-            long long e1 = e0 + g.per_vec - 1;
-            if (e1 > g.total_elems - 1) e1 = g.total_elems - 1;
-            p0 = e0 / g.c;
-            p1 = e1 / g.c;
+            const unsigned int e0 = (unsigned int)v * g.per_vec;
+            unsigned int e1 = e0 + g.per_vec - 1;
+            if (e1 > (unsigned int)g.total_elems - 1) e1 = (unsigned int)g.total_elems - 1;
+            p0 = (int)(e0 / (unsigned int)g.c);
+            p1 = (int)(e1 / (unsigned int)g.c);
         } else if ((prev_mask >> (threadIdx.x & 63)) & 1ull) {
             // changed last step, unchanged now: restore the zero of the difference buffer
-            if (!g.scatter) {
+            if (!SCATTER) {
                 d0[v] = make_uint4(0, 0, 0, 0);
                 if (DT == RRM_BF16_F32) d1[v] = make_uint4(0, 0, 0, 0);
             } else {
-                const unsigned int z[4] = {0u, 0u, 0u, 0u};
-                scatter_unit<DT>(g, v, z, z, d0, d1);
+                scatter_unit<DT>(g, v, make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), d0, d1);
             }
         }
     }
     // mark the output blocks that see the changed positions
     if (DT == RRM_BIN_I32) {
-        for (long long p = p0; p <= p1; ++p) mark_tiles(g, p, tileflag, stamp);
+        for (int p = p0; p <= p1; ++p) mark_tiles(g, p, tileflag, stamp);
     } else {
-        for (long long p = p0; p <= p1; ++p) mark_subtiles(g, p, reinterpret_cast<unsigned char*>(tileflag));
+        for (int p = p0; p <= p1; ++p) mark_subtiles(g, (unsigned int)p, reinterpret_cast<unsigned char*>(tileflag));
     }
     const unsigned long long mask = __ballot(changed);
     if ((threadIdx.x & 63) == 0 && v < nvec) bitmap[v >> 6] = mask;
@@ -249,15 +265,17 @@ hipError_t launch_scan(int dtype, const void* x_t, void* x_snap, void* d0, void*
     if (blocks <= 0) return hipSuccess;
     dim3 grid((unsigned int)blocks), block(256);
     const unsigned char* xt = static_cast<const unsigned char*>(x_t);
-    if (dtype == RRM_I8_I32)
-        hipLaunchKernelGGL(scan_kernel<RRM_I8_I32>, grid, block, 0, s, xt, (uint4*)x_snap, (uint4*)d0, (uint4*)d1,
-                           bitmap, tileflag, stamp, g, nvec, total_bytes, stats);
-    else if (dtype == RRM_BF16_F32)
-        hipLaunchKernelGGL(scan_kernel<RRM_BF16_F32>, grid, block, 0, s, xt, (uint4*)x_snap, (uint4*)d0, (uint4*)d1,
-                           bitmap, tileflag, stamp, g, nvec, total_bytes, stats);
-    else
-        hipLaunchKernelGGL(scan_kernel<RRM_BIN_I32>, grid, block, 0, s, xt, (uint4*)x_snap, (uint4*)d0, (uint4*)d1,
-                           bitmap, tileflag, stamp, g, nvec, total_bytes, stats);
+#define RRM_SCAN(DTV, SC)                                                                                        \
+    hipLaunchKernelGGL((scan_kernel<DTV, SC>), grid, block, 0, s, xt, (uint4*)x_snap, (uint4*)d0, (uint4*)d1, bitmap, \
+                       tileflag, stamp, g, nvec, total_bytes, stats)
+    if (dtype == RRM_I8_I32) {
+        if (g.scatter) RRM_SCAN(RRM_I8_I32, true); else RRM_SCAN(RRM_I8_I32, false);
+    } else if (dtype == RRM_BF16_F32) {
+        if (g.scatter) RRM_SCAN(RRM_BF16_F32, true); else RRM_SCAN(RRM_BF16_F32, false);
+    } else {
+        RRM_SCAN(RRM_BIN_I32, false);
+    }
+#undef RRM_SCAN
     return hipGetLastError();
 }
 
