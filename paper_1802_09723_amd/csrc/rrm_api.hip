@@ -10,6 +10,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -306,7 +307,12 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     }
     g.early_weights = small ? 1 : 0;
     bool ok = false;
-    for (long long budget : {(small ? 96ll : 156ll) * 1024, 156ll * 1024}) {
+    long long first_budget = (small ? 96ll : 156ll) * 1024;
+    if (const char* env = std::getenv("RRM_CONV_LDS_KB")) {  // tuning knob: preferred LDS bytes per workgroup
+        const long long kb = std::atoll(env);
+        if (kb >= 16 && kb <= 156) first_budget = kb * 1024;
+    }
+    for (long long budget : {first_budget, 156ll * 1024}) {
         for (const Cand& c : cands) {
             ConvGeom t = g;
             // a slab should hold at least 4 chunks (or all of them) to amortise its barriers
