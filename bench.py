@@ -180,10 +180,10 @@ def conv_alg_bytes(shape, esize, changed_units_per_step, active_tiles_per_step, 
     scan: both copies of x are read once; changed 16-byte units write their difference (terms
           buffers) and the snapshot.
     tile: the changed difference units are read once, the weights once (if anything changed),
-          and the touched 8x8 output tiles are read and written once (4-byte outputs)."""
+          and the touched 4x4 output sub-tiles are read and written once (4-byte outputs)."""
     xb = shape.n * shape.h * shape.w * shape.c_in * esize
     wb = shape.c_out * shape.kh * shape.kw * (shape.c_in // shape.groups) * esize
-    tile_y = 64 * shape.c_out * 4
+    tile_y = 16 * shape.c_out * 4
     scan = 2 * xb + changed_units_per_step * 16 * (1 + terms)
     tile = changed_units_per_step * 16 * terms + 2 * active_tiles_per_step * tile_y + (wb if active_tiles_per_step > 0 else 0)
     return scan, tile
@@ -436,7 +436,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=320)
     ap.add_argument("--warmup", type=int, default=32)
-    ap.add_argument("--streams", type=int, default=int(os.environ.get("RRM_BENCH_STREAMS", "1")))
+    ap.add_argument("--streams", type=int, default=int(os.environ.get("RRM_BENCH_STREAMS", "32")))
     ap.add_argument("--no-graph", action="store_true", help="issue every launch from Python instead of replaying a HIP graph")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--sweep", action="store_true")
