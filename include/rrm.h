@@ -123,7 +123,8 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
 
 /* Options (value semantics per key):
  *   "path"        0 auto, 1 sparse delta path always, 2 recompute densely every step
- *   "fc_splits"   FC: number of workgroups the changed-column list is split over (0 = heuristic)
+ *   "fc_splits"   FC: upper bound on the workgroups the changed-column list is split over, in
+ *                 [1, the default chosen at create] (the partial-sum scratch is sized for the default)
  *   "bf16_terms"  BF16 conv: 2 = difference carried as hi+lo bf16 pair (default), 1 = hi only
  *   "bin_cout_per_wave"  binary conv: output channels per wavefront, 8 / 16 (0 = heuristic)
  *   "profile"     1 = bracket every kernel of the following rrm_step calls with HIP events on the

@@ -7,8 +7,10 @@
 //               wavefront popcount + LDS prefix sum.
 //   fc_scatter  streams only the listed columns.  The weights are stored input-major
 //               (W^T [c_in][c_out], every column of W contiguous), each lane owns 16 bytes worth of
-//               output channels, the list is split over workgroups, and partial sums are combined
-//               with atomics (exact for int32; fp32 order differs run to run within rounding).
+//               output channels, and the list is split over workgroups so that enough loads are in
+//               flight to stream at memory speed; every split writes its partial sums to scratch.
+//   fc_reduce   adds the partial sums of the splits, in split order, into the stored projection
+//               (no atomics: exact for int32, and bit-reproducible run to run for fp32).
 // The layer is memory-bound: bytes moved are (changed columns) x c_out x element size.
 #include <type_traits>
 
@@ -19,7 +21,7 @@ namespace rrm {
 namespace {
 
 constexpr int FC_SCAN_THREADS = 1024;
-constexpr int FC_MIN_COLS = 4;  // columns per active workgroup before the list is split further
+constexpr int FC_MIN_COLS = 8;  // columns per active workgroup before the list is split further
 
 __device__ __forceinline__ float bf16_to_f32(unsigned int h) { return __uint_as_float(h << 16); }
 
@@ -133,20 +135,26 @@ __global__ __launch_bounds__(FC_SCAN_THREADS) void fc_scan_kernel(const unsigned
     }
 }
 
+// number of workgroups the column list is split over, from the list length (same in both kernels)
+__device__ __forceinline__ int fc_active_splits(int cnt, int splits) {
+    int s_eff = (cnt + FC_MIN_COLS - 1) / FC_MIN_COLS;
+    return s_eff > splits ? splits : s_eff;
+}
+
 template <int DT, int DENSE>
 __global__ __launch_bounds__(256) void fc_scatter_kernel(const unsigned char* __restrict__ wT,
                                                          const int* __restrict__ idx, const void* __restrict__ val_v,
                                                          const int* __restrict__ count,
-                                                         const unsigned char* __restrict__ x, void* __restrict__ y_v,
+                                                         const unsigned char* __restrict__ x, void* __restrict__ part_v,
                                                          FcGeom g, int splits) {
     constexpr int PV = DT == RRM_I8_I32 ? 16 : 8;
     constexpr int ESIZE = DT == RRM_I8_I32 ? 1 : 2;
+    constexpr int UN = 8;  // columns in flight per lane
     typedef typename std::conditional<DT == RRM_I8_I32, int, float>::type val_t;
     const val_t* val = static_cast<const val_t*>(val_v);
     const int b = blockIdx.z, s = blockIdx.y;
     const int cnt = DENSE ? g.c_in : count[b];
-    int s_eff = (cnt + FC_MIN_COLS - 1) / FC_MIN_COLS;
-    if (s_eff > splits) s_eff = splits;
+    const int s_eff = fc_active_splits(cnt, splits);
     if (s >= s_eff) return;
     const int co0 = (blockIdx.x * 256 + threadIdx.x) * PV;
     if (co0 >= g.c_out_p) return;
@@ -181,21 +189,16 @@ __global__ __launch_bounds__(256) void fc_scatter_kernel(const unsigned char* __
     };
 
     int k = s;
-    for (; k + 3 * s_eff < cnt; k += 4 * s_eff) {
-        int j0, j1, j2, j3;
-        val_t d0, d1, d2, d3;
-        column(k, j0, d0);
-        column(k + s_eff, j1, d1);
-        column(k + 2 * s_eff, j2, d2);
-        column(k + 3 * s_eff, j3, d3);
-        const uint4 w0 = *reinterpret_cast<const uint4*>(wcol + j0 * pitch);
-        const uint4 w1 = *reinterpret_cast<const uint4*>(wcol + j1 * pitch);
-        const uint4 w2 = *reinterpret_cast<const uint4*>(wcol + j2 * pitch);
-        const uint4 w3 = *reinterpret_cast<const uint4*>(wcol + j3 * pitch);
-        fma16(w0, d0);
-        fma16(w1, d1);
-        fma16(w2, d2);
-        fma16(w3, d3);
+    for (; k + (UN - 1) * s_eff < cnt; k += UN * s_eff) {
+        int j[UN];
+        val_t d[UN];
+        uint4 w[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) column(k + u * s_eff, j[u], d[u]);
+#pragma unroll
+        for (int u = 0; u < UN; ++u) w[u] = *reinterpret_cast<const uint4*>(wcol + j[u] * pitch);
+#pragma unroll
+        for (int u = 0; u < UN; ++u) fma16(w[u], d[u]);
     }
     for (; k < cnt; k += s_eff) {
         int j0;
@@ -203,10 +206,46 @@ __global__ __launch_bounds__(256) void fc_scatter_kernel(const unsigned char* __
         column(k, j0, d0);
         fma16(*reinterpret_cast<const uint4*>(wcol + j0 * pitch), d0);
     }
-    val_t* y = static_cast<val_t*>(y_v) + (long long)b * g.c_out;
+    // partial sums of this split: scratch [stream][split][c_out_p]
+    val_t* part = static_cast<val_t*>(part_v) + ((long long)b * splits + s) * g.c_out_p + co0;
 #pragma unroll
-    for (int e = 0; e < PV; ++e)
-        if (co0 + e < g.c_out && acc[e] != (val_t)0) atomicAdd(&y[co0 + e], acc[e]);
+    for (int e = 0; e < PV; e += 4) {
+        typedef typename std::conditional<DT == RRM_I8_I32, int4, float4>::type vec_t;
+        vec_t o;
+        o.x = acc[e]; o.y = acc[e + 1]; o.z = acc[e + 2]; o.w = acc[e + 3];
+        *reinterpret_cast<vec_t*>(part + e) = o;
+    }
+}
+
+template <int DT, int DENSE>
+__global__ __launch_bounds__(256) void fc_reduce_kernel(const void* __restrict__ part_v, const int* __restrict__ count,
+                                                        const void* __restrict__ bias_v, void* __restrict__ y_v, FcGeom g,
+                                                        int splits) {
+    typedef typename std::conditional<DT == RRM_I8_I32, int, float>::type val_t;
+    const int b = blockIdx.y;
+    const int co = blockIdx.x * 256 + threadIdx.x;
+    if (co >= g.c_out) return;
+    const int cnt = DENSE ? g.c_in : count[b];
+    const int s_eff = fc_active_splits(cnt, splits);
+    const val_t* part = static_cast<const val_t*>(part_v) + (long long)b * splits * g.c_out_p + co;
+    val_t sum = 0;
+    int s = 0;
+    for (; s + 3 < s_eff; s += 4) {  // four loads in flight, added in split order
+        const val_t p0 = part[(long long)s * g.c_out_p], p1 = part[(long long)(s + 1) * g.c_out_p];
+        const val_t p2 = part[(long long)(s + 2) * g.c_out_p], p3 = part[(long long)(s + 3) * g.c_out_p];
+        sum += p0;
+        sum += p1;
+        sum += p2;
+        sum += p3;
+    }
+    for (; s < s_eff; ++s) sum += part[(long long)s * g.c_out_p];
+    val_t* y = static_cast<val_t*>(y_v) + (long long)b * g.c_out + co;
+    if (DENSE) {
+        const val_t* bias = static_cast<const val_t*>(bias_v);
+        *y = (bias ? bias[co] : (val_t)0) + sum;
+    } else if (sum != (val_t)0) {
+        *y += sum;
+    }
 }
 
 }  // namespace
@@ -224,23 +263,23 @@ hipError_t launch_fc_scan(int dtype, const void* x_t, void* x_snap, int* idx, vo
 }
 
 hipError_t launch_fc_scatter(int dtype, int dense, int splits, const void* wT, const int* idx, const void* val,
-                             const int* count, const void* x, void* y, const FcGeom& g, DevStats* stats,
+                             const int* count, const void* x, void* part, const void* bias, void* y, const FcGeom& g,
                              hipStream_t s) {
-    (void)stats;
     dim3 grid((unsigned int)g.slices, (unsigned int)splits, (unsigned int)g.n), block(256);
+    dim3 rgrid((unsigned int)((g.c_out + 255) / 256), (unsigned int)g.n);
     const unsigned char* w = static_cast<const unsigned char*>(wT);
     const unsigned char* xx = static_cast<const unsigned char*>(x);
+#define RRM_FC(DTV, DV)                                                                                              \
+    do {                                                                                                            \
+        hipLaunchKernelGGL((fc_scatter_kernel<DTV, DV>), grid, block, 0, s, w, idx, val, count, xx, part, g, splits); \
+        hipLaunchKernelGGL((fc_reduce_kernel<DTV, DV>), rgrid, block, 0, s, part, count, bias, y, g, splits);        \
+    } while (0)
     if (dtype == RRM_I8_I32) {
-        if (dense)
-            hipLaunchKernelGGL((fc_scatter_kernel<RRM_I8_I32, 1>), grid, block, 0, s, w, idx, val, count, xx, y, g, splits);
-        else
-            hipLaunchKernelGGL((fc_scatter_kernel<RRM_I8_I32, 0>), grid, block, 0, s, w, idx, val, count, xx, y, g, splits);
+        if (dense) RRM_FC(RRM_I8_I32, 1); else RRM_FC(RRM_I8_I32, 0);
     } else {
-        if (dense)
-            hipLaunchKernelGGL((fc_scatter_kernel<RRM_BF16_F32, 1>), grid, block, 0, s, w, idx, val, count, xx, y, g, splits);
-        else
-            hipLaunchKernelGGL((fc_scatter_kernel<RRM_BF16_F32, 0>), grid, block, 0, s, w, idx, val, count, xx, y, g, splits);
+        if (dense) RRM_FC(RRM_BF16_F32, 1); else RRM_FC(RRM_BF16_F32, 0);
     }
+#undef RRM_FC
     return hipGetLastError();
 }
 

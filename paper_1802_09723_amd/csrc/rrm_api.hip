@@ -69,6 +69,8 @@ struct rrm_layer {
     int* fc_idx = nullptr;
     void* fc_val = nullptr;
     int* fc_count = nullptr;
+    void* fc_part = nullptr;  // FC: per-split partial sums [n][fc_nsplit][c_out_p]
+    int fc_nsplit = 0;
     DevStats* stats = nullptr;
     // state
     bool has_snapshot = false;
@@ -81,7 +83,7 @@ struct rrm_layer {
     int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0;
 
     ~rrm_layer() {
-        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, ctrl, zero16, fc_idx, fc_val, fc_count, stats};
+        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, ctrl, zero16, fc_idx, fc_val, fc_count, fc_part, stats};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
         for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
@@ -385,6 +387,9 @@ rrm_status setup_fc(rrm_layer* L, const std::vector<unsigned char>& w) {
     if (st != RRM_OK) return st;
     if ((st = dalloc((size_t)s.n * s.c_in * sizeof(int), (void**)&L->fc_idx)) != RRM_OK) return st;
     if ((st = dalloc((size_t)s.n * s.c_in * 4, &L->fc_val)) != RRM_OK) return st;
+    // enough workgroups to keep memory busy: about 1024 in total, at most 256 splits per stream
+    L->fc_nsplit = std::max(1, std::min(256, 1024 / (g.slices * s.n)));
+    if ((st = dalloc((size_t)s.n * L->fc_nsplit * g.c_out_p * 4, &L->fc_part)) != RRM_OK) return st;
     return dalloc((size_t)s.n * sizeof(int), (void**)&L->fc_count);
 }
 
@@ -410,13 +415,7 @@ int bin_cw(const rrm_layer* L) {
     return ((long long)g.n * g.tiles_y * g.tiles_x * g.groups * ((g.og + 63) / 64) >= 512) ? 16 : 8;
 }
 
-int fc_splits(const rrm_layer* L) {
-    if (L->opt_fc_splits) return L->opt_fc_splits;
-    int s = 1024 / (L->fg.slices * L->fg.n);
-    if (s < 1) s = 1;
-    if (s > 256) s = 256;
-    return s;
-}
+int fc_splits(const rrm_layer* L) { return L->opt_fc_splits > 0 ? L->opt_fc_splits : L->fc_nsplit; }
 
 rrm_status check_ptr(const void* p, const char* what) {
     if (!p) return fail(RRM_ERR_NULL, std::string(what) + " is NULL");
@@ -427,8 +426,8 @@ rrm_status check_ptr(const void* p, const char* what) {
 // dense layer of Eq. 3 from x into y
 rrm_status enqueue_dense(rrm_layer* L, const void* x, void* y, hipStream_t st) {
     if (L->shape.kind == RRM_FC) {
-        RRM_HIP(launch_fill_bias(L->dtype == RRM_BF16_F32, y, L->bias, L->shape.n, L->shape.c_out, st));
-        RRM_HIP(launch_fc_scatter(L->dtype, 1, fc_splits(L), L->wpack, nullptr, nullptr, nullptr, x, y, L->fg, L->stats, st));
+        RRM_HIP(launch_fc_scatter(L->dtype, 1, fc_splits(L), L->wpack, nullptr, nullptr, nullptr, x, L->fc_part, L->bias, y,
+                                  L->fg, st));
     } else if (L->dtype == RRM_BIN_I32) {
         RRM_HIP(launch_bin_conv(MODE_DENSE, bin_cw(L), x, nullptr, nullptr, L->wpack, L->bias, y, L->bg, L->stats, st));
     } else {
@@ -558,7 +557,7 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
         RRM_HIP(launch_fc_scan(L->dtype, x_t, L->x_snap, L->fc_idx, L->fc_val, L->fc_count, L->fg, L->stats, s));
         if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
         RRM_HIP(launch_fc_scatter(L->dtype, 0, fc_splits(L), L->wpack, L->fc_idx, L->fc_val, L->fc_count, nullptr,
-                                  L->y_snap, L->fg, L->stats, s));
+                                  L->fc_part, nullptr, L->y_snap, L->fg, s));
         if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
         ++L->delta_steps;
         L->total_tiles += (unsigned long long)L->shape.n * L->shape.c_in;
@@ -639,7 +638,9 @@ rrm_status rrm_set_option(rrm_layer* L, const char* key, long value) {
         if (value < 0 || value > 2) return fail(RRM_ERR_OPTION, "path must be 0, 1 or 2");
         L->opt_path = (int)value;
     } else if (k == "fc_splits") {
-        if (value < 0 || value > 4096) return fail(RRM_ERR_OPTION, "fc_splits must be in [0, 4096]");
+        // the scratch of the partial sums was sized for fc_nsplit at create: only fewer are allowed
+        if (L->shape.kind != RRM_FC || value < 1 || value > L->fc_nsplit)
+            return fail(RRM_ERR_OPTION, "fc_splits must be in [1, the layer's default]");
         L->opt_fc_splits = (int)value;
     } else if (k == "bf16_terms") {
         if (value != 1 && value != 2) return fail(RRM_ERR_OPTION, "bf16_terms must be 1 or 2");

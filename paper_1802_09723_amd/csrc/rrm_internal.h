@@ -124,8 +124,10 @@ hipError_t launch_conv(int dtype, int mode, int ncb, int nt, int terms, const vo
 hipError_t launch_fc_scan(int dtype, const void* x_t, void* x_snap, int* idx, void* val, int* count,
                           const FcGeom& g, DevStats* stats, hipStream_t s);
 
+// column scatter into per-split partial sums (scratch `part`: [n][splits][c_out_p] 4-byte values),
+// then the reduction of the splits into y (dense: y = bias + sum; delta: y += sum)
 hipError_t launch_fc_scatter(int dtype, int dense, int splits, const void* wT, const int* idx, const void* val,
-                             const int* count, const void* x, void* y, const FcGeom& g, DevStats* stats,
+                             const int* count, const void* x, void* part, const void* bias, void* y, const FcGeom& g,
                              hipStream_t s);
 
 hipError_t launch_bin_conv(int mode, int cw, const void* xsrc, const void* flip, unsigned int* tileflag,
