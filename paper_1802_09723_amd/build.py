@@ -15,6 +15,9 @@ SOURCES = ["rrm_api.hip", "scan.hip", "conv_gather.hip", "fc.hip", "bin_conv.hip
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared", "-fvisibility=hidden",
     "-munsafe-fp-atomics",
+    # no wave-level aggregation of atomics: it reads the result back at once (a wait for the memory round
+    # trip), while the kernels issue their few atomics from one lane and need the result late or never
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",

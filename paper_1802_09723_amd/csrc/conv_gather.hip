@@ -142,13 +142,22 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
     if (g.early_weights) stage_weights(0);
 
     // ---- which sub-tiles does this workgroup own? ----------------------------------------------------
-    int count, excl = 0;
-    const int wpt = (g.n_words + CONV_THREADS - 1) / CONV_THREADS;  // flag words (4 flags each) per thread
-    const int w_lo = tid * wpt, w_hi = min(w_lo + wpt, g.n_words);
+    // The flag array (one byte per sub-tile, padded with zeros to whole 16-byte vectors) is split into
+    // contiguous runs of vectors, one run per thread, loaded in one go and kept in registers.
+    constexpr int FW = 8;  // words per thread held in registers (more are re-read: > 8192 sub-tiles)
+    constexpr unsigned int LOW = 0x01010101u;
+    const int wpt = (g.n_words + CONV_THREADS - 1) / CONV_THREADS;
+    const int w_lo = tid * wpt;
+    unsigned int fw[FW];
+    int count, excl = 0, mine = 0;
     if (MODE == MODE_DELTA) {
-        // popcount prefix sum over the flag array (every workgroup does the same small scan)
-        int mine = 0;
-        for (int w = w_lo; w < w_hi; ++w) mine += __popc(flags[w] & 0x01010101u);
+#pragma unroll
+        for (int i = 0; i < FW; ++i) fw[i] = (i < wpt && w_lo + i < g.n_words) ? flags[w_lo + i] & LOW : 0u;
+#pragma unroll
+        for (int i = 0; i < FW; ++i) mine += __popc(fw[i]);
+        for (int i = FW; i < wpt; ++i)
+            if (w_lo + i < g.n_words) mine += __popc(flags[w_lo + i] & LOW);
+        // popcount prefix sum (every workgroup does the same small scan)
         int incl = mine;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -163,54 +172,73 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
     } else {
         count = g.n_sub;
     }
-    // few active sub-tiles are spread one per workgroup, many are packed up to NT per workgroup
-    int per = (count + (int)gridDim.x - 1) / (int)gridDim.x;
+    RRM_STAMP(16);
+    // The active sub-tiles are spread over as many workgroups as the chip runs at once (one per compute
+    // unit, counting the channel-block dimension of the grid), not more: few sub-tiles per workgroup
+    // keep its latency low, but a second round of workgroups would cost more than it saves.
+    int tgt = NUM_CU / (int)gridDim.y;
+    if (tgt < 1) tgt = 1;
+    if (tgt > (int)gridDim.x) tgt = (int)gridDim.x;
+    int per = (count + tgt - 1) / tgt;
     if (per < 1) per = 1;
-    if (per > NT) per = NT;  // cannot bind: gridDim.x * NT >= n_sub >= count
+    if (per > NT) per = NT;  // gridDim.x * NT >= n_sub >= count: the list always fits
     const int first = (int)blockIdx.x * per;
     int mycount = count - first;
     if (mycount > per) mycount = per;
 
+    unsigned int arrived_before = 0;  // thread 0: workgroups that signalled before this one
     if (MODE == MODE_DELTA) {
-        if (mycount > 0) {
-            // the rank of a set flag is the number of set flags before it; keep ranks first .. first+mycount-1
-            int rank = excl;
-            for (int w = w_lo; w < w_hi; ++w) {
-                unsigned int bits = flags[w] & 0x01010101u;
+        // the rank of a set flag is the number of set flags before it; keep ranks first .. first+mycount-1
+        if (mycount > 0 && excl + mine > first && excl < first + mycount) {
+            int rank = excl - first;
+            auto take = [&](unsigned int word, int widx) {
+                unsigned int bits = word & LOW;
                 while (bits) {
                     const int bpos = __ffs(bits) - 1;
                     bits &= bits - 1;
-                    const int r = rank - first;
-                    if (r >= 0 && r < mycount) s_sub[r] = w * 4 + (bpos >> 3);
+                    if (rank >= 0 && rank < mycount) s_sub[rank] = widx * 4 + (bpos >> 3);
                     ++rank;
                 }
-            }
+            };
+#pragma unroll
+            for (int i = 0; i < FW; ++i) take(fw[i], w_lo + i);
+            for (int i = FW; i < wpt; ++i)
+                if (w_lo + i < g.n_words) take(flags[w_lo + i], w_lo + i);
         }
-        // arrival: after this workgroup's last read of the flag array
+        // this workgroup's last read of the flag array is behind it
         __syncthreads();
-        if (tid == 0) {
-            __threadfence();
-            const unsigned int total = gridDim.x * gridDim.y;
-            const unsigned int old = atomicAdd(&ctrl[0], 1u);
-            s_last = (old == total - 1u) ? 1 : 0;
-        }
+    } else if (tid < mycount) {
+        s_sub[tid] = first + tid;
+    }
+    RRM_STAMP(17);
+    // Arrival signal.  Every thread has consumed its flag loads before the barrier above and this kernel
+    // has written nothing yet, so no memory fence is needed (a device-scope fence would write back the
+    // whole L2).  The answer is needed only at the end; the signal is sent where no load of the issuing
+    // thread follows closely (returns are in order: a later load would wait for the atomic as well).
+    auto arrive = [&]() {
+        if (MODE == MODE_DELTA && tid == 0) arrived_before = atomicAdd(&ctrl[0], 1u);
+    };
+    // The last workgroup to arrive knows that every workgroup has read the flags: it clears them (and
+    // the arrival counter) for the next step, at its own end, off everybody's critical path.
+    auto retire = [&]() {
+        if (MODE != MODE_DELTA) return;
+        if (tid == 0) s_last = (arrived_before == gridDim.x * gridDim.y - 1u) ? 1 : 0;
         __syncthreads();
         if (s_last) {
-            // every workgroup has read the flags: clear them for the next step
             for (int w = tid; w < g.n_words; w += CONV_THREADS) flags[w] = 0u;
             if (tid == 0) {
                 ctrl[0] = 0u;
                 if (count) atomicAdd(&stats[0].active_tiles, (unsigned long long)count);
             }
         }
-    } else if (tid < mycount) {
-        s_sub[tid] = first + tid;
-    }
+    };
     if (mycount <= 0) {
         __builtin_amdgcn_s_waitcnt(0);  // let an early weight copy land before the LDS is released
+        arrive();
+        retire();
         return;
     }
-    __syncthreads();
+    if (MODE != MODE_DELTA) __syncthreads();  // (delta: the list was completed before the barrier above)
     // per-slot geometry, once
     if (tid < mycount) {
         const int id = s_sub[tid];
@@ -222,6 +250,7 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
         s_ix0[tid] = 4 * sx * g.str_x - g.pad_x;
         s_ypos[tid] = (b * g.ho + 4 * sy) * g.wo + 4 * sx;
     }
+    RRM_STAMP(18);
     for (int e = tid; e < g.nq * 4; e += CONV_THREADS) tab[e] = offtab[e];  // the same for every slab
     __syncthreads();
     RRM_STAMP(1);
@@ -329,35 +358,7 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
         }
     };
 
-    RRM_STAMP(2);
-    if (!g.early_weights) stage_weights(0);
-    stage_windows(0);
-    RRM_STAMP(3);
-    for (int slab = 0; slab < g.nslab; ++slab) {
-        if (slab < 2) RRM_STAMP(4 + 5 * slab);
-        __builtin_amdgcn_s_waitcnt(0);  // this wavefront's copies for this slab have landed in LDS
-        if (slab < 2) RRM_STAMP(5 + 5 * slab);
-        __syncthreads();  // ... and everyone else's; everyone is also done with the other buffer
-        if (slab < 2) RRM_STAMP(6 + 5 * slab);
-        if (slab + 1 < g.nslab) {  // next slab in flight during this slab's K loop
-            stage_weights(slab + 1);
-            stage_windows(slab + 1);
-        }
-        if (slab < 2) RRM_STAMP(7 + 5 * slab);
-        const unsigned char* aw = lds + (slab & (nbuf - 1)) * a_bytes;
-        const unsigned char* bw = bbase + (slab & (nbuf - 1)) * b_bytes;
-        if (nact > 2) {
-            if constexpr (NS >= 4) k_loop.template operator()<4>(aw, bw);
-        } else if (nact > 1) {
-            if constexpr (NS >= 2) k_loop.template operator()<2>(aw, bw);
-        } else if (nact > 0) {
-            k_loop.template operator()<1>(aw, bw);
-        }
-        if (slab < 2) RRM_STAMP(8 + 5 * slab);
-    }
-    RRM_STAMP(14);
-
-    // ---- epilogue: lane holds 4 consecutive output channels of one position ----------------------------
+    // ---- output addresses: lane holds 4 consecutive output channels of one position ----------------------
     // Addresses first, then every load (stored projection / bias) in flight together, then the stores:
     // a read-modify-write per accumulator would serialise one memory round trip after another.
     sc_t* y = static_cast<sc_t*>(y_v);
@@ -380,15 +381,58 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
         }
     }
     const bool all_vec = g.vec_store && (cbg * NCB + NCB) * 16 <= g.og;  // every lane's 4 channels exist
-    if (all_vec) {
-        if (MODE == MODE_DELTA) {
-            vec_t old[NCB][NS];
+    // what the epilogue adds to: the stored projection (delta) or the bias (dense), fetched while the last
+    // slab multiplies
+    vec_t old[NCB][MODE == MODE_DELTA ? NS : 1];
+    auto prefetch_old = [&]() {
+        if (!all_vec) return;
 #pragma unroll
-            for (int c = 0; c < NCB; ++c)
+        for (int c = 0; c < NCB; ++c) {
+            if (MODE == MODE_DELTA) {
 #pragma unroll
                 for (int s = 0; s < NS; ++s)
                     if (pos_ok[s])
                         old[c][s] = *reinterpret_cast<const vec_t*>(y + (ybase[s] + (unsigned int)((cbg * NCB + c) * 16 + 4 * kgrp)));
+            } else {
+                old[c][0] = vec_t{0, 0, 0, 0};
+                if (bias) old[c][0] = *reinterpret_cast<const vec_t*>(bias + grp * g.og + (cbg * NCB + c) * 16 + 4 * kgrp);
+            }
+        }
+    };
+
+    RRM_STAMP(2);
+    arrive();
+    if (!g.early_weights) stage_weights(0);
+    stage_windows(0);
+    RRM_STAMP(3);
+    for (int slab = 0; slab < g.nslab; ++slab) {
+        if (slab < 2) RRM_STAMP(4 + 5 * slab);
+        __builtin_amdgcn_s_waitcnt(0);  // this wavefront's copies for this slab have landed in LDS
+        if (slab < 2) RRM_STAMP(5 + 5 * slab);
+        __syncthreads();  // ... and everyone else's; everyone is also done with the other buffer
+        if (slab < 2) RRM_STAMP(6 + 5 * slab);
+        if (slab + 1 < g.nslab) {  // next slab in flight during this slab's K loop
+            stage_weights(slab + 1);
+            stage_windows(slab + 1);
+        }
+        if (slab == g.nslab - 1) prefetch_old();
+        if (slab < 2) RRM_STAMP(7 + 5 * slab);
+        const unsigned char* aw = lds + (slab & (nbuf - 1)) * a_bytes;
+        const unsigned char* bw = bbase + (slab & (nbuf - 1)) * b_bytes;
+        if (nact > 2) {
+            if constexpr (NS >= 4) k_loop.template operator()<4>(aw, bw);
+        } else if (nact > 1) {
+            if constexpr (NS >= 2) k_loop.template operator()<2>(aw, bw);
+        } else if (nact > 0) {
+            k_loop.template operator()<1>(aw, bw);
+        }
+        if (slab < 2) RRM_STAMP(8 + 5 * slab);
+    }
+    RRM_STAMP(14);
+
+    // ---- epilogue ----------------------------------------------------------------------------------------
+    if (all_vec) {
+        if (MODE == MODE_DELTA) {
 #pragma unroll
             for (int c = 0; c < NCB; ++c)
 #pragma unroll
@@ -396,17 +440,11 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
                     if (!pos_ok[s]) continue;
                     const acc_t r = acc[c][s];
                     if (r[0] == (sc_t)0 && r[1] == (sc_t)0 && r[2] == (sc_t)0 && r[3] == (sc_t)0) continue;
-                    vec_t o = old[c][s];
+                    vec_t o = old[c][MODE == MODE_DELTA ? s : 0];
                     o.x += r[0]; o.y += r[1]; o.z += r[2]; o.w += r[3];
                     *reinterpret_cast<vec_t*>(y + (ybase[s] + (unsigned int)((cbg * NCB + c) * 16 + 4 * kgrp))) = o;
                 }
         } else {
-            vec_t bv[NCB];
-#pragma unroll
-            for (int c = 0; c < NCB; ++c) {
-                bv[c] = vec_t{0, 0, 0, 0};
-                if (bias) bv[c] = *reinterpret_cast<const vec_t*>(bias + grp * g.og + (cbg * NCB + c) * 16 + 4 * kgrp);
-            }
 #pragma unroll
             for (int c = 0; c < NCB; ++c)
 #pragma unroll
@@ -414,7 +452,8 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
                     if (!pos_ok[s]) continue;
                     const acc_t r = acc[c][s];
                     vec_t o;
-                    o.x = r[0] + bv[c].x; o.y = r[1] + bv[c].y; o.z = r[2] + bv[c].z; o.w = r[3] + bv[c].w;
+                    const vec_t bv = old[c][0];
+                    o.x = r[0] + bv.x; o.y = r[1] + bv.y; o.z = r[2] + bv.z; o.w = r[3] + bv.w;
                     *reinterpret_cast<vec_t*>(y + (ybase[s] + (unsigned int)((cbg * NCB + c) * 16 + 4 * kgrp))) = o;
                 }
         }
@@ -438,6 +477,7 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
             }
         }
     }
+    retire();
     RRM_STAMP(15);
 }
 

@@ -11,6 +11,7 @@ namespace rrm {
 constexpr int TILE = 8;          // output tile side (positions); 4 MFMA sub-tiles of 4x4
 constexpr int WAVE = 64;
 constexpr int CONV_THREADS = 256;
+constexpr int NUM_CU = 256;       // compute units of the MI355X
 
 enum Mode : int { MODE_DELTA = 0, MODE_DENSE = 1 };
 
