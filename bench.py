@@ -82,7 +82,7 @@ class Stack:
         # frames of two different sequences back to back: 0..T-1 of A, 0..T-1 of B
         self.frames = [torch.from_numpy(f).cuda() for s in seqs for f in s["frames"]]
         self.host_frames = [f for s in seqs for f in s["frames"]]
-        self.xin = torch.empty_like(self.frames[0])
+        self.xin = self.frames[0].clone()  # static graph input; always holds a valid frame
         self.bufs, self.meta = [], []
         for l, L in zip(self.cfg["layers"], self.layers):
             sh = l["shape"]

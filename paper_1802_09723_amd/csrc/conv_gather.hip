@@ -19,7 +19,7 @@
 //     chunk, so a slab is a contiguous run of 1 KiB fragments per channel block; wavefronts copy them
 //     with LDS-direct loads (global_load_lds_dwordx4, no registers), double-buffered across slabs;
 //   * activations: the gathered sub-tiles' input windows, gathered 16 bytes per lane with the same
-//     LDS-direct loads (chunk index XOR-swizzled by position against bank conflicts; units outside the
+//     LDS-direct loads (chunk index rotated by position against bank conflicts; units outside the
 //     image read a block of zeros), also double-buffered.  In delta mode the source is the difference
 //     buffer, zero where nothing changed.
 // The source is always in a 16-byte-chunk layout [stream][row][column][group][chunk]: the caller's x
@@ -33,6 +33,8 @@
 // Every output element has exactly one owner: no atomics on y, results reproducible run to run.
 // The last workgroup to arrive clears the flag array and the arrival counter, so nothing on the host
 // changes between steps (HIP-graph replay safe).
+#include <algorithm>
+
 #include "rrm_internal.h"
 
 namespace rrm {
@@ -86,7 +88,7 @@ typedef const void __attribute__((address_space(1))) * gptr_t;
 typedef void __attribute__((address_space(3))) * lptr_t;
 
 template <int DT, int MODE, int NCB, int NT, int TERMS>
-__global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
+__global__ __launch_bounds__(CONV_THREADS, 2) void conv_gather_kernel(
     const unsigned char* __restrict__ src0, const unsigned char* __restrict__ src1,
     const unsigned char* __restrict__ zero16, unsigned int* flags, unsigned int* ctrl,
     const uint4* __restrict__ wpack, const int* __restrict__ offtab, const void* __restrict__ bias_v, void* y_v,
@@ -106,7 +108,7 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
     const int plane_bytes = NT * g.slot_bytes;  // one term's windows
     const int b_bytes = TERMS * plane_bytes;
     unsigned char* bbase = lds + nbuf * a_bytes;
-    int* tab = reinterpret_cast<int*>(bbase + nbuf * b_bytes);
+    int2* tab = reinterpret_cast<int2*>(bbase + nbuf * b_bytes);
     __shared__ int s_sub[NT];   // gathered sub-tile ids
     __shared__ int s_pix[NT];   // first input position of the sub-tile's image: b*h*w
     __shared__ int s_iy0[NT];   // window origin in the input map (may be negative: padding)
@@ -173,48 +175,21 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
         count = g.n_sub;
     }
     RRM_STAMP(16);
-    // The active sub-tiles are spread over as many workgroups as the chip runs at once (one per compute
-    // unit, counting the channel-block dimension of the grid), not more: few sub-tiles per workgroup
-    // keep its latency low, but a second round of workgroups would cost more than it saves.
-    int tgt = NUM_CU / (int)gridDim.y;
-    if (tgt < 1) tgt = 1;
-    if (tgt > (int)gridDim.x) tgt = (int)gridDim.x;
-    int per = (count + tgt - 1) / tgt;
+    // The grid holds at most as many workgroups as the chip runs at once.  The active sub-tiles are cut
+    // into work units of `per` sub-tiles: few sub-tiles are spread thinly (a unit's latency grows with its
+    // size), many are packed NT per unit (operand reuse), and a workgroup takes units blockIdx.x,
+    // blockIdx.x + gridDim.x, ... until the list is exhausted (the same bound for every workgroup).
+    int per = (count + (int)gridDim.x - 1) / (int)gridDim.x;
     if (per < 1) per = 1;
-    if (per > NT) per = NT;  // gridDim.x * NT >= n_sub >= count: the list always fits
-    const int first = (int)blockIdx.x * per;
-    int mycount = count - first;
-    if (mycount > per) mycount = per;
+    if (per > NT) per = NT;
+    const int nunits = (count + per - 1) / per;
 
     unsigned int arrived_before = 0;  // thread 0: workgroups that signalled before this one
-    if (MODE == MODE_DELTA) {
-        // the rank of a set flag is the number of set flags before it; keep ranks first .. first+mycount-1
-        if (mycount > 0 && excl + mine > first && excl < first + mycount) {
-            int rank = excl - first;
-            auto take = [&](unsigned int word, int widx) {
-                unsigned int bits = word & LOW;
-                while (bits) {
-                    const int bpos = __ffs(bits) - 1;
-                    bits &= bits - 1;
-                    if (rank >= 0 && rank < mycount) s_sub[rank] = widx * 4 + (bpos >> 3);
-                    ++rank;
-                }
-            };
-#pragma unroll
-            for (int i = 0; i < FW; ++i) take(fw[i], w_lo + i);
-            for (int i = FW; i < wpt; ++i)
-                if (w_lo + i < g.n_words) take(flags[w_lo + i], w_lo + i);
-        }
-        // this workgroup's last read of the flag array is behind it
-        __syncthreads();
-    } else if (tid < mycount) {
-        s_sub[tid] = first + tid;
-    }
-    RRM_STAMP(17);
-    // Arrival signal.  Every thread has consumed its flag loads before the barrier above and this kernel
-    // has written nothing yet, so no memory fence is needed (a device-scope fence would write back the
-    // whole L2).  The answer is needed only at the end; the signal is sent where no load of the issuing
-    // thread follows closely (returns are in order: a later load would wait for the atomic as well).
+    // Arrival signal, sent once this workgroup has read the flags for the last time.  Every thread has
+    // consumed its flag loads before a barrier by then and the signalling thread's stores do not matter to
+    // the flags, so no memory fence is needed (a device-scope fence would write back the whole L2).  The
+    // answer is needed only at the end; the signal is sent where no load of the issuing thread follows
+    // closely (returns are in order: a later load would wait for the atomic as well).
     auto arrive = [&]() {
         if (MODE == MODE_DELTA && tid == 0) arrived_before = atomicAdd(&ctrl[0], 1u);
     };
@@ -232,13 +207,55 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
             }
         }
     };
-    if (mycount <= 0) {
+    if ((int)blockIdx.x >= nunits) {
         __builtin_amdgcn_s_waitcnt(0);  // let an early weight copy land before the LDS is released
         arrive();
         retire();
         return;
     }
-    if (MODE != MODE_DELTA) __syncthreads();  // (delta: the list was completed before the barrier above)
+    for (int e = tid; e < g.nq * 4; e += CONV_THREADS)  // K-pair table, the same for every slab
+        tab[e] = reinterpret_cast<const int2*>(offtab)[e];
+    // a single slab of weights serves every unit of the workgroup
+    const bool w_resident = g.nslab == 1;
+    if (w_resident && !g.early_weights) stage_weights(0);
+
+    const int j = lane & 15, kgrp = lane >> 4;
+    // lane-constant window position of its output position (tap 0,0)
+    const int off_lane = (((j >> 2) * g.str_y) * g.ww + (j & 3) * g.str_x) * g.sc * 16;
+    const int rot_lane = g.rot_a * (j >> 2) + g.rot_b * (j & 3);  // this position's share of the chunk rotation
+    sc_t* y = static_cast<sc_t*>(y_v);
+    const sc_t* bias = static_cast<const sc_t*>(bias_v);
+    const bool all_vec = g.vec_store && (cbg * NCB + NCB) * 16 <= g.og;  // every lane's 4 channels exist
+
+    for (int unit = (int)blockIdx.x; unit < nunits; unit += (int)gridDim.x) {
+    const bool first_unit = unit == (int)blockIdx.x, last_unit = unit + (int)gridDim.x >= nunits;
+    const int first = unit * per;
+    int mycount = count - first;
+    if (mycount > per) mycount = per;
+    if (!first_unit) __syncthreads();  // the previous unit is done with the list and the staged windows
+    if (MODE == MODE_DELTA) {
+        // the rank of a set flag is the number of set flags before it; keep ranks first .. first+mycount-1
+        if (excl + mine > first && excl < first + mycount) {
+            int rank = excl - first;
+            auto take = [&](unsigned int word, int widx) {
+                unsigned int bits = word & LOW;
+                while (bits) {
+                    const int bpos = __ffs(bits) - 1;
+                    bits &= bits - 1;
+                    if (rank >= 0 && rank < mycount) s_sub[rank] = widx * 4 + (bpos >> 3);
+                    ++rank;
+                }
+            };
+#pragma unroll
+            for (int i = 0; i < FW; ++i) take(fw[i], w_lo + i);
+            for (int i = FW; i < wpt; ++i)
+                if (w_lo + i < g.n_words) take(flags[w_lo + i], w_lo + i);
+        }
+    } else if (tid < mycount) {
+        s_sub[tid] = first + tid;
+    }
+    __syncthreads();
+    RRM_STAMP(17);
     // per-slot geometry, once
     if (tid < mycount) {
         const int id = s_sub[tid];
@@ -250,15 +267,13 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
         s_ix0[tid] = 4 * sx * g.str_x - g.pad_x;
         s_ypos[tid] = (b * g.ho + 4 * sy) * g.wo + 4 * sx;
     }
-    RRM_STAMP(18);
-    for (int e = tid; e < g.nq * 4; e += CONV_THREADS) tab[e] = offtab[e];  // the same for every slab
     __syncthreads();
     RRM_STAMP(1);
 
     // ---- window staging --------------------------------------------------------------------------------
     // A staged unit is 16 bytes of one (sub-tile, window position, chunk-in-slab).  Unit v lives at LDS
-    // byte 16*v of its plane, v = (slot*wpos + hp)*sc + cs, where the chunk is XOR-swizzled with the
-    // position, cs = cc ^ (hp & swz), so that the MFMA operand reads of neighbouring positions fall into
+    // byte 16*v of its plane, v = (slot*wpos + hp)*sc + cs, where slot cs of a position holds chunk
+    // (cs - rotation(position)) mod rot_p, so that the MFMA operand reads of a sub-tile's 16 positions fall into
     // different banks.  Consecutive lanes own consecutive units, which is what the LDS-direct gather
     // (per-lane global address, LDS address = wave base + 16*lane) needs.  The decomposition does not
     // depend on the slab, so each thread works out the source offsets of its units once; a slab only adds
@@ -276,7 +291,9 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
             const int r = fdiv(v, g.magic_sc[0]), cs = v - r * g.sc;
             const int slot = fdiv(r, g.magic_wsc[0]), hp = r - slot * g.wpos;
             const int hy = fdiv(hp, g.magic_ww), hx = hp - hy * g.ww;
-            const int cc = cs ^ (hp & g.swz);
+            int cc = cs;  // the chunk held by slot cs of this position (see rot_p)
+            if (cs < g.rot_p)
+                cc = (cs - g.rot_a * fdiv(hy, g.magic_sy) - g.rot_b * fdiv(hx, g.magic_sx)) & (g.rot_p - 1);
             const int iy = s_iy0[slot] + hy, ix = s_ix0[slot] + hx;
             if (cc >= g.last_sc) ulast |= 1u << i;
             if (iy >= 0 && iy < g.src_h && ix >= 0 && ix < g.src_w)
@@ -303,66 +320,10 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
         }
     };
 
-    const int j = lane & 15, kgrp = lane >> 4;
-    // lane-constant window position of its output position (tap 0,0)
-    const int hp_lane = ((j >> 2) * g.str_y) * g.ww + (j & 3) * g.str_x;
     // this wavefront's sub-tile slots are wave, wave + 4, ...: how many of them are in use
     const int nact = mycount > wave ? (mycount - wave + 3) / 4 : 0;
 
-    acc_t acc[NCB][NS];
-#pragma unroll
-    for (int c = 0; c < NCB; ++c)
-#pragma unroll
-        for (int s = 0; s < NS; ++s) acc[c][s] = acc_t{0, 0, 0, 0};
-
-    // ---- K loop of one slab, compiled per number of sub-tiles in use by the wavefront (no per-sub-tile
-    //      branches; unused slots read stale LDS and their results are dropped) --------------------------
-    auto k_loop = [&]<int NSA>(const unsigned char* aw, const unsigned char* bw) {
-        const unsigned char* ap = aw + lane * 16;
-        const unsigned char* bp = bw + wave * g.slot_bytes;
-        const int sstride = 4 * g.slot_bytes;
-        const int* tp = tab + kgrp;
-        const int sc16 = g.sc * 16;
-        uint4 a[NCB], b0[NSA], b1[TERMS == 2 ? NSA : 1];
-        auto fetch = [&](int q, uint4(&a_)[NCB], uint4(&b0_)[NSA], uint4(&b1_)[TERMS == 2 ? NSA : 1]) {
-            const int t = tp[4 * q];                  // (window position of the tap) | chunk << 16
-            const int hp = hp_lane + (t & 0xFFFF);
-            const int off = hp * sc16 + (((t >> 16) ^ (hp & g.swz)) << 4);
-#pragma unroll
-            for (int c = 0; c < NCB; ++c) a_[c] = *reinterpret_cast<const uint4*>(ap + (c * g.nq + q) * 1024);
-#pragma unroll
-            for (int s = 0; s < NSA; ++s) {
-                b0_[s] = *reinterpret_cast<const uint4*>(bp + off + s * sstride);
-                if (TERMS == 2) b1_[s] = *reinterpret_cast<const uint4*>(bp + plane_bytes + off + s * sstride);
-            }
-        };
-        // software pipeline: the operands of K step q+1 are read from LDS while step q multiplies
-        fetch(0, a, b0, b1);
-        for (int q = 0; q < g.nq; ++q) {
-            uint4 an[NCB], b0n[NSA], b1n[TERMS == 2 ? NSA : 1];
-            fetch(min(q + 1, g.nq - 1), an, b0n, b1n);
-#pragma unroll
-            for (int c = 0; c < NCB; ++c)
-#pragma unroll
-                for (int s = 0; s < NSA; ++s) {
-                    acc[c][s] = mma(a[c], b0[s], acc[c][s]);
-                    if (TERMS == 2) acc[c][s] = mma(a[c], b1[s], acc[c][s]);
-                }
-#pragma unroll
-            for (int c = 0; c < NCB; ++c) a[c] = an[c];
-#pragma unroll
-            for (int s = 0; s < NSA; ++s) {
-                b0[s] = b0n[s];
-                if (TERMS == 2) b1[s] = b1n[s];
-            }
-        }
-    };
-
     // ---- output addresses: lane holds 4 consecutive output channels of one position ----------------------
-    // Addresses first, then every load (stored projection / bias) in flight together, then the stores:
-    // a read-modify-write per accumulator would serialise one memory round trip after another.
-    sc_t* y = static_cast<sc_t*>(y_v);
-    const sc_t* bias = static_cast<const sc_t*>(bias_v);
     unsigned int ybase[NS];
     bool pos_ok[NS];
 #pragma unroll
@@ -380,29 +341,69 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
             ybase[s] = (unsigned int)(yp + py * g.wo + px) * (unsigned int)g.c_out + (unsigned int)(grp * g.og);
         }
     }
-    const bool all_vec = g.vec_store && (cbg * NCB + NCB) * 16 <= g.og;  // every lane's 4 channels exist
-    // what the epilogue adds to: the stored projection (delta) or the bias (dense), fetched while the last
-    // slab multiplies
-    vec_t old[NCB][MODE == MODE_DELTA ? NS : 1];
-    auto prefetch_old = [&]() {
-        if (!all_vec) return;
+    // The accumulators start from what the result is added to -- the stored projection (delta: Algorithm 1,
+    // P_t = P_{t-1} + F * dI) or the bias (dense: Eq. 3) -- so these loads overlap the staging of the first
+    // slab and the epilogue is a plain store.  (Ragged channel counts start from zero and add at the end.)
+    acc_t acc[NCB][NS];
 #pragma unroll
-        for (int c = 0; c < NCB; ++c) {
-            if (MODE == MODE_DELTA) {
+    for (int c = 0; c < NCB; ++c) {
+        vec_t bv = vec_t{0, 0, 0, 0};
+        if (MODE == MODE_DENSE && all_vec && bias)
+            bv = *reinterpret_cast<const vec_t*>(bias + grp * g.og + (cbg * NCB + c) * 16 + 4 * kgrp);
 #pragma unroll
-                for (int s = 0; s < NS; ++s)
-                    if (pos_ok[s])
-                        old[c][s] = *reinterpret_cast<const vec_t*>(y + (ybase[s] + (unsigned int)((cbg * NCB + c) * 16 + 4 * kgrp)));
-            } else {
-                old[c][0] = vec_t{0, 0, 0, 0};
-                if (bias) old[c][0] = *reinterpret_cast<const vec_t*>(bias + grp * g.og + (cbg * NCB + c) * 16 + 4 * kgrp);
+        for (int s = 0; s < NS; ++s) {
+            vec_t v = bv;
+            if (MODE == MODE_DELTA && all_vec && pos_ok[s])
+                v = *reinterpret_cast<const vec_t*>(y + (ybase[s] + (unsigned int)((cbg * NCB + c) * 16 + 4 * kgrp)));
+            acc[c][s] = acc_t{v.x, v.y, v.z, v.w};
+        }
+    }
+
+    // ---- K loop of one slab, compiled per number of sub-tiles in use by the wavefront (no per-sub-tile
+    //      branches; unused slots read stale LDS and their results are dropped) --------------------------
+    auto k_loop = [&]<int NSA>(const unsigned char* aw, const unsigned char* bw) {
+        const unsigned char* ap = aw + lane * 16;
+        const unsigned char* bp = bw + wave * g.slot_bytes;
+        const int sstride = 4 * g.slot_bytes;
+        const int2* tp = tab + kgrp;
+        uint4 a[NCB], b0[NSA], b1[TERMS == 2 ? NSA : 1];
+        auto fetch = [&](int q, uint4(&a_)[NCB], uint4(&b0_)[NSA], uint4(&b1_)[TERMS == 2 ? NSA : 1]) {
+            const int2 t = tp[4 * q];  // tap's byte offset; rotated chunk | mask << 8
+            const int off = off_lane + t.x + ((((t.y & 0xFF) + rot_lane) & (t.y >> 8)) << 4);
+#pragma unroll
+            for (int c = 0; c < NCB; ++c) a_[c] = *reinterpret_cast<const uint4*>(ap + (c * g.nq + q) * 1024);
+#pragma unroll
+            for (int s = 0; s < NSA; ++s) {
+                b0_[s] = *reinterpret_cast<const uint4*>(bp + off + s * sstride);
+                if (TERMS == 2) b1_[s] = *reinterpret_cast<const uint4*>(bp + plane_bytes + off + s * sstride);
+            }
+        };
+        // software pipeline: the operands of K step q+1 are read from LDS while step q multiplies
+        fetch(0, a, b0, b1);
+        for (int q = 0; q < g.nq; ++q) {
+            uint4 an[NCB], b0n[NSA], b1n[TERMS == 2 ? NSA : 1];
+            fetch(min(q + 1, g.nq - 1), an, b0n, b1n);
+            __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the multiplies (the scheduler would sink them)
+#pragma unroll
+            for (int c = 0; c < NCB; ++c)
+#pragma unroll
+                for (int s = 0; s < NSA; ++s) {
+                    acc[c][s] = mma(a[c], b0[s], acc[c][s]);
+                    if (TERMS == 2) acc[c][s] = mma(a[c], b1[s], acc[c][s]);
+                }
+#pragma unroll
+            for (int c = 0; c < NCB; ++c) a[c] = an[c];
+#pragma unroll
+            for (int s = 0; s < NSA; ++s) {
+                b0[s] = b0n[s];
+                if (TERMS == 2) b1[s] = b1n[s];
             }
         }
     };
 
     RRM_STAMP(2);
-    arrive();
-    if (!g.early_weights) stage_weights(0);
+    if (last_unit) arrive();
+    if (!w_resident && !(g.early_weights && first_unit)) stage_weights(0);
     stage_windows(0);
     RRM_STAMP(3);
     for (int slab = 0; slab < g.nslab; ++slab) {
@@ -411,11 +412,10 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
         if (slab < 2) RRM_STAMP(5 + 5 * slab);
         __syncthreads();  // ... and everyone else's; everyone is also done with the other buffer
         if (slab < 2) RRM_STAMP(6 + 5 * slab);
-        if (slab + 1 < g.nslab) {  // next slab in flight during this slab's K loop
+        if (slab + 1 < g.nslab) {  // next slab in flight during this slab's K loop (nslab > 1: weights are not resident)
             stage_weights(slab + 1);
             stage_windows(slab + 1);
         }
-        if (slab == g.nslab - 1) prefetch_old();
         if (slab < 2) RRM_STAMP(7 + 5 * slab);
         const unsigned char* aw = lds + (slab & (nbuf - 1)) * a_bytes;
         const unsigned char* bw = bbase + (slab & (nbuf - 1)) * b_bytes;
@@ -432,31 +432,16 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
 
     // ---- epilogue ----------------------------------------------------------------------------------------
     if (all_vec) {
-        if (MODE == MODE_DELTA) {
 #pragma unroll
-            for (int c = 0; c < NCB; ++c)
+        for (int c = 0; c < NCB; ++c)
 #pragma unroll
-                for (int s = 0; s < NS; ++s) {
-                    if (!pos_ok[s]) continue;
-                    const acc_t r = acc[c][s];
-                    if (r[0] == (sc_t)0 && r[1] == (sc_t)0 && r[2] == (sc_t)0 && r[3] == (sc_t)0) continue;
-                    vec_t o = old[c][MODE == MODE_DELTA ? s : 0];
-                    o.x += r[0]; o.y += r[1]; o.z += r[2]; o.w += r[3];
-                    *reinterpret_cast<vec_t*>(y + (ybase[s] + (unsigned int)((cbg * NCB + c) * 16 + 4 * kgrp))) = o;
-                }
-        } else {
-#pragma unroll
-            for (int c = 0; c < NCB; ++c)
-#pragma unroll
-                for (int s = 0; s < NS; ++s) {
-                    if (!pos_ok[s]) continue;
-                    const acc_t r = acc[c][s];
-                    vec_t o;
-                    const vec_t bv = old[c][0];
-                    o.x = r[0] + bv.x; o.y = r[1] + bv.y; o.z = r[2] + bv.z; o.w = r[3] + bv.w;
-                    *reinterpret_cast<vec_t*>(y + (ybase[s] + (unsigned int)((cbg * NCB + c) * 16 + 4 * kgrp))) = o;
-                }
-        }
+            for (int s = 0; s < NS; ++s) {
+                if (!pos_ok[s]) continue;
+                const acc_t r = acc[c][s];
+                vec_t o;
+                o.x = r[0]; o.y = r[1]; o.z = r[2]; o.w = r[3];
+                *reinterpret_cast<vec_t*>(y + (ybase[s] + (unsigned int)((cbg * NCB + c) * 16 + 4 * kgrp))) = o;
+            }
     } else {
         // ragged channel counts: element by element
 #pragma unroll
@@ -477,6 +462,7 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_gather_kernel(
             }
         }
     }
+    }  // units
     retire();
     RRM_STAMP(15);
 }
@@ -486,8 +472,12 @@ hipError_t launch_one(const void* src0, const void* src1, const void* zero16, un
                       unsigned int* ctrl, const void* wpack, const int* offtab, const void* bias, void* y,
                       const ConvGeom& g, DevStats* stats, hipStream_t s) {
     const int ncbg = (g.ncb + NCB - 1) / NCB;
-    dim3 grid((unsigned int)((g.n_sub + NT - 1) / NT), (unsigned int)(g.groups * ncbg));
     const size_t lds = conv_lds_bytes(g, NCB, NT, TERMS);
+    // no more workgroups than are resident at once (the kernel loops over its work units)
+    const int gy = g.groups * ncbg;
+    const int resident = NUM_CU * (lds * 2 <= 160 * 1024 ? 2 : 1);
+    const int gx = std::min((g.n_sub + NT - 1) / NT, std::max(1, resident / gy));
+    dim3 grid((unsigned int)gx, (unsigned int)gy);
     auto kern = conv_gather_kernel<DT, MODE, NCB, NT, TERMS>;
     if (lds > 64 * 1024) {
         static size_t granted = 0;  // one per instantiation; creation and launches of a process share it
@@ -520,7 +510,7 @@ hipError_t launch_shape(int ncb, int nt, const void* src0, const void* src1, con
 
 size_t conv_lds_bytes(const ConvGeom& g, int ncb, int nt, int terms) {
     return (size_t)(g.nslab > 1 ? 2 : 1) * ((size_t)ncb * g.nq * 1024 + (size_t)terms * nt * g.slot_bytes) +
-           (size_t)g.nq * 4 * sizeof(int);
+           (size_t)g.nq * 4 * sizeof(int2);
 }
 
 hipError_t launch_conv(int dtype, int mode, int ncb, int nt, int terms, const void* src0, const void* src1,

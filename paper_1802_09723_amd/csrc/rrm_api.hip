@@ -162,13 +162,23 @@ rrm_status pack_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     const rrm_shape& s = L->shape;
     ConvGeom& g = L->cg;
     const int ntaps = s.kh * g.kw_eff;
-    // LDS offsets of a slab's K pairs (the same for every slab); padded pairs point at offset 0 and
-    // carry zero weights.
-    std::vector<int> tab((size_t)g.nq * 4, 0);
+    // K-pair table of a slab (the same for every slab), two words per pair:
+    //   [0] LDS byte offset of the tap's window position (+ the chunk's, for chunks that are not rotated)
+    //   [1] rotated chunks: (chunk + the tap's rotation term) mod rot_p | (rot_p - 1) << 8; others 0
+    // Padded pairs point at offset 0 and carry zero weights.
+    std::vector<int> tab((size_t)g.nq * 4 * 2, 0);
     for (int e = 0; e < ntaps * g.sc && e < g.nq * 4; ++e) {
         const int cc = e / ntaps, tap = e % ntaps;
         const int ky = tap / g.kw_eff, ku = tap % g.kw_eff;
-        tab[e] = (ky * g.ww + ku) | (cc << 16);  // window position of the tap | chunk in slab
+        const int hp = ky * g.ww + ku;
+        if (cc < g.rot_p) {
+            const int rt = (g.rot_a * (ky / g.str_y) + g.rot_b * (ku / g.str_x)) & (g.rot_p - 1);
+            tab[2 * e] = hp * g.sc * 16;
+            tab[2 * e + 1] = ((cc + rt) & (g.rot_p - 1)) | ((g.rot_p - 1) << 8);
+        } else {
+            tab[2 * e] = hp * g.sc * 16 + cc * 16;
+            tab[2 * e + 1] = 0;
+        }
     }
     rrm_status st = upload(tab.data(), tab.size() * sizeof(int), (void**)&L->offtab);
     if (st != RRM_OK) return st;
@@ -214,6 +224,47 @@ rrm_status pack_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     return upload(pack.data(), pack.size(), &L->wpack);
 }
 
+// LDS bank spreading for the window reads of the K loop.  The 16 lanes that read the same (tap, chunk)
+// for the 16 positions of a sub-tile should hit 16 different 16-byte bank groups of the 256-byte bank
+// row.  The rotation coefficients are chosen by exhaustive search over the layer's taps.
+void choose_rotation(ConvGeom& t, int ntaps) {
+    int P = 1;
+    while (P * 2 <= t.sc) P *= 2;
+    t.rot_p = P;
+    t.rot_a = t.rot_b = 0;
+    t.magic_sy = magic_for(t.str_y);
+    t.magic_sx = magic_for(t.str_x);
+    if (P == 1) return;
+    long long best = -1;
+    for (int a = 0; a < P; ++a)
+        for (int b = 0; b < P; ++b) {
+            long long cost = 0;
+            for (int tap = 0; tap < ntaps; ++tap) {
+                const int ky = tap / t.kw_eff, ku = tap % t.kw_eff;
+                for (int cc = 0; cc < P; ++cc) {
+                    int addr[16], worst = 1;
+                    for (int j = 0; j < 16; ++j) {
+                        const int hy = (j >> 2) * t.str_y + ky, hx = (j & 3) * t.str_x + ku;
+                        const int cs = (cc + a * (hy / t.str_y) + b * (hx / t.str_x)) & (P - 1);
+                        addr[j] = ((hy * t.ww + hx) * t.sc + cs) * 16;
+                    }
+                    for (int j = 0; j < 16; ++j) {
+                        int same = 1;
+                        for (int k = 0; k < j; ++k)
+                            if ((addr[k] & 255) / 16 == (addr[j] & 255) / 16 && addr[k] != addr[j]) ++same;
+                        worst = std::max(worst, same);
+                    }
+                    cost += worst;
+                }
+            }
+            if (best < 0 || cost < best) {
+                best = cost;
+                t.rot_a = a;
+                t.rot_b = b;
+            }
+        }
+}
+
 // Fill the slab-dependent fields for (blocks, sub-tiles) per workgroup with the largest slab that fits
 // the LDS budget; false if none does.
 bool conv_try_shape(ConvGeom& g, int terms, int wg_cb, int nt, int ntaps, long long budget) {
@@ -233,7 +284,7 @@ bool conv_try_shape(ConvGeom& g, int terms, int wg_cb, int nt, int ntaps, long l
         if ((long long)nt * t.wpos * sc > max_units) continue;  // staged units per thread are bounded
         t.magic_sc[0] = t.magic_sc[1] = magic_for(sc);
         t.magic_wsc[0] = t.magic_wsc[1] = magic_for(t.wpos);
-        t.swz = (sc & -sc) - 1;
+        choose_rotation(t, ntaps);
         t.last_sc = t.chunks - (t.nslab - 1) * sc;
         g = t;
         return true;

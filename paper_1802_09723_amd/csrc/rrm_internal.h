@@ -72,7 +72,12 @@ struct ConvGeom {
     int nslab;           // ceil(chunks / sc)
     int pitch;           // LDS bytes per staged position: 16*sc
     int slot_bytes;      // wpos*pitch: LDS bytes of one sub-tile's window
-    int swz;             // XOR mask applied to the chunk index by the window position (bank spreading)
+    // Bank spreading: within a staged position the first rot_p chunks (a power of two) are rotated by
+    // rot_a * (row / str_y) + rot_b * (column / str_x), so that the 16 positions of a sub-tile read
+    // different LDS banks for the same (tap, chunk); the reader splits the rotation into a per-lane and a
+    // per-tap term (the tap's term is folded into the K-pair table).
+    int rot_p, rot_a, rot_b;
+    unsigned int magic_sy, magic_sx;  // reciprocals of str_y, str_x
     int last_sc;         // chunks present in the last slab
     int nq;              // MFMA K steps per slab: ceil(kh*kw*sc / 4)
     int ncb;             // 16-wide output-channel blocks per group
