@@ -9,11 +9,12 @@
 // input.  Every workgroup of this kernel reads that flag array (a few KB at most), ranks the set flags
 // with a popcount prefix sum, and takes its share of the ranked list: up to NT active sub-tiles from
 // anywhere in the batch.  They become the N dimension of one GEMM per workgroup:
-//     M = NCB blocks of 16 output channels
-//     N = 16 x (gathered sub-tiles)
-//     K = (filter tap, 16-byte channel chunk) pairs, four per MFMA
-//         (v_mfma_i32_16x16x64_i8 / v_mfma_f32_16x16x32_bf16; lane l supplies row/column l%16 and the
-//          16 bytes of pair 4q + l/16).
+//     M = NCB blocks of 32 output channels
+//     N = 16 x (gathered sub-tiles), two sub-tiles per MFMA
+//     K = (filter tap, 16-byte channel chunk) pairs, two per MFMA
+//         (v_mfma_i32_32x32x32_i8 / v_mfma_f32_32x32x16_bf16; lane l supplies row/column l%32 and the
+//          16 bytes of pair 2k + l/32).  The 32x32 shapes are used because one wavefront per SIMD issues
+//         them back to back at the full rate, which the 16x16 shapes only reach with two wavefronts.
 // Both operands go through LDS, one slab of channel chunks at a time:
 //   * weights: the filters are packed at create time in per-lane MFMA order, K pairs ordered chunk by
 //     chunk, so a slab is a contiguous run of 1 KiB fragments per channel block; wavefronts copy them
@@ -26,8 +27,8 @@
 // when its channel runs are 16-byte multiples, otherwise the padded (or column-folded) copy that the
 // scan / repack kernels write (see scan.hip); the kernel itself only sees "source positions" of
 // pos_bytes bytes with their own strides and window size.
-// Each wavefront owns every fourth gathered sub-tile and all NCB channel blocks (register blocking
-// NCB x NT/4), so one weight fragment read feeds NT/4 MFMAs and one window read feeds NCB MFMAs.
+// Each wavefront owns every fourth pair of gathered sub-tiles and all NCB channel blocks (register
+// blocking NCB x NT/8), so one weight fragment read feeds NT/8 MFMAs and one window read feeds NCB MFMAs.
 // The number of sub-tiles per workgroup adapts on the device: few active sub-tiles are spread one per
 // workgroup (latency), many are packed NT per workgroup (operand reuse).
 // Every output element has exactly one owner: no atomics on y, results reproducible run to run.
@@ -42,30 +43,45 @@ namespace rrm {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-typedef float v4f __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 template <int DT>
 struct Acc;
 template <>
 struct Acc<RRM_I8_I32> {
-    typedef v4i type;
+    typedef v16i type;
     typedef int4 vec;
     typedef int scalar;
 };
 template <>
 struct Acc<RRM_BF16_F32> {
-    typedef v4f type;
+    typedef v16f type;
     typedef float4 vec;
     typedef float scalar;
 };
 
-__device__ __forceinline__ v4i mma(const uint4& a, const uint4& b, v4i c) {
-    return __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, a), __builtin_bit_cast(v4i, b), c, 0, 0, 0);
+// D (32x32) += A (32 x K) * B (K x 32); lane l holds row / column l%32 of A / B and 16 bytes of K
+// (half l/32), and of D the column l%32 with rows 8*(r/4) + 4*(l/32) + r%4 in register r.
+__device__ __forceinline__ v16i mma(const uint4& a, const uint4& b, v16i c) {
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(v4i, a), __builtin_bit_cast(v4i, b), c, 0, 0, 0);
 }
-__device__ __forceinline__ v4f mma(const uint4& a, const uint4& b, v4f c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0,
+__device__ __forceinline__ v16f mma(const uint4& a, const uint4& b, v16f c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0,
                                                    0);
+}
+
+// Issue order of a K step for the instruction scheduler: N_MFMA matrix instructions with N_READ LDS reads
+// spread evenly between them.
+template <int I, int N_MFMA, int N_READ>
+__device__ __forceinline__ void sched_interleave() {
+    if constexpr (I < N_MFMA) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+        constexpr int R = (N_READ * (I + 1)) / N_MFMA - (N_READ * I) / N_MFMA;
+        if constexpr (R > 0) __builtin_amdgcn_sched_group_barrier(0x100, R, 0);  // R LDS reads
+        sched_interleave<I + 1, N_MFMA, N_READ>();
+    }
 }
 
 // u / d for small u through a precomputed reciprocal (magic == 0 means d == 1)
@@ -88,7 +104,7 @@ typedef const void __attribute__((address_space(1))) * gptr_t;
 typedef void __attribute__((address_space(3))) * lptr_t;
 
 template <int DT, int MODE, int NCB, int NT, int TERMS>
-__global__ __launch_bounds__(CONV_THREADS, 2) void conv_gather_kernel(
+__global__ __launch_bounds__(CONV_THREADS, (NCB * NT >= 32 ? 1 : 2)) void conv_gather_kernel(
     const unsigned char* __restrict__ src0, const unsigned char* __restrict__ src1,
     const unsigned char* __restrict__ zero16, unsigned int* flags, unsigned int* ctrl,
     const uint4* __restrict__ wpack, const int* __restrict__ offtab, const void* __restrict__ bias_v, void* y_v,
@@ -96,21 +112,22 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_gather_kernel(
     typedef typename Acc<DT>::type acc_t;
     typedef typename Acc<DT>::vec vec_t;
     typedef typename Acc<DT>::scalar sc_t;
-    constexpr int NS = NT / 4;  // gathered sub-tiles per wavefront
+    constexpr int NP = NT / 8;  // pairs of gathered sub-tiles per wavefront
     constexpr int MAXU = CONV_MAX_STAGE_UNITS;  // staged 16-byte units per thread and slab (host guarantees)
-    static_assert(NT % 4 == 0, "NT must be a multiple of the wavefront count");
+    static_assert(NT % 8 == 0, "NT must be a multiple of two sub-tiles per wavefront");
 
     // LDS: [weights x nbuf][windows (TERMS planes) x nbuf][K-pair table]
     extern __shared__ uint4 smem[];
     unsigned char* lds = reinterpret_cast<unsigned char*>(smem);
     const int nbuf = g.nslab > 1 ? 2 : 1;
-    const int a_bytes = NCB * g.nq * 1024;
+    const int nq2 = 2 * g.nq;  // MFMA steps (two K pairs each) per slab; a K step is two of them
+    const int a_bytes = NCB * nq2 * 1024;
     const int plane_bytes = NT * g.slot_bytes;  // one term's windows
     const int b_bytes = TERMS * plane_bytes;
     unsigned char* bbase = lds + nbuf * a_bytes;
     int2* tab = reinterpret_cast<int2*>(bbase + nbuf * b_bytes);
     __shared__ int s_sub[NT];   // gathered sub-tile ids
-    __shared__ int s_pix[NT];   // first input position of the sub-tile's image: b*h*w
+    __shared__ unsigned int s_base[NT];  // source byte offset of the window origin (wraps when the origin is in the padding)
     __shared__ int s_iy0[NT];   // window origin in the input map (may be negative: padding)
     __shared__ int s_ix0[NT];
     __shared__ int s_ypos[NT];  // output position index of the sub-tile's corner: (b*ho + 4sy)*wo + 4sx
@@ -124,17 +141,17 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_gather_kernel(
     const int ncbg = (g.ncb + NCB - 1) / NCB;  // channel-block groups per filter group
     const int grp = blockIdx.y / ncbg;
     const int cbg = blockIdx.y - grp * ncbg;
-    // packed weights: [group][channel block (padded to ncbg*NCB)][K step][lane]; a slab is K steps
-    // slab*nq .. slab*nq + nq - 1 of each of this workgroup's NCB blocks
-    const int kall = g.nslab * g.nq;
+    // packed weights: [group][32-channel block (padded to ncbg*NCB)][MFMA step][lane]; a slab is MFMA steps
+    // slab*nq2 .. slab*nq2 + nq2 - 1 of each of this workgroup's NCB blocks
+    const int kall = g.nslab * nq2;
     const uint4* wbase = wpack + ((size_t)(grp * ncbg + cbg) * NCB) * kall * 64 + lane;
     auto stage_weights = [&](int slab) {
         unsigned char* dst = lds + (slab & (nbuf - 1)) * a_bytes;
 #pragma unroll
         for (int c = 0; c < NCB; ++c) {
-            const uint4* src = wbase + (size_t)(c * kall + slab * g.nq) * 64;
-            for (int q = wave; q < g.nq; q += 4)
-                __builtin_amdgcn_global_load_lds((gptr_t)(src + (size_t)q * 64), (lptr_t)(dst + (c * g.nq + q) * 1024), 16,
+            const uint4* src = wbase + (size_t)(c * kall + slab * nq2) * 64;
+            for (int q = wave; q < nq2; q += 4)
+                __builtin_amdgcn_global_load_lds((gptr_t)(src + (size_t)q * 64), (lptr_t)(dst + (c * nq2 + q) * 1024), 16,
                                                  0, 0);
         }
     };
@@ -148,6 +165,9 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_gather_kernel(
     // contiguous runs of vectors, one run per thread, loaded in one go and kept in registers.
     constexpr int FW = 8;  // words per thread held in registers (more are re-read: > 8192 sub-tiles)
     constexpr unsigned int LOW = 0x01010101u;
+    const int2* utab = reinterpret_cast<const int2*>(offtab) + g.nq * 4;
+    for (int e = tid; e < g.nq * 4; e += CONV_THREADS)  // K-pair table, the same for every slab
+        tab[e] = reinterpret_cast<const int2*>(offtab)[e];
     const int wpt = (g.n_words + CONV_THREADS - 1) / CONV_THREADS;
     const int w_lo = tid * wpt;
     unsigned int fw[FW];
@@ -213,19 +233,18 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_gather_kernel(
         retire();
         return;
     }
-    for (int e = tid; e < g.nq * 4; e += CONV_THREADS)  // K-pair table, the same for every slab
-        tab[e] = reinterpret_cast<const int2*>(offtab)[e];
     // a single slab of weights serves every unit of the workgroup
     const bool w_resident = g.nslab == 1;
     if (w_resident && !g.early_weights) stage_weights(0);
 
-    const int j = lane & 15, kgrp = lane >> 4;
+    // lane roles: position j of sub-tile `half` of a pair (MFMA column l%32), K pair `khalf` of an MFMA step;
+    // of the result it holds channels 8*g + 4*khalf + (0..3), g = 0..3, of each 32-channel block
+    const int j = lane & 15, half = (lane >> 4) & 1, khalf = lane >> 5;
     // lane-constant window position of its output position (tap 0,0)
     const int off_lane = (((j >> 2) * g.str_y) * g.ww + (j & 3) * g.str_x) * g.sc * 16;
     const int rot_lane = g.rot_a * (j >> 2) + g.rot_b * (j & 3);  // this position's share of the chunk rotation
     sc_t* y = static_cast<sc_t*>(y_v);
     const sc_t* bias = static_cast<const sc_t*>(bias_v);
-    const bool all_vec = g.vec_store && (cbg * NCB + NCB) * 16 <= g.og;  // every lane's 4 channels exist
 
     for (int unit = (int)blockIdx.x; unit < nunits; unit += (int)gridDim.x) {
     const bool first_unit = unit == (int)blockIdx.x, last_unit = unit + (int)gridDim.x >= nunits;
@@ -233,6 +252,14 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_gather_kernel(
     int mycount = count - first;
     if (mycount > per) mycount = per;
     if (!first_unit) __syncthreads();  // the previous unit is done with the list and the staged windows
+    // this thread's rows of the staging table, and the first weight slab: neither depends on the list
+    int2 ut[MAXU];
+#pragma unroll
+    for (int i = 0; i < MAXU; ++i) {
+        const int v = tid + i * CONV_THREADS;
+        ut[i] = v < NT * g.wpos * g.sc ? utab[v] : int2{0, 0};
+    }
+    if (!w_resident && !(g.early_weights && first_unit)) stage_weights(0);
     if (MODE == MODE_DELTA) {
         // the rank of a set flag is the number of set flags before it; keep ranks first .. first+mycount-1
         if (excl + mine > first && excl < first + mycount) {
@@ -262,9 +289,11 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_gather_kernel(
         const int b = fdiv(id, g.magic_sub);
         const int r = id - b * (g.sty * g.stx);
         const int sy = fdiv(r, g.magic_stx), sx = r - sy * g.stx;
-        s_pix[tid] = b * g.src_h * g.src_w;
-        s_iy0[tid] = 4 * sy * g.str_y - g.pad_y;
-        s_ix0[tid] = 4 * sx * g.str_x - g.pad_x;
+        const int iy0 = 4 * sy * g.str_y - g.pad_y, ix0 = 4 * sx * g.str_x - g.pad_x;
+        s_iy0[tid] = iy0;
+        s_ix0[tid] = ix0;
+        s_base[tid] = (unsigned int)((b * g.src_h + iy0) * g.src_w + ix0) * (unsigned int)g.pos_bytes +
+                      (unsigned int)(grp * g.grp_bytes);
         s_ypos[tid] = (b * g.ho + 4 * sy) * g.wo + 4 * sx;
     }
     __syncthreads();
@@ -276,8 +305,8 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_gather_kernel(
     // (cs - rotation(position)) mod rot_p, so that the MFMA operand reads of a sub-tile's 16 positions fall into
     // different banks.  Consecutive lanes own consecutive units, which is what the LDS-direct gather
     // (per-lane global address, LDS address = wave base + 16*lane) needs.  The decomposition does not
-    // depend on the slab, so each thread works out the source offsets of its units once; a slab only adds
-    // its channel offset.  Units outside the image, or whose chunk does not exist in the last slab, read
+    // depend on the slab or on the sub-tiles, so it comes from a table made at create time; a thread adds
+    // the window origins of its units' sub-tiles once per work unit, and a slab only adds its channel offset.  Units outside the image, or whose chunk does not exist in the last slab, read
     // a 16-byte block of zeros instead.
     const int units = mycount * g.wpos * g.sc;
     const int my_units = units > tid ? (units - tid + CONV_THREADS - 1) / CONV_THREADS : 0;  // this thread's share
@@ -287,18 +316,11 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_gather_kernel(
     for (int i = 0; i < MAXU; ++i) {
         uoff[i] = 0xFFFFFFFFu;
         if (i < my_units) {
-            const int v = tid + i * CONV_THREADS;
-            const int r = fdiv(v, g.magic_sc[0]), cs = v - r * g.sc;
-            const int slot = fdiv(r, g.magic_wsc[0]), hp = r - slot * g.wpos;
-            const int hy = fdiv(hp, g.magic_ww), hx = hp - hy * g.ww;
-            int cc = cs;  // the chunk held by slot cs of this position (see rot_p)
-            if (cs < g.rot_p)
-                cc = (cs - g.rot_a * fdiv(hy, g.magic_sy) - g.rot_b * fdiv(hx, g.magic_sx)) & (g.rot_p - 1);
+            const int2 u = ut[i];
+            const int slot = u.x & 31, hy = (u.x >> 5) & 255, hx = (u.x >> 13) & 255;
             const int iy = s_iy0[slot] + hy, ix = s_ix0[slot] + hx;
-            if (cc >= g.last_sc) ulast |= 1u << i;
-            if (iy >= 0 && iy < g.src_h && ix >= 0 && ix < g.src_w)
-                uoff[i] = (unsigned int)(s_pix[slot] + iy * g.src_w + ix) * (unsigned int)g.pos_bytes +
-                          (unsigned int)(grp * g.grp_bytes + cc * 16);
+            ulast |= (unsigned int)((u.x >> 21) & 1) << i;
+            if (iy >= 0 && iy < g.src_h && ix >= 0 && ix < g.src_w) uoff[i] = s_base[slot] + (unsigned int)u.y;
         }
     }
     const unsigned int slab_src_bytes = (unsigned int)(g.sc * 16);  // source bytes between consecutive slabs
@@ -320,90 +342,125 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_gather_kernel(
         }
     };
 
-    // this wavefront's sub-tile slots are wave, wave + 4, ...: how many of them are in use
-    const int nact = mycount > wave ? (mycount - wave + 3) / 4 : 0;
+    // this wavefront's pairs are slots (2*(wave + 4p), 2*(wave + 4p) + 1): how many pairs are in use
+    const int nact = mycount > 2 * wave ? (mycount - 2 * wave + 7) / 8 : 0;
 
-    // ---- output addresses: lane holds 4 consecutive output channels of one position ----------------------
-    unsigned int ybase[NS];
-    bool pos_ok[NS];
+    // ---- output addresses: per pair, this lane's position of its sub-tile --------------------------------
+    unsigned int ybase[NP];
+    bool pos_ok[NP];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        const int slot = wave + 4 * s;
-        pos_ok[s] = false;
-        ybase[s] = 0;
+    for (int p = 0; p < NP; ++p) {
+        const int slot = 2 * (wave + 4 * p) + half;
+        pos_ok[p] = false;
+        ybase[p] = 0;
         if (slot < mycount) {
             const int yp = s_ypos[slot];               // (b*ho + 4sy)*wo + 4sx
             const int py = j >> 2, px = j & 3;
             const int row = fdiv(yp, g.magic_wo);      // b*ho + 4sy
             const int col = yp - row * g.wo + px;      // 4sx + px
             const int rin = row - fdiv(row, g.magic_ho) * g.ho + py;  // 4sy + py
-            pos_ok[s] = col < g.wo && rin < g.ho;
-            ybase[s] = (unsigned int)(yp + py * g.wo + px) * (unsigned int)g.c_out + (unsigned int)(grp * g.og);
+            pos_ok[p] = col < g.wo && rin < g.ho;
+            ybase[p] = (unsigned int)(yp + py * g.wo + px) * (unsigned int)g.c_out + (unsigned int)(grp * g.og);
         }
     }
+    // channel (within the filter group) of register 4*gq of block c; the 4 registers are 4 consecutive channels
+    auto chan = [&](int c, int gq) { return (cbg * NCB + c) * 32 + 8 * gq + 4 * khalf; };
     // The accumulators start from what the result is added to -- the stored projection (delta: Algorithm 1,
     // P_t = P_{t-1} + F * dI) or the bias (dense: Eq. 3) -- so these loads overlap the staging of the first
-    // slab and the epilogue is a plain store.  (Ragged channel counts start from zero and add at the end.)
-    acc_t acc[NCB][NS];
+    // slab and the epilogue is a plain store.  (Channel counts that are not multiples of 4 start from zero
+    // and add element by element at the end.)
+    acc_t acc[NCB][NP];
 #pragma unroll
-    for (int c = 0; c < NCB; ++c) {
-        vec_t bv = vec_t{0, 0, 0, 0};
-        if (MODE == MODE_DENSE && all_vec && bias)
-            bv = *reinterpret_cast<const vec_t*>(bias + grp * g.og + (cbg * NCB + c) * 16 + 4 * kgrp);
+    for (int c = 0; c < NCB; ++c)
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            vec_t v = bv;
-            if (MODE == MODE_DELTA && all_vec && pos_ok[s])
-                v = *reinterpret_cast<const vec_t*>(y + (ybase[s] + (unsigned int)((cbg * NCB + c) * 16 + 4 * kgrp)));
-            acc[c][s] = acc_t{v.x, v.y, v.z, v.w};
+        for (int gq = 0; gq < 4; ++gq) {
+            const int co = chan(c, gq);
+            const bool ch_ok = g.vec_store && co < g.og;
+            vec_t bv = vec_t{0, 0, 0, 0};
+            if (MODE == MODE_DENSE && ch_ok && bias) bv = *reinterpret_cast<const vec_t*>(bias + grp * g.og + co);
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                vec_t v = bv;
+                if (MODE == MODE_DELTA && ch_ok && pos_ok[p]) v = *reinterpret_cast<const vec_t*>(y + (ybase[p] + (unsigned int)co));
+                acc[c][p][4 * gq + 0] = v.x;
+                acc[c][p][4 * gq + 1] = v.y;
+                acc[c][p][4 * gq + 2] = v.z;
+                acc[c][p][4 * gq + 3] = v.w;
+            }
         }
-    }
 
-    // ---- K loop of one slab, compiled per number of sub-tiles in use by the wavefront (no per-sub-tile
-    //      branches; unused slots read stale LDS and their results are dropped) --------------------------
-    auto k_loop = [&]<int NSA>(const unsigned char* aw, const unsigned char* bw) {
+    // ---- K loop of one slab, compiled per number of sub-tile pairs in use by the wavefront (no per-pair
+    //      branches; unused slots read stale LDS and their results are dropped).  A K step is four K pairs,
+    //      i.e. two MFMA steps.  Software pipeline: while K step q multiplies, the operands of step q+1 are
+    //      read from LDS into a second register set (the sets swap roles every step, nothing is copied) and
+    //      the table entries of step q+2 are fetched, so that no address waits for a table read.  The reads
+    //      are issued one by one between the MFMAs: a wavefront that issues them in a batch leaves the
+    //      matrix pipeline idle meanwhile. ----------------------------------------------------------------
+    auto k_loop = [&]<int NPA>(const unsigned char* aw, const unsigned char* bw) {
         const unsigned char* ap = aw + lane * 16;
-        const unsigned char* bp = bw + wave * g.slot_bytes;
-        const int sstride = 4 * g.slot_bytes;
-        const int2* tp = tab + kgrp;
-        uint4 a[NCB], b0[NSA], b1[TERMS == 2 ? NSA : 1];
-        auto fetch = [&](int q, uint4(&a_)[NCB], uint4(&b0_)[NSA], uint4(&b1_)[TERMS == 2 ? NSA : 1]) {
-            const int2 t = tp[4 * q];  // tap's byte offset; rotated chunk | mask << 8
-            const int off = off_lane + t.x + ((((t.y & 0xFF) + rot_lane) & (t.y >> 8)) << 4);
+        const unsigned char* bp = bw + (2 * wave + half) * g.slot_bytes;
+        const int pstride = 8 * g.slot_bytes;
+        const int2* tp = tab + khalf;
+        constexpr int NB1 = TERMS == 2 ? NPA : 1;
+        struct Ops {
+            uint4 a[2][NCB], b0[2][NPA], b1[2][NB1];
+        };
+        constexpr int N_MFMA = 2 * NCB * NPA * TERMS;
+        constexpr int N_READ = 2 * (NCB + NPA * TERMS);
+        auto load_tab = [&](int q, int2(&t)[2]) {
+            t[0] = tp[4 * q];  // tap's byte offset; rotated chunk | mask << 8
+            t[1] = tp[4 * q + 2];
+        };
+        auto fetch = [&](int q, const int2(&t)[2], Ops& o) {
 #pragma unroll
-            for (int c = 0; c < NCB; ++c) a_[c] = *reinterpret_cast<const uint4*>(ap + (c * g.nq + q) * 1024);
+            for (int h = 0; h < 2; ++h) {
+                const int off = off_lane + t[h].x + ((((t[h].y & 0xFF) + rot_lane) & (t[h].y >> 8)) << 4);
 #pragma unroll
-            for (int s = 0; s < NSA; ++s) {
-                b0_[s] = *reinterpret_cast<const uint4*>(bp + off + s * sstride);
-                if (TERMS == 2) b1_[s] = *reinterpret_cast<const uint4*>(bp + plane_bytes + off + s * sstride);
+                for (int c = 0; c < NCB; ++c) o.a[h][c] = *reinterpret_cast<const uint4*>(ap + (c * nq2 + 2 * q + h) * 1024);
+#pragma unroll
+                for (int p = 0; p < NPA; ++p) {
+                    o.b0[h][p] = *reinterpret_cast<const uint4*>(bp + off + p * pstride);
+                    if (TERMS == 2) o.b1[h][p] = *reinterpret_cast<const uint4*>(bp + plane_bytes + off + p * pstride);
+                }
             }
         };
-        // software pipeline: the operands of K step q+1 are read from LDS while step q multiplies
-        fetch(0, a, b0, b1);
-        for (int q = 0; q < g.nq; ++q) {
-            uint4 an[NCB], b0n[NSA], b1n[TERMS == 2 ? NSA : 1];
-            fetch(min(q + 1, g.nq - 1), an, b0n, b1n);
-            __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the multiplies (the scheduler would sink them)
+        auto multiply = [&](const Ops& o) {
 #pragma unroll
-            for (int c = 0; c < NCB; ++c)
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int s = 0; s < NSA; ++s) {
-                    acc[c][s] = mma(a[c], b0[s], acc[c][s]);
-                    if (TERMS == 2) acc[c][s] = mma(a[c], b1[s], acc[c][s]);
-                }
+                for (int c = 0; c < NCB; ++c)
 #pragma unroll
-            for (int c = 0; c < NCB; ++c) a[c] = an[c];
-#pragma unroll
-            for (int s = 0; s < NSA; ++s) {
-                b0[s] = b0n[s];
-                if (TERMS == 2) b1[s] = b1n[s];
-            }
+                    for (int p = 0; p < NPA; ++p) {
+                        acc[c][p] = mma(o.a[h][c], o.b0[h][p], acc[c][p]);
+                        if (TERMS == 2) acc[c][p] = mma(o.a[h][c], o.b1[h][p], acc[c][p]);
+                    }
+        };
+        // one K step: multiply `cur`, read step q1 into `nxt`, fetch the table entries of step q2
+        auto step = [&](const Ops& cur, Ops& nxt, int2(&t)[2], int q1, int q2) {
+            int2 tn[2];
+            load_tab(q2, tn);
+            fetch(q1, t, nxt);
+            multiply(cur);
+            t[0] = tn[0];
+            t[1] = tn[1];
+            // issue order: the table reads, then MFMAs with the operand reads spread between them
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            sched_interleave<0, N_MFMA, N_READ>();
+        };
+        Ops o0, o1;
+        int2 t[2];
+        const int qmax = g.nq - 1;
+        load_tab(0, t);
+        fetch(0, t, o0);
+        load_tab(min(1, qmax), t);
+        for (int q = 0; q < g.nq; q += 2) {
+            step(o0, o1, t, min(q + 1, qmax), min(q + 2, qmax));
+            if (q + 1 < g.nq) step(o1, o0, t, min(q + 2, qmax), min(q + 3, qmax));
         }
     };
 
     RRM_STAMP(2);
     if (last_unit) arrive();
-    if (!w_resident && !(g.early_weights && first_unit)) stage_weights(0);
     stage_windows(0);
     RRM_STAMP(3);
     for (int slab = 0; slab < g.nslab; ++slab) {
@@ -419,10 +476,8 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_gather_kernel(
         if (slab < 2) RRM_STAMP(7 + 5 * slab);
         const unsigned char* aw = lds + (slab & (nbuf - 1)) * a_bytes;
         const unsigned char* bw = bbase + (slab & (nbuf - 1)) * b_bytes;
-        if (nact > 2) {
-            if constexpr (NS >= 4) k_loop.template operator()<4>(aw, bw);
-        } else if (nact > 1) {
-            if constexpr (NS >= 2) k_loop.template operator()<2>(aw, bw);
+        if (nact > 1) {
+            if constexpr (NP >= 2) k_loop.template operator()<2>(aw, bw);
         } else if (nact > 0) {
             k_loop.template operator()<1>(aw, bw);
         }
@@ -431,36 +486,45 @@ __global__ __launch_bounds__(CONV_THREADS, 2) void conv_gather_kernel(
     RRM_STAMP(14);
 
     // ---- epilogue ----------------------------------------------------------------------------------------
-    if (all_vec) {
+    if (g.vec_store) {
 #pragma unroll
         for (int c = 0; c < NCB; ++c)
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                if (!pos_ok[s]) continue;
-                const acc_t r = acc[c][s];
-                vec_t o;
-                o.x = r[0]; o.y = r[1]; o.z = r[2]; o.w = r[3];
-                *reinterpret_cast<vec_t*>(y + (ybase[s] + (unsigned int)((cbg * NCB + c) * 16 + 4 * kgrp))) = o;
+            for (int gq = 0; gq < 4; ++gq) {
+                const int co = chan(c, gq);
+                if (co >= g.og) continue;
+#pragma unroll
+                for (int p = 0; p < NP; ++p) {
+                    if (!pos_ok[p]) continue;
+                    vec_t o;
+                    o.x = acc[c][p][4 * gq + 0];
+                    o.y = acc[c][p][4 * gq + 1];
+                    o.z = acc[c][p][4 * gq + 2];
+                    o.w = acc[c][p][4 * gq + 3];
+                    *reinterpret_cast<vec_t*>(y + (ybase[p] + (unsigned int)co)) = o;
+                }
             }
     } else {
-        // ragged channel counts: element by element
+        // channel counts that are not multiples of 4: element by element
 #pragma unroll
-        for (int c = 0; c < NCB; ++c) {
-            const int co0 = (cbg * NCB + c) * 16 + 4 * kgrp;  // within the filter group
+        for (int c = 0; c < NCB; ++c)
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                if (!pos_ok[s] || co0 >= g.og) continue;
-                sc_t* yp4 = y + (ybase[s] + (unsigned int)co0);
-                const acc_t r = acc[c][s];
-                for (int k = 0; k < 4 && co0 + k < g.og; ++k) {
-                    if (MODE == MODE_DELTA) {
-                        if (r[k] != (sc_t)0) yp4[k] += r[k];
-                    } else {
-                        yp4[k] = r[k] + (bias ? bias[grp * g.og + co0 + k] : (sc_t)0);
+            for (int gq = 0; gq < 4; ++gq) {
+                const int co0 = chan(c, gq);
+#pragma unroll
+                for (int p = 0; p < NP; ++p) {
+                    if (!pos_ok[p] || co0 >= g.og) continue;
+                    sc_t* yp4 = y + (ybase[p] + (unsigned int)co0);
+                    for (int k = 0; k < 4 && co0 + k < g.og; ++k) {
+                        const sc_t r = acc[c][p][4 * gq + k];
+                        if (MODE == MODE_DELTA) {
+                            if (r != (sc_t)0) yp4[k] += r;
+                        } else {
+                            yp4[k] = r + (bias ? bias[grp * g.og + co0 + k] : (sc_t)0);
+                        }
                     }
                 }
             }
-        }
     }
     }  // units
     retire();
@@ -475,7 +539,7 @@ hipError_t launch_one(const void* src0, const void* src1, const void* zero16, un
     const size_t lds = conv_lds_bytes(g, NCB, NT, TERMS);
     // no more workgroups than are resident at once (the kernel loops over its work units)
     const int gy = g.groups * ncbg;
-    const int resident = NUM_CU * (lds * 2 <= 160 * 1024 ? 2 : 1);
+    const int resident = NUM_CU * ((lds * 2 <= 160 * 1024 && NCB * NT < 32) ? 2 : 1);  // (the largest shape uses > 256 registers)
     const int gx = std::min((g.n_sub + NT - 1) / NT, std::max(1, resident / gy));
     dim3 grid((unsigned int)gx, (unsigned int)gy);
     auto kern = conv_gather_kernel<DT, MODE, NCB, NT, TERMS>;
@@ -501,7 +565,7 @@ hipError_t launch_shape(int ncb, int nt, const void* src0, const void* src1, con
 #define RRM_CASE(CBV, NTV)                                                                                          \
     if (ncb == CBV && nt == NTV)                                                                                     \
         return launch_one<DT, MODE, CBV, NTV, TERMS>(src0, src1, zero16, flags, ctrl, wpack, offtab, bias, y, g, stats, s);
-    RRM_CASE(4, 4) RRM_CASE(4, 8) RRM_CASE(4, 16) RRM_CASE(1, 4) RRM_CASE(1, 8) RRM_CASE(1, 16)
+    RRM_CASE(2, 16) RRM_CASE(2, 8) RRM_CASE(1, 16) RRM_CASE(1, 8)
 #undef RRM_CASE
     return hipErrorInvalidValue;
 }
@@ -509,7 +573,7 @@ hipError_t launch_shape(int ncb, int nt, const void* src0, const void* src1, con
 }  // namespace
 
 size_t conv_lds_bytes(const ConvGeom& g, int ncb, int nt, int terms) {
-    return (size_t)(g.nslab > 1 ? 2 : 1) * ((size_t)ncb * g.nq * 1024 + (size_t)terms * nt * g.slot_bytes) +
+    return (size_t)(g.nslab > 1 ? 2 : 1) * ((size_t)ncb * 2 * g.nq * 1024 + (size_t)terms * nt * g.slot_bytes) +
            (size_t)g.nq * 4 * sizeof(int2);
 }
 

@@ -54,7 +54,7 @@ struct rrm_layer {
     FcGeom fg{};
     // device memory
     void* wpack = nullptr;   // conv: MFMA fragment order; FC: W^T; binary: scalar-load order
-    int* offtab = nullptr;   // conv: LDS offsets of the K pairs, per slab
+    int* offtab = nullptr;   // conv: K-pair table of a slab, then the staging table of a workgroup
     void* bias = nullptr;
     void* x_snap = nullptr;
     void* y_snap = nullptr;
@@ -180,15 +180,33 @@ rrm_status pack_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
             tab[2 * e + 1] = 0;
         }
     }
+    // Staging table, appended: what staged unit v = (slot*wpos + hp)*sc + cs of a workgroup holds, two
+    // words per unit:
+    //   [0] slot | window row << 5 | window column << 13 | (chunk missing in the last slab) << 21
+    //   [1] source byte offset relative to the window origin at slab 0: (row*src_w + column)*pos_bytes + chunk*16
+    const int n_units = g.nt * g.wpos * g.sc;
+    tab.resize(tab.size() + (size_t)n_units * 2, 0);
+    int* ut = tab.data() + (size_t)g.nq * 4 * 2;
+    for (int v = 0; v < n_units; ++v) {
+        const int r = v / g.sc, cs = v % g.sc;
+        const int slot = r / g.wpos, hp = r % g.wpos;
+        const int hy = hp / g.ww, hx = hp % g.ww;
+        int cc = cs;  // the chunk held by slot cs of this position (see rot_p)
+        if (cs < g.rot_p) cc = (cs - g.rot_a * (hy / g.str_y) - g.rot_b * (hx / g.str_x)) & (g.rot_p - 1);
+        ut[2 * v] = slot | (hy << 5) | (hx << 13) | ((cc >= g.last_sc ? 1 : 0) << 21);
+        ut[2 * v + 1] = (hy * g.src_w + hx) * g.pos_bytes + cc * 16;
+    }
     rrm_status st = upload(tab.data(), tab.size() * sizeof(int), (void**)&L->offtab);
     if (st != RRM_OK) return st;
 
-    // Weights in per-lane MFMA operand order: [group][16-channel block][K step][lane] x 16 bytes, with
-    // lane l -> output channel 16*block + l%16, K pair 4*step + l/16.  The block dimension is padded to
-    // a multiple of the workgroup's block count; padded blocks, channels and pairs are zero.
+    // Weights in per-lane MFMA operand order: [group][32-channel block][MFMA step][lane] x 16 bytes, with
+    // lane l -> output channel 32*block + l%32, K pair 2*step + l/32 (two MFMA steps per K step).  The block
+    // dimension is padded to a multiple of the workgroup's block count; padded blocks, channels and pairs
+    // are zero.
     const int NCB = g.wg_cb;
     const int ncb_p = (g.ncb + NCB - 1) / NCB * NCB;
-    const int kall = g.nslab * g.nq;
+    const int nq2 = 2 * g.nq;
+    const int kall = g.nslab * nq2;
     const size_t nfrag = (size_t)s.groups * ncb_p * kall;
     std::vector<unsigned char> pack(nfrag * 64 * 16, 0);
     const int es = L->esize;
@@ -196,15 +214,15 @@ rrm_status pack_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     for (int grp = 0; grp < s.groups; ++grp)
         for (int cb = 0; cb < g.ncb; ++cb)
             for (int slab = 0; slab < g.nslab; ++slab)
-                for (int q = 0; q < g.nq; ++q)
+                for (int q = 0; q < nq2; ++q)
                     for (int lane = 0; lane < 64; ++lane) {
-                        const int co = cb * 16 + (lane & 15);
-                        const int e = 4 * q + (lane >> 4);
+                        const int co = cb * 32 + (lane & 31);
+                        const int e = 2 * q + (lane >> 5);
                         if (co >= g.og || e >= ntaps * g.sc) continue;
                         const int chunk = slab * g.sc + e / ntaps, tap = e % ntaps;
                         if (chunk >= g.chunks) continue;
                         const int ky = tap / g.kw_eff, ku = tap % g.kw_eff;
-                        const size_t frag = ((size_t)(grp * ncb_p + cb) * kall + (size_t)slab * g.nq + q);
+                        const size_t frag = ((size_t)(grp * ncb_p + cb) * kall + (size_t)slab * nq2 + q);
                         unsigned char* dst = pack.data() + (frag * 64 + lane) * 16;
                         const size_t wrow = (size_t)(grp * g.og + co) * real_taps;
                         for (int k = 0; k < g.per_vec; ++k) {
@@ -337,7 +355,7 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     g.wh = 3 * g.str_y + s.kh;
     g.ww = 3 * g.str_x + g.kw_eff;
     g.wpos = g.wh * g.ww;
-    g.ncb = (g.og + 15) / 16;
+    g.ncb = (g.og + 31) / 32;  // 32-channel MFMA blocks per group
     g.magic_ww = magic_for(g.ww);
     g.magic_sub = magic_for(g.sty * g.stx);
     g.magic_stx = magic_for(g.stx);
@@ -347,16 +365,16 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     const int ntaps = s.kh * g.kw_eff;
     const int terms = L->dtype == RRM_BF16_F32 ? 2 : 1;
     // Workgroup shape.  Few sub-tiles in total (one stream of a small map): latency matters, so one
-    // channel block and up to 4 sub-tiles per workgroup, the whole K range in as few slabs as fit.
-    // Many sub-tiles (many streams): operand reuse matters, so 4 channel blocks x 16 sub-tiles.
+    // 32-channel block and up to 8 sub-tiles per workgroup, the whole K range in as few slabs as fit.
+    // Many sub-tiles (many streams): operand reuse matters, so 2 channel blocks x 16 sub-tiles.
     struct Cand { int cb, nt; };
     std::vector<Cand> cands;
-    const bool small = (long long)g.n_sub * g.ncb * s.groups <= 2048;
+    const bool small = (long long)g.n_sub * g.ncb * s.groups <= 1024;
     if (small || g.ncb < 2) {
-        cands = {{1, 4}, {1, 8}, {1, 16}};
-        if (!small) cands = {{1, 16}, {1, 8}, {1, 4}};
+        cands = {{1, 8}, {1, 16}};
+        if (!small) cands = {{1, 16}, {1, 8}};
     } else {
-        cands = {{4, 16}, {4, 8}, {4, 4}, {1, 16}, {1, 8}, {1, 4}};
+        cands = {{2, 16}, {2, 8}, {1, 16}, {1, 8}};
     }
     g.early_weights = small ? 1 : 0;
     bool ok = false;

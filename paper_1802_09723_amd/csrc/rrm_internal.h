@@ -8,7 +8,7 @@
 
 namespace rrm {
 
-constexpr int TILE = 8;          // output tile side (positions); 4 MFMA sub-tiles of 4x4
+constexpr int TILE = 8;          // output tile side of the binary kernel (positions)
 constexpr int WAVE = 64;
 constexpr int CONV_THREADS = 256;
 constexpr int NUM_CU = 256;       // compute units of the MI355X
@@ -79,9 +79,9 @@ struct ConvGeom {
     int rot_p, rot_a, rot_b;
     unsigned int magic_sy, magic_sx;  // reciprocals of str_y, str_x
     int last_sc;         // chunks present in the last slab
-    int nq;              // MFMA K steps per slab: ceil(kh*kw*sc / 4)
-    int ncb;             // 16-wide output-channel blocks per group
-    int wg_cb, nt;       // workgroup shape: 16-channel blocks (1 or 4) and gathered sub-tiles (4, 8, 16)
+    int nq;              // K steps (4 K pairs = 2 MFMAs deep) per slab: ceil(kh*kw*sc / 4)
+    int ncb;             // 32-wide output-channel blocks per group
+    int wg_cb, nt;       // workgroup shape: 32-channel blocks (1 or 2) and gathered sub-tiles (8, 16)
     unsigned int magic_sc[2];   // reciprocals (floor(2^32/d)+1, 0 for d = 1): [0] d = sc
     unsigned int magic_wsc[2];  // [0] d = wpos
     unsigned int magic_wo, magic_ho;  // d = wo, d = ho
