@@ -371,19 +371,19 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     std::vector<Cand> cands;
     const bool small = (long long)g.n_sub * g.ncb * s.groups <= 1024;
     if (small || g.ncb < 2) {
-        cands = {{1, 8}, {1, 16}};
-        if (!small) cands = {{1, 16}, {1, 8}};
+        cands = {{1, 8}, {1, 16}, {1, 4}};
+        if (!small) cands = {{1, 16}, {1, 8}, {1, 4}};
     } else {
-        cands = {{2, 16}, {2, 8}, {1, 16}, {1, 8}};
+        cands = {{2, 16}, {2, 8}, {1, 16}, {1, 8}, {1, 4}};
     }
-    g.early_weights = small ? 1 : 0;
     bool ok = false;
-    long long first_budget = (small ? 96ll : 156ll) * 1024;
+    // (the kernel's static LDS, about 5 KB, comes on top of the dynamic budget; 160 KB per workgroup in all)
+    long long first_budget = (small ? 96ll : 154ll) * 1024;
     if (const char* env = std::getenv("RRM_CONV_LDS_KB")) {  // tuning knob: preferred LDS bytes per workgroup
         const long long kb = std::atoll(env);
-        if (kb >= 16 && kb <= 156) first_budget = kb * 1024;
+        if (kb >= 16 && kb <= 154) first_budget = kb * 1024;
     }
-    for (long long budget : {first_budget, 156ll * 1024}) {
+    for (long long budget : {first_budget, 154ll * 1024}) {
         for (const Cand& c : cands) {
             ConvGeom t = g;
             // a slab should hold at least 4 chunks (or all of them) to amortise its barriers
@@ -397,7 +397,7 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     }
     if (!ok)
         for (const Cand& c : cands)
-            if (!ok) ok = conv_try_shape(g, terms, c.cb, c.nt, ntaps, 156 * 1024);
+            if (!ok) ok = conv_try_shape(g, terms, c.cb, c.nt, ntaps, 154 * 1024);
     if (!ok) return fail(RRM_ERR_SHAPE, "input window of one output sub-tile does not fit LDS");
     return pack_conv(L, w);
 }

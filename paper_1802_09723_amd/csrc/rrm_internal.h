@@ -88,7 +88,6 @@ struct ConvGeom {
     unsigned int magic_ww;      // d = ww
     unsigned int magic_sub;     // d = sty*stx
     unsigned int magic_stx;     // d = stx
-    int early_weights;   // 1: small grid, start the first weight slab's copy before the flag scan
     int vec_store;       // 1: y rows allow 16-byte read-modify-write
 };
 
