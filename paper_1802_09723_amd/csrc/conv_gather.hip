@@ -143,7 +143,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     __shared__ unsigned int s_base[4][NT];   // per producer wavefront: source byte offset of the window origin
     __shared__ int s_iy0[4][NT];             //   (wraps when the origin is in the padding) and the origin itself
     __shared__ int s_ix0[4][NT];
-    __shared__ int s_ypos[2][NT];  // output position index of the sub-tile's corner, by unit parity
     __shared__ int s_scan[CONV_THREADS / WAVE];
     __shared__ int s_last;
 
@@ -178,22 +177,38 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         tab[e] = reinterpret_cast<const int2*>(offtab)[e];
 
     // ---- how many sub-tiles are active? -------------------------------------------------------------
-    // The flag array (one byte per sub-tile, four per word) is split into contiguous runs of words, one run
-    // per producer thread, loaded in one go and kept in registers.
-    constexpr int FW = 8;  // words per thread held in registers (more are re-read: > 8192 sub-tiles)
+    // The flag array (one byte per sub-tile) is split into contiguous runs of 16-byte vectors, one run per
+    // producer thread, loaded in one go and kept in registers.
+    constexpr int FV = 8;  // 16-byte vectors (16 flags) per thread held in registers (more are re-read: > 32768 sub-tiles)
     constexpr unsigned int LOW = 0x01010101u;
-    const int wpt = (g.n_words + CONV_THREADS - 1) / CONV_THREADS;
-    const int w_lo = tid * wpt;
-    unsigned int fw[FW];
+    const uint4* fvp = reinterpret_cast<const uint4*>(flags);  // (the array is padded with zeros to whole vectors)
+    const int n_vec = (g.n_words + 3) >> 2;
+    const int vpt = (n_vec + CONV_THREADS - 1) / CONV_THREADS;
+    const int v_lo = tid * vpt;
+    uint4 fv[FV];
+    auto popc4 = [&](const uint4& v) {
+        return __popc(v.x & LOW) + __popc(v.y & LOW) + __popc(v.z & LOW) + __popc(v.w & LOW);
+    };
+    // vectors FV .. vpt-1 of this thread, four loads in flight at a time
+    auto for_more_vectors = [&](auto&& f) {
+        for (int i = FV; i < vpt; i += 4) {
+            uint4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[u] = (i + u < vpt && v_lo + i + u < n_vec) ? fvp[v_lo + i + u] : uint4{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) f(v[u], v_lo + i + u);
+        }
+    };
     int count, excl = 0, mine = 0;
     if (MODE == MODE_DELTA) {
         if (producer) {
 #pragma unroll
-            for (int i = 0; i < FW; ++i) fw[i] = (i < wpt && w_lo + i < g.n_words) ? flags[w_lo + i] & LOW : 0u;
+            for (int i = 0; i < FV; ++i)
+                fv[i] = (i < vpt && v_lo + i < n_vec) ? fvp[v_lo + i] : uint4{0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int i = 0; i < FW; ++i) mine += __popc(fw[i]);
-            for (int i = FW; i < wpt; ++i)
-                if (w_lo + i < g.n_words) mine += __popc(flags[w_lo + i] & LOW);
+            for (int i = 0; i < FV; ++i) mine += popc4(fv[i]);
+            for_more_vectors([&](const uint4& v, int) { mine += popc4(v); });
             // popcount prefix sum (every workgroup does the same small scan)
             int incl = mine;
 #pragma unroll
@@ -297,10 +312,15 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
                     }
                 }
             };
+            auto take4 = [&](const uint4& v, int vidx) {
+                take(v.x, 4 * vidx);
+                take(v.y, 4 * vidx + 1);
+                take(v.z, 4 * vidx + 2);
+                take(v.w, 4 * vidx + 3);
+            };
 #pragma unroll
-            for (int q = 0; q < FW; ++q) take(fw[q], w_lo + q);
-            for (int q = FW; q < wpt; ++q)
-                if (w_lo + q < g.n_words) take(flags[w_lo + q], w_lo + q);
+            for (int q = 0; q < FV; ++q) take4(fv[q], v_lo + q);
+            for_more_vectors(take4);
         }
         __syncthreads();  // the list is published
     } else if (r0 == 0) {
@@ -313,7 +333,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     const int first = unit * per;
     int mycount = count - first;
     if (mycount > per) mycount = per;
-    const int par = iu & 1;
     if (iu == 0) RRM_STAMP(1);
     {
         // ---- window origins of the unit's sub-tiles (each producer wavefront keeps its own copy: no barrier) --
@@ -333,7 +352,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             s_ix0[wave][lane] = ix0;
             s_base[wave][lane] = (unsigned int)((b * g.src_h + iy0) * g.src_w + ix0) * (unsigned int)g.pos_bytes +
                                  (unsigned int)(grp * g.grp_bytes);
-            if (wave == 0) s_ypos[par][lane] = (b * g.ho + 4 * sy) * g.wo + 4 * sx;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // LDS operations of one wavefront execute in order
         __builtin_amdgcn_wave_barrier();
@@ -407,6 +425,53 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     }  // units of the round
     }  // rounds
     } else {
+    // Consumer state of a unit: output addresses (per pair, this lane's position of its sub-tile) and the
+    // accumulators.  The accumulators start from what the result is added to -- the stored projection (delta:
+    // Algorithm 1, P_t = P_{t-1} + F * dI) or the bias (dense: Eq. 3) -- so the epilogue is a plain store.
+    // They are fetched as soon as the previous unit's results are stored (the sub-tile ids come from the
+    // ranked list, not from the producers), long before the unit's first slab is staged.  (Channel counts
+    // that are not multiples of 4 start from zero and add element by element at the end.)
+    unsigned int ybase[NP];
+    bool pos_ok[NP];
+    acc_t acc[NCB][NP];
+    auto begin_unit = [&](int iu2, int r0) {
+        const int first2 = ((int)blockIdx.x + iu2 * gx) * per;
+        const int mycount2 = min(per, count - first2);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int slot = 2 * (cw + 4 * p) + half;
+            pos_ok[p] = false;
+            ybase[p] = 0;
+            if (slot < mycount2) {
+                const int id = MODE == MODE_DELTA ? s_list[(iu2 - r0) * per + slot] : first2 + slot;
+                const int b = fdiv(id, g.magic_sub);
+                const int r = id - b * (g.sty * g.stx);
+                const int sy = fdiv(r, g.magic_stx), sx = r - sy * g.stx;
+                const int oy = 4 * sy + (j >> 2), ox = 4 * sx + (j & 3);
+                pos_ok[p] = ox < g.wo && oy < g.ho;
+                ybase[p] = (unsigned int)((b * g.ho + oy) * g.wo + ox) * (unsigned int)g.c_out + (unsigned int)(grp * g.og);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < NCB; ++c)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int co = chan(c, gq);
+                const bool ch_ok = g.vec_store && co < g.og;
+                vec_t bv = vec_t{0, 0, 0, 0};
+                if (MODE == MODE_DENSE && ch_ok && bias) bv = *reinterpret_cast<const vec_t*>(bias + grp * g.og + co);
+#pragma unroll
+                for (int p = 0; p < NP; ++p) {
+                    vec_t v = bv;
+                    if (MODE == MODE_DELTA && ch_ok && pos_ok[p])
+                        v = *reinterpret_cast<const vec_t*>(y + (ybase[p] + (unsigned int)co));
+                    acc[c][p][4 * gq + 0] = v.x;
+                    acc[c][p][4 * gq + 1] = v.y;
+                    acc[c][p][4 * gq + 2] = v.z;
+                    acc[c][p][4 * gq + 3] = v.w;
+                }
+            }
+    };
     for (int r0 = 0; r0 < my_nunits; r0 += ur) {
     const int r1 = min(r0 + ur, my_nunits);
     // the barriers of the ranking round
@@ -416,17 +481,14 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     } else if (r0 == 0) {
         __syncthreads();
     }
+    begin_unit(r0, r0);
     for (int iu = r0; iu < r1; ++iu) {
     const int unit = (int)blockIdx.x + iu * gx;
     const int first = unit * per;
     int mycount = count - first;
     if (mycount > per) mycount = per;
-    const int par = iu & 1;
     if (iu == 0) RRM_STAMP(41);
     const int nact = mycount > 2 * cw ? (mycount - 2 * cw + 7) / 8 : 0;  // pairs in use (slots 2*(cw+4p), +1)
-    unsigned int ybase[NP];
-    bool pos_ok[NP];
-    acc_t acc[NCB][NP];
     {
         // ---- consumers ---------------------------------------------------------------------------------
         // K loop of one slab, compiled per number of sub-tile pairs in use by the wavefront (no per-pair
@@ -504,49 +566,8 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
 
         for (int k = 0; k < g.nslab; ++k) {
             if (iu < 2 && k < 6) RRM_STAMP(42 + 18 * iu + 3 * k);
-            __syncthreads();  // slab k is staged (and, for k = 0, the unit's output positions are published)
+            __syncthreads();  // slab k is staged
             if (iu < 2 && k < 6) RRM_STAMP(43 + 18 * iu + 3 * k);
-            if (k == 0) {
-                // output addresses: per pair, this lane's position of its sub-tile
-#pragma unroll
-                for (int p = 0; p < NP; ++p) {
-                    const int slot = 2 * (cw + 4 * p) + half;
-                    pos_ok[p] = false;
-                    ybase[p] = 0;
-                    if (slot < mycount) {
-                        const int yp = s_ypos[par][slot];          // (b*ho + 4sy)*wo + 4sx
-                        const int py = j >> 2, px = j & 3;
-                        const int row = fdiv(yp, g.magic_wo);      // b*ho + 4sy
-                        const int col = yp - row * g.wo + px;      // 4sx + px
-                        const int rin = row - fdiv(row, g.magic_ho) * g.ho + py;  // 4sy + py
-                        pos_ok[p] = col < g.wo && rin < g.ho;
-                        ybase[p] = (unsigned int)(yp + py * g.wo + px) * (unsigned int)g.c_out + (unsigned int)(grp * g.og);
-                    }
-                }
-                // The accumulators start from what the result is added to -- the stored projection (delta:
-                // Algorithm 1, P_t = P_{t-1} + F * dI) or the bias (dense: Eq. 3) -- so the epilogue is a plain
-                // store.  (Channel counts that are not multiples of 4 start from zero and add element by
-                // element at the end.)
-#pragma unroll
-                for (int c = 0; c < NCB; ++c)
-#pragma unroll
-                    for (int gq = 0; gq < 4; ++gq) {
-                        const int co = chan(c, gq);
-                        const bool ch_ok = g.vec_store && co < g.og;
-                        vec_t bv = vec_t{0, 0, 0, 0};
-                        if (MODE == MODE_DENSE && ch_ok && bias) bv = *reinterpret_cast<const vec_t*>(bias + grp * g.og + co);
-#pragma unroll
-                        for (int p = 0; p < NP; ++p) {
-                            vec_t v = bv;
-                            if (MODE == MODE_DELTA && ch_ok && pos_ok[p])
-                                v = *reinterpret_cast<const vec_t*>(y + (ybase[p] + (unsigned int)co));
-                            acc[c][p][4 * gq + 0] = v.x;
-                            acc[c][p][4 * gq + 1] = v.y;
-                            acc[c][p][4 * gq + 2] = v.z;
-                            acc[c][p][4 * gq + 3] = v.w;
-                        }
-                    }
-            }
             const unsigned char* aw = lds + (nbuf_a == 2 ? (gs & 1) : 0) * a_bytes;
             const unsigned char* bw = bbase + (gs & 1) * b_bytes;
             ++gs;
@@ -603,6 +624,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
                     }
                 }
         }
+        if (iu + 1 < r1) begin_unit(iu + 1, r0);  // (a new round's first unit waits for its ranking)
     }
     if (iu < 2) RRM_STAMP(60 + 18 * iu);
     }  // units of the round
