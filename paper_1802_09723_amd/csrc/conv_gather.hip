@@ -566,7 +566,10 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
 
         for (int k = 0; k < g.nslab; ++k) {
             if (iu < 2 && k < 6) RRM_STAMP(42 + 18 * iu + 3 * k);
-            __syncthreads();  // slab k is staged
+            // slab k is staged.  A bare barrier: the producers waited for their copies before they arrived,
+            // and this wavefront's own stores and loads of stored projections (previous / this unit) need not
+            // have completed -- __syncthreads() would wait for all of them.
+            asm volatile("s_barrier" ::: "memory");
             if (iu < 2 && k < 6) RRM_STAMP(43 + 18 * iu + 3 * k);
             const unsigned char* aw = lds + (nbuf_a == 2 ? (gs & 1) : 0) * a_bytes;
             const unsigned char* bw = bbase + (gs & 1) * b_bytes;
