@@ -125,7 +125,8 @@ class Stack:
         for i, L in enumerate(self.layers):
             L.step(x)
             n, ho, wo, c, pool = self.meta[i]
-            rrm.relu_requant_pool_i8(self.ysnap[i], self.bufs[i], n, ho, wo, c, self.shifts[i], pool)
+            # f only where the step changed the projection (bufs[i] holds the previous frame's result)
+            L.relu_requant_pool_changed(self.bufs[i], self.shifts[i], pool)
             x = self.bufs[i]
 
     def capture(self):
@@ -478,7 +479,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=320)
     ap.add_argument("--warmup", type=int, default=32)
-    ap.add_argument("--streams", type=int, default=int(os.environ.get("RRM_BENCH_STREAMS", "32")))
+    ap.add_argument("--streams", type=int, default=int(os.environ.get("RRM_BENCH_STREAMS", "128")))
     ap.add_argument("--no-graph", action="store_true", help="issue every launch from Python instead of replaying a HIP graph")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--sweep", action="store_true")

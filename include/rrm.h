@@ -153,6 +153,16 @@ const char* rrm_last_error(void);
 rrm_status rrm_aux_relu_requant_pool_i8(const void* y, void* out, int n, int h, int w, int c, int shift,
                                         int pool, void* hip_stream);
 
+/* The same map applied to the stored projection of an int8 convolution layer (c_out a multiple of 4),
+ * recomputing only the outputs whose window touches a 4x4 block of output positions that the layer's last
+ * rrm_step wrote (Algorithm 1 applies f to all of P; where P did not change, f(P) did not either).  `out`
+ * ([n][ho'][wo'][c_out] int8, 4-byte aligned, device, caller-owned) must hold the result of the previous call
+ * for this layer: entries that are not recomputed keep it.  Call it once after every rrm_step, on the same
+ * stream; after rrm_layer_create, rrm_reset or a dense step everything is recomputed.
+ * Errors: RRM_ERR_NULL, RRM_ERR_SHAPE (not an int8 conv layer, c_out % 4 != 0, bad shift / pool),
+ * RRM_ERR_ALIGN, RRM_ERR_HIP. */
+rrm_status rrm_aux_relu_requant_pool_changed_i8(rrm_layer* layer, void* out, int shift, int pool, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -79,8 +79,10 @@ def lib():
         L.rrm_status_string.restype = ctypes.c_char_p
         L.rrm_last_error.restype = ctypes.c_char_p
         L.rrm_aux_relu_requant_pool_i8.argtypes = [P, P, I, I, I, I, I, I, P]
+        L.rrm_aux_relu_requant_pool_changed_i8.argtypes = [P, P, I, I, P]
         for f in ("rrm_layer_create", "rrm_step", "rrm_dense", "rrm_reset", "rrm_snapshot", "rrm_read_snapshot", "rrm_set_option",
-                  "rrm_get_stats", "rrm_get_kernel_times", "rrm_aux_relu_requant_pool_i8"):
+                  "rrm_get_stats", "rrm_get_kernel_times", "rrm_aux_relu_requant_pool_i8",
+                  "rrm_aux_relu_requant_pool_changed_i8"):
             getattr(L, f).restype = I
         _lib = L
     return _lib
@@ -149,6 +151,12 @@ class Layer:
 
     def reset(self, stream=None) -> None:
         _check(lib().rrm_reset(self._h, _stream_ptr(stream)))
+
+    def relu_requant_pool_changed(self, out, shift, pool, stream=None) -> None:
+        """Harness nonlinearity on the stored projection, recomputing only what the last step changed
+        (``rrm_aux_relu_requant_pool_changed_i8``); ``out`` must hold the previous call's result."""
+        _check(lib().rrm_aux_relu_requant_pool_changed_i8(self._h, _dptr(out), int(shift), int(bool(pool)),
+                                                           _stream_ptr(stream)))
 
     def snapshot_ptrs(self):
         xs, ys = ctypes.c_void_p(), ctypes.c_void_p()

@@ -249,7 +249,10 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         if (tid == 0) s_last = (arrived_before == gridDim.x * gridDim.y - 1u) ? 1 : 0;
         __syncthreads();
         if (s_last) {
-            for (int w = tid; w < g.n_words; w += WG_THREADS) flags[w] = 0u;
+            for (int w = tid; w < g.n_words; w += WG_THREADS) {
+                if (g.touched) g.touched[w] = flags[w];  // what this step wrote in y, for an incremental nonlinearity
+                flags[w] = 0u;
+            }
             if (tid == 0) {
                 ctrl[0] = 0u;
                 if (count) atomicAdd(&stats[0].active_tiles, (unsigned long long)count);

@@ -63,6 +63,8 @@ struct rrm_layer {
     void* xpad = nullptr;    // dense path of layers whose channel runs are not 16-byte multiples: repacked x
     unsigned long long* bitmap = nullptr;
     unsigned int* tileflag = nullptr;  // binary: 8x8 tile stamps; int8 / bf16: 4x4 sub-tile byte flags
+    unsigned int* touched = nullptr;   // int8 / bf16 conv: the sub-tile flags of the last step (what it wrote in y_snap)
+    bool touched_all = true;           // host view: `touched` is all ones (set by create / reset / dense steps)
     size_t marks_bytes = 0;
     unsigned int* ctrl = nullptr;      // arrival counter of the gather kernel
     void* zero16 = nullptr;            // a block of zeros: source of staged units outside the image
@@ -83,7 +85,7 @@ struct rrm_layer {
     int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0;
 
     ~rrm_layer() {
-        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, ctrl, zero16, fc_idx, fc_val, fc_count, fc_part, stats};
+        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, zero16, fc_idx, fc_val, fc_count, fc_part, stats};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
         for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
@@ -571,6 +573,10 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
         sg.tiles_y = (int)((ho + TILE - 1) / TILE);
         sg.tiles_x = (int)((wo + TILE - 1) / TILE);
         sg.per_vec = 16 / L->esize;
+        sg.r_c = 1.0 / (double)sg.c;
+        sg.r_hw = 1.0 / ((double)s.h * (double)s.w);
+        sg.r_w = 1.0 / (double)s.w;
+        sg.magic_stride = magic_for(s.stride);
         const size_t nvec = round16(L->x_bytes) / 16;
         // difference buffer: x's own layout, or the padded / folded layout of the gather kernel
         L->d_bytes = L->x_bytes;
@@ -593,6 +599,12 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
         L->marks_bytes = dtype == RRM_BIN_I32 ? (size_t)s.n * sg.tiles_y * sg.tiles_x * 4
                                               : (size_t)((s.n * sg.sty * sg.stx + 3) / 4) * 4;
         if ((st = dalloc(L->marks_bytes, (void**)&L->tileflag)) != RRM_OK) return bail(st);
+        if (dtype != RRM_BIN_I32) {
+            // everything counts as written until the first step has run (y_snap = bias everywhere)
+            if ((st = dalloc(L->marks_bytes, (void**)&L->touched)) != RRM_OK) return bail(st);
+            if (hipMemset(L->touched, 1, round16(L->marks_bytes)) != hipSuccess) return bail(fail(RRM_ERR_HIP, "hipMemset failed"));
+            L->cg.touched = L->touched;
+        }
         if ((st = dalloc(16, (void**)&L->ctrl)) != RRM_OK) return bail(st);
         if ((st = dalloc(256, &L->zero16)) != RRM_OK) return bail(st);
     }
@@ -620,6 +632,10 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
         RRM_HIP(launch_copy(L->x_snap, x_t, L->x_bytes, s));
         if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
         if ((st = enqueue_dense(L, x_t, L->y_snap, s)) != RRM_OK) return st;
+        if (L->touched && !L->touched_all) {  // a full recomputation writes every sub-tile
+            RRM_HIP(launch_fill_word(L->touched, round16(L->marks_bytes), 0x01010101u, s));
+            L->touched_all = true;
+        }
         if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
     } else if (L->shape.kind == RRM_FC) {
         if ((st = prof_mark(L, 0, s)) != RRM_OK) return st;
@@ -645,6 +661,7 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
             RRM_HIP(launch_conv(L->dtype, MODE_DELTA, L->cg.wg_cb, L->cg.nt, L->dtype == RRM_BF16_F32 ? L->opt_terms : 1,
                                 L->d0, L->d1, L->zero16, L->tileflag, L->ctrl, L->wpack, L->offtab, nullptr, L->y_snap, L->cg,
                                 L->stats, s));
+            L->touched_all = false;  // the kernel's last workgroup copies the step's flags there
         }
         if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
         ++L->delta_steps;
@@ -678,8 +695,10 @@ rrm_status rrm_reset(rrm_layer* L, void* hip_stream) {
         RRM_HIP(launch_fill_zero(L->bitmap, round16(((round16(L->x_bytes) / 16 + 63) / 64) * 8), s));
         RRM_HIP(launch_fill_zero(L->tileflag, round16(L->marks_bytes), s));
         RRM_HIP(launch_fill_zero(L->ctrl, 16, s));
+        if (L->touched) RRM_HIP(launch_fill_word(L->touched, round16(L->marks_bytes), 0x01010101u, s));
     }
     L->has_snapshot = false;
+    L->touched_all = true;
     L->steps = L->delta_steps = L->total_tiles = 0;
     return RRM_OK;
 }
@@ -803,7 +822,20 @@ rrm_status rrm_aux_relu_requant_pool_i8(const void* y, void* out, int n, int h, 
     if (!y || !out) return fail(RRM_ERR_NULL, "y / out is NULL");
     if (n < 1 || h < 1 || w < 1 || c < 1 || shift < 0 || shift > 31 || (pool && (h < 3 || w < 3)))
         return fail(RRM_ERR_SHAPE, "bad shape for relu_requant_pool");
-    RRM_HIP(launch_relu_requant_pool(y, out, n, h, w, c, shift, pool, static_cast<hipStream_t>(hip_stream)));
+    RRM_HIP(launch_relu_requant_pool(y, out, nullptr, n, h, w, c, shift, pool, static_cast<hipStream_t>(hip_stream)));
+    return RRM_OK;
+}
+
+rrm_status rrm_aux_relu_requant_pool_changed_i8(rrm_layer* L, void* out, int shift, int pool, void* hip_stream) {
+    if (!L || !out) return fail(RRM_ERR_NULL, "layer / out is NULL");
+    const rrm_shape& s = L->shape;
+    if (s.kind != RRM_CONV || L->dtype != RRM_I8_I32 || !L->touched || s.c_out % 4 != 0)
+        return fail(RRM_ERR_SHAPE, "the incremental nonlinearity needs an int8 conv layer with c_out % 4 == 0");
+    const int ho = L->cg.ho, wo = L->cg.wo;
+    if (shift < 0 || shift > 31 || (pool && (ho < 3 || wo < 3))) return fail(RRM_ERR_SHAPE, "bad shape for relu_requant_pool");
+    if (reinterpret_cast<uintptr_t>(out) & 3) return fail(RRM_ERR_ALIGN, "out must be 4-byte aligned");
+    RRM_HIP(launch_relu_requant_pool(L->y_snap, out, L->touched, s.n, ho, wo, s.c_out, shift, pool,
+                                     static_cast<hipStream_t>(hip_stream)));
     return RRM_OK;
 }
 

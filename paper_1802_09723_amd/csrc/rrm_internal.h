@@ -42,6 +42,10 @@ struct ScanGeom {
     // ((r*wp + ix)*groups + c / cg)*cp + c % cg, i.e. rows padded to wp columns and every group's
     // channels padded to cp, so that the gather kernel only ever sees whole 16-byte chunks.
     int scatter, wp, cp, cg, groups;
+    // reciprocals for the scan's index arithmetic: doubles for dividends up to 2^30 (see udiv_big), a
+    // 32-bit one for the small dividends of the receptive-field bounds (floor(2^32/stride)+1, 0 for 1)
+    double r_c, r_hw, r_w;
+    unsigned int magic_stride;
 };
 
 constexpr int CONV_MAX_STAGE_UNITS = 12;  // 16-byte units a thread stages per slab (half for 2 terms)
@@ -89,6 +93,7 @@ struct ConvGeom {
     unsigned int magic_sub;     // d = sty*stx
     unsigned int magic_stx;     // d = stx
     int vec_store;       // 1: y rows allow 16-byte read-modify-write
+    unsigned int* touched;  // copy of the sub-tile flags of the last delta step (what it wrote in y), or nullptr
 };
 
 // Geometry of the binary (XNOR / popcount) convolution.
@@ -145,7 +150,9 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 // x (caller layout) -> the padded / folded source layout described by g (pad elements are left untouched)
 hipError_t launch_repack(int esize, const void* x, void* dst, const ScanGeom& g, hipStream_t s);
-hipError_t launch_relu_requant_pool(const void* y, void* out, int n, int h, int w, int c, int shift, int pool,
-                                    hipStream_t s);
+hipError_t launch_fill_word(void* p, size_t bytes, unsigned int word, hipStream_t s);
+// touched: nullptr = every output; else byte flags per 4x4 sub-tile of y, only outputs under a set flag
+hipError_t launch_relu_requant_pool(const void* y, void* out, const void* touched, int n, int h, int w, int c, int shift,
+                                    int pool, hipStream_t s);
 
 }  // namespace rrm

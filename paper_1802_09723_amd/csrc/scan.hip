@@ -32,6 +32,16 @@ __device__ __forceinline__ unsigned int f32_to_bf16(float f) {
     return u >> 16;
 }
 
+// floor(u / d) for u < 2^31 through the reciprocal rd = 1.0 / d: (u + 0.5) / d is at least 0.5 / d away
+// from an integer, far more than the rounding error of the product, so the truncation is exact.
+__device__ __forceinline__ unsigned int udiv_big(unsigned int u, double rd) {
+    return (unsigned int)(((double)u + 0.5) * rd);
+}
+// floor(u / d) for u * d < 2^32 through magic = floor(2^32 / d) + 1 (0 encodes d == 1)
+__device__ __forceinline__ int udiv_small(int u, unsigned int magic) {
+    return magic ? (int)__umulhi((unsigned int)u, magic) : u;
+}
+
 __device__ __forceinline__ uint4 load_x_guarded(const unsigned char* x, long long off, long long total_bytes) {
     if (off + 16 <= total_bytes) return *reinterpret_cast<const uint4*>(x + off);
     unsigned int w[4] = {0u, 0u, 0u, 0u};
@@ -43,13 +53,13 @@ __device__ __forceinline__ uint4 load_x_guarded(const unsigned char* x, long lon
 __device__ __forceinline__ void mark_tiles(const ScanGeom& g, int pos, unsigned int* tileflag,
                                            unsigned int stamp) {
     const int hw = g.h * g.w;
-    const int b = pos / hw;
+    const int b = (int)udiv_big((unsigned int)pos, g.r_hw);
     const int r = pos - b * hw;
-    const int iy = r / g.w, ix = r - iy * g.w;
+    const int iy = (int)udiv_big((unsigned int)r, g.r_w), ix = r - iy * g.w;
     const int ty0 = iy + g.pad - (g.kh - 1), tx0 = ix + g.pad - (g.kw - 1);
-    const int oy_lo = ty0 <= 0 ? 0 : (ty0 + g.stride - 1) / g.stride;
-    const int ox_lo = tx0 <= 0 ? 0 : (tx0 + g.stride - 1) / g.stride;
-    int oy_hi = (iy + g.pad) / g.stride, ox_hi = (ix + g.pad) / g.stride;
+    const int oy_lo = ty0 <= 0 ? 0 : udiv_small(ty0 + g.stride - 1, g.magic_stride);
+    const int ox_lo = tx0 <= 0 ? 0 : udiv_small(tx0 + g.stride - 1, g.magic_stride);
+    int oy_hi = udiv_small(iy + g.pad, g.magic_stride), ox_hi = udiv_small(ix + g.pad, g.magic_stride);
     if (oy_hi > g.ho - 1) oy_hi = g.ho - 1;
     if (ox_hi > g.wo - 1) ox_hi = g.wo - 1;
     if (oy_lo > oy_hi || ox_lo > ox_hi) return;
@@ -62,13 +72,13 @@ __device__ __forceinline__ void mark_tiles(const ScanGeom& g, int pos, unsigned 
 // (every writer stores the same value, so no atomics and no same-address serialisation).
 __device__ __forceinline__ void mark_subtiles(const ScanGeom& g, unsigned int pos, unsigned char* flags) {
     const unsigned int hw = (unsigned int)(g.h * g.w);
-    const int b = (int)(pos / hw);
+    const int b = (int)udiv_big(pos, g.r_hw);
     const int r = (int)(pos - (unsigned int)b * hw);
-    const int iy = r / g.w, ix = r - iy * g.w;
+    const int iy = (int)udiv_big((unsigned int)r, g.r_w), ix = r - iy * g.w;
     const int ty0 = iy + g.pad - (g.kh - 1), tx0 = ix + g.pad - (g.kw - 1);
-    const int oy_lo = ty0 <= 0 ? 0 : (ty0 + g.stride - 1) / g.stride;
-    const int ox_lo = tx0 <= 0 ? 0 : (tx0 + g.stride - 1) / g.stride;
-    int oy_hi = (iy + g.pad) / g.stride, ox_hi = (ix + g.pad) / g.stride;
+    const int oy_lo = ty0 <= 0 ? 0 : udiv_small(ty0 + g.stride - 1, g.magic_stride);
+    const int ox_lo = tx0 <= 0 ? 0 : udiv_small(tx0 + g.stride - 1, g.magic_stride);
+    int oy_hi = udiv_small(iy + g.pad, g.magic_stride), ox_hi = udiv_small(ix + g.pad, g.magic_stride);
     if (oy_hi > g.ho - 1) oy_hi = g.ho - 1;
     if (ox_hi > g.wo - 1) ox_hi = g.wo - 1;
     if (oy_lo > oy_hi || ox_lo > ox_hi) return;
@@ -95,9 +105,9 @@ __device__ __forceinline__ void scatter_unit(const ScanGeom& g, long long v, uin
     constexpr int PV = DT == RRM_I8_I32 ? 16 : 8;
     const unsigned int e0 = (unsigned int)v * PV;
     const unsigned int total = (unsigned int)g.total_elems;
-    const unsigned int p = e0 / (unsigned int)g.c;
+    const unsigned int p = udiv_big(e0, g.r_c);
     int c = (int)(e0 - p * (unsigned int)g.c);
-    const unsigned int r0 = p / (unsigned int)g.w;
+    const unsigned int r0 = udiv_big(p, g.r_w);
     int ix = (int)(p - r0 * (unsigned int)g.w);
     unsigned int rowbase = r0 * (unsigned int)g.wp;
 #pragma unroll
@@ -211,8 +221,8 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
             const unsigned int e0 = (unsigned int)v * g.per_vec;
             unsigned int e1 = e0 + g.per_vec - 1;
             if (e1 > (unsigned int)g.total_elems - 1) e1 = (unsigned int)g.total_elems - 1;
-            p0 = (int)(e0 / (unsigned int)g.c);
-            p1 = (int)(e1 / (unsigned int)g.c);
+            p0 = (int)udiv_big(e0, g.r_c);
+            p1 = (int)udiv_big(e1, g.r_c);
         } else if ((prev_mask >> (threadIdx.x & 63)) & 1ull) {
             // changed last step, unchanged now: restore the zero of the difference buffer
             if (!SCATTER) {

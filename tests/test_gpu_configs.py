@@ -17,6 +17,7 @@ def _alexnet_parity(n, T, groups45=1):
     cfg = S.config1(n=n, T=T, groups45=groups45)
     layers = [rrm.Layer(l["shape"], S.I8, l["weights"], l["bias"]) for l in cfg["layers"]]
     shifts = None
+    inc = []  # outputs of the incremental nonlinearity, one per layer, kept across frames
     for t, frame in enumerate(cfg["frames"]):
         # CPU side
         xs_cpu, ys_cpu = [frame], []
@@ -39,6 +40,11 @@ def _alexnet_parity(n, T, groups45=1):
             _, ys = L.snapshot_ptrs()
             rrm.relu_requant_pool_i8(ys, nxt, sh.n, ho, wo, sh.c_out, shifts[i], l["pool"])
             assert np.array_equal(nxt.cpu().numpy(), xs_cpu[i + 1]), f"frame {t} {l['name']}: nonlinearity differs"
+            # the incremental form, fed with its own previous output, must give the same tensor
+            if t == 0:
+                inc.append(torch.full_like(nxt, -1))
+            L.relu_requant_pool_changed(inc[i], shifts[i], l["pool"])
+            assert np.array_equal(inc[i].cpu().numpy(), xs_cpu[i + 1]), f"frame {t} {l['name']}: incremental nonlinearity differs"
             x = nxt
     stats = [L.stats() for L in layers]
     for L in layers:
