@@ -13,7 +13,8 @@ JSON line; everything else goes to stderr.
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--streams S] [--sweep]
 
 --sweep additionally times every layer of configs 2-4 (ResNet bf16, FC sparse-delta, binary) over
-their density grids and writes gpurun_out/sweep.jsonl plus a table on stderr.
+their density grids, at one stream (the configs' batch 1: launch-latency bound) and at --sweep-streams
+streams (throughput), and writes gpurun_out/sweep.jsonl plus a table on stderr.
 """
 from __future__ import annotations
 
@@ -407,61 +408,73 @@ def run_sweep(args):
     def dev_bin(f):
         return torch.from_numpy(S.pack_pm1(f).view(np.int32)).cuda()
 
-    # config 2: ResNet-18-shaped bf16 3x3 convs
-    for layer, hw, c in S.RESNET_LAYERS:
-        for frac in S.RESNET_DENSITIES:
-            seq = S.config2(layer, frac)
-            r = time_layer(seq, dev_bf16, seq.weights)
-            sh, stt = seq.shape, r["stats"]
-            scan_b, tile_b = conv_alg_bytes(sh, 2, stt["changed_units"], stt["active_tiles"], terms=2)
-            rho_elem = stt["changed_elems"] / (hw * hw * c)
-            ops = 2 * rho_elem * macs(sh)
-            kt = r["delta_scan_us"] + r["delta_compute_us"]
-            roof = max((scan_b + tile_b) / HBM_PEAK, ops / MFMA_PEAK[1]) * 1e6
-            rows.append({"config": 2, "case": seq.name, "rho_elem": rho_elem, "rho_tile": stt["active_tiles"] / max(stt["total_tiles"], 1),
-                         "step_us": r["delta_us"], "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"],
-                         "compute_us": r["delta_compute_us"], "dense_kernel_us": r["dense_compute_us"],
-                         "frames_per_s": 1e6 / r["delta_us"], "dense_equiv_gops": 2 * macs(sh) / r["delta_us"] * 1e-3,
-                         "speedup_vs_dense": r["dense_us"] / r["delta_us"], "alg_bytes": scan_b + tile_b, "roof_us": roof,
-                         "roof_bound": "hbm" if (scan_b + tile_b) / HBM_PEAK >= ops / MFMA_PEAK[1] else "mfma",
-                         "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]})
-            log("[sweep]", json.dumps(rows[-1]))
-    # config 3: FC sparse-delta mat-vec
-    for layer, ci, co in S.FC_LAYERS:
-        for dt, es in ((S.I8, 1), (S.BF16, 2)):
-            for frac in S.FC_DENSITIES:
-                seq = S.config3(layer, dt, frac)
-                r = time_layer(seq, dev_i8 if dt == S.I8 else dev_bf16, seq.weights)
-                nnz = r["stats"]["changed_elems"]
-                byts = nnz * co * es + 2 * ci * es + 2 * co * 4
+    for ns in sorted({1, max(1, args.sweep_streams)}):
+        # many streams: shorter sequences keep the synthetic data small; one stream: the configs' lengths
+        Tc, Tf, Tb = (16, 64, 32) if ns == 1 else (6, 8, 6)
+        sfx = "" if ns == 1 else f"_s{ns}"
+        # config 2: ResNet-18-shaped bf16 3x3 convs
+        for layer, hw, c in S.RESNET_LAYERS:
+            for frac in S.RESNET_DENSITIES:
+                seq = S.config2(layer, frac, n=ns, T=Tc)
+                r = time_layer(seq, dev_bf16, seq.weights)
+                sh, stt = seq.shape, r["stats"]
+                scan_b, tile_b = conv_alg_bytes(sh, 2, stt["changed_units"], stt["active_tiles"], terms=2)
+                rho_elem = stt["changed_elems"] / (ns * hw * hw * c)
+                ops = 2 * rho_elem * macs(sh)
                 kt = r["delta_scan_us"] + r["delta_compute_us"]
-                roof = byts / HBM_PEAK * 1e6
-                rows.append({"config": 3, "case": seq.name, "rho_elem": nnz / ci, "step_us": r["delta_us"],
-                             "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"], "compute_us": r["delta_compute_us"],
-                             "dense_kernel_us": r["dense_compute_us"], "frames_per_s": 1e6 / r["delta_us"],
-                             "dense_equiv_gops": 2 * ci * co / r["delta_us"] * 1e-3, "speedup_vs_dense": r["dense_us"] / r["delta_us"],
-                             "alg_bytes": byts, "roof_us": roof, "roof_bound": "hbm",
-                             "scatter_GBps": nnz * co * es / (r["delta_compute_us"] * 1e-6) / 1e9,
-                             "dense_GBps": ci * co * es / (r["dense_compute_us"] * 1e-6) / 1e9,
+                roof = max((scan_b + tile_b) / HBM_PEAK, ops / MFMA_PEAK[1]) * 1e6
+                rows.append({"config": 2, "case": seq.name + sfx, "streams": ns, "rho_elem": rho_elem,
+                             "rho_tile": stt["active_tiles"] / max(stt["total_tiles"], 1),
+                             "step_us": r["delta_us"], "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"],
+                             "compute_us": r["delta_compute_us"], "dense_kernel_us": r["dense_compute_us"],
+                             "frames_per_s": ns * 1e6 / r["delta_us"], "dense_equiv_gops": 2 * macs(sh) / r["delta_us"] * 1e-3,
+                             "speedup_vs_dense": r["dense_us"] / r["delta_us"], "alg_bytes": scan_b + tile_b, "roof_us": roof,
+                             "roof_bound": "hbm" if (scan_b + tile_b) / HBM_PEAK >= ops / MFMA_PEAK[1] else "mfma",
                              "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]})
                 log("[sweep]", json.dumps(rows[-1]))
-    # config 4: binary conv
-    for layer, hw, c in S.XNOR_LAYERS:
-        for frac in S.XNOR_FLIPS:
-            seq = S.config4(layer, frac)
-            r = time_layer(seq, dev_bin, S.pack_pm1(seq.weights))
-            sh, stt = seq.shape, r["stats"]
-            words = stt["changed_units"] * 4  # upper bound on 32-bit words holding a flipped bit
-            lane_instr = 2 * words * c * 9
-            roof = max(lane_instr / VALU_LANE_PEAK, (2 * hw * hw * c / 8 + 2 * stt["active_tiles"] * 64 * c * 4) / HBM_PEAK) * 1e6
-            kt = r["delta_scan_us"] + r["delta_compute_us"]
-            rows.append({"config": 4, "case": seq.name, "rho_elem": stt["changed_elems"] / (hw * hw * c),
-                         "rho_tile": stt["active_tiles"] / max(stt["total_tiles"], 1), "step_us": r["delta_us"],
-                         "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"], "compute_us": r["delta_compute_us"],
-                         "dense_kernel_us": r["dense_compute_us"], "frames_per_s": 1e6 / r["delta_us"],
-                         "dense_equiv_gops": 2 * macs(sh) / r["delta_us"] * 1e-3, "speedup_vs_dense": r["dense_us"] / r["delta_us"],
-                         "roof_us": roof, "roof_bound": "alu", "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]})
-            log("[sweep]", json.dumps(rows[-1]))
+        # config 3: FC sparse-delta mat-vec
+        for layer, ci, co in S.FC_LAYERS:
+            for dt, es in ((S.I8, 1), (S.BF16, 2)):
+                for frac in S.FC_DENSITIES:
+                    seq = S.config3(layer, dt, frac, n=ns, T=Tf)
+                    r = time_layer(seq, dev_i8 if dt == S.I8 else dev_bf16, seq.weights)
+                    nnz = r["stats"]["changed_elems"]  # over all streams
+                    # a column of W is read once however many streams need it
+                    byts = min(nnz, ci) * co * es + ns * (2 * ci * es + 2 * co * 4)
+                    kt = r["delta_scan_us"] + r["delta_compute_us"]
+                    roof = byts / HBM_PEAK * 1e6
+                    rows.append({"config": 3, "case": seq.name + sfx, "streams": ns, "rho_elem": nnz / (ns * ci),
+                                 "step_us": r["delta_us"], "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"],
+                                 "compute_us": r["delta_compute_us"], "dense_kernel_us": r["dense_compute_us"],
+                                 "frames_per_s": ns * 1e6 / r["delta_us"],
+                                 "dense_equiv_gops": 2 * ns * ci * co / r["delta_us"] * 1e-3,
+                                 "speedup_vs_dense": r["dense_us"] / r["delta_us"],
+                                 "alg_bytes": byts, "roof_us": roof, "roof_bound": "hbm",
+                                 "scatter_GBps": nnz * co * es / (r["delta_compute_us"] * 1e-6) / 1e9,
+                                 "dense_GBps": ns * ci * co * es / (r["dense_compute_us"] * 1e-6) / 1e9,
+                                 "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]})
+                    log("[sweep]", json.dumps(rows[-1]))
+        # config 4: binary conv
+        for layer, hw, c in S.XNOR_LAYERS:
+            for frac in S.XNOR_FLIPS:
+                seq = S.config4(layer, frac, n=ns, T=Tb)
+                r = time_layer(seq, dev_bin, S.pack_pm1(seq.weights))
+                sh, stt = seq.shape, r["stats"]
+                words = stt["changed_units"] * 4  # upper bound on 32-bit words holding a flipped bit
+                lane_instr = 2 * words * c * 9
+                roof = max(lane_instr / VALU_LANE_PEAK,
+                           (2 * ns * hw * hw * c / 8 + 2 * stt["active_tiles"] * 64 * c * 4) / HBM_PEAK) * 1e6
+                kt = r["delta_scan_us"] + r["delta_compute_us"]
+                rows.append({"config": 4, "case": seq.name + sfx, "streams": ns,
+                             "rho_elem": stt["changed_elems"] / (ns * hw * hw * c),
+                             "rho_tile": stt["active_tiles"] / max(stt["total_tiles"], 1), "step_us": r["delta_us"],
+                             "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"], "compute_us": r["delta_compute_us"],
+                             "dense_kernel_us": r["dense_compute_us"], "frames_per_s": ns * 1e6 / r["delta_us"],
+                             "dense_equiv_gops": 2 * macs(sh) / r["delta_us"] * 1e-3,
+                             "speedup_vs_dense": r["dense_us"] / r["delta_us"],
+                             "roof_us": roof, "roof_bound": "alu", "roof_frac_kernels": roof / kt,
+                             "roof_frac_wall": roof / r["delta_us"]})
+                log("[sweep]", json.dumps(rows[-1]))
     os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
     with open(os.path.join(ROOT, "gpurun_out", "sweep.jsonl"), "w") as f:
         for r in rows:
@@ -483,6 +496,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="issue every launch from Python instead of replaying a HIP graph")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--sweep-streams", type=int, default=64,
+                    help="--sweep times every layer at 1 stream (the configs' batch) and at this many streams")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (video streams are independent and would shard without any "

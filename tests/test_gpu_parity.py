@@ -139,3 +139,22 @@ def test_determinism_bf16_conv_is_bit_reproducible():
         outs.append(layer.y_snapshot().clone())
         layer.destroy()
     assert torch.equal(outs[0], outs[1])
+
+
+def test_conv_list_longer_than_one_ranking_round():
+    """So many active sub-tiles that a workgroup's share of the ranked list does not fit its LDS list at
+    once (more than 64 work units per workgroup): the gather kernel ranks in several rounds."""
+    n = 80000  # streams of 8x8 maps: 320000 sub-tiles
+    shp = S.conv_shape(8, 8, 16, 16, 3, 1, 1, n=n)
+    rng = S.rng_for(S.seed_for(0, 77))
+    w = S.draw_i8_weight(rng, shp.w_shape)
+    bias = S.draw_i32_bias(rng, shp.c_out)
+    f0 = S.draw_i8_act(rng, shp.x_shape)
+    f1 = f0.copy()
+    redraw = rng.random(n) < 0.9  # most streams change completely: still several rounds
+    f1[redraw] = S.draw_i8_act(rng, (int(redraw.sum()),) + shp.x_shape[1:])
+    f2 = f1.copy()
+    f2[::7, 2:5, 3:6, :] = S.draw_i8_act(rng, f2[::7, 2:5, 3:6, :].shape)  # a sparse step: one round
+    seq = S.Sequence_(shp, S.I8, w, bias, [f0, f1, f2], "many_units")
+    st, _ = run_sequence(seq, check_frames=(0, 1, 2), check_dense=(), check_x=False)
+    assert st["active_tiles"] > 2 * 64 * 16 * 256
