@@ -458,8 +458,8 @@ rrm_status setup_fc(rrm_layer* L, const std::vector<unsigned char>& w) {
     if (st != RRM_OK) return st;
     if ((st = dalloc((size_t)s.n * s.c_in * sizeof(int), (void**)&L->fc_idx)) != RRM_OK) return st;
     if ((st = dalloc((size_t)s.n * s.c_in * 4, &L->fc_val)) != RRM_OK) return st;
-    // enough workgroups to keep memory busy: about 1024 in total, at most 256 splits per stream
-    L->fc_nsplit = std::max(1, std::min(256, 1024 / (g.slices * s.n)));
+    // enough 1024-thread workgroups to keep memory busy: about 256 in total, at most 64 splits per stream
+    L->fc_nsplit = std::max(1, std::min(64, 256 / (g.slices * s.n)));
     if ((st = dalloc((size_t)s.n * L->fc_nsplit * g.c_out_p * 4, &L->fc_part)) != RRM_OK) return st;
     return dalloc((size_t)s.n * sizeof(int), (void**)&L->fc_count);
 }
