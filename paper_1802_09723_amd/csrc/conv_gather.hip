@@ -170,45 +170,59 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         }
     };
     RRM_STAMP(producer ? 0 : 40);
-    // The first weight slab does not depend on the work list: its copy starts at once.
+    // The first weight slab does not depend on the work list: its copy starts at once.  So do the loads
+    // of this thread's rows of the staging table, which serve every unit.
     if (producer) stage_weights(0, 0);
     const int2* utab = reinterpret_cast<const int2*>(offtab) + g.nq * 4;
+    int2 ut[MAXU];
+    if (producer) {
+#pragma unroll
+        for (int i = 0; i < MAXU; ++i) {
+            const int v = tid + i * CONV_THREADS;
+            ut[i] = v < g.nt * g.wpos * g.sc ? utab[v] : int2{0, 0};
+        }
+    }
     for (int e = tid; e < g.nq * 4; e += WG_THREADS)  // K-pair table, the same for every slab
         tab[e] = reinterpret_cast<const int2*>(offtab)[e];
 
     // ---- how many sub-tiles are active? -------------------------------------------------------------
-    // The flag array (one byte per sub-tile) is split into contiguous runs of 16-byte vectors, one run per
-    // producer thread, loaded in one go and kept in registers.
-    constexpr int FV = 8;  // 16-byte vectors (16 flags) per thread held in registers (more are re-read: > 32768 sub-tiles)
+    // The flag array (one byte per sub-tile) is split into contiguous runs of 64-flag groups, one run per
+    // producer thread.  A group is loaded as four 16-byte vectors and squeezed into a 64-bit mask; a thread's
+    // first group stays in registers, further ones (more than 16384 sub-tiles per launch) are re-read.  Up to
+    // 256 sub-tiles (one stream of a small map), a thread takes a single flag instead.
     constexpr unsigned int LOW = 0x01010101u;
-    const uint4* fvp = reinterpret_cast<const uint4*>(flags);  // (the array is padded with zeros to whole vectors)
+    const uint4* fvp = reinterpret_cast<const uint4*>(flags);
     const int n_vec = (g.n_words + 3) >> 2;
-    const int vpt = (n_vec + CONV_THREADS - 1) / CONV_THREADS;
-    const int v_lo = tid * vpt;
-    uint4 fv[FV];
-    auto popc4 = [&](const uint4& v) {
-        return __popc(v.x & LOW) + __popc(v.y & LOW) + __popc(v.z & LOW) + __popc(v.w & LOW);
-    };
-    // vectors FV .. vpt-1 of this thread, four loads in flight at a time
-    auto for_more_vectors = [&](auto&& f) {
-        for (int i = FV; i < vpt; i += 4) {
-            uint4 v[4];
+    const int n_grp = (n_vec + 3) >> 2;
+    const int gpt = (n_grp + CONV_THREADS - 1) / CONV_THREADS;
+    const int g_lo = tid * gpt;
+    auto load_group = [&](int gi) {
+        uint4 v[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                v[u] = (i + u < vpt && v_lo + i + u < n_vec) ? fvp[v_lo + i + u] : uint4{0u, 0u, 0u, 0u};
+        for (int u = 0; u < 4; ++u) v[u] = 4 * gi + u < n_vec ? fvp[4 * gi + u] : uint4{0u, 0u, 0u, 0u};
+        unsigned long long m = 0;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) f(v[u], v_lo + i + u);
+        for (int u = 0; u < 4; ++u) {
+            // byte flags 0/1 of a word -> 4 bits: the product moves byte i's bit to bit 24 + i
+            auto nib = [](unsigned int w) { return ((w & LOW) * 0x01020408u) >> 24; };
+            const unsigned int h = nib(v[u].x) | nib(v[u].y) << 4 | nib(v[u].z) << 8 | nib(v[u].w) << 12;
+            m |= (unsigned long long)h << (16 * u);
         }
+        return m;
     };
+    const bool tiny = g.n_sub <= CONV_THREADS;  // (then gpt == 1)
+    unsigned long long fm0 = 0;
     int count, excl = 0, mine = 0;
     if (MODE == MODE_DELTA) {
         if (producer) {
-#pragma unroll
-            for (int i = 0; i < FV; ++i)
-                fv[i] = (i < vpt && v_lo + i < n_vec) ? fvp[v_lo + i] : uint4{0u, 0u, 0u, 0u};
-#pragma unroll
-            for (int i = 0; i < FV; ++i) mine += popc4(fv[i]);
-            for_more_vectors([&](const uint4& v, int) { mine += popc4(v); });
+            if (tiny)  // one flag per thread: nobody walks more than one bit in the ranking
+                fm0 = tid < g.n_sub ? (unsigned long long)(reinterpret_cast<const unsigned char*>(flags)[tid] & 1u) : 0ull;
+            else if (g_lo < n_grp)
+                fm0 = load_group(g_lo);
+            mine = __popcll(fm0);
+            for (int i = 1; i < gpt; ++i)
+                if (g_lo + i < n_grp) mine += __popcll(load_group(g_lo + i));
+            if (mine >= 0) RRM_STAMP(80);
             // popcount prefix sum (every workgroup does the same small scan)
             int incl = mine;
 #pragma unroll
@@ -221,6 +235,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         }
         __syncthreads();
         count = s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3];
+        if (producer) RRM_STAMP(81);
         if (producer)
             for (int w = 0; w < wave; ++w) excl += s_scan[w];
     } else {
@@ -233,6 +248,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     if (per < 1) per = 1;
     if (per > g.nt) per = g.nt;
     const int nunits = (count + per - 1) / per;
+    if (producer) RRM_STAMP(84);
 
     unsigned int arrived_before = 0;  // thread 0: workgroups that signalled before this one
     // Arrival signal, sent once this workgroup has read the flags for the last time.  Every thread has
@@ -281,6 +297,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     auto chan = [&](int c, int gq) { return (cbg * NCB + c) * 32 + 8 * gq + 4 * khalf; };
     const unsigned int slab_src_bytes = (unsigned int)(g.sc * 16);  // source bytes between consecutive slabs
 
+    if (producer) RRM_STAMP(85);
     int gs = 0;  // stages (slabs) done so far: the window buffer, and the weight buffer if there are two, alternate
 
     // The two roles run the same loops (ranking rounds, units, slabs) and meet at the same barriers, but
@@ -296,16 +313,16 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             // The rank of a set flag is the number of set flags before it; rank = unit*per + k.  The unit,
             // its index i among this workgroup's units ((unit - blockIdx.x) / gx when that divides) and k are
             // stepped along with the rank.
+            if (r0 == 0) RRM_STAMP(86);
             int u = excl / per, k = excl - u * per;
             const int d = u - (int)blockIdx.x;
             int i = d >= 0 ? d / gx : -1 - ((-d - 1) / gx);
             int um = d - i * gx;  // 0 <=> the unit is this workgroup's i-th
-            auto take = [&](unsigned int word, int widx) {
-                unsigned int bits = word & LOW;
-                while (bits) {
-                    const int bpos = __ffs(bits) - 1;
-                    bits &= bits - 1;
-                    if (um == 0 && i >= r0 && i < r1) s_list[(i - r0) * per + k] = widx * 4 + (bpos >> 3);
+            auto take = [&](unsigned long long m, int id0) {  // id0: sub-tile of bit 0
+                while (m) {
+                    const int bpos = __ffsll((long long)m) - 1;
+                    m &= m - 1;
+                    if (um == 0 && i >= r0 && i < r1) s_list[(i - r0) * per + k] = id0 + bpos;
                     if (++k == per) {
                         k = 0;
                         if (++um == gx) {
@@ -315,17 +332,14 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
                     }
                 }
             };
-            auto take4 = [&](const uint4& v, int vidx) {
-                take(v.x, 4 * vidx);
-                take(v.y, 4 * vidx + 1);
-                take(v.z, 4 * vidx + 2);
-                take(v.w, 4 * vidx + 3);
-            };
-#pragma unroll
-            for (int q = 0; q < FV; ++q) take4(fv[q], v_lo + q);
-            for_more_vectors(take4);
+            if (r0 == 0) RRM_STAMP(87);
+            take(fm0, tiny ? tid : g_lo * 64);
+            for (int q = 1; q < gpt; ++q)
+                if (g_lo + q < n_grp) take(load_group(g_lo + q), (g_lo + q) * 64);
         }
+        if (r0 == 0) RRM_STAMP(82);
         __syncthreads();  // the list is published
+        if (r0 == 0) RRM_STAMP(83);
     } else if (r0 == 0) {
         __syncthreads();  // (the K-pair table is published)
     }
@@ -339,12 +353,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     if (iu == 0) RRM_STAMP(1);
     {
         // ---- window origins of the unit's sub-tiles (each producer wavefront keeps its own copy: no barrier) --
-        int2 ut[MAXU];  // this thread's rows of the staging table
-#pragma unroll
-        for (int i = 0; i < MAXU; ++i) {
-            const int v = tid + i * CONV_THREADS;
-            ut[i] = v < g.nt * g.wpos * g.sc ? utab[v] : int2{0, 0};
-        }
         if (lane < mycount) {
             const int id = MODE == MODE_DELTA ? s_list[(iu - r0) * per + lane] : first + lane;
             const int b = fdiv(id, g.magic_sub);
