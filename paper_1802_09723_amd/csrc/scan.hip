@@ -188,15 +188,13 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
 #pragma unroll
                     for (int k = 0; k < 2; ++k) {
                         const unsigned int xa = (aw[i] >> (16 * k)) & 0xFFFFu, xb = (bw[i] >> (16 * k)) & 0xFFFFu;
-                        unsigned int hi = 0, lo = 0;
-                        if (xa != xb) {
-                            ++nelem;
-                            // difference in fp32 (exact unless the operands are > 2^15 apart in
-                            // magnitude), then split into a bf16 head and a bf16 tail
-                            const float d = bf16_to_f32(xa) - bf16_to_f32(xb);
-                            hi = f32_to_bf16(d);
-                            lo = f32_to_bf16(d - bf16_to_f32(hi));
-                        }
+                        nelem += xa != xb ? 1u : 0u;
+                        // difference in fp32 (exact unless the operands are > 2^15 apart in magnitude),
+                        // then split into a bf16 head and a bf16 tail; equal inputs give 0 and 0 (no
+                        // branch: the lanes of a wavefront would diverge on it)
+                        const float d = bf16_to_f32(xa) - bf16_to_f32(xb);
+                        const unsigned int hi = f32_to_bf16(d);
+                        const unsigned int lo = f32_to_bf16(d - bf16_to_f32(hi));
                         hi2 |= hi << (16 * k);
                         lo2 |= lo << (16 * k);
                     }
