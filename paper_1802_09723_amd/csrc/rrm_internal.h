@@ -18,7 +18,7 @@ enum Mode : int { MODE_DELTA = 0, MODE_DENSE = 1 };
 // Device-side counters (totals), updated with atomics by the kernels.  There are STAT_SLOTS copies
 // (a workgroup uses slot blockIdx.x % STAT_SLOTS) so that same-address atomics do not serialise
 // the scan; rrm_get_stats sums them.
-constexpr int STAT_SLOTS = 64;
+constexpr int STAT_SLOTS = 256;
 struct DevStats {
     unsigned long long changed_elems;
     unsigned long long changed_units;

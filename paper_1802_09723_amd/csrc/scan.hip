@@ -239,12 +239,21 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
     }
     const unsigned long long mask = __ballot(changed);
     if ((threadIdx.x & 63) == 0 && v < nvec) bitmap[v >> 6] = mask;
-    if (mask) {
+    // change counts: summed over the wavefront, then over the workgroup, one pair of atomics per workgroup
+    // (atomics on one address serialise: a pair per wavefront was the slowest part of a busy scan)
+    __shared__ unsigned int s_ne[4], s_nu[4];
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) nelem += __shfl_xor(nelem, o);
-        if ((threadIdx.x & 63) == 0) {
-            atomicAdd(&stats->changed_elems, (unsigned long long)nelem);
-            atomicAdd(&stats->changed_units, (unsigned long long)__popcll(mask));
+    for (int o = 32; o > 0; o >>= 1) nelem += __shfl_xor(nelem, o);
+    if ((threadIdx.x & 63) == 0) {
+        s_ne[threadIdx.x >> 6] = nelem;
+        s_nu[threadIdx.x >> 6] = (unsigned int)__popcll(mask);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned int ne = s_ne[0] + s_ne[1] + s_ne[2] + s_ne[3], nu = s_nu[0] + s_nu[1] + s_nu[2] + s_nu[3];
+        if (nu) {
+            atomicAdd(&stats->changed_elems, (unsigned long long)ne);
+            atomicAdd(&stats->changed_units, (unsigned long long)nu);
         }
     }
 }
