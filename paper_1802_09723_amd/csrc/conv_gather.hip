@@ -241,6 +241,15 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     } else {
         count = g.n_sub;
     }
+    // Above a density of active sub-tiles where reading and re-writing the stored projection costs more than
+    // recomputing it, a delta launch recomputes everything instead (Eq. 3): all sub-tiles, the committed
+    // input x_t (the scan has made the snapshot equal to it) as the source, one term, accumulators from the
+    // bias.  The switch is the same in every workgroup (same count).
+    const int n_flagged = count;
+    const bool full = MODE == MODE_DELTA && g.xfull != nullptr && (long long)count * 100 > (long long)g.n_sub * g.full_pct;
+    if (full) count = g.n_sub;
+    const bool listed = MODE == MODE_DELTA && !full;  // sub-tile ids come from the ranked list (else: all, in order)
+    const bool from_y = listed;                        // accumulators start from the stored projection (else: bias)
     // The active sub-tiles are cut into work units of `per` sub-tiles: few sub-tiles are spread thinly (a
     // unit's latency grows with its size), many are packed NT per unit (operand reuse).
     const int gx = (int)gridDim.x;
@@ -266,12 +275,12 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         __syncthreads();
         if (s_last) {
             for (int w = tid; w < g.n_words; w += WG_THREADS) {
-                if (g.touched) g.touched[w] = flags[w];  // what this step wrote in y, for an incremental nonlinearity
+                if (g.touched) g.touched[w] = full ? LOW : flags[w];  // what this step wrote in y, for an incremental nonlinearity
                 flags[w] = 0u;
             }
             if (tid == 0) {
                 ctrl[0] = 0u;
-                if (count) atomicAdd(&stats[0].active_tiles, (unsigned long long)count);
+                if (n_flagged) atomicAdd(&stats[0].active_tiles, (unsigned long long)n_flagged);
             }
         }
     };
@@ -309,7 +318,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     // ---- ranking round: the sub-tile ids of units r0 .. r1-1 of this workgroup go to s_list ------------
     if (MODE == MODE_DELTA) {
         if (r0 > 0) __syncthreads();  // the previous round's list is no longer in use
-        if (mine > 0) {
+        if (mine > 0 && listed) {
             // The rank of a set flag is the number of set flags before it; rank = unit*per + k.  The unit,
             // its index i among this workgroup's units ((unit - blockIdx.x) / gx when that divides) and k are
             // stepped along with the rank.
@@ -354,7 +363,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     {
         // ---- window origins of the unit's sub-tiles (each producer wavefront keeps its own copy: no barrier) --
         if (lane < mycount) {
-            const int id = MODE == MODE_DELTA ? s_list[(iu - r0) * per + lane] : first + lane;
+            const int id = listed ? s_list[(iu - r0) * per + lane] : first + lane;
             const int b = fdiv(id, g.magic_sub);
             const int r = id - b * (g.sty * g.stx);
             const int sy = fdiv(r, g.magic_stx), sx = r - sy * g.stx;
@@ -406,9 +415,9 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
                 const bool real = uoff[i] != 0xFFFFFFFFu && !(last && ((ulast >> i) & 1u));
                 const unsigned int o = uoff[i] + (unsigned int)slab * slab_src_bytes;
                 unsigned char* d = dst + (i * CONV_THREADS + wave * 64) * 16;  // wave-uniform; lane adds 16*lane
-                const unsigned char* p0 = real ? src0 + o : zero16;
+                const unsigned char* p0 = real ? (full ? g.xfull : src0) + o : zero16;
                 __builtin_amdgcn_global_load_lds((gptr_t)p0, (lptr_t)d, 16, 0, 0);
-                if (TERMS == 2) {
+                if (TERMS == 2 && !full) {
                     const unsigned char* p1 = real ? src1 + o : zero16;
                     __builtin_amdgcn_global_load_lds((gptr_t)p1, (lptr_t)(d + plane_bytes), 16, 0, 0);
                 }
@@ -454,7 +463,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             pos_ok[p] = false;
             ybase[p] = 0;
             if (slot < mycount2) {
-                const int id = MODE == MODE_DELTA ? s_list[(iu2 - r0) * per + slot] : first2 + slot;
+                const int id = listed ? s_list[(iu2 - r0) * per + slot] : first2 + slot;
                 const int b = fdiv(id, g.magic_sub);
                 const int r = id - b * (g.sty * g.stx);
                 const int sy = fdiv(r, g.magic_stx), sx = r - sy * g.stx;
@@ -470,11 +479,11 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
                 const int co = chan(c, gq);
                 const bool ch_ok = g.vec_store && co < g.og;
                 vec_t bv = vec_t{0, 0, 0, 0};
-                if (MODE == MODE_DENSE && ch_ok && bias) bv = *reinterpret_cast<const vec_t*>(bias + grp * g.og + co);
+                if (!from_y && ch_ok && bias) bv = *reinterpret_cast<const vec_t*>(bias + grp * g.og + co);
 #pragma unroll
                 for (int p = 0; p < NP; ++p) {
                     vec_t v = bv;
-                    if (MODE == MODE_DELTA && ch_ok && pos_ok[p])
+                    if (from_y && ch_ok && pos_ok[p])
                         v = *reinterpret_cast<const vec_t*>(y + (ybase[p] + (unsigned int)co));
                     acc[c][p][4 * gq + 0] = v.x;
                     acc[c][p][4 * gq + 1] = v.y;
@@ -509,19 +518,19 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         // the table entries of step q+2 are fetched, so that no address waits for a table read.  The reads
         // are issued one by one between the MFMAs: a wavefront that issues them in a batch leaves the
         // matrix pipeline idle meanwhile.
-        auto k_loop = [&]<int NPA>(const unsigned char* aw, const unsigned char* bw) {
+        auto k_loop = [&]<int NPA, int T>(const unsigned char* aw, const unsigned char* bw) {  // T: terms multiplied
             const unsigned char* ap = aw + lane * 16;
             // (slots beyond the allocated ones are never in use; their lanes read slot 0 instead of running
             // off the buffer)
             const unsigned char* bp = bw + (2 * cw + half < g.nt ? 2 * cw + half : 0) * g.slot_bytes;
             const int pstride = NPA > 1 ? 8 * g.slot_bytes : 0;
             const int2* tp = tab + khalf;
-            constexpr int NB1 = TERMS == 2 ? NPA : 1;
+            constexpr int NB1 = T == 2 ? NPA : 1;
             struct Ops {
                 uint4 a[2][NCB], b0[2][NPA], b1[2][NB1];
             };
-            constexpr int N_MFMA = 2 * NCB * NPA * TERMS;
-            constexpr int N_READ = 2 * (NCB + NPA * TERMS);
+            constexpr int N_MFMA = 2 * NCB * NPA * T;
+            constexpr int N_READ = 2 * (NCB + NPA * T);
             auto load_tab = [&](int q, int2(&t)[2]) {
                 t[0] = tp[4 * q];  // tap's byte offset; rotated chunk | mask << 8
                 t[1] = tp[4 * q + 2];
@@ -536,7 +545,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
 #pragma unroll
                     for (int p = 0; p < NPA; ++p) {
                         o.b0[h][p] = *reinterpret_cast<const uint4*>(bp + off + p * pstride);
-                        if (TERMS == 2) o.b1[h][p] = *reinterpret_cast<const uint4*>(bp + plane_bytes + off + p * pstride);
+                        if (T == 2) o.b1[h][p] = *reinterpret_cast<const uint4*>(bp + plane_bytes + off + p * pstride);
                     }
                 }
             };
@@ -548,7 +557,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
 #pragma unroll
                         for (int p = 0; p < NPA; ++p) {
                             acc[c][p] = mma(o.a[h][c], o.b0[h][p], acc[c][p]);
-                            if (TERMS == 2) acc[c][p] = mma(o.a[h][c], o.b1[h][p], acc[c][p]);
+                            if (T == 2) acc[c][p] = mma(o.a[h][c], o.b1[h][p], acc[c][p]);
                         }
             };
             // one K step: multiply `cur`, read step q1 into `nxt`, fetch the table entries of step q2
@@ -585,10 +594,16 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             const unsigned char* aw = lds + (nbuf_a == 2 ? (gs & 1) : 0) * a_bytes;
             const unsigned char* bw = bbase + (gs & 1) * b_bytes;
             ++gs;
-            if (nact > 1) {
-                if constexpr (NP >= 2) k_loop.template operator()<2>(aw, bw);
+            if (TERMS == 2 && !full) {
+                if (nact > 1) {
+                    if constexpr (NP >= 2 && TERMS == 2) k_loop.template operator()<2, 2>(aw, bw);
+                } else if (nact > 0) {
+                    if constexpr (TERMS == 2) k_loop.template operator()<1, 2>(aw, bw);
+                }
+            } else if (nact > 1) {
+                if constexpr (NP >= 2) k_loop.template operator()<2, 1>(aw, bw);
             } else if (nact > 0) {
-                k_loop.template operator()<1>(aw, bw);
+                k_loop.template operator()<1, 1>(aw, bw);
             }
             if (iu < 2 && k < 6) RRM_STAMP(44 + 18 * iu + 3 * k);
         }
@@ -629,7 +644,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
                         sc_t* yp4 = y + (ybase[p] + (unsigned int)co0);
                         for (int k = 0; k < 4 && co0 + k < g.og; ++k) {
                             const sc_t r = acc[c][p][4 * gq + k];
-                            if (MODE == MODE_DELTA) {
+                            if (from_y) {
                                 if (r != (sc_t)0) yp4[k] += r;
                             } else {
                                 yp4[k] = r + (bias ? bias[grp * g.og + co0 + k] : (sc_t)0);

@@ -604,6 +604,10 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
             if ((st = dalloc(L->marks_bytes, (void**)&L->touched)) != RRM_OK) return bail(st);
             if (hipMemset(L->touched, 1, round16(L->marks_bytes)) != hipSuccess) return bail(fail(RRM_ERR_HIP, "hipMemset failed"));
             L->cg.touched = L->touched;
+            // Above this share of active sub-tiles a delta step recomputes the layer instead (the stored
+            // input, equal to x_t after the scan, is the source: only layers whose x layout is the kernel's)
+            L->cg.xfull = L->cg.aligned ? static_cast<const unsigned char*>(L->x_snap) : nullptr;
+            L->cg.full_pct = 62;
         }
         if ((st = dalloc(16, (void**)&L->ctrl)) != RRM_OK) return bail(st);
         if ((st = dalloc(256, &L->zero16)) != RRM_OK) return bail(st);
@@ -659,7 +663,7 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
             RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag, 0u, L->sg, L->stats, s));
             if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
             RRM_HIP(launch_conv(L->dtype, MODE_DELTA, L->cg.wg_cb, L->cg.nt, L->dtype == RRM_BF16_F32 ? L->opt_terms : 1,
-                                L->d0, L->d1, L->zero16, L->tileflag, L->ctrl, L->wpack, L->offtab, nullptr, L->y_snap, L->cg,
+                                L->d0, L->d1, L->zero16, L->tileflag, L->ctrl, L->wpack, L->offtab, L->bias, L->y_snap, L->cg,
                                 L->stats, s));
             L->touched_all = false;  // the kernel's last workgroup copies the step's flags there
         }
@@ -733,6 +737,9 @@ rrm_status rrm_set_option(rrm_layer* L, const char* key, long value) {
     } else if (k == "bf16_terms") {
         if (value != 1 && value != 2) return fail(RRM_ERR_OPTION, "bf16_terms must be 1 or 2");
         L->opt_terms = (int)value;
+    } else if (k == "dense_switch_pct") {
+        if (value < 1 || value > 100) return fail(RRM_ERR_OPTION, "dense_switch_pct must be in [1, 100]");
+        L->cg.full_pct = (int)value;
     } else if (k == "profile") {
         if (value != 0 && value != 1) return fail(RRM_ERR_OPTION, "profile must be 0 or 1");
         L->prof_on = value != 0;

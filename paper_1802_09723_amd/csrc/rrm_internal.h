@@ -94,6 +94,8 @@ struct ConvGeom {
     unsigned int magic_stx;     // d = stx
     int vec_store;       // 1: y rows allow 16-byte read-modify-write
     unsigned int* touched;  // copy of the sub-tile flags of the last delta step (what it wrote in y), or nullptr
+    const unsigned char* xfull;  // delta launches: the committed input in source layout (full recomputation above
+    int full_pct;                //   full_pct % active sub-tiles), or nullptr: never
 };
 
 // Geometry of the binary (XNOR / popcount) convolution.

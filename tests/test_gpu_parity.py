@@ -158,3 +158,12 @@ def test_conv_list_longer_than_one_ranking_round():
     seq = S.Sequence_(shp, S.I8, w, bias, [f0, f1, f2], "many_units")
     st, _ = run_sequence(seq, check_frames=(0, 1, 2), check_dense=(), check_x=False)
     assert st["active_tiles"] > 2 * 64 * 16 * 256
+
+
+@pytest.mark.parametrize("pct", [1, 100])
+def test_dense_switch_threshold_both_ways(pct):
+    """A delta step above the threshold recomputes the projection instead of updating it: forced always
+    (1 %) and never (100 %), both must match the oracle on every frame."""
+    run_sequence(S.config0(T=5), dense_switch_pct=pct)
+    run_sequence(S.config2("r14", 0.25, T=5), dense_switch_pct=pct)
+    run_sequence(S.random_layer(4321, S.conv_shape(19, 23, 24, 40, 3, 1, 1, n=3), S.I8, T=4, frac=0.3), dense_switch_pct=pct)
