@@ -128,7 +128,7 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
  *   "bf16_terms"  BF16 conv: 2 = difference carried as hi+lo bf16 pair (default), 1 = hi only
  *   "dense_switch_pct"  INT8 / BF16 conv: a delta step whose changes touch more than this percentage of the
  *                 4x4 output blocks recomputes the whole projection (same result; cheaper than reading and
- *                 re-writing most of it); 1..100, default 62, 100 = never
+ *                 re-writing most of it); 1..100, default 62 (int8) / 40 (bf16), 100 = never
  *   "bin_cout_per_wave"  binary conv: output channels per wavefront, 8 / 16 (0 = heuristic)
  *   "profile"     1 = bracket every kernel of the following rrm_step calls with HIP events on the
  *                 caller's stream (see rrm_get_kernel_times; not for use under graph capture), 0 = off */

@@ -607,7 +607,8 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
             // Above this share of active sub-tiles a delta step recomputes the layer instead (the stored
             // input, equal to x_t after the scan, is the source: only layers whose x layout is the kernel's)
             L->cg.xfull = L->cg.aligned ? static_cast<const unsigned char*>(L->x_snap) : nullptr;
-            L->cg.full_pct = 62;
+            // (a bf16 delta multiplies two terms, a recomputation one: it pays off earlier)
+            L->cg.full_pct = dtype == RRM_BF16_F32 ? 40 : 62;
         }
         if ((st = dalloc(16, (void**)&L->ctrl)) != RRM_OK) return bail(st);
         if ((st = dalloc(256, &L->zero16)) != RRM_OK) return bail(st);
