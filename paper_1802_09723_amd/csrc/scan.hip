@@ -110,6 +110,39 @@ __device__ __forceinline__ void scatter_unit(const ScanGeom& g, long long v, uin
     const unsigned int r0 = udiv_big(p, g.r_w);
     int ix = (int)(p - r0 * (unsigned int)g.w);
     unsigned int rowbase = r0 * (unsigned int)g.wp;
+    if (DT == RRM_I8_I32 && g.groups == 1 && g.cp == 4) {
+        // Few int8 channels padded to one 32-bit word per position (e.g. RGB -> RGBX): a position that lies
+        // wholly inside the unit is one word store (its pad byte is zero anyway); the cut positions at the
+        // unit's ends go byte by byte.
+        const unsigned long long lo = (unsigned long long)w0.x | (unsigned long long)w0.y << 32;
+        const unsigned long long hi = (unsigned long long)w0.z | (unsigned long long)w0.w << 32;
+        const unsigned int keep = g.c >= 4 ? 0xFFFFFFFFu : (1u << (8 * g.c)) - 1u;
+        unsigned int* dw = reinterpret_cast<unsigned int*>(d0);
+        unsigned char* db = reinterpret_cast<unsigned char*>(d0);
+        int k = 0;
+        while (k < 16 && e0 + (unsigned int)k < total) {
+            // the four bytes of the unit starting at byte k (zeros beyond its end)
+            const unsigned int four = k < 8 ? (unsigned int)(lo >> (8 * k)) | (k ? (unsigned int)(hi << (64 - 8 * k)) : 0u)
+                                            : (unsigned int)(hi >> (8 * (k - 8)));
+            if (c == 0 && k + g.c <= 16 && e0 + (unsigned int)(k + g.c) <= total) {
+                dw[rowbase + ix] = four & keep;
+                k += g.c;
+                c = g.c;
+            } else {
+                db[(rowbase + ix) * 4u + (unsigned int)c] = (unsigned char)four;
+                ++k;
+                ++c;
+            }
+            if (c == g.c) {
+                c = 0;
+                if (++ix == g.w) {
+                    ix = 0;
+                    rowbase += (unsigned int)g.wp;
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int k = 0; k < PV; ++k) {
         if (e0 + k >= total) break;
