@@ -222,7 +222,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             mine = __popcll(fm0);
             for (int i = 1; i < gpt; ++i)
                 if (g_lo + i < n_grp) mine += __popcll(load_group(g_lo + i));
-            if (mine >= 0) RRM_STAMP(80);
             // popcount prefix sum (every workgroup does the same small scan)
             int incl = mine;
 #pragma unroll
@@ -235,7 +234,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         }
         __syncthreads();
         count = s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3];
-        if (producer) RRM_STAMP(81);
         if (producer)
             for (int w = 0; w < wave; ++w) excl += s_scan[w];
     } else {
@@ -257,7 +255,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     if (per < 1) per = 1;
     if (per > g.nt) per = g.nt;
     const int nunits = (count + per - 1) / per;
-    if (producer) RRM_STAMP(84);
 
     unsigned int arrived_before = 0;  // thread 0: workgroups that signalled before this one
     // Arrival signal, sent once this workgroup has read the flags for the last time.  Every thread has
@@ -306,7 +303,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     auto chan = [&](int c, int gq) { return (cbg * NCB + c) * 32 + 8 * gq + 4 * khalf; };
     const unsigned int slab_src_bytes = (unsigned int)(g.sc * 16);  // source bytes between consecutive slabs
 
-    if (producer) RRM_STAMP(85);
     int gs = 0;  // stages (slabs) done so far: the window buffer, and the weight buffer if there are two, alternate
 
     // The two roles run the same loops (ranking rounds, units, slabs) and meet at the same barriers, but
@@ -322,7 +318,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             // The rank of a set flag is the number of set flags before it; rank = unit*per + k.  The unit,
             // its index i among this workgroup's units ((unit - blockIdx.x) / gx when that divides) and k are
             // stepped along with the rank.
-            if (r0 == 0) RRM_STAMP(86);
             int u = excl / per, k = excl - u * per;
             const int d = u - (int)blockIdx.x;
             int i = d >= 0 ? d / gx : -1 - ((-d - 1) / gx);
@@ -341,14 +336,11 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
                     }
                 }
             };
-            if (r0 == 0) RRM_STAMP(87);
             take(fm0, tiny ? tid : g_lo * 64);
             for (int q = 1; q < gpt; ++q)
                 if (g_lo + q < n_grp) take(load_group(g_lo + q), (g_lo + q) * 64);
         }
-        if (r0 == 0) RRM_STAMP(82);
         __syncthreads();  // the list is published
-        if (r0 == 0) RRM_STAMP(83);
     } else if (r0 == 0) {
         __syncthreads();  // (the K-pair table is published)
     }
