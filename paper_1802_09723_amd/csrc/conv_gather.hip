@@ -188,8 +188,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     // ---- how many sub-tiles are active? -------------------------------------------------------------
     // The flag array (one byte per sub-tile) is split into contiguous runs of 64-flag groups, one run per
     // producer thread.  A group is loaded as four 16-byte vectors and squeezed into a 64-bit mask; a thread's
-    // first group stays in registers, further ones (more than 16384 sub-tiles per launch) are re-read.  Up to
-    // 256 sub-tiles (one stream of a small map), a thread takes a single flag instead.
+    // first group stays in registers, further ones (more than 16384 sub-tiles per launch) are re-read.
     constexpr unsigned int LOW = 0x01010101u;
     const uint4* fvp = reinterpret_cast<const uint4*>(flags);
     const int n_vec = (g.n_words + 3) >> 2;
@@ -203,22 +202,33 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         unsigned long long m = 0;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            // byte flags 0/1 of a word -> 4 bits: the product moves byte i's bit to bit 24 + i
+            // (byte flags 0/1 of a word -> 4 bits: the product moves byte i's bit to bit 24 + i)
             auto nib = [](unsigned int w) { return ((w & LOW) * 0x01020408u) >> 24; };
             const unsigned int h = nib(v[u].x) | nib(v[u].y) << 4 | nib(v[u].z) << 8 | nib(v[u].w) << 12;
             m |= (unsigned long long)h << (16 * u);
         }
         return m;
     };
-    const bool tiny = g.n_sub <= CONV_THREADS;  // (then gpt == 1)
+    // Small flag arrays are spread over more threads -- 1, 4 or 16 flags each instead of 64 -- because the
+    // ranking walks a thread's set bits one by one.  (Then gpt == 1.)
+    const int fpt = g.n_sub <= CONV_THREADS ? 1 : g.n_sub <= 4 * CONV_THREADS ? 4 : g.n_sub <= 16 * CONV_THREADS ? 16 : 64;
+    auto nib = [](unsigned int w) { return ((w & LOW) * 0x01020408u) >> 24; };  // byte flags of a word -> 4 bits
     unsigned long long fm0 = 0;
     int count, excl = 0, mine = 0;
     if (MODE == MODE_DELTA) {
         if (producer) {
-            if (tiny)  // one flag per thread: nobody walks more than one bit in the ranking
+            if (fpt == 1) {
                 fm0 = tid < g.n_sub ? (unsigned long long)(reinterpret_cast<const unsigned char*>(flags)[tid] & 1u) : 0ull;
-            else if (g_lo < n_grp)
+            } else if (fpt == 4) {
+                fm0 = tid < g.n_words ? (unsigned long long)nib(flags[tid]) : 0ull;
+            } else if (fpt == 16) {
+                if (tid < n_vec) {
+                    const uint4 v = fvp[tid];
+                    fm0 = (unsigned long long)(nib(v.x) | nib(v.y) << 4 | nib(v.z) << 8 | nib(v.w) << 12);
+                }
+            } else if (g_lo < n_grp) {
                 fm0 = load_group(g_lo);
+            }
             mine = __popcll(fm0);
             for (int i = 1; i < gpt; ++i)
                 if (g_lo + i < n_grp) mine += __popcll(load_group(g_lo + i));
@@ -336,7 +346,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
                     }
                 }
             };
-            take(fm0, tiny ? tid : g_lo * 64);
+            take(fm0, fpt < 64 ? tid * fpt : g_lo * 64);
             for (int q = 1; q < gpt; ++q)
                 if (g_lo + q < n_grp) take(load_group(g_lo + q), (g_lo + q) * 64);
         }
