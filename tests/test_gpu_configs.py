@@ -97,3 +97,44 @@ def test_config4_binary(layer, frac):
     st, _ = run_sequence(seq, check_frames=check, check_dense=(0,), check_x=True)
     flips = sum(int((a != b).sum()) for a, b in zip(seq.frames[:-1], seq.frames[1:]))
     assert st["changed_elems"] == flips
+
+
+def test_config1_in_the_benchmark_configuration_sampled_streams():
+    """The stack as bench.py runs it (128 streams, incremental nonlinearity): every layer of three sampled
+    streams against the oracle on every frame, and every stream against the library's own dense projection
+    of the same input (a property that holds at any size)."""
+    import torch
+    import paper_1802_09723_amd as rrm
+    n, T, sample = 128, 3, (0, 57, 127)
+    cfg = S.config1(n=n, T=T)
+    layers = [rrm.Layer(l["shape"], S.I8, l["weights"], l["bias"]) for l in cfg["layers"]]
+    shapes1 = [l["shape"].with_n(1) for l in cfg["layers"]]
+    shifts, bufs = None, []
+    for t, frame in enumerate(cfg["frames"]):
+        want = {}
+        for s in sample:  # CPU side, one stream at a time
+            x = np.ascontiguousarray(frame[s:s + 1])
+            for i, l in enumerate(cfg["layers"]):
+                y = oracle.dense(shapes1[i], S.I8, l["weights"], l["bias"], x)
+                if shifts is None or len(shifts) <= i:
+                    shifts = (shifts or []) + [oracle.calibrate_shift(y)]
+                want[(s, i)] = y
+                x = oracle.relu_requant_pool(y, shifts[i], l["pool"])
+        x = to_device(frame, S.I8)
+        for i, (l, L) in enumerate(zip(cfg["layers"], layers)):
+            L.step(x)
+            got = L.y_snapshot()
+            for s in sample:
+                assert_matches(got[s:s + 1].cpu().numpy(), want[(s, i)], S.I8, f"frame {t} {l['name']} stream {s}")
+            yd = torch.empty_like(got)
+            L.dense(x, yd)
+            assert torch.equal(got, yd), f"frame {t} {l['name']}: delta result differs from the dense projection"
+            if t == 0:
+                sh = l["shape"]
+                ho, wo = L.y_shape[1], L.y_shape[2]
+                po, qo = ((ho - 3) // 2 + 1, (wo - 3) // 2 + 1) if l["pool"] else (ho, wo)
+                bufs.append(torch.full((sh.n, po, qo, sh.c_out), -1, dtype=torch.int8, device="cuda"))
+            L.relu_requant_pool_changed(bufs[i], shifts[i], l["pool"])
+            x = bufs[i]
+    for L in layers:
+        L.destroy()
