@@ -215,7 +215,21 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     auto nib = [](unsigned int w) { return ((w & LOW) * 0x01020408u) >> 24; };  // byte flags of a word -> 4 bits
     unsigned long long fm0 = 0;
     int count, excl = 0, mine = 0;
-    if (MODE == MODE_DELTA) {
+    // Few sub-tiles in all (one stream of a small map: every group of nt consecutive sub-tiles has a workgroup
+    // of its own in the grid): the launch is latency bound, so there is no global list.  A workgroup reads
+    // the flags of its own group only, compacts them with one ballot, and is done after one barrier.
+    const bool own_group = MODE == MODE_DELTA && g.n_sub <= (int)gridDim.x * g.nt;
+    if (own_group) {
+        if (wave == 0) {
+            const int id = (int)blockIdx.x * g.nt + lane;
+            const bool f = lane < g.nt && id < g.n_sub && (reinterpret_cast<const unsigned char*>(flags)[id] & 1u);
+            const unsigned long long m = __ballot(f);
+            if (f) s_list[__popcll(m & ((1ull << lane) - 1ull))] = id;
+            if (lane < 4) s_scan[lane] = lane == 0 ? (int)__popcll(m) : 0;
+        }
+        __syncthreads();
+        count = s_scan[0];
+    } else if (MODE == MODE_DELTA) {
         if (producer) {
             if (fpt == 1) {
                 fm0 = tid < g.n_sub ? (unsigned long long)(reinterpret_cast<const unsigned char*>(flags)[tid] & 1u) : 0ull;
@@ -254,13 +268,16 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     // input x_t (the scan has made the snapshot equal to it) as the source, one term, accumulators from the
     // bias.  The switch is the same in every workgroup (same count).
     const int n_flagged = count;
-    const bool full = MODE == MODE_DELTA && g.xfull != nullptr && (long long)count * 100 > (long long)g.n_sub * g.full_pct;
+    const bool full = MODE == MODE_DELTA && !own_group && g.xfull != nullptr &&
+                      (long long)count * 100 > (long long)g.n_sub * g.full_pct;
     if (full) count = g.n_sub;
     const bool listed = MODE == MODE_DELTA && !full;  // sub-tile ids come from the ranked list (else: all, in order)
     const bool from_y = listed;                        // accumulators start from the stored projection (else: bias)
     // The active sub-tiles are cut into work units of `per` sub-tiles: few sub-tiles are spread thinly (a
     // unit's latency grows with its size), many are packed NT per unit (operand reuse).
-    const int gx = (int)gridDim.x;
+    // (a workgroup with a sub-tile group of its own: one unit, the group's active sub-tiles)
+    const int gx = own_group ? 1 : (int)gridDim.x;
+    const int bx = own_group ? 0 : (int)blockIdx.x;
     int per = (count + gx - 1) / gx;
     if (per < 1) per = 1;
     if (per > g.nt) per = g.nt;
@@ -287,18 +304,21 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             }
             if (tid == 0) {
                 ctrl[0] = 0u;
-                if (n_flagged) atomicAdd(&stats[0].active_tiles, (unsigned long long)n_flagged);
+                if (n_flagged && !own_group) atomicAdd(&stats[0].active_tiles, (unsigned long long)n_flagged);
             }
         }
+        // (each workgroup counted only its own group's flags)
+        if (own_group && tid == 0 && n_flagged && blockIdx.y == 0)
+            atomicAdd(&stats[blockIdx.x & (STAT_SLOTS - 1)].active_tiles, (unsigned long long)n_flagged);
     };
-    if ((int)blockIdx.x >= nunits) {
+    if (bx >= nunits) {
         __builtin_amdgcn_s_waitcnt(0);  // let the early weight copy land before the LDS is released
         arrive();
         retire();
         return;
     }
     // this workgroup's units: blockIdx.x + i*gx, i = 0 .. my_nunits-1, ranked in rounds of `ur` units
-    const int my_nunits = (nunits - (int)blockIdx.x + gx - 1) / gx;
+    const int my_nunits = (nunits - bx + gx - 1) / gx;
     const int ur = LIST_CAP / per;
 
     // lane roles of a consumer: position j of sub-tile `half` of a pair (MFMA column l%32), K pair `khalf` of
@@ -324,12 +344,12 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     // ---- ranking round: the sub-tile ids of units r0 .. r1-1 of this workgroup go to s_list ------------
     if (MODE == MODE_DELTA) {
         if (r0 > 0) __syncthreads();  // the previous round's list is no longer in use
-        if (mine > 0 && listed) {
+        if (mine > 0 && listed && !own_group) {  // (own_group: the list was made with the count)
             // The rank of a set flag is the number of set flags before it; rank = unit*per + k.  The unit,
             // its index i among this workgroup's units ((unit - blockIdx.x) / gx when that divides) and k are
             // stepped along with the rank.
             int u = excl / per, k = excl - u * per;
-            const int d = u - (int)blockIdx.x;
+            const int d = u - bx;
             int i = d >= 0 ? d / gx : -1 - ((-d - 1) / gx);
             int um = d - i * gx;  // 0 <=> the unit is this workgroup's i-th
             auto take = [&](unsigned long long m, int id0) {  // id0: sub-tile of bit 0
@@ -357,7 +377,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
 
 
     for (int iu = r0; iu < r1; ++iu) {
-    const int unit = (int)blockIdx.x + iu * gx;
+    const int unit = bx + iu * gx;
     const int first = unit * per;
     int mycount = count - first;
     if (mycount > per) mycount = per;
@@ -457,7 +477,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     bool pos_ok[NP];
     acc_t acc[NCB][NP];
     auto begin_unit = [&](int iu2, int r0) {
-        const int first2 = ((int)blockIdx.x + iu2 * gx) * per;
+        const int first2 = (bx + iu2 * gx) * per;
         const int mycount2 = min(per, count - first2);
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
@@ -505,7 +525,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     }
     begin_unit(r0, r0);
     for (int iu = r0; iu < r1; ++iu) {
-    const int unit = (int)blockIdx.x + iu * gx;
+    const int unit = bx + iu * gx;
     const int first = unit * per;
     int mycount = count - first;
     if (mycount > per) mycount = per;
