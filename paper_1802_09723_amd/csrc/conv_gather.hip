@@ -215,10 +215,10 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     auto nib = [](unsigned int w) { return ((w & LOW) * 0x01020408u) >> 24; };  // byte flags of a word -> 4 bits
     unsigned long long fm0 = 0;
     int count, excl = 0, mine = 0;
-    // Few sub-tiles in all (one stream of a small map: every group of nt consecutive sub-tiles has a workgroup
-    // of its own in the grid): the launch is latency bound, so there is no global list.  A workgroup reads
+    // Few sub-tiles in all (one stream of a small map: at most 256, and every group of nt consecutive sub-tiles
+    // has a workgroup of its own in the grid): the launch is latency bound, so there is no global list.  A workgroup reads
     // the flags of its own group only, compacts them with one ballot, and is done after one barrier.
-    const bool own_group = MODE == MODE_DELTA && g.n_sub <= (int)gridDim.x * g.nt;
+    const bool own_group = MODE == MODE_DELTA && g.n_sub <= (int)gridDim.x * g.nt && g.n_sub <= CONV_THREADS;
     if (own_group) {
         if (wave == 0) {
             const int id = (int)blockIdx.x * g.nt + lane;
