@@ -60,9 +60,10 @@ def lib():
         for name in ("orc_dense_i8", "orc_dense_f64"):
             getattr(L, name).argtypes = [ctypes.POINTER(_Shape), P, P, P, P]
             getattr(L, name).restype = ctypes.c_int
-        for name in ("orc_step_i8", "orc_step_f64"):
-            getattr(L, name).argtypes = [ctypes.POINTER(_Shape), P, P, P, P, ctypes.POINTER(ctypes.c_int64)]
-            getattr(L, name).restype = ctypes.c_int
+        L.orc_step_i8.argtypes = [ctypes.POINTER(_Shape), P, P, P, P, ctypes.POINTER(ctypes.c_int64)]
+        L.orc_step_f64.argtypes = [ctypes.POINTER(_Shape), P, P, P, P, ctypes.c_float, ctypes.POINTER(ctypes.c_int64),
+                                   ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
+        L.orc_step_i8.restype = L.orc_step_f64.restype = ctypes.c_int
         L.orc_threads.restype = ctypes.c_int
         L.orc_set_threads.argtypes = [ctypes.c_int]
         _lib = L
@@ -155,14 +156,23 @@ class State:
             self.p_prev += _as_values(dtype, bias, True).reshape((1,) * (len(ys) - 1) + (-1,))
         self.last_nnz = 0
 
-    def step(self, x_t: np.ndarray) -> np.ndarray:
-        """One (layer, frame) iteration of Algorithm 1; returns P_t (a view of the state)."""
+    def step(self, x_t: np.ndarray, eps: float = 0.0) -> np.ndarray:
+        """One (layer, frame) iteration of Algorithm 1; returns P_t (a view of the state).
+
+        ``eps`` > 0 (bf16 only) truncates differences below the threshold (Sec. 3.3, "Improving
+        sparsity"); what is truncated is not committed to the stored input, so P = b + W (*) I holds.
+        ``last_truncated`` / ``last_truncated_sumsq`` describe the truncated map of this step."""
         xv = _as_values(self.dtype, x_t)
         nnz = ctypes.c_int64(0)
+        self.last_truncated, self.last_truncated_sumsq = 0, 0.0
         if self.dtype == BF16:
+            ntr, ssq = ctypes.c_int64(0), ctypes.c_double(0.0)
             lib().orc_step_f64(ctypes.byref(self.cs), _ptr(self.w), _ptr(self.i_prev), _ptr(self.p_prev),
-                               _ptr(xv), ctypes.byref(nnz))
+                               _ptr(xv), ctypes.c_float(eps), ctypes.byref(nnz), ctypes.byref(ntr), ctypes.byref(ssq))
+            self.last_truncated, self.last_truncated_sumsq = int(ntr.value), float(ssq.value)
         else:
+            if eps:
+                raise ValueError("the truncation threshold is defined for the floating-point path only")
             ovf = lib().orc_step_i8(ctypes.byref(self.cs), _ptr(self.w), _ptr(self.i_prev), _ptr(self.p_prev),
                                     _ptr(xv), ctypes.byref(nnz))
             if ovf:

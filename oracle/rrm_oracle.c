@@ -32,6 +32,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include <string.h>
+#include <math.h>
 #ifdef _OPENMP
 #include <omp.h>
 #endif
@@ -206,20 +207,35 @@ int orc_step_i8(const orc_shape* s, const int8_t* wt, int8_t* i_prev, int32_t* p
     return overflow;
 }
 
+/* Sparsity enhancement (Sec. 3.3, "Improving sparsity"): a difference whose magnitude is below the threshold
+ * eps is truncated to zero.  Reading taken here: only what was applied to P is committed to I, so that
+ * P = b + W (*) I stays true and a truncated difference is still pending at the next frame (nothing is lost
+ * for good).  The decision is taken on the single-precision difference, the precision the inputs' difference
+ * is formed in on the device.  eps = 0 is the exact method.  ntrunc / sumsq (nullable) receive the number
+ * of truncated entries and the sum of their squares (the l2 norm of the truncated map of Eq. 7, squared). */
 int orc_step_f64(const orc_shape* s, const double* wt, double* i_prev, double* p_prev, const double* x_t,
-                 int64_t* nnz) {
-    int64_t count = 0;
+                 float eps, int64_t* nnz, int64_t* ntrunc, double* sumsq) {
+    int64_t count = 0, ntr = 0;
+    double ssq = 0.0;
     if (s->kind == 1) {
         for (int b = 0; b < s->n; ++b)
             for (int j = 0; j < s->c_in; ++j) {
                 const double d = x_t[(size_t)b * s->c_in + j] - i_prev[(size_t)b * s->c_in + j];
                 if (d == 0.0) continue;
+                const float d32 = (float)x_t[(size_t)b * s->c_in + j] - (float)i_prev[(size_t)b * s->c_in + j];
+                if (fabsf(d32) < eps) {
+                    ++ntr;
+                    ssq += (double)d32 * (double)d32;
+                    continue;
+                }
                 ++count;
                 for (int o = 0; o < s->c_out; ++o)
                     p_prev[(size_t)b * s->c_out + o] += d * wt[(size_t)o * s->c_in + j];
                 i_prev[(size_t)b * s->c_in + j] = x_t[(size_t)b * s->c_in + j];
             }
         if (nnz) *nnz = count;
+        if (ntrunc) *ntrunc = ntr;
+        if (sumsq) *sumsq = ssq;
         return 0;
     }
     const int ho = out_h(s), wo = out_w(s);
@@ -231,6 +247,12 @@ int orc_step_f64(const orc_shape* s, const double* wt, double* i_prev, double* p
                     const size_t xi = (((size_t)b * s->h + iy) * s->w + ix) * s->c_in + ci;
                     const double d = x_t[xi] - i_prev[xi];
                     if (d == 0.0) continue;
+                    const float d32 = (float)x_t[xi] - (float)i_prev[xi];
+                    if (fabsf(d32) < eps) {
+                        ++ntr;
+                        ssq += (double)d32 * (double)d32;
+                        continue;
+                    }
                     ++count;
                     const int g = ci / cg, c = ci % cg;
                     for (int ky = 0; ky < s->kh; ++ky) {
@@ -253,5 +275,7 @@ int orc_step_f64(const orc_shape* s, const double* wt, double* i_prev, double* p
                     i_prev[xi] = x_t[xi];
                 }
     if (nnz) *nnz = count;
+    if (ntrunc) *ntrunc = ntr;
+    if (sumsq) *sumsq = ssq;
     return 0;
 }

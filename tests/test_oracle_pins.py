@@ -339,3 +339,59 @@ def test_generators_are_seeded_and_shaped():
     c1 = S.config1(T=3)
     assert c1["frames"][0].shape == (1, 227, 227, 3)
     assert 0.01 < S.density(c1["frames"][0], c1["frames"][1])["rho_pos"] < 0.12
+
+
+# ---- truncation threshold (Sec. 3.3, "Improving sparsity") ----------------------------------------
+def _eps_case(T=5, n=2):
+    shp = S.conv_shape(9, 7, 8, 6, 3, 1, 1, n=n)
+    seq = S.random_layer(991, shp, S.BF16, T=T, frac=0.4, block=2)
+    rng = S.rng_for(992)
+    # small perturbations on top of the block redraws, so that some differences fall below a threshold
+    frames = [seq.frames[0]]
+    for t in range(1, T):
+        f = S.bf16_bits_to_f32(seq.frames[t]) + rng.normal(0, 0.02, size=seq.frames[t].shape).astype(np.float32) * (rng.random(seq.frames[t].shape) < 0.5)
+        frames.append(S.f32_to_bf16_bits(np.maximum(f, 0).astype(np.float32)))
+    return seq, frames
+
+
+def test_threshold_zero_is_the_exact_method():
+    seq, frames = _eps_case()
+    a = oracle.State(seq.shape, S.BF16, seq.weights, seq.bias)
+    b = oracle.State(seq.shape, S.BF16, seq.weights, seq.bias)
+    for x in frames:
+        pa = a.step(x).copy()
+        pb = b.step(x, eps=0.0)
+        assert np.array_equal(pa, pb) and b.last_truncated == 0
+
+
+def test_threshold_keeps_projection_consistent_with_stored_input():
+    """What is truncated is not committed: after every step P equals the dense projection (Eq. 3) of the
+    stored input, and the stored input differs from x_t exactly where a difference was truncated."""
+    seq, frames = _eps_case()
+    st = oracle.State(seq.shape, S.BF16, seq.weights, seq.bias)
+    eps = 0.03
+    total_trunc = 0
+    for x in frames:
+        before = st.i_prev.copy()
+        p = st.step(x, eps=eps)
+        xv = oracle.bf16_to_f64(x)
+        d32 = xv.astype(np.float32) - before.astype(np.float32)
+        trunc = (d32 != 0) & (np.abs(d32) < np.float32(eps))
+        # brute-force classification of every entry, written independently of the C loop
+        assert st.last_truncated == int(trunc.sum())
+        assert np.isclose(st.last_truncated_sumsq, float((d32[trunc].astype(np.float64) ** 2).sum()), rtol=1e-12, atol=0)
+        assert np.array_equal(st.i_prev[trunc], before[trunc]) and np.array_equal(st.i_prev[~trunc], xv[~trunc])
+        stored_bits = S.f32_to_bf16_bits(st.i_prev.astype(np.float32))
+        want = oracle.dense(seq.shape, S.BF16, seq.weights, seq.bias, stored_bits)
+        assert np.abs(p - want).max() <= 1e-9 * max(1.0, np.abs(want).max())
+        total_trunc += st.last_truncated
+    assert total_trunc > 0  # the case does exercise the threshold
+
+
+def test_threshold_above_every_difference_changes_nothing():
+    seq, frames = _eps_case(T=3)
+    st = oracle.State(seq.shape, S.BF16, seq.weights, seq.bias)
+    p0 = st.p_prev.copy()
+    for x in frames:
+        st.step(x, eps=1e30)
+        assert np.array_equal(st.p_prev, p0) and not st.i_prev.any() and st.last_nnz == 0
