@@ -86,6 +86,8 @@ typedef struct {
                                  (FC: c_in per step) */
     int32_t range_error;      /* non-zero once an int8 difference overflowed */
     int32_t reserved;
+    uint64_t truncated_elems; /* BF16 with a threshold: differences below it (neither applied nor committed) */
+    double truncated_sumsq;   /* and the sum of their squares: sum over steps of l2(u)^2 of Eq. 7's truncated maps */
 } rrm_stats;
 
 /* Create a layer handle (Eq. 3 defines the layer; Sec. 3.2 the state it keeps).
@@ -138,6 +140,15 @@ rrm_status rrm_set_option(rrm_layer* layer, const char* key, long value);
  * the stream has been synchronised, outside timed regions.  Returns RRM_ERR_RANGE (with *out
  * filled) if the sticky range flag is set. */
 rrm_status rrm_get_stats(rrm_layer* layer, rrm_stats* out);
+
+/* Truncation threshold of a BF16 layer (Sec. 3.3, "Improving sparsity": small values of the difference are
+ * truncated to zero to gain sparsity; the experiments use 1e-2).  An entry with |x_t - x_snap| < epsilon
+ * (difference formed in fp32) is not applied to the stored projection and not committed to the stored input,
+ * so y_snap == b + W (*) x_snap stays true and the entry is still pending at the next frame; x_snap then
+ * differs from x_t by less than epsilon per entry.  epsilon = 0 (the default) is the exact method.  Takes
+ * effect at the next rrm_step; steps with "path" = 2 ignore it.
+ * Errors: RRM_ERR_NULL, RRM_ERR_DTYPE (not BF16), RRM_ERR_OPTION (negative or not finite). */
+rrm_status rrm_set_threshold(rrm_layer* layer, float epsilon);
 
 /* Kernel times of the rrm_step calls made since "profile" was switched on (or since the last call
  * of this function): sums, in microseconds, of the event-bracketed durations of the scan kernel

@@ -34,10 +34,11 @@ class Stats(ctypes.Structure):
     """``rrm_stats``"""
     _fields_ = [("steps", ctypes.c_uint64), ("delta_steps", ctypes.c_uint64), ("changed_elems", ctypes.c_uint64),
                 ("changed_units", ctypes.c_uint64), ("active_tiles", ctypes.c_uint64), ("total_tiles", ctypes.c_uint64),
-                ("range_error", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("range_error", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("truncated_elems", ctypes.c_uint64), ("truncated_sumsq", ctypes.c_double)]
 
     def as_dict(self):
-        return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
+        return {k: (float if k == "truncated_sumsq" else int)(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
 
 
 class RRMError(RuntimeError):
@@ -80,9 +81,10 @@ def lib():
         L.rrm_last_error.restype = ctypes.c_char_p
         L.rrm_aux_relu_requant_pool_i8.argtypes = [P, P, I, I, I, I, I, I, P]
         L.rrm_aux_relu_requant_pool_changed_i8.argtypes = [P, P, I, I, P]
+        L.rrm_set_threshold.argtypes = [P, ctypes.c_float]
         for f in ("rrm_layer_create", "rrm_step", "rrm_dense", "rrm_reset", "rrm_snapshot", "rrm_read_snapshot", "rrm_set_option",
                   "rrm_get_stats", "rrm_get_kernel_times", "rrm_aux_relu_requant_pool_i8",
-                  "rrm_aux_relu_requant_pool_changed_i8"):
+                  "rrm_aux_relu_requant_pool_changed_i8", "rrm_set_threshold"):
             getattr(L, f).restype = I
         _lib = L
     return _lib
@@ -151,6 +153,10 @@ class Layer:
 
     def reset(self, stream=None) -> None:
         _check(lib().rrm_reset(self._h, _stream_ptr(stream)))
+
+    def set_threshold(self, epsilon: float) -> None:
+        """Truncation threshold of a bf16 layer's input difference (``rrm_set_threshold``)."""
+        _check(lib().rrm_set_threshold(self._h, float(epsilon)))
 
     def relu_requant_pool_changed(self, out, shift, pool, stream=None) -> None:
         """Harness nonlinearity on the stored projection, recomputing only what the last step changed

@@ -43,6 +43,8 @@ __global__ __launch_bounds__(FC_SCAN_THREADS) void fc_scan_kernel(const unsigned
     const int nunits = (g.c_in + PV - 1) / PV;
     if (tid == 0) running = 0;
     __syncthreads();
+    unsigned int ntrunc = 0;  // truncated differences of this thread (bf16 with a threshold) and their squares
+    float tsq = 0.f;
     for (int u0 = 0; u0 < nunits; u0 += FC_SCAN_THREADS) {
         const int u = u0 + tid;
         val_t dv[PV];
@@ -55,6 +57,7 @@ __global__ __launch_bounds__(FC_SCAN_THREADS) void fc_scan_kernel(const unsigned
                 const uint4 s = *sp;
                 if ((a.x ^ s.x) | (a.y ^ s.y) | (a.z ^ s.z) | (a.w ^ s.w)) {
                     const unsigned int aw[4] = {a.x, a.y, a.z, a.w}, sw[4] = {s.x, s.y, s.z, s.w};
+                    unsigned int nw[4] = {a.x, a.y, a.z, a.w};  // the unit's new snapshot
 #pragma unroll
                     for (int e = 0; e < PV; ++e) {
                         if (DT == RRM_I8_I32) {
@@ -63,13 +66,24 @@ __global__ __launch_bounds__(FC_SCAN_THREADS) void fc_scan_kernel(const unsigned
                             dv[e] = (val_t)(xa - xb);
                             if (xa != xb) mask |= 1u << e;
                         } else {
+                            // (truncation threshold, Sec. 3.3 "Improving sparsity": a difference below g.eps is
+                            // neither listed nor committed; eps = 0 is the exact method)
                             const unsigned int xa = (aw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
                             const unsigned int xb = (sw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-                            dv[e] = (val_t)(bf16_to_f32(xa) - bf16_to_f32(xb));
-                            if (xa != xb) mask |= 1u << e;
+                            const float d = bf16_to_f32(xa) - bf16_to_f32(xb);
+                            dv[e] = (val_t)d;
+                            if (xa != xb) {
+                                if (fabsf(d) < g.eps) {
+                                    ++ntrunc;
+                                    tsq += d * d;
+                                    nw[e >> 1] = (nw[e >> 1] & ~(0xFFFFu << (16 * (e & 1)))) | (xb << (16 * (e & 1)));
+                                } else {
+                                    mask |= 1u << e;
+                                }
+                            }
                         }
                     }
-                    *sp = a;
+                    if (mask) *sp = make_uint4(nw[0], nw[1], nw[2], nw[3]);
                 }
             } else {
                 for (int e = 0; e < PV; ++e) {
@@ -87,9 +101,15 @@ __global__ __launch_bounds__(FC_SCAN_THREADS) void fc_scan_kernel(const unsigned
                         const unsigned short xa = reinterpret_cast<const unsigned short*>(x_t)[row + e0 + e];
                         unsigned short* sp = reinterpret_cast<unsigned short*>(x_snap) + row + e0 + e;
                         if (xa != *sp) {
-                            mask |= 1u << e;
-                            dv[e] = (val_t)(bf16_to_f32(xa) - bf16_to_f32(*sp));
-                            *sp = xa;
+                            const float d = bf16_to_f32(xa) - bf16_to_f32(*sp);
+                            if (fabsf(d) < g.eps) {
+                                ++ntrunc;
+                                tsq += d * d;
+                            } else {
+                                mask |= 1u << e;
+                                dv[e] = (val_t)d;
+                                *sp = xa;
+                            }
                         }
                     }
                 }
@@ -124,6 +144,17 @@ __global__ __launch_bounds__(FC_SCAN_THREADS) void fc_scan_kernel(const unsigned
         __syncthreads();
         if (tid == 0) running += btot;
         __syncthreads();
+    }
+    if (DT == RRM_BF16_F32) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            ntrunc += __shfl_xor(ntrunc, o);
+            tsq += __shfl_xor(tsq, o);
+        }
+        if (lane == 0 && ntrunc) {
+            atomicAdd(&stats->truncated_elems, (unsigned long long)ntrunc);
+            atomicAdd(&stats->truncated_sumsq, (double)tsq);
+        }
     }
     if (tid == 0) {
         const int total = running;

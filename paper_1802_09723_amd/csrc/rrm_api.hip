@@ -754,6 +754,15 @@ rrm_status rrm_set_option(rrm_layer* L, const char* key, long value) {
     return RRM_OK;
 }
 
+rrm_status rrm_set_threshold(rrm_layer* L, float epsilon) {
+    if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
+    if (L->dtype != RRM_BF16_F32) return fail(RRM_ERR_DTYPE, "the truncation threshold is defined for BF16 layers");
+    if (!(epsilon >= 0.0f) || epsilon > 3.0e38f) return fail(RRM_ERR_OPTION, "epsilon must be finite and >= 0");
+    L->sg.eps = epsilon;
+    L->fg.eps = epsilon;
+    return RRM_OK;
+}
+
 rrm_status rrm_get_stats(rrm_layer* L, rrm_stats* out) {
     if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
     if (!out) return fail(RRM_ERR_NULL, "out is NULL");
@@ -765,6 +774,8 @@ rrm_status rrm_get_stats(rrm_layer* L, rrm_stats* out) {
         d.changed_units += t.changed_units;
         d.active_tiles += t.active_tiles;
         d.range_error |= t.range_error;
+        d.truncated_elems += t.truncated_elems;
+        d.truncated_sumsq += t.truncated_sumsq;
     }
     out->steps = L->steps;
     out->delta_steps = L->delta_steps;
@@ -774,6 +785,8 @@ rrm_status rrm_get_stats(rrm_layer* L, rrm_stats* out) {
     out->total_tiles = L->total_tiles;
     out->range_error = (int32_t)d.range_error;
     out->reserved = 0;
+    out->truncated_elems = d.truncated_elems;
+    out->truncated_sumsq = d.truncated_sumsq;
     if (d.range_error) return fail(RRM_ERR_RANGE, "an int8 input difference did not fit int8");
     return RRM_OK;
 }

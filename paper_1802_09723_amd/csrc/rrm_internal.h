@@ -25,6 +25,8 @@ struct DevStats {
     unsigned long long active_tiles;
     unsigned int range_error;
     unsigned int pad_;
+    unsigned long long truncated_elems;  // bf16 with a threshold: differences below it (not applied, not committed)
+    double truncated_sumsq;              //   and the sum of their squares
 };
 
 // Geometry of the flat scan over x (delta + change map), one element = int8 / bf16 / u32 word.
@@ -46,6 +48,7 @@ struct ScanGeom {
     // 32-bit one for the small dividends of the receptive-field bounds (floor(2^32/stride)+1, 0 for 1)
     double r_c, r_hw, r_w;
     unsigned int magic_stride;
+    float eps;  // bf16: truncation threshold of the difference (0 = exact)
 };
 
 constexpr int CONV_MAX_STAGE_UNITS = 12;  // 16-byte units a thread stages per slab (half for 2 terms)
@@ -119,6 +122,7 @@ struct FcGeom {
     int per_vec;         // output channels per lane per 16-byte load: 16 / 8
     int slices;          // ceil(c_out_p / (256 * per_vec))
     int vec_ok;          // 1: x rows are 16-byte aligned multiples
+    float eps;           // bf16: truncation threshold of the difference (0 = exact)
 };
 
 // ---- launchers implemented in the kernel translation units ------------------------------------

@@ -190,7 +190,8 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
     const unsigned long long prev_mask = v < nvec ? bitmap[v >> 6] : 0ull;  // wave-uniform word
     bool changed = false;
     int p0 = 0, p1 = -1;  // input positions of this unit, when it changed
-    unsigned int nelem = 0;
+    unsigned int nelem = 0, ntrunc = 0;
+    float tsq = 0.f;  // truncated entries of this unit: count and sum of squares (bf16 with a threshold)
     uint4 a = make_uint4(0, 0, 0, 0);
     if (v < nvec) {
         a = load_x_guarded(x_t, v * 16, total_bytes);
@@ -201,6 +202,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
             const unsigned int aw[4] = {a.x, a.y, a.z, a.w};
             const unsigned int bw[4] = {b.x, b.y, b.z, b.w};
             unsigned int dw[4], lw[4] = {0u, 0u, 0u, 0u};
+            unsigned int sw[4] = {a.x, a.y, a.z, a.w};  // the unit's new snapshot (bf16: entry by entry)
             if (DT == RRM_I8_I32) {
                 const unsigned int H = 0x80808080u;
                 unsigned int ovf = 0;
@@ -215,25 +217,38 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
                 }
                 if (ovf) atomicOr(&stats->range_error, 1u);
             } else if (DT == RRM_BF16_F32) {
+                // Truncation threshold (Sec. 3.3, "Improving sparsity"): an entry whose difference is below
+                // g.eps in magnitude is not applied and not committed (its snapshot entry keeps the old
+                // value), so the stored projection stays the projection of the stored input.  eps = 0: exact.
+                bool any_pass = false;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    unsigned int hi2 = 0, lo2 = 0;
+                    unsigned int hi2 = 0, lo2 = 0, sn2 = 0;
 #pragma unroll
                     for (int k = 0; k < 2; ++k) {
                         const unsigned int xa = (aw[i] >> (16 * k)) & 0xFFFFu, xb = (bw[i] >> (16 * k)) & 0xFFFFu;
-                        nelem += xa != xb ? 1u : 0u;
                         // difference in fp32 (exact unless the operands are > 2^15 apart in magnitude),
                         // then split into a bf16 head and a bf16 tail; equal inputs give 0 and 0 (no
                         // branch: the lanes of a wavefront would diverge on it)
                         const float d = bf16_to_f32(xa) - bf16_to_f32(xb);
-                        const unsigned int hi = f32_to_bf16(d);
-                        const unsigned int lo = f32_to_bf16(d - bf16_to_f32(hi));
+                        const bool differ = xa != xb;
+                        const bool trunc = differ && fabsf(d) < g.eps;
+                        const bool pass = differ && !trunc;
+                        any_pass |= pass;
+                        nelem += pass ? 1u : 0u;
+                        ntrunc += trunc ? 1u : 0u;
+                        tsq += trunc ? d * d : 0.f;
+                        const unsigned int hi = pass ? f32_to_bf16(d) : 0u;
+                        const unsigned int lo = pass ? f32_to_bf16(d - bf16_to_f32(hi)) : 0u;
                         hi2 |= hi << (16 * k);
                         lo2 |= lo << (16 * k);
+                        sn2 |= (pass ? xa : xb) << (16 * k);
                     }
                     dw[i] = hi2;
                     lw[i] = lo2;
+                    sw[i] = sn2;
                 }
+                changed = any_pass;
             } else {  // binary: the flip mask
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -241,20 +256,23 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
                     nelem += __popc(dw[i]);
                 }
             }
-            if (!SCATTER) {
-                d0[v] = make_uint4(dw[0], dw[1], dw[2], dw[3]);
-                if (DT == RRM_BF16_F32) d1[v] = make_uint4(lw[0], lw[1], lw[2], lw[3]);
-            } else {
-                scatter_unit<DT>(g, v, make_uint4(dw[0], dw[1], dw[2], dw[3]), make_uint4(lw[0], lw[1], lw[2], lw[3]), d0, d1);
+            if (changed) {  // (bf16: every differing entry of the unit may have been truncated)
+                if (!SCATTER) {
+                    d0[v] = make_uint4(dw[0], dw[1], dw[2], dw[3]);
+                    if (DT == RRM_BF16_F32) d1[v] = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+                } else {
+                    scatter_unit<DT>(g, v, make_uint4(dw[0], dw[1], dw[2], dw[3]), make_uint4(lw[0], lw[1], lw[2], lw[3]), d0, d1);
+                }
+                x_snap[v] = make_uint4(sw[0], sw[1], sw[2], sw[3]);  // snapshot of the input, only where it changed
+                // input positions covered by this unit
+                const unsigned int e0 = (unsigned int)v * g.per_vec;
+                unsigned int e1 = e0 + g.per_vec - 1;
+                if (e1 > (unsigned int)g.total_elems - 1) e1 = (unsigned int)g.total_elems - 1;
+                p0 = (int)udiv_big(e0, g.r_c);
+                p1 = (int)udiv_big(e1, g.r_c);
             }
-            x_snap[v] = a;  // snapshot of the input, only where it changed
-            // input positions covered by this unit
-            const unsigned int e0 = (unsigned int)v * g.per_vec;
-            unsigned int e1 = e0 + g.per_vec - 1;
-            if (e1 > (unsigned int)g.total_elems - 1) e1 = (unsigned int)g.total_elems - 1;
-            p0 = (int)udiv_big(e0, g.r_c);
-            p1 = (int)udiv_big(e1, g.r_c);
-        } else if ((prev_mask >> (threadIdx.x & 63)) & 1ull) {
+        }
+        if (!changed && ((prev_mask >> (threadIdx.x & 63)) & 1ull)) {
             // changed last step, unchanged now: restore the zero of the difference buffer
             if (!SCATTER) {
                 d0[v] = make_uint4(0, 0, 0, 0);
@@ -274,12 +292,22 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
     if ((threadIdx.x & 63) == 0 && v < nvec) bitmap[v >> 6] = mask;
     // change counts: summed over the wavefront, then over the workgroup, one pair of atomics per workgroup
     // (atomics on one address serialise: a pair per wavefront was the slowest part of a busy scan)
-    __shared__ unsigned int s_ne[4], s_nu[4];
+    __shared__ unsigned int s_ne[4], s_nu[4], s_nt[4];
+    __shared__ float s_tq[4];
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) nelem += __shfl_xor(nelem, o);
+    if (DT == RRM_BF16_F32) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            ntrunc += __shfl_xor(ntrunc, o);
+            tsq += __shfl_xor(tsq, o);
+        }
+    }
     if ((threadIdx.x & 63) == 0) {
         s_ne[threadIdx.x >> 6] = nelem;
         s_nu[threadIdx.x >> 6] = (unsigned int)__popcll(mask);
+        s_nt[threadIdx.x >> 6] = ntrunc;
+        s_tq[threadIdx.x >> 6] = tsq;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -287,6 +315,11 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
         if (nu) {
             atomicAdd(&stats->changed_elems, (unsigned long long)ne);
             atomicAdd(&stats->changed_units, (unsigned long long)nu);
+        }
+        const unsigned int nt = s_nt[0] + s_nt[1] + s_nt[2] + s_nt[3];
+        if (DT == RRM_BF16_F32 && nt) {
+            atomicAdd(&stats->truncated_elems, (unsigned long long)nt);
+            atomicAdd(&stats->truncated_sumsq, (double)s_tq[0] + (double)s_tq[1] + (double)s_tq[2] + (double)s_tq[3]);
         }
     }
 }

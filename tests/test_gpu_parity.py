@@ -167,3 +167,52 @@ def test_dense_switch_threshold_both_ways(pct):
     run_sequence(S.config0(T=5), dense_switch_pct=pct)
     run_sequence(S.config2("r14", 0.25, T=5), dense_switch_pct=pct)
     run_sequence(S.random_layer(4321, S.conv_shape(19, 23, 24, 40, 3, 1, 1, n=3), S.I8, T=4, frac=0.3), dense_switch_pct=pct)
+
+
+def _perturbed_frames(seq, seed, sigma=0.02):
+    """The sequence's frames plus small perturbations of half of the entries, so that many differences fall
+    below a truncation threshold of a few hundredths."""
+    rng = S.rng_for(seed)
+    frames = [seq.frames[0]]
+    for f in seq.frames[1:]:
+        v = S.bf16_bits_to_f32(f) + rng.normal(0, sigma, size=f.shape).astype(np.float32) * (rng.random(f.shape) < 0.5)
+        frames.append(S.f32_to_bf16_bits(np.maximum(v, 0).astype(np.float32)))
+    return frames
+
+
+@pytest.mark.parametrize("kind", ["conv", "conv_multi", "fc"])
+@pytest.mark.parametrize("eps", [0.0, 0.03])
+def test_bf16_truncation_threshold_matches_oracle(kind, eps):
+    """rrm_set_threshold: stored input bit-identical to the oracle's (same fp32 decision per entry), stored
+    projection within the bf16 tolerance, same number of truncated entries (Sec. 3.3, Improving sparsity)."""
+    if kind == "fc":
+        seq = S.config3("fc7", S.BF16, 0.10, n=2, T=5)
+    elif kind == "conv":
+        seq = S.config2("r28", 0.10, T=5)
+    else:
+        seq = S.random_layer(7007, S.conv_shape(21, 17, 24, 40, 3, 1, 1, n=3), S.BF16, T=5, frac=0.3, block=3)
+    frames = _perturbed_frames(seq, 4242)
+    layer = make_layer(seq)
+    layer.set_threshold(eps)
+    st = oracle.State(seq.shape, S.BF16, seq.weights, seq.bias)
+    trunc = 0
+    for t, x in enumerate(frames):
+        layer.step(to_device(x, S.BF16))
+        want_p = st.step(x, eps=eps)
+        trunc += st.last_truncated
+        got_x = layer.x_snapshot_bytes().cpu().numpy().view(np.uint16).reshape(x.shape)
+        want_x = S.f32_to_bf16_bits(st.i_prev.astype(np.float32))
+        assert np.array_equal(S.bf16_bits_to_f32(got_x), S.bf16_bits_to_f32(want_x)), f"frame {t}: stored input differs"
+        assert_matches(layer.y_snapshot().cpu().numpy(), want_p, S.BF16, f"{kind} eps {eps} frame {t}")
+    stats = layer.stats()
+    assert stats["truncated_elems"] == trunc
+    assert (trunc > 0) == (eps > 0)
+    layer.destroy()
+
+
+def test_threshold_is_refused_for_integer_layers():
+    import paper_1802_09723_amd as rrm
+    layer = make_layer(S.config0(T=1))
+    with pytest.raises(rrm.RRMError):
+        layer.set_threshold(0.01)
+    layer.destroy()
