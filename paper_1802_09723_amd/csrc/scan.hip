@@ -178,6 +178,19 @@ __global__ void repack_kernel(const unsigned char* __restrict__ x, unsigned char
         reinterpret_cast<unsigned short*>(dst)[d] = reinterpret_cast<const unsigned short*>(x)[e];
 }
 
+// The same re-layout for few int8 channels padded to one 32-bit word per position (e.g. RGB -> RGBX): one
+// thread per position, one word store.
+__global__ void repack_word_kernel(const unsigned char* __restrict__ x, unsigned int* __restrict__ dst, ScanGeom g,
+                                   unsigned int n_pos) {
+    const unsigned int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n_pos) return;
+    const unsigned int r = udiv_big(p, g.r_w), ix = p - r * (unsigned int)g.w;
+    const unsigned char* src = x + (size_t)p * (unsigned int)g.c;
+    unsigned int word = 0;
+    for (int c = 0; c < g.c; ++c) word |= (unsigned int)src[c] << (8 * c);
+    dst[r * (unsigned int)g.wp + ix] = word;
+}
+
 template <int DT, bool SCATTER>
 __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restrict__ x_t, uint4* __restrict__ x_snap,
                                                    uint4* __restrict__ d0, uint4* __restrict__ d1,
@@ -329,6 +342,12 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
 hipError_t launch_repack(int esize, const void* x, void* dst, const ScanGeom& g, hipStream_t s) {
     const long long blocks = (g.total_elems + 255) / 256;
     if (blocks <= 0) return hipSuccess;
+    if (esize == 1 && g.groups == 1 && g.cp == 4 && g.c <= 4) {
+        const long long n_pos = g.total_elems / g.c;
+        hipLaunchKernelGGL(repack_word_kernel, dim3((unsigned int)((n_pos + 255) / 256)), dim3(256), 0, s,
+                           (const unsigned char*)x, (unsigned int*)dst, g, (unsigned int)n_pos);
+        return hipGetLastError();
+    }
     if (esize == 1)
         hipLaunchKernelGGL(repack_kernel<1>, dim3((unsigned int)blocks), dim3(256), 0, s, (const unsigned char*)x,
                            (unsigned char*)dst, g);
