@@ -216,3 +216,65 @@ def test_threshold_is_refused_for_integer_layers():
     with pytest.raises(rrm.RRMError):
         layer.set_threshold(0.01)
     layer.destroy()
+
+
+def _random_conv_shapes(count, seed):
+    """Seeded random convolution shapes: kernels 1..5 (also non-square), strides 1..3, pads 0..2, groups 1..4,
+    channel counts on and off the 16-byte chunk, 1..6 streams."""
+    rng = S.rng_for(seed)
+    out = []
+    while len(out) < count:
+        groups = int(rng.choice([1, 1, 1, 2, 3, 4]))
+        cg = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16, 20, 32, 48]))
+        og = int(rng.choice([1, 3, 4, 7, 8, 16, 24, 33, 40, 64]))
+        kh, kw = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        stride, pad = int(rng.integers(1, 4)), int(rng.integers(0, 3))
+        h, w = int(rng.integers(max(kh - 2 * pad, 1) + 2, 26)), int(rng.integers(max(kw - 2 * pad, 1) + 2, 26))
+        n = int(rng.integers(1, 7))
+        if (h + 2 * pad - kh) < 0 or (w + 2 * pad - kw) < 0:
+            continue
+        shp = S.LayerShape(S.CONV, n, h, w, cg * groups, og * groups, kh, kw, stride, pad, groups)
+        if shp.h_out < 1 or shp.w_out < 1 or n * h * w * cg * groups * og * kh * kw > 4e8:
+            continue
+        out.append(shp)
+    return out
+
+
+@pytest.mark.parametrize("idx", range(24))
+def test_random_conv_shapes(idx):
+    shp = _random_conv_shapes(24, 20240)[idx]
+    dt = S.I8 if idx % 2 == 0 else S.BF16
+    seq = S.random_layer(8100 + idx, shp, dt, T=4, frac=0.25, block=2)
+    run_sequence(seq, check_dense=(0, 3))
+
+
+def _random_bin_shapes(count, seed):
+    rng = S.rng_for(seed)
+    out = []
+    while len(out) < count:
+        groups = int(rng.choice([1, 1, 2, 4]))
+        cg = 32 * int(rng.integers(1, 6))
+        og = int(rng.choice([1, 4, 8, 12, 16, 24, 40]))
+        kh, kw = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        stride, pad = int(rng.integers(1, 3)), int(rng.integers(0, 3))
+        h, w = int(rng.integers(4, 22)), int(rng.integers(4, 22))
+        shp = S.LayerShape(S.CONV, int(rng.integers(1, 5)), h, w, cg * groups, og * groups, kh, kw, stride, pad, groups)
+        if (h + 2 * pad - kh) < 0 or (w + 2 * pad - kw) < 0 or shp.h_out < 1 or shp.w_out < 1:
+            continue
+        out.append(shp)
+    return out
+
+
+@pytest.mark.parametrize("idx", range(10))
+def test_random_binary_shapes(idx):
+    shp = _random_bin_shapes(10, 777)[idx]
+    seq = S.random_layer(8300 + idx, shp, S.BIN, T=4, frac=0.1, block=2)
+    run_sequence(seq, check_dense=(0, 3))
+
+
+@pytest.mark.parametrize("idx", range(8))
+def test_random_fc_shapes(idx):
+    rng = S.rng_for(900 + idx)
+    shp = S.fc_shape(int(rng.integers(1, 3000)), int(rng.integers(1, 3000)), n=int(rng.integers(1, 5)))
+    seq = S.random_layer(8400 + idx, shp, S.I8 if idx % 2 else S.BF16, T=4, frac=float(rng.choice([0.01, 0.1, 0.5])))
+    run_sequence(seq, check_dense=(0, 3), rel=1e-4)
