@@ -278,3 +278,29 @@ def test_random_fc_shapes(idx):
     shp = S.fc_shape(int(rng.integers(1, 3000)), int(rng.integers(1, 3000)), n=int(rng.integers(1, 5)))
     seq = S.random_layer(8400 + idx, shp, S.I8 if idx % 2 else S.BF16, T=4, frac=float(rng.choice([0.01, 0.1, 0.5])))
     run_sequence(seq, check_dense=(0, 3), rel=1e-4)
+
+
+@pytest.mark.parametrize("case", [
+    # (h, c_in, c_out, k, groups, streams, changed fraction): flag arrays of 320 .. 4900 sub-tiles, several work
+    # units per workgroup, densities below and above the recomputation switch
+    (13, 64, 128, 3, 1, 20, 0.10), (13, 64, 128, 3, 1, 64, 0.30), (13, 96, 64, 3, 2, 100, 0.05),
+    (27, 32, 64, 5, 1, 100, 0.15), (13, 64, 128, 3, 1, 64, 0.90),
+])
+@pytest.mark.parametrize("dt", [S.I8, S.BF16])
+def test_many_streams_mid_size(case, dt):
+    h, ci, co, k, groups, n, frac = case
+    shp = S.conv_shape(h, h, ci, co, k, 1, k // 2, groups, n=n)
+    rng = S.rng_for(8500 + n + h)
+    draw = S.draw_i8_act if dt == S.I8 else S.draw_bf16_relu
+    w = S.draw_i8_weight(rng, shp.w_shape) if dt == S.I8 else S.draw_bf16_weight(rng, shp.w_shape)
+    frames = [draw(rng, shp.x_shape)]
+    for t in range(3):  # per frame: a random subset of streams gets a re-drawn 6x6 block
+        f = frames[-1].copy()
+        for b in np.nonzero(rng.random(n) < min(1.0, 4 * frac))[0]:
+            y0, x0 = int(rng.integers(0, h - 5)), int(rng.integers(0, h - 5))
+            f[b, y0:y0 + 6, x0:x0 + 6, :] = draw(rng, (6, 6, ci))
+        if frac > 0.5:
+            f = draw(rng, shp.x_shape)
+        frames.append(f)
+    seq = S.Sequence_(shp, dt, w, None, frames, "mid")
+    run_sequence(seq, check_dense=(1,), check_x=False)
