@@ -582,27 +582,25 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
                             if (T == 2) acc[c][p] = mma(o.a[h][c], o.b1[h][p], acc[c][p]);
                         }
             };
-            // one K step: multiply `cur`, read step q1 into `nxt`, fetch the table entries of step q2
-            auto step = [&](const Ops& cur, Ops& nxt, int2(&t)[2], int q1, int q2) {
-                int2 tn[2];
+            // one K step: multiply `cur`, read step q1 (table entries `t`) into `nxt`, fetch the table entries
+            // of step q2 into `tn`; operand sets and table registers swap roles every step, nothing is copied
+            auto step = [&](const Ops& cur, Ops& nxt, const int2(&t)[2], int2(&tn)[2], int q1, int q2) {
                 load_tab(q2, tn);
                 fetch(q1, t, nxt);
                 multiply(cur);
-                t[0] = tn[0];
-                t[1] = tn[1];
                 // issue order: the table read, then MFMAs with the operand reads spread between them
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 sched_interleave<0, N_MFMA, N_READ>();
             };
             Ops o0, o1;
-            int2 t[2];
+            int2 ta[2], tb[2];
             const int qmax = g.nq - 1;
-            load_tab(0, t);
-            fetch(0, t, o0);
-            load_tab(min(1, qmax), t);
+            load_tab(0, tb);
+            fetch(0, tb, o0);
+            load_tab(min(1, qmax), ta);
             for (int q = 0; q < g.nq; q += 2) {
-                step(o0, o1, t, min(q + 1, qmax), min(q + 2, qmax));
-                if (q + 1 < g.nq) step(o1, o0, t, min(q + 2, qmax), min(q + 3, qmax));
+                step(o0, o1, ta, tb, min(q + 1, qmax), min(q + 2, qmax));
+                if (q + 1 < g.nq) step(o1, o0, tb, ta, min(q + 2, qmax), min(q + 3, qmax));
             }
         };
 
