@@ -1,9 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the MI355X Recurrent Residual Module library.
 
-Default run (the driver's contract): the AlexNet-shaped int8 conv stack of the benchmark's
-configs[1] -- five conv layers with ReLU / requantisation / max-pool between them -- over
-synthetic 32-frame moving-patch sequences for `--streams` independent video streams (chunks
+Default run: the headline workload, an AlexNet-shaped int8 conv stack -- five conv layers with
+ReLU / requantisation / max-pool between them -- over synthetic 32-frame moving-patch sequences for `--streams` independent video streams (chunks
 processed in parallel, Sec. 3.2 of the paper).  One "step" is one frame of every stream through
 the whole stack: per layer one rrm_step (delta + change map, then the tile kernel on changed
 tiles) followed by the harness nonlinearity.  Every 32nd step starts a new sequence, i.e. a frame
@@ -14,7 +13,7 @@ JSON line; everything else goes to stderr.
 
 --sweep additionally times every layer of configs 2-4 (ResNet bf16, FC sparse-delta, binary) over
 their density grids, at one stream (the configs' batch 1: launch-latency bound) and at --sweep-streams
-streams (throughput), and writes gpurun_out/sweep.jsonl plus a table on stderr.
+streams (throughput), and writes sweep.jsonl into the output folder plus a table on stderr.
 """
 from __future__ import annotations
 
