@@ -46,6 +46,15 @@ def _create(shape, dtype, weights=b"\0" * 64, out=True):
                               ctypes.byref(h) if out else None)
 
 
+def test_stats_struct_matches_header_field_order():
+    text = open(os.path.join(ROOT, "include", "rrm.h")).read()
+    body = re.search(r"typedef struct \{([^}]*)\}\s*rrm_stats;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    decl = [(t, n) for t, n in re.findall(r"(uint64_t|int32_t|double)\s+([a-z_]+)\s*;", body)]
+    ctype = {"uint64_t": ctypes.c_uint64, "int32_t": ctypes.c_int32, "double": ctypes.c_double}
+    assert [(n, ctype[t]) for t, n in decl] == list(rrm.binding.Stats._fields_)
+
+
 def test_argument_errors_come_back_as_status_codes():
     L = rrm.lib()
     ok = S.conv_shape(8, 8, 16, 16, 3, 1, 1)
