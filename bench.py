@@ -353,12 +353,14 @@ def cpu_baseline_stack(st, budget_s: float = 12.0):
 # ------------------------------------------------------------------------------------------------
 # sweep over configs 2-4 (one layer at a time)
 # ------------------------------------------------------------------------------------------------
-def time_layer(seq, to_dev, weights, reps: int = 5):
+def time_layer(seq, to_dev, weights, reps: int = 5, eps: float = 0.0):
     """Per-step wall time (graph of one whole sequence, delta and dense path) and event-bracketed
-    kernel times of one layer over its frame sequence."""
+    kernel times of one layer over its frame sequence.  eps: truncation threshold (bf16 layers)."""
     import torch
     import paper_1802_09723_amd as rrm
     L = rrm.Layer(seq.shape, seq.dtype, weights, seq.bias)
+    if eps:
+        L.set_threshold(eps)
     xs = [to_dev(f) for f in seq.frames]
     T = len(xs)
     res = {}
@@ -390,7 +392,8 @@ def time_layer(seq, to_dev, weights, reps: int = 5):
         s1 = L.stats()
         res[f"{tag}_scan_us"], res[f"{tag}_compute_us"] = a / max(n, 1), c / max(n, 1)
         if path == 0:
-            res["stats"] = {k: (s1[k] - s0[k]) / max(n, 1) for k in ("changed_elems", "changed_units", "active_tiles", "total_tiles")}
+            res["stats"] = {k: (s1[k] - s0[k]) / max(n, 1)
+                            for k in ("changed_elems", "changed_units", "active_tiles", "total_tiles", "truncated_elems")}
     L.destroy()
     return res
 
@@ -434,6 +437,35 @@ def run_sweep(args):
                              "roof_bound": "hbm" if (scan_b + tile_b) / HBM_PEAK >= ops / MFMA_PEAK[1] else "mfma",
                              "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]})
                 log("[sweep]", json.dumps(rows[-1]))
+        # The truncation threshold (Sec. 3.3, "Improving sparsity"; the paper's experiments use 1e-2): the same
+        # block-redraw sequences with a little noise on every entry, as a camera would add; without a
+        # threshold every entry changes, with it the noise is truncated.
+        if ns > 1:
+            for layer, hw, c in S.RESNET_LAYERS[:2]:
+                base = S.config2(layer, 0.05, n=ns, T=Tc)
+                rng = S.rng_for(S.seed_for(2, 900) + hw)
+                noisy = [base.frames[0]] + [
+                    S.f32_to_bf16_bits(np.maximum(S.bf16_bits_to_f32(f) + rng.normal(0, 0.0015, size=f.shape).astype(np.float32), 0))
+                    for f in base.frames[1:]]
+                seq = S.Sequence_(base.shape, base.dtype, base.weights, base.bias, noisy, base.name)
+                for eps in (0.0, 1e-2):
+                    r = time_layer(seq, dev_bf16, seq.weights, eps=eps)
+                    sh, stt = seq.shape, r["stats"]
+                    scan_b, tile_b = conv_alg_bytes(sh, 2, stt["changed_units"], stt["active_tiles"], terms=2)
+                    rho_elem = stt["changed_elems"] / (ns * hw * hw * c)
+                    ops = 2 * rho_elem * macs(sh)
+                    kt = r["delta_scan_us"] + r["delta_compute_us"]
+                    roof = max((scan_b + tile_b) / HBM_PEAK, ops / MFMA_PEAK[1]) * 1e6
+                    rows.append({"config": 2, "case": f"{seq.name}_noise_eps{eps:g}{sfx}", "streams": ns, "rho_elem": rho_elem,
+                                 "rho_tile": stt["active_tiles"] / max(stt["total_tiles"], 1), "epsilon": eps,
+                                 "truncated_frac": stt["truncated_elems"] / (ns * hw * hw * c),
+                                 "step_us": r["delta_us"], "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"],
+                                 "compute_us": r["delta_compute_us"], "dense_kernel_us": r["dense_compute_us"],
+                                 "frames_per_s": ns * 1e6 / r["delta_us"], "dense_equiv_gops": 2 * macs(sh) / r["delta_us"] * 1e-3,
+                                 "speedup_vs_dense": r["dense_us"] / r["delta_us"], "alg_bytes": scan_b + tile_b, "roof_us": roof,
+                                 "roof_bound": "hbm" if (scan_b + tile_b) / HBM_PEAK >= ops / MFMA_PEAK[1] else "mfma",
+                                 "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]})
+                    log("[sweep]", json.dumps(rows[-1]))
         # config 3: FC sparse-delta mat-vec
         for layer, ci, co in S.FC_LAYERS:
             for dt, es in ((S.I8, 1), (S.BF16, 2)):
