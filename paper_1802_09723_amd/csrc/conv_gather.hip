@@ -278,7 +278,10 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     // (a workgroup with a sub-tile group of its own: one unit, the group's active sub-tiles)
     const int gx = own_group ? 1 : (int)gridDim.x;
     const int bx = own_group ? 0 : (int)blockIdx.x;
-    int per = (count + gx - 1) / gx;
+    // (several units per workgroup: as many as full-size units would need, but of equal size, so that the
+    // last pass over the grid is not a nearly empty one of full-size units)
+    const int passes = max(1, (count + gx * g.nt - 1) / (gx * g.nt));
+    int per = (count + gx * passes - 1) / (gx * passes);
     if (per < 1) per = 1;
     if (per > g.nt) per = g.nt;
     const int nunits = (count + per - 1) / per;
