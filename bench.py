@@ -70,12 +70,13 @@ class Timer:
 # config 1: the AlexNet-shaped int8 stack
 # ------------------------------------------------------------------------------------------------
 class Stack:
-    def __init__(self, streams: int, T: int = 32):
+    def __init__(self, streams: int, T: int = 32, fuse: bool = True):
         import torch
         import paper_1802_09723_amd as rrm
         import rrm_synth as S
         self.torch, self.rrm, self.S = torch, rrm, S
         self.B, self.T = streams, T
+        self.fuse, self.path = fuse, 0
         seqs = [S.config1(seed=S.seed_for(1, k), n=streams, T=T) for k in range(2)]
         self.cfg = seqs[0]
         self.layers = [rrm.Layer(l["shape"], S.I8, l["weights"], l["bias"]) for l in self.cfg["layers"]]
@@ -118,15 +119,23 @@ class Stack:
     def set_path(self, path: int):
         for L in self.layers:
             L.set_option("path", path)
+        self.path = path
         self.graph = None
 
     def frame(self, x):
-        rrm = self.rrm
+        """One frame of every stream through the stack.  Delta path: conv2-conv5 take their input straight
+        from the stored projection of the layer before (rrm_step_from_projection: f and the difference in
+        one pass, only where that projection changed); the last layer's f, and every f with --no-fuse or on
+        the dense path, is the separate kernel (bufs[i] holds the previous frame's result)."""
+        last = len(self.layers) - 1
         for i, L in enumerate(self.layers):
-            L.step(x)
             n, ho, wo, c, pool = self.meta[i]
-            # f only where the step changed the projection (bufs[i] holds the previous frame's result)
-            L.relu_requant_pool_changed(self.bufs[i], self.shifts[i], pool)
+            if i > 0 and self.fuse and self.path != 2:
+                L.step_from_projection(self.layers[i - 1], self.shifts[i - 1], self.meta[i - 1][4])
+            else:
+                L.step(x)
+            if i == last or not self.fuse or self.path == 2:
+                L.relu_requant_pool_changed(self.bufs[i], self.shifts[i], pool)
             x = self.bufs[i]
 
     def capture(self):
@@ -225,7 +234,7 @@ def measured_traffic(kernel: str, streams: int):
 def run_stack(args):
     import torch
     calibration_copy()
-    st = Stack(args.streams)
+    st = Stack(args.streams, fuse=not args.no_fuse)
     B = st.B
     shapes = [l["shape"] for l in st.cfg["layers"]]
     names = [l["name"] for l in st.cfg["layers"]]
@@ -298,7 +307,7 @@ def run_stack(args):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_delta, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "cfg1_alexnet_conv_stack_int8", "streams": B, "frames_per_sequence": st.T,
-                   "graph_replay": not args.no_graph},
+                   "graph_replay": not args.no_graph, "fused_f": not args.no_fuse},
         "dense_equiv_gops": round(2 * total_macs / (ms_delta * 1e-3) * 1e-9, 1),
         "ms_per_step_dense_path": round(ms_dense, 5),
         "speedup_vs_dense_path": round(ms_dense / ms_delta, 3),
@@ -529,6 +538,8 @@ def main():
     ap.add_argument("--streams", type=int, default=int(os.environ.get("RRM_BENCH_STREAMS", "128")))
     ap.add_argument("--no-graph", action="store_true", help="issue every launch from Python instead of replaying a HIP graph")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--no-fuse", action="store_true",
+                    help="delta path: write every layer's input to memory (separate f kernel) instead of rrm_step_from_projection")
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--sweep-streams", type=int, default=64,
                     help="--sweep times every layer at 1 stream (the configs' batch) and at this many streams")

@@ -141,6 +141,20 @@ rrm_status rrm_set_option(rrm_layer* layer, const char* key, long value);
  * filled) if the sticky range flag is set. */
 rrm_status rrm_get_stats(rrm_layer* layer, rrm_stats* out);
 
+/* rrm_step for a layer whose input is f(P) of the layer before it, without materialising that input
+ * (Algorithm 1: the non-linear map f is applied to the projection and the result is the next layer's
+ * input I).  f is the benchmark's int8 map of rrm_aux_relu_requant_pool_i8: ReLU, arithmetic right shift, clamp
+ * to 127, optional 3x3 / stride-2 max pooling.  Equivalent to rrm_step(layer, f(producer's y_snap), ...), but
+ * an input entry is computed and compared only under the 4x4 blocks of the projection that the producer's last
+ * step wrote: elsewhere neither P nor f(P) changed.  Both layers INT8 convolutions with equal n, layer's c_in ==
+ * producer's c_out (a multiple of 16), layer's (h, w) == the mapped size of the producer's (h_out, w_out).
+ * Call it once after every step of the producer, on the same stream, and feed `layer` through this call
+ * only (its stored input must be the mapped projection of the producer's previous step; a freshly created or
+ * reset `layer` compares everything).  Not available with "path" = 2.
+ * Errors: RRM_ERR_NULL, RRM_ERR_DTYPE, RRM_ERR_SHAPE, RRM_ERR_STATE, RRM_ERR_ALIGN, RRM_ERR_HIP. */
+rrm_status rrm_step_from_projection(rrm_layer* layer, rrm_layer* producer, int shift, int pool, void* y_out,
+                                    void* hip_stream);
+
 /* Truncation threshold of a BF16 layer (Sec. 3.3, "Improving sparsity": small values of the difference are
  * truncated to zero to gain sparsity; the experiments use 1e-2).  An entry with |x_t - x_snap| < epsilon
  * (difference formed in fp32) is not applied to the stored projection and not committed to the stored input,

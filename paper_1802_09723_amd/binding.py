@@ -82,9 +82,10 @@ def lib():
         L.rrm_aux_relu_requant_pool_i8.argtypes = [P, P, I, I, I, I, I, I, P]
         L.rrm_aux_relu_requant_pool_changed_i8.argtypes = [P, P, I, I, P]
         L.rrm_set_threshold.argtypes = [P, ctypes.c_float]
+        L.rrm_step_from_projection.argtypes = [P, P, I, I, P, P]
         for f in ("rrm_layer_create", "rrm_step", "rrm_dense", "rrm_reset", "rrm_snapshot", "rrm_read_snapshot", "rrm_set_option",
                   "rrm_get_stats", "rrm_get_kernel_times", "rrm_aux_relu_requant_pool_i8",
-                  "rrm_aux_relu_requant_pool_changed_i8", "rrm_set_threshold"):
+                  "rrm_aux_relu_requant_pool_changed_i8", "rrm_set_threshold", "rrm_step_from_projection"):
             getattr(L, f).restype = I
         _lib = L
     return _lib
@@ -147,6 +148,11 @@ class Layer:
     # -- the C calls --------------------------------------------------------------------------
     def step(self, x_t, y_out=None, stream=None) -> None:
         _check(lib().rrm_step(self._h, _dptr(x_t), _dptr(y_out), _stream_ptr(stream)))
+
+    def step_from_projection(self, producer: "Layer", shift: int, pool: bool, y_out=None, stream=None) -> None:
+        """``rrm_step_from_projection``: this layer's input is f(producer's stored projection)."""
+        _check(lib().rrm_step_from_projection(self._h, producer._h, int(shift), int(bool(pool)), _dptr(y_out),
+                                              _stream_ptr(stream)))
 
     def dense(self, x, y, stream=None) -> None:
         _check(lib().rrm_dense(self._h, _dptr(x), _dptr(y), _stream_ptr(stream)))

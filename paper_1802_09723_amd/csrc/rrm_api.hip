@@ -679,6 +679,44 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
     return RRM_OK;
 }
 
+rrm_status rrm_step_from_projection(rrm_layer* L, rrm_layer* P, int shift, int pool, void* y_out, void* hip_stream) {
+    if (!L || !P) return fail(RRM_ERR_NULL, "layer / producer is NULL");
+    if (L == P) return fail(RRM_ERR_STATE, "a layer cannot be its own producer");
+    const rrm_shape& s = L->shape;
+    const rrm_shape& ps = P->shape;
+    if (s.kind != RRM_CONV || ps.kind != RRM_CONV || L->dtype != RRM_I8_I32 || P->dtype != RRM_I8_I32 || !P->touched)
+        return fail(RRM_ERR_DTYPE, "rrm_step_from_projection needs two int8 convolution layers");
+    const int hy = P->cg.ho, wy = P->cg.wo;
+    const int hx = pool ? (hy - 3) / 2 + 1 : hy, wx = pool ? (wy - 3) / 2 + 1 : wy;
+    if (shift < 0 || shift > 31 || (pool && (hy < 3 || wy < 3)) || s.n != ps.n || s.c_in != ps.c_out || s.h != hx || s.w != wx)
+        return fail(RRM_ERR_SHAPE, "the producer's projection, mapped by f, does not have this layer's input shape");
+    if (s.c_in % 16 != 0 || L->sg.scatter)
+        return fail(RRM_ERR_SHAPE, "rrm_step_from_projection needs c_in to be a multiple of 16");
+    if (L->opt_path == 2) return fail(RRM_ERR_STATE, "not available with \"path\" = 2: that path needs x_t in memory");
+    if (y_out && (reinterpret_cast<uintptr_t>(y_out) & 15)) return fail(RRM_ERR_ALIGN, "y_out is not 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    FusedSrc src{};
+    src.y = static_cast<const int*>(P->y_snap);
+    src.touched = reinterpret_cast<const unsigned char*>(P->touched);
+    src.hy = hy; src.wy = wy; src.sty = P->sg.sty; src.stx = P->sg.stx;
+    src.shift = shift; src.pool = pool ? 1 : 0;
+    src.all = L->has_snapshot ? 0 : 1;  // a fresh / reset layer holds no f(P) yet: everything is compared
+    rrm_status rs;
+    if ((rs = prof_mark(L, 0, st)) != RRM_OK) return rs;
+    RRM_HIP(launch_scan_fused(src, L->x_snap, L->d0, L->bitmap, L->tileflag, L->sg, L->stats, st));
+    if ((rs = prof_mark(L, 1, st)) != RRM_OK) return rs;
+    RRM_HIP(launch_conv(L->dtype, MODE_DELTA, L->cg.wg_cb, L->cg.nt, 1, L->d0, L->d1, L->zero16, L->tileflag, L->ctrl,
+                        L->wpack, L->offtab, L->bias, L->y_snap, L->cg, L->stats, st));
+    L->touched_all = false;
+    if ((rs = prof_mark(L, 2, st)) != RRM_OK) return rs;
+    ++L->delta_steps;
+    L->total_tiles += (unsigned long long)s.n * L->sg.sty * L->sg.stx;
+    L->has_snapshot = true;
+    ++L->steps;
+    if (y_out) RRM_HIP(launch_copy(y_out, L->y_snap, L->y_bytes, st));
+    return RRM_OK;
+}
+
 rrm_status rrm_dense(rrm_layer* L, const void* x, void* y, void* hip_stream) {
     if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
     rrm_status st = check_ptr(x, "x");

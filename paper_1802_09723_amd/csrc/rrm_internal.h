@@ -51,6 +51,18 @@ struct ScanGeom {
     float eps;  // bf16: truncation threshold of the difference (0 = exact)
 };
 
+// A scan whose input is not a tensor in memory but f(P) of the layer before (Algorithm 1 applies the
+// non-linear map f to the projection and feeds the result to the next layer): ReLU, right shift, clamp to 127
+// and optional 3x3 / 2 max pooling of the producer's stored int32 projection, computed per 16-byte unit, and
+// only under the 4x4 blocks of the projection that the producer's last step wrote.
+struct FusedSrc {
+    const int* y;                 // producer's stored projection [n][hy][wy][c], c = this layer's c_in
+    const unsigned char* touched; // producer's byte flags per 4x4 block of (hy, wy)
+    int hy, wy, sty, stx;
+    int shift, pool;
+    int all;                      // 1: ignore `touched`, every unit is computed and compared
+};
+
 constexpr int CONV_MAX_STAGE_UNITS = 12;  // 16-byte units a thread stages per slab (half for 2 terms)
 
 // Geometry of the gather-tile implicit-GEMM convolution (int8 / bf16 MFMA path).
@@ -131,6 +143,10 @@ struct FcGeom {
 hipError_t launch_scan(int dtype, const void* x_t, void* x_snap, void* d0, void* d1, unsigned long long* bitmap,
                        unsigned int* marks, unsigned int stamp, const ScanGeom& g, DevStats* stats,
                        hipStream_t s);
+// the same scan with the input computed from the producer's projection (int8 layers in the kernel's own
+// layout, c_in a multiple of 16)
+hipError_t launch_scan_fused(const FusedSrc& src, void* x_snap, void* d0, unsigned long long* bitmap, unsigned int* marks,
+                             const ScanGeom& g, DevStats* stats, hipStream_t s);
 
 size_t conv_lds_bytes(const ConvGeom& g, int ncb, int nt, int terms);  // dynamic LDS of the gather kernel
 hipError_t launch_conv(int dtype, int mode, int ncb, int nt, int terms, const void* src0, const void* src1,

@@ -191,13 +191,15 @@ __global__ void repack_word_kernel(const unsigned char* __restrict__ x, unsigned
     dst[r * (unsigned int)g.wp + ix] = word;
 }
 
-template <int DT, bool SCATTER>
+// FUSED: the unit's input is computed from the producer's projection (see FusedSrc); a unit none of whose
+// source blocks was written by the producer's last step cannot have changed and is not even loaded.
+template <int DT, bool SCATTER, bool FUSED>
 __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restrict__ x_t, uint4* __restrict__ x_snap,
                                                    uint4* __restrict__ d0, uint4* __restrict__ d1,
                                                    unsigned long long* __restrict__ bitmap,
                                                    unsigned int* __restrict__ tileflag, unsigned int stamp,
                                                    ScanGeom g, long long nvec, long long total_bytes,
-                                                   DevStats* __restrict__ stats_base) {
+                                                   DevStats* __restrict__ stats_base, FusedSrc fs) {
     const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     DevStats* __restrict__ stats = stats_base + (blockIdx.x & (STAT_SLOTS - 1));
     const unsigned long long prev_mask = v < nvec ? bitmap[v >> 6] : 0ull;  // wave-uniform word
@@ -206,8 +208,56 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
     unsigned int nelem = 0, ntrunc = 0;
     float tsq = 0.f;  // truncated entries of this unit: count and sum of squares (bf16 with a threshold)
     uint4 a = make_uint4(0, 0, 0, 0);
+    bool compare = v < nvec;
+    if (FUSED && compare) {
+        // (c_in is a multiple of 16: the unit is 16 channels of one position)
+        const unsigned int e0 = (unsigned int)v * 16u;
+        const unsigned int p = udiv_big(e0, g.r_c), c0 = e0 - p * (unsigned int)g.c;
+        const unsigned int bb = udiv_big(p, g.r_hw), r = p - bb * (unsigned int)(g.h * g.w);
+        const int iy = (int)udiv_big(r, g.r_w), ix = (int)r - iy * g.w;
+        const int y0 = fs.pool ? 2 * iy : iy, x0 = fs.pool ? 2 * ix : ix, span = fs.pool ? 2 : 0;
+        const unsigned char* t = fs.touched + (size_t)bb * fs.sty * fs.stx;
+        const int sy0 = y0 >> 2, sy1 = (y0 + span) >> 2, sx0 = x0 >> 2, sx1 = (x0 + span) >> 2;
+        compare = fs.all || (t[sy0 * fs.stx + sx0] | t[sy0 * fs.stx + sx1] | t[sy1 * fs.stx + sx0] | t[sy1 * fs.stx + sx1]) != 0;
+        if (compare) {
+            int best[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) best[k] = 0;
+            const int4* yb = reinterpret_cast<const int4*>(fs.y + (((size_t)bb * fs.hy + y0) * fs.wy + x0) * g.c + c0);
+            const size_t c4 = (size_t)g.c / 4;
+            // a row of the window at a time: its (up to) 12 loads are in flight together
+#pragma unroll
+            for (int dy = 0; dy < 3; ++dy) {
+                if (dy > span) break;
+                int4 w[3][4];
+#pragma unroll
+                for (int dx = 0; dx < 3; ++dx)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        w[dx][q] = dx <= span ? yb[(size_t)(dy * fs.wy + dx) * c4 + q] : make_int4(0, 0, 0, 0);
+#pragma unroll
+                for (int dx = 0; dx < 3; ++dx)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        best[4 * q + 0] = max(best[4 * q + 0], w[dx][q].x);
+                        best[4 * q + 1] = max(best[4 * q + 1], w[dx][q].y);
+                        best[4 * q + 2] = max(best[4 * q + 2], w[dx][q].z);
+                        best[4 * q + 3] = max(best[4 * q + 3], w[dx][q].w);
+                    }
+            }
+            // max commutes with the monotone map v -> min(127, max(0, v) >> shift)
+            unsigned int wds[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                wds[q] = (unsigned int)min(127, best[4 * q] >> fs.shift) | (unsigned int)min(127, best[4 * q + 1] >> fs.shift) << 8 |
+                         (unsigned int)min(127, best[4 * q + 2] >> fs.shift) << 16 |
+                         (unsigned int)min(127, best[4 * q + 3] >> fs.shift) << 24;
+            a = make_uint4(wds[0], wds[1], wds[2], wds[3]);
+        }
+    }
     if (v < nvec) {
-        a = load_x_guarded(x_t, v * 16, total_bytes);
+      if (compare) {
+        if (!FUSED) a = load_x_guarded(x_t, v * 16, total_bytes);
         const uint4 b = x_snap[v];
         const unsigned int za = a.x ^ b.x, zb = a.y ^ b.y, zc = a.z ^ b.z, zd = a.w ^ b.w;
         changed = (za | zb | zc | zd) != 0u;
@@ -285,6 +335,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
                 p1 = (int)udiv_big(e1, g.r_c);
             }
         }
+      }  // compare
         if (!changed && ((prev_mask >> (threadIdx.x & 63)) & 1ull)) {
             // changed last step, unchanged now: restore the zero of the difference buffer
             if (!SCATTER) {
@@ -367,9 +418,10 @@ hipError_t launch_scan(int dtype, const void* x_t, void* x_snap, void* d0, void*
     if (blocks <= 0) return hipSuccess;
     dim3 grid((unsigned int)blocks), block(256);
     const unsigned char* xt = static_cast<const unsigned char*>(x_t);
-#define RRM_SCAN(DTV, SC)                                                                                        \
-    hipLaunchKernelGGL((scan_kernel<DTV, SC>), grid, block, 0, s, xt, (uint4*)x_snap, (uint4*)d0, (uint4*)d1, bitmap, \
-                       tileflag, stamp, g, nvec, total_bytes, stats)
+    const FusedSrc none{};
+#define RRM_SCAN(DTV, SC)                                                                                               \
+    hipLaunchKernelGGL((scan_kernel<DTV, SC, false>), grid, block, 0, s, xt, (uint4*)x_snap, (uint4*)d0, (uint4*)d1, bitmap, \
+                       tileflag, stamp, g, nvec, total_bytes, stats, none)
     if (dtype == RRM_I8_I32) {
         if (g.scatter) RRM_SCAN(RRM_I8_I32, true); else RRM_SCAN(RRM_I8_I32, false);
     } else if (dtype == RRM_BF16_F32) {
@@ -378,6 +430,19 @@ hipError_t launch_scan(int dtype, const void* x_t, void* x_snap, void* d0, void*
         RRM_SCAN(RRM_BIN_I32, false);
     }
 #undef RRM_SCAN
+    return hipGetLastError();
+}
+
+hipError_t launch_scan_fused(const FusedSrc& src, void* x_snap, void* d0, unsigned long long* bitmap, unsigned int* marks,
+                             const ScanGeom& g, DevStats* stats, hipStream_t s) {
+    if (g.scatter || g.c % 16 != 0) return hipErrorInvalidValue;
+    const long long total_bytes = g.total_elems;
+    const long long nvec = total_bytes / 16;
+    const long long blocks = (nvec + 255) / 256;
+    if (blocks <= 0) return hipSuccess;
+    hipLaunchKernelGGL((scan_kernel<RRM_I8_I32, false, true>), dim3((unsigned int)blocks), dim3(256), 0, s,
+                       (const unsigned char*)nullptr, (uint4*)x_snap, (uint4*)d0, (uint4*)nullptr, bitmap, marks, 0u, g, nvec,
+                       total_bytes, stats, src);
     return hipGetLastError();
 }
 

@@ -138,3 +138,66 @@ def test_config1_in_the_benchmark_configuration_sampled_streams():
             x = bufs[i]
     for L in layers:
         L.destroy()
+
+
+def _alexnet_parity_fused(n, T, sample=None, groups45=1):
+    """The stack with conv2-conv5 fed through rrm_step_from_projection (the input f(P) of a layer is never
+    written to memory): every layer's stored projection against the oracle, for all or for sampled streams."""
+    import paper_1802_09723_amd as rrm
+    cfg = S.config1(n=n, T=T, groups45=groups45)
+    layers = [rrm.Layer(l["shape"], S.I8, l["weights"], l["bias"]) for l in cfg["layers"]]
+    streams = list(range(n)) if sample is None else list(sample)
+    shapes1 = [l["shape"].with_n(1) for l in cfg["layers"]]
+    shifts = None
+    for t, frame in enumerate(cfg["frames"]):
+        want = {}
+        for s in streams:
+            x = np.ascontiguousarray(frame[s:s + 1])
+            for i, l in enumerate(cfg["layers"]):
+                y = oracle.dense(shapes1[i], S.I8, l["weights"], l["bias"], x)
+                if shifts is None or len(shifts) <= i:
+                    shifts = (shifts or []) + [oracle.calibrate_shift(y)]
+                want[(s, i)] = y
+                x = oracle.relu_requant_pool(y, shifts[i], l["pool"])
+        for i, (l, L) in enumerate(zip(cfg["layers"], layers)):
+            if i == 0:
+                L.step(to_device(frame, S.I8))
+            else:
+                L.step_from_projection(layers[i - 1], shifts[i - 1], cfg["layers"][i - 1]["pool"])
+            got = L.y_snapshot()
+            for s in streams:
+                assert_matches(got[s:s + 1].cpu().numpy(), want[(s, i)], S.I8, f"frame {t} {l['name']} stream {s}")
+    stats = [L.stats() for L in layers]
+    for L in layers:
+        L.destroy()
+    return stats
+
+
+def test_config1_stack_through_fused_steps():
+    _alexnet_parity_fused(n=1, T=4)
+    _alexnet_parity_fused(n=2, T=3, groups45=2)
+
+
+def test_config1_stack_through_fused_steps_benchmark_configuration():
+    _alexnet_parity_fused(n=128, T=3, sample=(0, 57, 127))
+
+
+def test_fused_step_after_reset_compares_everything():
+    import paper_1802_09723_amd as rrm
+    cfg = S.config1(n=1, T=3)
+    l0, l1 = cfg["layers"][0], cfg["layers"][1]
+    A = rrm.Layer(l0["shape"], S.I8, l0["weights"], l0["bias"])
+    B = rrm.Layer(l1["shape"], S.I8, l1["weights"], l1["bias"])
+    shift = None
+    for t, frame in enumerate(cfg["frames"]):
+        y0 = oracle.dense(l0["shape"], S.I8, l0["weights"], l0["bias"], frame)
+        shift = oracle.calibrate_shift(y0) if shift is None else shift
+        x1 = oracle.relu_requant_pool(y0, shift, l0["pool"])
+        A.step(to_device(frame, S.I8))
+        if t == 1:
+            B.reset()  # the consumer forgets its input: the next fused step must not trust the producer's flags
+        B.step_from_projection(A, shift, l0["pool"])
+        want = oracle.dense(l1["shape"], S.I8, l1["weights"], l1["bias"], x1)
+        assert_matches(B.y_snapshot().cpu().numpy(), want, S.I8, f"frame {t}")
+    A.destroy()
+    B.destroy()
