@@ -200,7 +200,11 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
                                                    unsigned int* __restrict__ tileflag, unsigned int stamp,
                                                    ScanGeom g, long long nvec, long long total_bytes,
                                                    DevStats* __restrict__ stats_base, FusedSrc fs) {
-    const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    // FUSED: neighbouring workgroups read overlapping rows of the producer's projection (pooling windows), and
+    // consecutive workgroup ids go to different XCDs, each with an L2 of its own: the grid is a multiple of 8
+    // and workgroup id i works on block (i % 8) * (grid / 8) + i / 8, so that an XCD gets a contiguous range.
+    const unsigned int blk = FUSED ? (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
+    const long long v = (long long)blk * blockDim.x + threadIdx.x;
     DevStats* __restrict__ stats = stats_base + (blockIdx.x & (STAT_SLOTS - 1));
     const unsigned long long prev_mask = v < nvec ? bitmap[v >> 6] : 0ull;  // wave-uniform word
     bool changed = false;
@@ -209,6 +213,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
     float tsq = 0.f;  // truncated entries of this unit: count and sum of squares (bf16 with a threshold)
     uint4 a = make_uint4(0, 0, 0, 0);
     bool compare = v < nvec;
+    uint4 b_early = make_uint4(0, 0, 0, 0);
     if (FUSED && compare) {
         // (c_in is a multiple of 16: the unit is 16 channels of one position)
         const unsigned int e0 = (unsigned int)v * 16u;
@@ -220,6 +225,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
         const int sy0 = y0 >> 2, sy1 = (y0 + span) >> 2, sx0 = x0 >> 2, sx1 = (x0 + span) >> 2;
         compare = fs.all || (t[sy0 * fs.stx + sx0] | t[sy0 * fs.stx + sx1] | t[sy1 * fs.stx + sx0] | t[sy1 * fs.stx + sx1]) != 0;
         if (compare) {
+            b_early = x_snap[v];  // in flight together with the window's loads
             int best[16];
 #pragma unroll
             for (int k = 0; k < 16; ++k) best[k] = 0;
@@ -258,7 +264,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
     if (v < nvec) {
       if (compare) {
         if (!FUSED) a = load_x_guarded(x_t, v * 16, total_bytes);
-        const uint4 b = x_snap[v];
+        const uint4 b = FUSED ? b_early : x_snap[v];
         const unsigned int za = a.x ^ b.x, zb = a.y ^ b.y, zc = a.z ^ b.z, zd = a.w ^ b.w;
         changed = (za | zb | zc | zd) != 0u;
         if (changed) {
@@ -438,7 +444,7 @@ hipError_t launch_scan_fused(const FusedSrc& src, void* x_snap, void* d0, unsign
     if (g.scatter || g.c % 16 != 0) return hipErrorInvalidValue;
     const long long total_bytes = g.total_elems;
     const long long nvec = total_bytes / 16;
-    const long long blocks = (nvec + 255) / 256;
+    const long long blocks = ((nvec + 255) / 256 + 7) / 8 * 8;  // a multiple of the 8 XCDs (see the kernel)
     if (blocks <= 0) return hipSuccess;
     hipLaunchKernelGGL((scan_kernel<RRM_I8_I32, false, true>), dim3((unsigned int)blocks), dim3(256), 0, s,
                        (const unsigned char*)nullptr, (uint4*)x_snap, (uint4*)d0, (uint4*)nullptr, bitmap, marks, 0u, g, nvec,
