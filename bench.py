@@ -257,10 +257,18 @@ def run_stack(args):
     total_macs = sum(macs(s) for s in shapes)  # for all B streams, one frame each
     layers = []
     dom = None
+    prev = None  # (shape, active sub-tiles per step) of the layer before
     for nm, sh, p, pd in zip(names, shapes, prof, prof_dense):
         n = max(p["steps"], 1)
         cu, at = p["changed_units"] / n, p["active_tiles"] / n
         scan_b, tile_b = conv_alg_bytes(sh, 1, cu, at)
+        if prev is not None and st.fuse:
+            # fused scan: the producer's written 4x4 blocks are read once (int32), the stored input is read
+            # only under them (about the same share of it), changed units are written twice
+            psh, pat = prev
+            share = pat / (psh.n * ((psh.h_out + 3) // 4) * ((psh.w_out + 3) // 4))
+            scan_b = pat * 16 * psh.c_out * 4 + share * sh.n * sh.h * sh.w * sh.c_in + cu * 32
+        prev = (sh, at)
         rho_elem = p["changed_elems"] / n / (sh.n * sh.h * sh.w * sh.c_in)
         rho_tile = p["active_tiles"] / max(p["total_tiles"], 1)
         ops_alg = 2 * rho_elem * macs(sh)
