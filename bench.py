@@ -543,7 +543,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=320)
     ap.add_argument("--warmup", type=int, default=32)
-    ap.add_argument("--streams", type=int, default=int(os.environ.get("RRM_BENCH_STREAMS", "128")))
+    ap.add_argument("--streams", type=int, default=int(os.environ.get("RRM_BENCH_STREAMS", "512")))
     ap.add_argument("--no-graph", action="store_true", help="issue every launch from Python instead of replaying a HIP graph")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--no-fuse", action="store_true",

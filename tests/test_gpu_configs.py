@@ -100,12 +100,12 @@ def test_config4_binary(layer, frac):
 
 
 def test_config1_in_the_benchmark_configuration_sampled_streams():
-    """The stack as bench.py runs it (128 streams, incremental nonlinearity): every layer of three sampled
+    """The stack as bench.py runs it (512 streams, incremental nonlinearity): every layer of three sampled
     streams against the oracle on every frame, and every stream against the library's own dense projection
     of the same input (a property that holds at any size)."""
     import torch
     import paper_1802_09723_amd as rrm
-    n, T, sample = 128, 3, (0, 57, 127)
+    n, T, sample = 512, 3, (0, 257, 511)
     cfg = S.config1(n=n, T=T)
     layers = [rrm.Layer(l["shape"], S.I8, l["weights"], l["bias"]) for l in cfg["layers"]]
     shapes1 = [l["shape"].with_n(1) for l in cfg["layers"]]
@@ -179,7 +179,7 @@ def test_config1_stack_through_fused_steps():
 
 
 def test_config1_stack_through_fused_steps_benchmark_configuration():
-    _alexnet_parity_fused(n=128, T=3, sample=(0, 57, 127))
+    _alexnet_parity_fused(n=512, T=3, sample=(0, 257, 511))
 
 
 def test_fused_step_after_reset_compares_everything():
