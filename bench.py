@@ -83,7 +83,6 @@ class Stack:
         # frames of two different sequences back to back: 0..T-1 of A, 0..T-1 of B
         self.frames = [torch.from_numpy(f).cuda() for s in seqs for f in s["frames"]]
         self.host_frames = [f for s in seqs for f in s["frames"]]
-        self.xin = self.frames[0].clone()  # static graph input; always holds a valid frame
         self.bufs, self.meta = [], []
         for l, L in zip(self.cfg["layers"], self.layers):
             sh = l["shape"]
@@ -139,20 +138,25 @@ class Stack:
             x = self.bufs[i]
 
     def capture(self):
+        """One HIP graph per frame of the two sequences: a step reads its frame where it lies in HBM (a single
+        graph with a static input would add a copy of every frame to every step)."""
         torch = self.torch
-        self.frame(self.xin)  # make sure nothing lazy happens inside the capture
+        self.frame(self.frames[0])  # make sure nothing lazy happens inside the captures
         torch.cuda.synchronize()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            self.frame(self.xin)
-        self.graph = g
+        self.graph = []
+        pool = None
+        for f in self.frames:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, pool=pool):
+                self.frame(f)
+            pool = pool or g.pool()
+            self.graph.append(g)
 
     def run_steps(self, k0: int, K: int, use_graph: bool):
         nf = len(self.frames)
         for k in range(k0, k0 + K):
             if use_graph:
-                self.xin.copy_(self.frames[k % nf], non_blocking=True)
-                self.graph.replay()
+                self.graph[k % nf].replay()
             else:
                 self.frame(self.frames[k % nf])
 
