@@ -99,11 +99,11 @@ __device__ __forceinline__ int fdiv(int u, unsigned int magic) {
 
 #ifdef RRM_TRACE
 // debug build only: cycle stamps of workgroup (0,0) (lane 0 of the first producer / consumer wavefront) into
-// the spare stats slots
+// the slots behind the counters
 #define RRM_STAMP(k)                                                                                \
     do {                                                                                            \
         if (blockIdx.x == 0 && blockIdx.y == 0 && lane == 0 && (wave == 0 || wave == 4))            \
-            reinterpret_cast<unsigned long long*>(stats + 32)[k] = __builtin_readcyclecounter();    \
+            reinterpret_cast<unsigned long long*>(stats + STAT_SLOTS)[k] = __builtin_readcyclecounter();    \
     } while (0)
 #else
 #define RRM_STAMP(k) do {} while (0)
@@ -144,6 +144,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     __shared__ int s_iy0[4][NT];             //   (wraps when the origin is in the padding) and the origin itself
     __shared__ int s_ix0[4][NT];
     __shared__ int s_scan[CONV_THREADS / WAVE];
+    __shared__ int s_excl[CONV_THREADS];     // per producer thread: set flags before its share, within its wavefront
     __shared__ int s_last;
 
     const int tid = threadIdx.x;
@@ -213,8 +214,28 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     // ranking walks a thread's set bits one by one.  (Then gpt == 1.)
     const int fpt = g.n_sub <= CONV_THREADS ? 1 : g.n_sub <= 4 * CONV_THREADS ? 4 : g.n_sub <= 16 * CONV_THREADS ? 16 : 64;
     auto nib = [](unsigned int w) { return ((w & LOW) * 0x01020408u) >> 24; };  // byte flags of a word -> 4 bits
-    unsigned long long fm0 = 0;
-    int count, excl = 0, mine = 0;
+    // The k-th 64-flag mask of (producer) thread t's share of the flag array, and the sub-tile of its bit 0.
+    auto thread_mask = [&](int t, int k, int& id0) -> unsigned long long {
+        if (fpt == 1) {
+            id0 = t;
+            return t < g.n_sub ? (unsigned long long)(reinterpret_cast<const unsigned char*>(flags)[t] & 1u) : 0ull;
+        }
+        if (fpt == 4) {
+            id0 = 4 * t;
+            return t < g.n_words ? (unsigned long long)nib(flags[t]) : 0ull;
+        }
+        if (fpt == 16) {
+            id0 = 16 * t;
+            if (t >= n_vec) return 0ull;
+            const uint4 v = fvp[t];
+            return (unsigned long long)(nib(v.x) | nib(v.y) << 4 | nib(v.z) << 8 | nib(v.w) << 12);
+        }
+        const int gi = t * gpt + k;
+        id0 = 64 * gi;
+        return gi < n_grp ? load_group(gi) : 0ull;
+    };
+    const int masks_per_thread = fpt == 64 ? gpt : 1;
+    int count, mine = 0;
     // Few sub-tiles in all (one stream of a small map: at most 256, and every group of nt consecutive sub-tiles
     // has a workgroup of its own in the grid): the launch is latency bound, so there is no global list.  A workgroup reads
     // the flags of its own group only, compacts them with one ballot, and is done after one barrier.
@@ -231,21 +252,17 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         count = s_scan[0];
     } else if (MODE == MODE_DELTA) {
         if (producer) {
-            if (fpt == 1) {
-                fm0 = tid < g.n_sub ? (unsigned long long)(reinterpret_cast<const unsigned char*>(flags)[tid] & 1u) : 0ull;
-            } else if (fpt == 4) {
-                fm0 = tid < g.n_words ? (unsigned long long)nib(flags[tid]) : 0ull;
-            } else if (fpt == 16) {
-                if (tid < n_vec) {
-                    const uint4 v = fvp[tid];
-                    fm0 = (unsigned long long)(nib(v.x) | nib(v.y) << 4 | nib(v.z) << 8 | nib(v.w) << 12);
+            // (four masks at a time: their loads are in flight together)
+            for (int k0 = 0; k0 < masks_per_thread; k0 += 4) {
+                unsigned long long m[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    int id0;
+                    m[k] = k0 + k < masks_per_thread ? thread_mask(tid, k0 + k, id0) : 0ull;
                 }
-            } else if (g_lo < n_grp) {
-                fm0 = load_group(g_lo);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) mine += __popcll(m[k]);
             }
-            mine = __popcll(fm0);
-            for (int i = 1; i < gpt; ++i)
-                if (g_lo + i < n_grp) mine += __popcll(load_group(g_lo + i));
             // popcount prefix sum (every workgroup does the same small scan)
             int incl = mine;
 #pragma unroll
@@ -254,12 +271,10 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
                 if (lane >= o) incl += t;
             }
             if (lane == 63) s_scan[wave] = incl;
-            excl = incl - mine;
+            s_excl[tid] = incl - mine;  // set flags before this thread's, within its wavefront
         }
         __syncthreads();
         count = s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3];
-        if (producer)
-            for (int w = 0; w < wave; ++w) excl += s_scan[w];
     } else {
         count = g.n_sub;
     }
@@ -347,31 +362,49 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     // ---- ranking round: the sub-tile ids of units r0 .. r1-1 of this workgroup go to s_list ------------
     if (MODE == MODE_DELTA) {
         if (r0 > 0) __syncthreads();  // the previous round's list is no longer in use
-        if (mine > 0 && listed && !own_group) {  // (own_group: the list was made with the count)
-            // The rank of a set flag is the number of set flags before it; rank = unit*per + k.  The unit,
-            // its index i among this workgroup's units ((unit - blockIdx.x) / gx when that divides) and k are
-            // stepped along with the rank.
-            int u = excl / per, k = excl - u * per;
-            const int d = u - bx;
-            int i = d >= 0 ? d / gx : -1 - ((-d - 1) / gx);
-            int um = d - i * gx;  // 0 <=> the unit is this workgroup's i-th
-            auto take = [&](unsigned long long m, int id0) {  // id0: sub-tile of bit 0
-                while (m) {
-                    const int bpos = __ffsll((long long)m) - 1;
-                    m &= m - 1;
-                    if (um == 0 && i >= r0 && i < r1) s_list[(i - r0) * per + k] = id0 + bpos;
-                    if (++k == per) {
-                        k = 0;
-                        if (++um == gx) {
-                            um = 0;
-                            ++i;
+        if (listed && !own_group) {  // (own_group: the list was made with the count)
+            // The rank of a set flag is the number of set flags before it; this workgroup owns the ranks
+            // unit*per .. unit*per + per - 1 of its units blockIdx.x + i*gx, i = r0 .. r1-1.  Every producer
+            // thread looks its share of those ranks up: which thread's flags hold the rank (binary search in
+            // the prefix counts), then which of that thread's set bits it is.  Nobody walks a long run of bits.
+            const int n_owned = (r1 - r0) * per;
+            for (int jj = tid; jj < n_owned; jj += CONV_THREADS) {
+                const int iu = jj / per, kk = jj - iu * per;
+                const int t = (bx + (r0 + iu) * gx) * per + kk;  // the rank
+                if (t >= count) continue;
+                int w = 0, lt = t;  // wavefront holding the rank, rank within it
+                while (lt >= s_scan[w]) lt -= s_scan[w++];
+                int lo = 0, hi = WAVE - 1;  // last thread of the wavefront with s_excl <= lt
+                while (lo < hi) {
+                    const int mid = (lo + hi + 1) >> 1;
+                    if (s_excl[w * WAVE + mid] <= lt) lo = mid;
+                    else hi = mid - 1;
+                }
+                const int owner = w * WAVE + lo;
+                int lr = lt - s_excl[owner];  // rank among the owner's flags
+                int id = -1;
+                for (int k0 = 0; k0 < masks_per_thread && id < 0; k0 += 4) {
+                    unsigned long long m[4];
+                    int id0[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        id0[k] = 0;
+                        m[k] = k0 + k < masks_per_thread ? thread_mask(owner, k0 + k, id0[k]) : 0ull;
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int pc = (int)__popcll(m[k]);
+                        if (id < 0 && lr < pc) {
+                            unsigned long long mm = m[k];
+                            while (lr-- > 0) mm &= mm - 1;  // drop the lr lowest set bits
+                            id = id0[k] + __ffsll((long long)mm) - 1;
+                        } else if (id < 0) {
+                            lr -= pc;
                         }
                     }
                 }
-            };
-            take(fm0, fpt < 64 ? tid * fpt : g_lo * 64);
-            for (int q = 1; q < gpt; ++q)
-                if (g_lo + q < n_grp) take(load_group(g_lo + q), (g_lo + q) * 64);
+                s_list[jj] = id;
+            }
         }
         __syncthreads();  // the list is published
     } else if (r0 == 0) {

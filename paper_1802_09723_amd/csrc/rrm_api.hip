@@ -379,13 +379,13 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
         cands = {{2, 16}, {2, 8}, {1, 16}, {1, 8}, {1, 4}};
     }
     bool ok = false;
-    // (the kernel's static LDS, about 5 KB, comes on top of the dynamic budget; 160 KB per workgroup in all)
-    long long first_budget = (small ? 96ll : 154ll) * 1024;
+    // (the kernel's static LDS, about 6 KB, comes on top of the dynamic budget; 160 KB per workgroup in all)
+    long long first_budget = (small ? 96ll : 153ll) * 1024;
     if (const char* env = std::getenv("RRM_CONV_LDS_KB")) {  // tuning knob: preferred LDS bytes per workgroup
         const long long kb = std::atoll(env);
-        if (kb >= 16 && kb <= 154) first_budget = kb * 1024;
+        if (kb >= 16 && kb <= 153) first_budget = kb * 1024;
     }
-    for (long long budget : {first_budget, 154ll * 1024}) {
+    for (long long budget : {first_budget, 153ll * 1024}) {
         for (const Cand& c : cands) {
             ConvGeom t = g;
             // a slab should hold at least 4 chunks (or all of them) to amortise its barriers
@@ -399,7 +399,7 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     }
     if (!ok)
         for (const Cand& c : cands)
-            if (!ok) ok = conv_try_shape(g, terms, c.cb, c.nt, ntaps, 154 * 1024);
+            if (!ok) ok = conv_try_shape(g, terms, c.cb, c.nt, ntaps, 153 * 1024);
     if (!ok) return fail(RRM_ERR_SHAPE, "input window of one output sub-tile does not fit LDS");
     return pack_conv(L, w);
 }
@@ -563,7 +563,8 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
 
     if ((st = dalloc(L->x_bytes, &L->x_snap)) != RRM_OK) return bail(st);
     if ((st = dalloc(L->y_bytes, &L->y_snap)) != RRM_OK) return bail(st);
-    if ((st = dalloc(sizeof(DevStats) * STAT_SLOTS, (void**)&L->stats)) != RRM_OK) return bail(st);
+    // (a debug build keeps cycle stamps behind the counters: STAT_TRACE_SLOTS more slots)
+    if ((st = dalloc(sizeof(DevStats) * (STAT_SLOTS + STAT_TRACE_SLOTS), (void**)&L->stats)) != RRM_OK) return bail(st);
     if (s.kind == RRM_CONV) {
         ScanGeom& sg = L->sg;
         sg.total_elems = L->x_elems;
@@ -848,9 +849,9 @@ rrm_status rrm_get_kernel_times(rrm_layer* L, double* scan_us, double* compute_u
 }
 
 #ifdef RRM_TRACE
-// debug build only: raw copy of the device statistics block
+// debug build only: raw copy of the cycle stamps kept behind the statistics slots
 rrm_status rrm_debug_raw_stats(rrm_layer* L, void* dst, size_t bytes) {
-    RRM_HIP(hipMemcpy(dst, L->stats, bytes < sizeof(DevStats) * STAT_SLOTS ? bytes : sizeof(DevStats) * STAT_SLOTS,
+    RRM_HIP(hipMemcpy(dst, L->stats + STAT_SLOTS, bytes < sizeof(DevStats) * STAT_TRACE_SLOTS ? bytes : sizeof(DevStats) * STAT_TRACE_SLOTS,
                       hipMemcpyDeviceToHost));
     return RRM_OK;
 }

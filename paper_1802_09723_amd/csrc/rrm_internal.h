@@ -19,6 +19,7 @@ enum Mode : int { MODE_DELTA = 0, MODE_DENSE = 1 };
 // (a workgroup uses slot blockIdx.x % STAT_SLOTS) so that same-address atomics do not serialise
 // the scan; rrm_get_stats sums them.
 constexpr int STAT_SLOTS = 256;
+constexpr int STAT_TRACE_SLOTS = 32;  // room behind the counters for a debug build's cycle stamps
 struct DevStats {
     unsigned long long changed_elems;
     unsigned long long changed_units;
