@@ -285,6 +285,8 @@ def test_random_fc_shapes(idx):
     # units per workgroup, densities below and above the recomputation switch
     (13, 64, 128, 3, 1, 20, 0.10), (13, 64, 128, 3, 1, 64, 0.30), (13, 96, 64, 3, 2, 100, 0.05),
     (27, 32, 64, 5, 1, 100, 0.15), (13, 64, 128, 3, 1, 64, 0.90),
+    # exactly 256 and 4096 sub-tiles: the borders between the ways the flag array is split over threads
+    (13, 64, 64, 3, 1, 16, 0.30), (13, 64, 64, 3, 1, 256, 0.10),
 ])
 @pytest.mark.parametrize("dt", [S.I8, S.BF16])
 def test_many_streams_mid_size(case, dt):
