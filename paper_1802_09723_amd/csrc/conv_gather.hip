@@ -109,6 +109,10 @@ __device__ __forceinline__ int fdiv(int u, unsigned int magic) {
 #define RRM_STAMP(k) do {} while (0)
 #endif
 
+// Workgroup barrier that publishes LDS contents only: it waits for this wavefront's LDS operations, not for its
+// outstanding global loads (__syncthreads() would also wait for the copies into LDS that were started early).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 typedef const void __attribute__((address_space(1))) * gptr_t;
 typedef void __attribute__((address_space(3))) * lptr_t;
 
@@ -171,18 +175,22 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         }
     };
     RRM_STAMP(producer ? 0 : 40);
-    // The first weight slab does not depend on the work list: its copy starts at once.  So do the loads
-    // of this thread's rows of the staging table, which serve every unit.
-    if (producer) stage_weights(0, 0);
+    // The first weight slab and this thread's rows of the staging table (which serve every unit) do not
+    // depend on the work list.  A dense launch starts their loads at once; a delta launch after the loads
+    // of the list phase, which would otherwise queue behind them (loads return in order), and not at all in
+    // a workgroup that gets no unit.
     const int2* utab = reinterpret_cast<const int2*>(offtab) + g.nq * 4;
     int2 ut[MAXU];
-    if (producer) {
+    auto early_loads = [&]() {
+        if (!producer) return;
+        stage_weights(0, 0);
 #pragma unroll
         for (int i = 0; i < MAXU; ++i) {
             const int v = tid + i * CONV_THREADS;
             ut[i] = v < g.nt * g.wpos * g.sc ? utab[v] : int2{0, 0};
         }
-    }
+    };
+    if (MODE == MODE_DENSE) early_loads();
     for (int e = tid; e < g.nq * 4; e += WG_THREADS)  // K-pair table, the same for every slab
         tab[e] = reinterpret_cast<const int2*>(offtab)[e];
 
@@ -248,7 +256,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             if (f) s_list[__popcll(m & ((1ull << lane) - 1ull))] = id;
             if (lane < 4) s_scan[lane] = lane == 0 ? (int)__popcll(m) : 0;
         }
-        __syncthreads();
+        lds_barrier();
         count = s_scan[0];
     } else if (MODE == MODE_DELTA) {
         if (producer) {
@@ -273,7 +281,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             if (lane == 63) s_scan[wave] = incl;
             s_excl[tid] = incl - mine;  // set flags before this thread's, within its wavefront
         }
-        __syncthreads();
+        lds_barrier();
         count = s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3];
     } else {
         count = g.n_sub;
@@ -406,9 +414,10 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
                 s_list[jj] = id;
             }
         }
-        __syncthreads();  // the list is published
+        if (r0 == 0) early_loads();
+        lds_barrier();  // the list is published
     } else if (r0 == 0) {
-        __syncthreads();  // (the K-pair table is published)
+        lds_barrier();  // (the K-pair table is published)
     }
 
 
@@ -555,9 +564,9 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     // the barriers of the ranking round
     if (MODE == MODE_DELTA) {
         if (r0 > 0) __syncthreads();
-        __syncthreads();
+        lds_barrier();
     } else if (r0 == 0) {
-        __syncthreads();
+        lds_barrier();
     }
     begin_unit(r0, r0);
     for (int iu = r0; iu < r1; ++iu) {
