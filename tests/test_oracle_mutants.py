@@ -13,7 +13,7 @@ import pytest
 
 import oracle
 import rrm_synth as S
-from test_oracle_pins import SHAPES, STEP_SHAPES, _torch_conv
+from test_oracle_pins import SHAPES, STEP_SHAPES, _torch_conv, test_float_fc_matches_numpy_matvec
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "rrm_oracle.c")
 
@@ -31,6 +31,16 @@ MUTANTS = {
 }
 MUTANTS["weight_taps_swapped"] = ("const int8_t* wp = wt + (((size_t)o * s->kh + ky) * s->kw + kx) * cg;",
                                   "const int8_t* wp = wt + (((size_t)o * s->kh + kx) * s->kw + ky) * cg;")
+# floating-point FC branches (a mutant may be a list of replacements applied together)
+_FC_DENSE_F64 = ("acc += wt[(size_t)o * s->c_in + j] * x[(size_t)b * s->c_in + j];",
+                 "acc += wt[(size_t)j * s->c_out + o] * x[(size_t)b * s->c_in + j];")
+_FC_STEP_F64 = ("p_prev[(size_t)b * s->c_out + o] += d * wt[(size_t)o * s->c_in + j];",
+                "p_prev[(size_t)b * s->c_out + o] += d * wt[(size_t)j * s->c_out + o];")
+MUTANTS["fc_f64_dense_transposed"] = _FC_DENSE_F64
+MUTANTS["fc_f64_step_transposed"] = _FC_STEP_F64
+MUTANTS["fc_f64_both_transposed"] = [_FC_DENSE_F64, _FC_STEP_F64]
+MUTANTS["fc_f64_bias_dropped"] = ("double acc = bias ? bias[o] : 0.0;\n                for (int j", "double acc = 0.0;\n                for (int j")
+MUTANTS["step_f64_sign"] = ("const double d = x_t[xi] - i_prev[xi];", "const double d = i_prev[xi] - x_t[xi];")
 
 
 def _pin_set():
@@ -45,11 +55,23 @@ def _pin_set():
     wt = S.draw_i8_weight(rng, (4, 4))
     x = S.draw_i8_act(rng, (1, 4))
     assert np.array_equal(oracle.dense(S.fc_shape(4, 4), S.I8, wt, None, x), x.astype(np.int64) @ wt.astype(np.int64).T)
-    for shp, dt in STEP_SHAPES[:5]:
+    for shp, dt in STEP_SHAPES:
         seq = S.random_layer(900 + shp.c_in, shp, dt, T=3, frac=0.25, block=2)
         st = oracle.State(shp, dt, seq.weights, seq.bias)
         for xx in seq.frames:
-            assert np.array_equal(st.step(xx), oracle.dense(shp, dt, seq.weights, seq.bias, xx))
+            p, d = st.step(xx), oracle.dense(shp, dt, seq.weights, seq.bias, xx)
+            if dt == S.BF16:
+                assert np.allclose(p, d, rtol=0, atol=1e-10 * max(1.0, np.abs(d).max()))
+            else:
+                assert np.array_equal(p, d)
+    # floating-point dense convolution against the library routine, FC branches against numpy
+    for shp in SHAPES[:2]:
+        rng = S.rng_for(200 + shp.h)
+        w = S.draw_bf16_weight(rng, shp.w_shape)
+        x = S.draw_bf16_relu(rng, shp.x_shape)
+        ref = _torch_conv(shp, oracle.bf16_to_f64(w), None, oracle.bf16_to_f64(x))
+        assert np.allclose(oracle.dense(shp, S.BF16, w, None, x), ref, rtol=1e-12, atol=1e-12)
+    test_float_fc_matches_numpy_matvec()
 
 
 def test_pin_set_passes_on_the_real_oracle():
@@ -58,10 +80,13 @@ def test_pin_set_passes_on_the_real_oracle():
 
 @pytest.mark.parametrize("name", sorted(MUTANTS))
 def test_pins_catch_planted_mistake(name, tmp_path, monkeypatch):
-    old, new = MUTANTS[name]
-    src = open(SRC).read()
-    assert src.count(old) >= 1, f"mutation site for {name} not found"
-    mutated = src.replace(old, new, 1)
+    edits = MUTANTS[name]
+    if isinstance(edits, tuple):
+        edits = [edits]
+    mutated = open(SRC).read()
+    for old, new in edits:
+        assert mutated.count(old) >= 1, f"mutation site for {name} not found"
+        mutated = mutated.replace(old, new, 1)
     c = tmp_path / "mut.c"
     so = tmp_path / "mut.so"
     c.write_text(mutated)

@@ -93,6 +93,35 @@ def test_special_cases_reduce_to_matvec():
     assert np.array_equal(full.reshape(2, co), ref2)
 
 
+def test_float_fc_matches_numpy_matvec():
+    """The floating-point FC branches (Eq. 3 in FC form; Algorithm 1, FC branch) against numpy's float64
+    matrix product on a non-square layer with two streams and a bias: the dense projection of every
+    frame and every frame of the recurrence.  A transposed weight index, in either branch or in both
+    at once, fails here (the layer is not square, so W and W^T index different entries)."""
+    rng = S.rng_for(6)
+    ci, co, n = 45, 13, 2
+    shp = S.fc_shape(ci, co, n)
+    wt = S.draw_bf16_weight(rng, (co, ci))
+    b = rng.normal(size=(co,)).astype(np.float32)
+    W = oracle.bf16_to_f64(wt)
+    st = oracle.State(shp, S.BF16, wt, b)
+    x_prev = np.zeros((n, ci))
+    for t in range(4):
+        x = S.draw_bf16_relu(rng, (n, ci))
+        if t:  # keep most entries so that the step is a genuine sparse difference
+            keep = rng.random((n, ci)) < 0.7
+            x = np.where(keep, prev_bits, x).astype(np.uint16)
+        prev_bits = x
+        xv = oracle.bf16_to_f64(x)
+        ref = xv @ W.T + b.astype(np.float64)
+        d = oracle.dense(shp, S.BF16, wt, b, x)
+        assert np.allclose(d, ref, rtol=1e-13, atol=1e-13)
+        p = st.step(x)
+        assert np.allclose(p, ref, rtol=0, atol=1e-11 * max(1.0, np.abs(ref).max()))
+        assert st.last_nnz == int((xv != x_prev).sum())
+        x_prev = xv
+
+
 # ------------------------------------------------------------------------------------------
 # Eq. 3, dense: an independent library routine (float64 is exact for these integers)
 # ------------------------------------------------------------------------------------------
