@@ -458,7 +458,7 @@ def run_sweep(args):
                              "roof_bound": "hbm" if (scan_b + tile_b) / HBM_PEAK >= ops / MFMA_PEAK[1] else "mfma",
                              "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]})
                 log("[sweep]", json.dumps(rows[-1]))
-        # The truncation threshold (Sec. 3.3, "Improving sparsity"; the paper's experiments use 1e-2): the same
+        # The truncation threshold (Sec. 3.4, "Improving sparsity"; the paper's experiments use 1e-2): the same
         # block-redraw sequences with a little noise on every entry, as a camera would add; without a
         # threshold every entry changes, with it the noise is truncated.
         if ns > 1:

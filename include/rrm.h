@@ -74,10 +74,12 @@ typedef struct {
     int n, h, w, c_in, c_out, kh, kw, stride, pad, groups;
 } rrm_shape;
 
-/* Counters of a handle.  All are totals since creation or the last rrm_reset. */
+/* Counters of a handle.  All are totals since creation or the last rrm_reset.  `steps` is counted by the host
+ * when a call is enqueued (a captured graph that is replayed does not advance it); every other counter is kept
+ * on the device by the kernels themselves and also advances under graph replay. */
 typedef struct {
-    uint64_t steps;           /* rrm_step calls enqueued */
-    uint64_t delta_steps;     /* of those, steps that took the sparse delta path */
+    uint64_t steps;           /* rrm_step calls enqueued by the host */
+    uint64_t delta_steps;     /* steps executed on the sparse delta path */
     uint64_t changed_elems;   /* input elements (binary: bits) that differed from the snapshot */
     uint64_t changed_units;   /* 16-byte input units with any difference (FC: = changed_elems) */
     uint64_t active_tiles;    /* int8 / bf16 conv: 4x4 output sub-tiles recomputed; binary conv: 8x8 output
@@ -125,8 +127,8 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
 
 /* Options (value semantics per key):
  *   "path"        0 auto, 1 sparse delta path always, 2 recompute densely every step
- *   "fc_splits"   FC: upper bound on the workgroups the changed-column list is split over, in
- *                 [1, the default chosen at create] (the partial-sum scratch is sized for the default)
+ *   "fc_splits"   FC, dense path: number of row splits of the weight matrix, in [1, the default chosen at
+ *                 create] (the partial-sum scratch is sized for the default)
  *   "bf16_terms"  BF16 conv: 2 = difference carried as hi+lo bf16 pair (default), 1 = hi only
  *   "dense_switch_pct"  INT8 / BF16 conv: a delta step whose changes touch more than this percentage of the
  *                 4x4 output blocks recomputes the whole projection (same result; cheaper than reading and
@@ -155,7 +157,7 @@ rrm_status rrm_get_stats(rrm_layer* layer, rrm_stats* out);
 rrm_status rrm_step_from_projection(rrm_layer* layer, rrm_layer* producer, int shift, int pool, void* y_out,
                                     void* hip_stream);
 
-/* Truncation threshold of a BF16 layer (Sec. 3.3, "Improving sparsity": small values of the difference are
+/* Truncation threshold of a BF16 layer (Sec. 3.4, "Improving sparsity": small values of the difference are
  * truncated to zero to gain sparsity; the experiments use 1e-2).  An entry with |x_t - x_snap| < epsilon
  * (difference formed in fp32) is not applied to the stored projection and not committed to the stored input,
  * so y_snap == b + W (*) x_snap stays true and the entry is still pending at the next frame; x_snap then

@@ -16,7 +16,7 @@ library never calls into it.
 
 bf16 tensors are passed as their 16-bit patterns (``uint16``) and widened exactly here;
 binary tensors are passed as +1/-1 ``int8`` arrays, so that the binary case *is* the integer
-case, as Sec. 4.4 reduces it ("taking their signs").
+case, as Sec. 4.3 reduces it ("taking their signs").
 """
 from __future__ import annotations
 
@@ -159,7 +159,7 @@ class State:
     def step(self, x_t: np.ndarray, eps: float = 0.0) -> np.ndarray:
         """One (layer, frame) iteration of Algorithm 1; returns P_t (a view of the state).
 
-        ``eps`` > 0 (bf16 only) truncates differences below the threshold (Sec. 3.3, "Improving
+        ``eps`` > 0 (bf16 only) truncates differences below the threshold (Sec. 3.4, "Improving
         sparsity"); what is truncated is not committed to the stored input, so P = b + W (*) I holds.
         ``last_truncated`` / ``last_truncated_sumsq`` describe the truncated map of this step."""
         xv = _as_values(self.dtype, x_t)

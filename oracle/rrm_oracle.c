@@ -207,7 +207,7 @@ int orc_step_i8(const orc_shape* s, const int8_t* wt, int8_t* i_prev, int32_t* p
     return overflow;
 }
 
-/* Sparsity enhancement (Sec. 3.3, "Improving sparsity"): a difference whose magnitude is below the threshold
+/* Sparsity enhancement (Sec. 3.4, "Improving sparsity"): a difference whose magnitude is below the threshold
  * eps is truncated to zero.  Reading taken here: only what was applied to P is committed to I, so that
  * P = b + W (*) I stays true and a truncated difference is still pending at the next frame (nothing is lost
  * for good).  The decision is taken on the single-precision difference, the precision the inputs' difference

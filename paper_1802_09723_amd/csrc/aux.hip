@@ -70,9 +70,9 @@ __global__ __launch_bounds__(256) void relu_requant_pool4_kernel(const int4* __r
     const int row = (int)blockIdx.x;  // b*ho + oy
     const int idx = (int)(blockIdx.y * blockDim.x + threadIdx.x);
     if (idx >= wo * c4) return;
-    const int b = magic_ho ? (int)__umulhi((unsigned int)row, magic_ho) : row;
+    const int b = (int)udiv_magic((unsigned int)row, (unsigned int)ho, magic_ho);
     const int oy = row - b * ho;
-    const int ox = magic_c4 ? (int)__umulhi((unsigned int)idx, magic_c4) : idx;
+    const int ox = (int)udiv_magic((unsigned int)idx, (unsigned int)c4, magic_c4);
     const int cv = idx - ox * c4;
     const int y0 = pool ? 2 * oy : oy, x0 = pool ? 2 * ox : ox;
     const int span = pool ? 2 : 0;

@@ -43,6 +43,7 @@
 // The last workgroup to arrive clears the flag array and the arrival counter, so nothing on the host
 // changes between steps (HIP-graph replay safe).
 #include <algorithm>
+#include <mutex>
 
 #include "rrm_internal.h"
 
@@ -91,23 +92,6 @@ __device__ __forceinline__ void sched_interleave() {
         sched_interleave<I + 1, N_MFMA, N_READ>();
     }
 }
-
-// u / d for small u through a precomputed reciprocal (magic == 0 means d == 1)
-__device__ __forceinline__ int fdiv(int u, unsigned int magic) {
-    return magic ? (int)__umulhi((unsigned int)u, magic) : u;
-}
-
-#ifdef RRM_TRACE
-// debug build only: cycle stamps of workgroup (0,0) (lane 0 of the first producer / consumer wavefront) into
-// the slots behind the counters
-#define RRM_STAMP(k)                                                                                \
-    do {                                                                                            \
-        if (blockIdx.x == 0 && blockIdx.y == 0 && lane == 0 && (wave == 0 || wave == 4))            \
-            reinterpret_cast<unsigned long long*>(stats + STAT_SLOTS)[k] = __builtin_readcyclecounter();    \
-    } while (0)
-#else
-#define RRM_STAMP(k) do {} while (0)
-#endif
 
 // Workgroup barrier that publishes LDS contents only: it waits for this wavefront's LDS operations, not for its
 // outstanding global loads (__syncthreads() would also wait for the copies into LDS that were started early).
@@ -174,7 +158,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
                                                  0, 0);
         }
     };
-    RRM_STAMP(producer ? 0 : 40);
     // The first weight slab and this thread's rows of the staging table (which serve every unit) do not
     // depend on the work list.  A dense launch starts their loads at once; a delta launch after the loads
     // of the list phase, which would otherwise queue behind them (loads return in order), and not at all in
@@ -330,6 +313,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             }
             if (tid == 0) {
                 ctrl[0] = 0u;
+                if (g.fresh) g.fresh[0] = 0u;  // the stored input now holds this step's input
                 if (n_flagged && !own_group) atomicAdd(&stats[0].active_tiles, (unsigned long long)n_flagged);
             }
         }
@@ -426,14 +410,13 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     const int first = unit * per;
     int mycount = count - first;
     if (mycount > per) mycount = per;
-    if (iu == 0) RRM_STAMP(1);
     {
         // ---- window origins of the unit's sub-tiles (each producer wavefront keeps its own copy: no barrier) --
         if (lane < mycount) {
             const int id = listed ? s_list[(iu - r0) * per + lane] : first + lane;
-            const int b = fdiv(id, g.magic_sub);
+            const int b = (int)udiv_magic((unsigned int)id, (unsigned int)(g.sty * g.stx), g.magic_sub);
             const int r = id - b * (g.sty * g.stx);
-            const int sy = fdiv(r, g.magic_stx), sx = r - sy * g.stx;
+            const int sy = (int)udiv_magic((unsigned int)r, (unsigned int)g.stx, g.magic_stx), sx = r - sy * g.stx;
             const int iy0 = 4 * sy * g.str_y - g.pad_y, ix0 = 4 * sx * g.str_x - g.pad_x;
             s_iy0[wave][lane] = iy0;
             s_ix0[wave][lane] = ix0;
@@ -472,7 +455,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         // the flags were read for the last time in the last ranking round (the signal is sent where no load
         // of the issuing thread is waited for soon: returns are in order, a wait would include the atomic)
         if (iu == r0 && r1 == my_nunits) arrive();
-        if (iu == 0) RRM_STAMP(2);
         auto stage_windows = [&](int slab, int buf) {
             unsigned char* dst = bbase + buf * b_bytes;
             const bool last = slab == g.nslab - 1;
@@ -494,21 +476,16 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         // while the consumers still multiply the previous unit's last slab (other parity).
         if (nbuf_a == 2 && iu > 0) stage_weights(0, gs & 1);  // (the very first slab was started at kernel entry)
         stage_windows(0, gs & 1);
-        if (iu == 0) RRM_STAMP(3);
         for (int k = 0; k < g.nslab; ++k) {
             __builtin_amdgcn_s_waitcnt(0);  // this wavefront's copies for slab k have landed in LDS
-            if (iu < 2 && k < 6) RRM_STAMP(4 + 18 * iu + 3 * k);
             __syncthreads();                // slab k is published; the consumers are done with slab k-1
-            if (iu < 2 && k < 6) RRM_STAMP(5 + 18 * iu + 3 * k);
             ++gs;
             if (k + 1 < g.nslab) {
                 stage_weights(k + 1, gs & 1);
                 stage_windows(k + 1, gs & 1);
             }
-            if (iu < 2 && k < 6) RRM_STAMP(6 + 18 * iu + 3 * k);
         }
     }
-    if (iu < 2) RRM_STAMP(22 + 18 * iu);
     }  // units of the round
     }  // rounds
     } else {
@@ -531,9 +508,9 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             ybase[p] = 0;
             if (slot < mycount2) {
                 const int id = listed ? s_list[(iu2 - r0) * per + slot] : first2 + slot;
-                const int b = fdiv(id, g.magic_sub);
+                const int b = (int)udiv_magic((unsigned int)id, (unsigned int)(g.sty * g.stx), g.magic_sub);
                 const int r = id - b * (g.sty * g.stx);
-                const int sy = fdiv(r, g.magic_stx), sx = r - sy * g.stx;
+                const int sy = (int)udiv_magic((unsigned int)r, (unsigned int)g.stx, g.magic_stx), sx = r - sy * g.stx;
                 const int oy = 4 * sy + (j >> 2), ox = 4 * sx + (j & 3);
                 pos_ok[p] = ox < g.wo && oy < g.ho;
                 ybase[p] = (unsigned int)((b * g.ho + oy) * g.wo + ox) * (unsigned int)g.c_out + (unsigned int)(grp * g.og);
@@ -574,7 +551,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     const int first = unit * per;
     int mycount = count - first;
     if (mycount > per) mycount = per;
-    if (iu == 0) RRM_STAMP(41);
     const int nact = mycount > 2 * cw ? (mycount - 2 * cw + 7) / 8 : 0;  // pairs in use (slots 2*(cw+4p), +1)
     {
         // ---- consumers ---------------------------------------------------------------------------------
@@ -650,12 +626,10 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         };
 
         for (int k = 0; k < g.nslab; ++k) {
-            if (iu < 2 && k < 6) RRM_STAMP(42 + 18 * iu + 3 * k);
             // slab k is staged.  A bare barrier: the producers waited for their copies before they arrived,
             // and this wavefront's own stores and loads of stored projections (previous / this unit) need not
             // have completed -- __syncthreads() would wait for all of them.
             asm volatile("s_barrier" ::: "memory");
-            if (iu < 2 && k < 6) RRM_STAMP(43 + 18 * iu + 3 * k);
             const unsigned char* aw = lds + (nbuf_a == 2 ? (gs & 1) : 0) * a_bytes;
             const unsigned char* bw = bbase + (gs & 1) * b_bytes;
             ++gs;
@@ -670,7 +644,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             } else if (nact > 0) {
                 k_loop.template operator()<1, 1>(aw, bw);
             }
-            if (iu < 2 && k < 6) RRM_STAMP(44 + 18 * iu + 3 * k);
         }
 
         // ---- epilogue ----------------------------------------------------------------------------------
@@ -701,9 +674,9 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
                     ny[sl] = nx[sl] = 0;
                     if (slot < mycount) {
                         const int id = listed ? s_list[(iu - r0) * per + slot] : first + slot;
-                        const int b = fdiv(id, g.magic_sub);
+                        const int b = (int)udiv_magic((unsigned int)id, (unsigned int)(g.sty * g.stx), g.magic_sub);
                         const int r = id - b * (g.sty * g.stx);
-                        const int sy = fdiv(r, g.magic_stx), sx = r - sy * g.stx;
+                        const int sy = (int)udiv_magic((unsigned int)r, (unsigned int)g.stx, g.magic_stx), sx = r - sy * g.stx;
                         ny[sl] = g.ho - 4 * sy;
                         nx[sl] = g.wo - 4 * sx;
                         corner[sl] = (unsigned int)((b * g.ho + 4 * sy) * g.wo + 4 * sx) * (unsigned int)g.c_out +
@@ -778,12 +751,10 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         }
         if (iu + 1 < r1) begin_unit(iu + 1, r0);  // (a new round's first unit waits for its ranking)
     }
-    if (iu < 2) RRM_STAMP(60 + 18 * iu);
     }  // units of the round
     }  // rounds
     }
     retire();
-    RRM_STAMP(producer ? 39 : 79);
 }
 
 template <int DT, int MODE, int NCB, int NT, int TERMS>
@@ -799,7 +770,11 @@ hipError_t launch_one(const void* src0, const void* src1, const void* zero16, un
     dim3 grid((unsigned int)gx, (unsigned int)gy);
     auto kern = conv_gather_kernel<DT, MODE, NCB, NT, TERMS>;
     if (lds > 64 * 1024) {
-        static size_t granted = 0;  // one per instantiation; creation and launches of a process share it
+        // one per instantiation, shared by every handle and thread of the process: guarded, so that
+        // distinct handles stay independent
+        static std::mutex mu;
+        static size_t granted = 0;
+        std::lock_guard<std::mutex> lock(mu);
         if (lds > granted) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

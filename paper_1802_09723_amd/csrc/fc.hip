@@ -1,18 +1,14 @@
-// Fully-connected sparse-delta path: P_t = P_{t-1} + W (I_t - I_{t-1})  (Algorithm 1, FC branch).
+// Fully-connected layers: the sparse-delta step P_t = P_{t-1} + W (I_t - I_{t-1}) (Algorithm 1, FC branch) and the
+// dense layer P = b + W I (Eq. 3, FC form).
 //
-// The engine the paper relies on (Sec. 3.5) scans the activation vector for non-zero entries,
-// broadcasts (a_j, j) and multiplies the weight column W_j, summing into row accumulators.  Here:
-//   fc_scan     one workgroup per stream compares x_t with the snapshot, commits changes, and
-//               compacts the changed entries (index j, difference a_j) into an ordered list with a
-//               wavefront popcount + LDS prefix sum.
-//   fc_scatter  streams only the listed columns.  The weights are stored input-major
-//               (W^T [c_in][c_out], every column of W contiguous), each lane owns 16 bytes worth of
-//               output channels, and the list is split over workgroups (and over four column groups
-//               inside a workgroup, combined through LDS) so that enough loads are in flight to stream
-//               at memory speed; every split writes its partial sums to scratch.
-//   fc_reduce   adds the partial sums of the splits, in a fixed order, into the stored projection
-//               (no atomics: exact for int32, and bit-reproducible run to run for fp32).
-// The layer is memory-bound: bytes moved are (changed columns) x c_out x element size.
+// The engine the paper relies on (Sec. 3.5) scans the activation vector for non-zero entries, broadcasts
+// (a_j, j) and multiplies the weight column W_j, summing into row accumulators.  Here the weights are stored
+// input-major (W^T [c_in][c_out], every column of W contiguous) and a step is ONE launch (fc_delta_kernel): compare,
+// compaction of the changed entries, the walk over their columns and the sum into the stored projection.  The
+// layer is memory bound: bytes moved are (changed columns) x c_out x element size.
+// The dense layer streams all of W^T, split over rows and output-channel slices (fc_dense_kernel), and adds the
+// splits' partial sums in a fixed order (fc_reduce_kernel): no atomics, bit-reproducible for fp32.
+#include <mutex>
 #include <type_traits>
 
 #include "rrm_internal.h"
@@ -21,203 +17,116 @@ namespace rrm {
 
 namespace {
 
-constexpr int FC_SCAN_THREADS = 1024;
-constexpr int FC_MIN_COLS = 2;  // columns per active workgroup before the list is split further
+constexpr int FCD_THREADS = 1024;  // 16 wavefronts
+constexpr int FCD_CH = 8192;        // inputs compared per round = capacity of the changed-column list in LDS
+constexpr int FCD_UN = 8;           // columns in flight per lane
+constexpr int FCD_SEG = 64;         // bytes of a weight column one workgroup owns (4 lanes of 16 bytes)
 
 __device__ __forceinline__ float bf16_to_f32(unsigned int h) { return __uint_as_float(h << 16); }
 
+// One launch per step (Algorithm 1, FC branch; the column walk of Sec. 3.5): workgroup (r, b) owns FCD_SEG bytes
+// worth of output channels of stream b.  Every workgroup compares x_t with the stored input itself (the vector is
+// a few KB: redoing the compare costs less than a second launch), compacts the changed entries (index, difference)
+// in index order into LDS, streams its 64-byte piece of every listed column of W (rows of W^T), and adds the
+// column sum into its own channels of the stored projection: one owner per output, no partial sums in memory, no
+// atomics on y, the same summation order in every run.  The stored input is committed by whichever workgroup of
+// the stream finishes its compare last (an arrival counter tells it that nobody reads the old values any more);
+// it also rearms the counter, so a step leaves no host-visible state behind (graph replay safe).
 template <int DT>
-__global__ __launch_bounds__(FC_SCAN_THREADS) void fc_scan_kernel(const unsigned char* __restrict__ x_t,
-                                                                  unsigned char* __restrict__ x_snap,
-                                                                  int* __restrict__ idx, void* __restrict__ val_v,
-                                                                  int* __restrict__ count, FcGeom g,
-                                                                  DevStats* __restrict__ stats) {
+__global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned char* __restrict__ x_t,
+                                                               unsigned char* x_snap,
+                                                               const unsigned char* __restrict__ wT, void* y_v,
+                                                               unsigned int* arrive, FcGeom g,
+                                                               DevStats* __restrict__ stats) {
     constexpr int PV = DT == RRM_I8_I32 ? 16 : 8;
     constexpr int ESIZE = DT == RRM_I8_I32 ? 1 : 2;
+    constexpr int NCG = FCD_THREADS / 4;  // column groups: 4 lanes (64 bytes) per column
     typedef typename std::conditional<DT == RRM_I8_I32, int, float>::type val_t;
-    val_t* val = static_cast<val_t*>(val_v);
-    __shared__ int wave_tot[FC_SCAN_THREADS / 64];
-    __shared__ int running;
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ unsigned short l_idx[FCD_CH];
+    __shared__ val_t l_val[FCD_CH];
+    __shared__ val_t red[FCD_THREADS / 64][4][PV];
+    __shared__ int wave_tot[FCD_THREADS / 64];
+    __shared__ unsigned int s_prev;
+    const int r = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = tid & 3, cgid = tid >> 2;
     const long long row = (long long)b * g.c_in;
-    const int nunits = (g.c_in + PV - 1) / PV;
-    if (tid == 0) running = 0;
-    __syncthreads();
-    unsigned int ntrunc = 0;  // truncated differences of this thread (bf16 with a threshold) and their squares
-    float tsq = 0.f;
-    for (int u0 = 0; u0 < nunits; u0 += FC_SCAN_THREADS) {
-        const int u = u0 + tid;
-        val_t dv[PV];
-        unsigned int mask = 0;
-        const int e0 = u * PV;
-        if (u < nunits) {
-            if (g.vec_ok) {
-                const uint4 a = *reinterpret_cast<const uint4*>(x_t + (row + e0) * ESIZE);
-                uint4* sp = reinterpret_cast<uint4*>(x_snap + (row + e0) * ESIZE);
-                const uint4 s = *sp;
-                if ((a.x ^ s.x) | (a.y ^ s.y) | (a.z ^ s.z) | (a.w ^ s.w)) {
-                    const unsigned int aw[4] = {a.x, a.y, a.z, a.w}, sw[4] = {s.x, s.y, s.z, s.w};
-                    unsigned int nw[4] = {a.x, a.y, a.z, a.w};  // the unit's new snapshot
+    const int co0 = r * (FCD_SEG / ESIZE) + sub * PV;  // this lane's first output channel
+    const bool live = co0 < g.c_out_p;
+    const unsigned char* wcol = wT + (long long)(live ? co0 : 0) * ESIZE;
+    const long long pitch = (long long)g.c_out_p * ESIZE;
+    val_t acc[PV];
 #pragma unroll
-                    for (int e = 0; e < PV; ++e) {
-                        if (DT == RRM_I8_I32) {
-                            const int xa = (int)(signed char)(aw[e >> 2] >> (8 * (e & 3)));
-                            const int xb = (int)(signed char)(sw[e >> 2] >> (8 * (e & 3)));
-                            dv[e] = (val_t)(xa - xb);
-                            if (xa != xb) mask |= 1u << e;
-                        } else {
-                            // (truncation threshold, Sec. 3.3 "Improving sparsity": a difference below g.eps is
-                            // neither listed nor committed; eps = 0 is the exact method)
-                            const unsigned int xa = (aw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-                            const unsigned int xb = (sw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-                            const float d = bf16_to_f32(xa) - bf16_to_f32(xb);
-                            dv[e] = (val_t)d;
-                            if (xa != xb) {
-                                if (fabsf(d) < g.eps) {
-                                    ++ntrunc;
-                                    tsq += d * d;
-                                    nw[e >> 1] = (nw[e >> 1] & ~(0xFFFFu << (16 * (e & 1)))) | (xb << (16 * (e & 1)));
-                                } else {
-                                    mask |= 1u << e;
-                                }
-                            }
-                        }
-                    }
-                    if (mask) *sp = make_uint4(nw[0], nw[1], nw[2], nw[3]);
-                }
-            } else {
-                for (int e = 0; e < PV; ++e) {
-                    dv[e] = 0;
-                    if (e0 + e >= g.c_in) continue;
-                    if (DT == RRM_I8_I32) {
-                        const signed char xa = (signed char)x_t[row + e0 + e];
-                        const signed char xb = (signed char)x_snap[row + e0 + e];
-                        if (xa != xb) {
-                            mask |= 1u << e;
-                            dv[e] = (val_t)((int)xa - (int)xb);
-                            x_snap[row + e0 + e] = (unsigned char)xa;
-                        }
-                    } else {
-                        const unsigned short xa = reinterpret_cast<const unsigned short*>(x_t)[row + e0 + e];
-                        unsigned short* sp = reinterpret_cast<unsigned short*>(x_snap) + row + e0 + e;
-                        if (xa != *sp) {
-                            const float d = bf16_to_f32(xa) - bf16_to_f32(*sp);
-                            if (fabsf(d) < g.eps) {
+    for (int e = 0; e < PV; ++e) acc[e] = 0;
+    unsigned int ntrunc = 0, total = 0;
+    float tsq = 0.f;
+
+    // difference of one 16-byte unit (PV entries from element e0 of the row): mask of entries to apply, values
+    auto diff_unit = [&](int e0, val_t (&dv)[PV], unsigned int& mask, uint4& a_out, uint4& n_out, bool count) {
+        mask = 0;
+        if (g.vec_ok) {
+            const uint4 a = *reinterpret_cast<const uint4*>(x_t + (row + e0) * ESIZE);
+            const uint4 s = *reinterpret_cast<const uint4*>(x_snap + (row + e0) * ESIZE);
+            a_out = a;
+            n_out = a;
+            if (!((a.x ^ s.x) | (a.y ^ s.y) | (a.z ^ s.z) | (a.w ^ s.w))) return;
+            const unsigned int aw[4] = {a.x, a.y, a.z, a.w}, sw[4] = {s.x, s.y, s.z, s.w};
+            unsigned int nw[4] = {a.x, a.y, a.z, a.w};  // the unit's new snapshot
+#pragma unroll
+            for (int e = 0; e < PV; ++e) {
+                if (DT == RRM_I8_I32) {
+                    const int xa = (int)(signed char)(aw[e >> 2] >> (8 * (e & 3)));
+                    const int xb = (int)(signed char)(sw[e >> 2] >> (8 * (e & 3)));
+                    dv[e] = (val_t)(xa - xb);
+                    if (xa != xb) mask |= 1u << e;
+                } else {
+                    // (truncation threshold, Sec. 3.4 "Improving sparsity": a difference below g.eps is
+                    // neither applied nor committed; eps = 0 is the exact method)
+                    const unsigned int xa = (aw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                    const unsigned int xb = (sw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                    const float d = bf16_to_f32(xa) - bf16_to_f32(xb);
+                    dv[e] = (val_t)d;
+                    if (xa != xb) {
+                        if (fabsf(d) < g.eps) {
+                            if (count) {
                                 ++ntrunc;
                                 tsq += d * d;
-                            } else {
-                                mask |= 1u << e;
-                                dv[e] = (val_t)d;
-                                *sp = xa;
                             }
+                            nw[e >> 1] = (nw[e >> 1] & ~(0xFFFFu << (16 * (e & 1)))) | (xb << (16 * (e & 1)));
+                        } else {
+                            mask |= 1u << e;
                         }
                     }
                 }
             }
-        }
-        // ---- ordered compaction: wave inclusive scan of the counts, then across waves in LDS -----
-        const int cnt = __popc(mask);
-        int incl = cnt;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int t = __shfl_up(incl, o);
-            if (lane >= o) incl += t;
-        }
-        if (lane == 63) wave_tot[wave] = incl;
-        __syncthreads();
-        int wbase = 0, btot = 0;
-        for (int w = 0; w < FC_SCAN_THREADS / 64; ++w) {
-            const int t = wave_tot[w];
-            if (w < wave) wbase += t;
-            btot += t;
-        }
-        int pos = running + wbase + incl - cnt;
-        if (mask) {
-#pragma unroll
-            for (int e = 0; e < PV; ++e)
-                if (mask & (1u << e)) {
-                    idx[row + pos] = e0 + e;
-                    val[row + pos] = dv[e];
-                    ++pos;
-                }
-        }
-        __syncthreads();
-        if (tid == 0) running += btot;
-        __syncthreads();
-    }
-    if (DT == RRM_BF16_F32) {
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            ntrunc += __shfl_xor(ntrunc, o);
-            tsq += __shfl_xor(tsq, o);
-        }
-        if (lane == 0 && ntrunc) {
-            atomicAdd(&stats->truncated_elems, (unsigned long long)ntrunc);
-            atomicAdd(&stats->truncated_sumsq, (double)tsq);
-        }
-    }
-    if (tid == 0) {
-        const int total = running;
-        count[b] = total;
-        if (total) {
-            atomicAdd(&stats->changed_elems, (unsigned long long)total);
-            atomicAdd(&stats->changed_units, (unsigned long long)total);
-            atomicAdd(&stats->active_tiles, (unsigned long long)total);
-        }
-    }
-}
-
-constexpr int FC_KG = 4;          // column groups of a scatter workgroup (1024 threads = 4 x 256 lanes)
-constexpr int FC_RG = 8;          // split groups of a reduce workgroup (1024 threads = 8 x 128 lanes)
-constexpr int FC_MAX_SPLITS = 64;
-
-// number of workgroups the column list is split over, from the list length (same in both kernels)
-__device__ __forceinline__ int fc_active_splits(int cnt, int splits) {
-    int s_eff = (cnt + FC_KG * FC_MIN_COLS - 1) / (FC_KG * FC_MIN_COLS);
-    if (s_eff < 1) s_eff = 1;
-    return s_eff > splits ? splits : s_eff;
-}
-
-// Workgroup (slice, split s, stream): 256 lanes of 16 bytes of output channels each, times FC_KG column
-// groups; column group kg of split s takes columns s*FC_KG + kg, + s_eff*FC_KG, ... of the list.  The four
-// groups' sums are added through LDS, so a split leaves one row of partial sums.
-template <int DT, int DENSE>
-__global__ __launch_bounds__(FC_KG * 256) void fc_scatter_kernel(const unsigned char* __restrict__ wT,
-                                                                 const int* __restrict__ idx, const void* __restrict__ val_v,
-                                                                 const int* __restrict__ count,
-                                                                 const unsigned char* __restrict__ x,
-                                                                 void* __restrict__ part_v, FcGeom g, int splits) {
-    constexpr int PV = DT == RRM_I8_I32 ? 16 : 8;
-    constexpr int ESIZE = DT == RRM_I8_I32 ? 1 : 2;
-    constexpr int UN = 8;  // columns in flight per lane
-    typedef typename std::conditional<DT == RRM_I8_I32, int, float>::type val_t;
-    typedef typename std::conditional<DT == RRM_I8_I32, int4, float4>::type vec_t;
-    __shared__ vec_t red[FC_KG - 1][PV / 4][256];
-    const val_t* val = static_cast<const val_t*>(val_v);
-    const int b = blockIdx.z, s = blockIdx.y;
-    const int cnt = DENSE ? g.c_in : count[b];
-    const int s_eff = fc_active_splits(cnt, splits);
-    if (s >= s_eff) return;  // (the whole workgroup)
-    const int lane = threadIdx.x & 255, kg = threadIdx.x >> 8;
-    const int co0 = (blockIdx.x * 256 + lane) * PV;
-    const bool live = co0 < g.c_out_p;
-    const long long row = (long long)b * g.c_in;
-    val_t acc[PV];
-#pragma unroll
-    for (int e = 0; e < PV; ++e) acc[e] = 0;
-    const unsigned char* wcol = wT + (long long)(live ? co0 : 0) * ESIZE;
-    const long long pitch = (long long)g.c_out_p * ESIZE;
-
-    auto column = [&](int k, int& j, val_t& d) {
-        if (DENSE) {
-            j = k;
-            if (DT == RRM_I8_I32)
-                d = (val_t)(int)(signed char)x[row + k];
-            else
-                d = (val_t)bf16_to_f32(reinterpret_cast<const unsigned short*>(x)[row + k]);
+            n_out = make_uint4(nw[0], nw[1], nw[2], nw[3]);
         } else {
-            j = idx[row + k];
-            d = val[row + k];
+            for (int e = 0; e < PV; ++e) {
+                dv[e] = 0;
+                if (e0 + e >= g.c_in) continue;
+                if (DT == RRM_I8_I32) {
+                    const signed char xa = (signed char)x_t[row + e0 + e];
+                    const signed char xb = (signed char)x_snap[row + e0 + e];
+                    if (xa != xb) {
+                        mask |= 1u << e;
+                        dv[e] = (val_t)((int)xa - (int)xb);
+                    }
+                } else {
+                    const unsigned short xa = reinterpret_cast<const unsigned short*>(x_t)[row + e0 + e];
+                    const unsigned short xb = reinterpret_cast<const unsigned short*>(x_snap)[row + e0 + e];
+                    if (xa != xb) {
+                        const float d = bf16_to_f32(xa) - bf16_to_f32(xb);
+                        if (fabsf(d) < g.eps) {
+                            if (count) {
+                                ++ntrunc;
+                                tsq += d * d;
+                            }
+                        } else {
+                            mask |= 1u << e;
+                            dv[e] = (val_t)d;
+                        }
+                    }
+                }
+            }
         }
     };
     auto fma16 = [&](const uint4& w, val_t d) {
@@ -231,38 +140,241 @@ __global__ __launch_bounds__(FC_KG * 256) void fc_scatter_kernel(const unsigned 
         }
     };
 
+    const int nchunk = (g.c_in + FCD_CH - 1) / FCD_CH;
+    for (int ch = 0; ch < nchunk; ++ch) {
+        const int base = ch * FCD_CH;
+        const int n_in = min(FCD_CH, g.c_in - base);
+        const int nunits = (n_in + PV - 1) / PV;
+        // ---- compare + ordered compaction of this round's inputs ------------------------------------------
+        int running = 0;
+        for (int u0 = 0; u0 < nunits; u0 += FCD_THREADS) {
+            const int u = u0 + tid;
+            val_t dv[PV];
+            unsigned int mask = 0;
+            uint4 a, nw;
+            if (u < nunits) diff_unit(base + u * PV, dv, mask, a, nw, true);
+            const int cnt = __popc(mask);
+            int incl = cnt;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(incl, o);
+                if (lane >= o) incl += t;
+            }
+            if (lane == 63) wave_tot[wave] = incl;
+            __syncthreads();
+            int wbase = 0, btot = 0;
+            for (int w = 0; w < FCD_THREADS / 64; ++w) {
+                const int t = wave_tot[w];
+                if (w < wave) wbase += t;
+                btot += t;
+            }
+            int pos = running + wbase + incl - cnt;
+            if (mask) {
+#pragma unroll
+                for (int e = 0; e < PV; ++e)
+                    if (mask & (1u << e)) {
+                        l_idx[pos] = (unsigned short)(u * PV + e);
+                        l_val[pos] = dv[e];
+                        ++pos;
+                    }
+            }
+            running += btot;
+            __syncthreads();  // the list is published (and wave_tot may be rewritten)
+        }
+        const int cnt = running;
+        total += (unsigned int)cnt;
+        // every read of the stored input by this workgroup is done: tell the stream's other workgroups
+        if (ch == nchunk - 1 && tid == 0) s_prev = atomicAdd(&arrive[b], 1u);
+        // ---- this workgroup's 64 bytes of every listed column ------------------------------------------------
+        if (live) {
+            int k = cgid;
+            for (; k + (FCD_UN - 1) * NCG < cnt; k += FCD_UN * NCG) {
+                int j[FCD_UN];
+                val_t d[FCD_UN];
+                uint4 w[FCD_UN];
+#pragma unroll
+                for (int u = 0; u < FCD_UN; ++u) {
+                    j[u] = base + l_idx[k + u * NCG];
+                    d[u] = l_val[k + u * NCG];
+                }
+#pragma unroll
+                for (int u = 0; u < FCD_UN; ++u) w[u] = *reinterpret_cast<const uint4*>(wcol + j[u] * pitch);
+#pragma unroll
+                for (int u = 0; u < FCD_UN; ++u) fma16(w[u], d[u]);
+            }
+            if (k < cnt) {  // the rest of this group's columns (fewer than FCD_UN), in flight together
+                int j[FCD_UN];
+                val_t d[FCD_UN];
+                uint4 w[FCD_UN];
+#pragma unroll
+                for (int u = 0; u < FCD_UN; ++u) {
+                    const bool ok = k + u * NCG < cnt;
+                    j[u] = ok ? base + l_idx[k + u * NCG] : 0;
+                    d[u] = ok ? l_val[k + u * NCG] : (val_t)0;
+                }
+#pragma unroll
+                for (int u = 0; u < FCD_UN; ++u)
+                    w[u] = k + u * NCG < cnt ? *reinterpret_cast<const uint4*>(wcol + j[u] * pitch) : uint4{0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int u = 0; u < FCD_UN; ++u) fma16(w[u], d[u]);
+            }
+        }
+        if (ch + 1 < nchunk) __syncthreads();  // the list is rewritten by the next round
+    }
+
+    // ---- column groups -> one sum per channel: butterfly inside the wavefront (lanes with the same `sub`), then
+    // the wavefronts in order through LDS.  The order is fixed, so fp32 results repeat from run to run.
+    if (total) {  // (the same in every thread: the list lengths)
+#pragma unroll
+        for (int e = 0; e < PV; ++e) {
+            val_t v = acc[e];
+            v += __shfl_xor(v, 4);
+            v += __shfl_xor(v, 8);
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 32);
+            acc[e] = v;
+        }
+        if (lane < 4) {
+#pragma unroll
+            for (int e = 0; e < PV; ++e) red[wave][lane][e] = acc[e];
+        }
+        __syncthreads();
+        if (tid < 4 * PV) {
+            val_t sum = 0;
+#pragma unroll
+            for (int w = 0; w < FCD_THREADS / 64; ++w) sum += red[w][tid / PV][tid % PV];
+            const int co = r * (FCD_SEG / ESIZE) + tid;
+            if (co < g.c_out) {
+                val_t* y = static_cast<val_t*>(y_v) + (long long)b * g.c_out + co;
+                *y += sum;
+            }
+        }
+    }
+    // ---- statistics (one workgroup per stream) ----------------------------------------------------------
+    if (r == 0) {
+        if (DT == RRM_BF16_F32) {
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                ntrunc += __shfl_xor(ntrunc, o);
+                tsq += __shfl_xor(tsq, o);
+            }
+            if (lane == 0 && ntrunc) {
+                atomicAdd(&stats->truncated_elems, (unsigned long long)ntrunc);
+                atomicAdd(&stats->truncated_sumsq, (double)tsq);
+            }
+        }
+        if (tid == 0) {
+            if (b == 0) {  // one launch = one delta step
+                atomicAdd(&stats->delta_steps, 1ull);
+                atomicAdd(&stats->total_tiles, (unsigned long long)g.n * (unsigned long long)g.c_in);
+            }
+            if (total) {
+                atomicAdd(&stats->changed_elems, (unsigned long long)total);
+                atomicAdd(&stats->changed_units, (unsigned long long)total);
+                atomicAdd(&stats->active_tiles, (unsigned long long)total);
+            }
+        }
+    }
+    // ---- commit: the workgroup that finished comparing last snapshots the input (applied entries only) -------
+    __syncthreads();  // (s_prev was written by thread 0 after the last round's barrier)
+    if (s_prev == gridDim.x - 1u) {
+        const int nunits = (g.c_in + PV - 1) / PV;
+        for (int u = tid; u < nunits; u += FCD_THREADS) {
+            val_t dv[PV];
+            unsigned int mask = 0;
+            uint4 a, nw;
+            diff_unit(u * PV, dv, mask, a, nw, false);
+            if (!mask) continue;
+            if (g.vec_ok) {
+                *reinterpret_cast<uint4*>(x_snap + (row + u * PV) * ESIZE) = nw;
+            } else {
+                for (int e = 0; e < PV; ++e)
+                    if (mask & (1u << e)) {
+                        if (DT == RRM_I8_I32)
+                            x_snap[row + u * PV + e] = x_t[row + u * PV + e];
+                        else
+                            reinterpret_cast<unsigned short*>(x_snap)[row + u * PV + e] =
+                                reinterpret_cast<const unsigned short*>(x_t)[row + u * PV + e];
+                    }
+            }
+        }
+        if (tid == 0) arrive[b] = 0u;
+    }
+}
+
+constexpr int FC_LANES = 64;      // lanes of a dense workgroup along the output channels (16 bytes each)
+constexpr int FC_KG = 8;          // row groups of a dense workgroup (512 threads = 8 wavefronts)
+constexpr int FC_RG = 8;          // split groups of a reduce workgroup (1024 threads = 8 x 128 lanes)
+constexpr int FC_MAX_SPLITS = 64;
+
+// Dense layer (Eq. 3, FC form), first of two kernels.  Workgroup (slice, split s, stream): 64 lanes of 16 bytes
+// of output channels each, times FC_KG wavefronts; wavefront kg of split s takes rows s*FC_KG + kg,
+// + splits*FC_KG, ... of W^T, eight 16-byte loads in flight per lane.  The wavefronts' sums are added through LDS
+// in a fixed order, so a split leaves one row of partial sums in the scratch `part` [stream][split][c_out_p].
+template <int DT>
+__global__ __launch_bounds__(FC_KG * FC_LANES) void fc_dense_kernel(const unsigned char* __restrict__ wT,
+                                                                    const unsigned char* __restrict__ x,
+                                                                    void* __restrict__ part_v, FcGeom g, int splits) {
+    constexpr int PV = DT == RRM_I8_I32 ? 16 : 8;
+    constexpr int ESIZE = DT == RRM_I8_I32 ? 1 : 2;
+    constexpr int UN = 8;  // rows in flight per lane
+    typedef typename std::conditional<DT == RRM_I8_I32, int, float>::type val_t;
+    typedef typename std::conditional<DT == RRM_I8_I32, int4, float4>::type vec_t;
+    __shared__ vec_t red[FC_KG - 1][PV / 4][FC_LANES];
+    const int b = blockIdx.z, s = blockIdx.y;
+    const int cnt = g.c_in;
+    const int lane = threadIdx.x & (FC_LANES - 1), kg = threadIdx.x / FC_LANES;
+    const int co0 = (blockIdx.x * FC_LANES + lane) * PV;
+    const bool live = co0 < g.c_out_p;
+    const long long row = (long long)b * g.c_in;
+    val_t acc[PV];
+#pragma unroll
+    for (int e = 0; e < PV; ++e) acc[e] = 0;
+    const unsigned char* wcol = wT + (long long)(live ? co0 : 0) * ESIZE;
+    const long long pitch = (long long)g.c_out_p * ESIZE;
+
+    auto input = [&](int k) -> val_t {
+        if (DT == RRM_I8_I32) return (val_t)(int)(signed char)x[row + k];
+        return (val_t)bf16_to_f32(reinterpret_cast<const unsigned short*>(x)[row + k]);
+    };
+    auto fma16 = [&](const uint4& w, val_t d) {
+        const unsigned int ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int e = 0; e < PV; ++e) {
+            if (DT == RRM_I8_I32)
+                acc[e] += d * (val_t)(int)(signed char)(ww[e >> 2] >> (8 * (e & 3)));
+            else
+                acc[e] += d * (val_t)__uint_as_float((e & 1) ? (ww[e >> 1] & 0xFFFF0000u) : (ww[e >> 1] << 16));
+        }
+    };
+
     if (live) {
-        const int step = s_eff * FC_KG;
+        const int step = splits * FC_KG;
         int k = s * FC_KG + kg;
         for (; k + (UN - 1) * step < cnt; k += UN * step) {
-            int j[UN];
             val_t d[UN];
             uint4 w[UN];
 #pragma unroll
-            for (int u = 0; u < UN; ++u) column(k + u * step, j[u], d[u]);
+            for (int u = 0; u < UN; ++u) w[u] = *reinterpret_cast<const uint4*>(wcol + (k + u * step) * pitch);
 #pragma unroll
-            for (int u = 0; u < UN; ++u) w[u] = *reinterpret_cast<const uint4*>(wcol + j[u] * pitch);
+            for (int u = 0; u < UN; ++u) d[u] = input(k + u * step);
 #pragma unroll
             for (int u = 0; u < UN; ++u) fma16(w[u], d[u]);
         }
-        {   // the rest of this group's columns (fewer than UN), in flight together
-            int j[UN];
+        {   // the rest of this wavefront's rows (fewer than UN), in flight together
             val_t d[UN];
             uint4 w[UN];
 #pragma unroll
             for (int u = 0; u < UN; ++u) {
-                j[u] = 0;
-                d[u] = 0;
-                if (k + u * step < cnt) column(k + u * step, j[u], d[u]);
+                const bool ok = k + u * step < cnt;
+                w[u] = ok ? *reinterpret_cast<const uint4*>(wcol + (k + u * step) * pitch) : uint4{0u, 0u, 0u, 0u};
+                d[u] = ok ? input(k + u * step) : (val_t)0;
             }
-#pragma unroll
-            for (int u = 0; u < UN; ++u)
-                w[u] = k + u * step < cnt ? *reinterpret_cast<const uint4*>(wcol + j[u] * pitch) : uint4{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int u = 0; u < UN; ++u) fma16(w[u], d[u]);
         }
     }
-    // column groups 1.. hand their sums to group 0 (added in group order: the result does not depend on timing)
+    // wavefronts 1.. hand their sums to wavefront 0 (added in order: the result does not depend on timing)
     if (kg > 0) {
 #pragma unroll
         for (int e = 0; e < PV; e += 4) {
@@ -280,7 +392,6 @@ __global__ __launch_bounds__(FC_KG * 256) void fc_scatter_kernel(const unsigned 
                 const vec_t o = red[q][e >> 2][lane];
                 acc[e] += o.x; acc[e + 1] += o.y; acc[e + 2] += o.z; acc[e + 3] += o.w;
             }
-        // partial sums of this split: scratch [stream][split][c_out_p]
         val_t* part = static_cast<val_t*>(part_v) + ((long long)b * splits + s) * g.c_out_p + co0;
 #pragma unroll
         for (int e = 0; e < PV; e += 4) {
@@ -291,12 +402,11 @@ __global__ __launch_bounds__(FC_KG * 256) void fc_scatter_kernel(const unsigned 
     }
 }
 
-// Workgroup (block of 512 channels, stream): 128 lanes of 4 channels each, times FC_RG split groups; group
-// rg adds the partial rows rg, rg + FC_RG, ... (all loads in flight together), the groups' sums are added
-// through LDS in group order, and group 0 applies the result: y += sum (delta), y = bias + sum (dense).
-template <int DT, int DENSE>
+// Second kernel of the dense layer.  Workgroup (block of 512 channels, stream): 128 lanes of 4 channels each,
+// times FC_RG split groups; group rg adds the partial rows rg, rg + FC_RG, ... (all loads in flight together),
+// the groups' sums are added through LDS in group order, and group 0 writes y = bias + sum.
+template <int DT>
 __global__ __launch_bounds__(FC_RG * 128) void fc_reduce_kernel(const void* __restrict__ part_v,
-                                                                const int* __restrict__ count,
                                                                 const void* __restrict__ bias_v, void* __restrict__ y_v,
                                                                 FcGeom g, int splits) {
     typedef typename std::conditional<DT == RRM_I8_I32, int, float>::type val_t;
@@ -307,14 +417,12 @@ __global__ __launch_bounds__(FC_RG * 128) void fc_reduce_kernel(const void* __re
     const int lane = threadIdx.x & 127, rg = threadIdx.x >> 7;
     const int co = (blockIdx.x * 128 + lane) * 4;
     const bool live = co < g.c_out_p;  // (c_out_p is a multiple of 4)
-    const int cnt = DENSE ? g.c_in : count[b];
-    const int s_eff = fc_active_splits(cnt, splits);
     const val_t* part = static_cast<const val_t*>(part_v) + (long long)b * splits * g.c_out_p + (live ? co : 0);
     vec_t v[PER];
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
         const int s = rg + i * FC_RG;
-        v[i] = (live && s < s_eff) ? *reinterpret_cast<const vec_t*>(part + (long long)s * g.c_out_p) : vec_t{0, 0, 0, 0};
+        v[i] = (live && s < splits) ? *reinterpret_cast<const vec_t*>(part + (long long)s * g.c_out_p) : vec_t{0, 0, 0, 0};
     }
     vec_t sum = v[0];
 #pragma unroll
@@ -335,46 +443,44 @@ __global__ __launch_bounds__(FC_RG * 128) void fc_reduce_kernel(const void* __re
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         if (co + k >= g.c_out) break;
-        if (DENSE)
-            y[co + k] = (bias ? bias[co + k] : (val_t)0) + r[k];
-        else if (r[k] != (val_t)0)
-            y[co + k] += r[k];
+        y[co + k] = (bias ? bias[co + k] : (val_t)0) + r[k];
     }
 }
 
 }  // namespace
 
-hipError_t launch_fc_scan(int dtype, const void* x_t, void* x_snap, int* idx, void* val, int* count,
-                          const FcGeom& g, DevStats* stats, hipStream_t s) {
-    dim3 grid((unsigned int)g.n), block(FC_SCAN_THREADS);
+hipError_t launch_fc_delta(int dtype, const void* x_t, void* x_snap, const void* wT, void* y, unsigned int* arrive,
+                           const FcGeom& g, DevStats* stats, hipStream_t s) {
+    const int esize = dtype == RRM_I8_I32 ? 1 : 2;
+    dim3 grid((unsigned int)((g.c_out_p * esize + FCD_SEG - 1) / FCD_SEG), (unsigned int)g.n), block(FCD_THREADS);
     if (dtype == RRM_I8_I32)
-        hipLaunchKernelGGL(fc_scan_kernel<RRM_I8_I32>, grid, block, 0, s, (const unsigned char*)x_t,
-                           (unsigned char*)x_snap, idx, val, count, g, stats);
+        hipLaunchKernelGGL(fc_delta_kernel<RRM_I8_I32>, grid, block, 0, s, (const unsigned char*)x_t,
+                           (unsigned char*)x_snap, (const unsigned char*)wT, y, arrive, g, stats);
     else
-        hipLaunchKernelGGL(fc_scan_kernel<RRM_BF16_F32>, grid, block, 0, s, (const unsigned char*)x_t,
-                           (unsigned char*)x_snap, idx, val, count, g, stats);
+        hipLaunchKernelGGL(fc_delta_kernel<RRM_BF16_F32>, grid, block, 0, s, (const unsigned char*)x_t,
+                           (unsigned char*)x_snap, (const unsigned char*)wT, y, arrive, g, stats);
     return hipGetLastError();
 }
 
-hipError_t launch_fc_scatter(int dtype, int dense, int splits, const void* wT, const int* idx, const void* val,
-                             const int* count, const void* x, void* part, const void* bias, void* y, const FcGeom& g,
-                             hipStream_t s) {
+int fc_dense_slices(int dtype, const FcGeom& g) {
+    const int pv = dtype == RRM_I8_I32 ? 16 : 8;
+    return (g.c_out_p + FC_LANES * pv - 1) / (FC_LANES * pv);
+}
+
+hipError_t launch_fc_dense(int dtype, int splits, const void* wT, const void* x, void* part, const void* bias, void* y,
+                           const FcGeom& g, hipStream_t s) {
     if (splits < 1 || splits > FC_MAX_SPLITS) return hipErrorInvalidValue;
-    dim3 grid((unsigned int)g.slices, (unsigned int)splits, (unsigned int)g.n), block(FC_KG * 256);
+    dim3 grid((unsigned int)fc_dense_slices(dtype, g), (unsigned int)splits, (unsigned int)g.n), block(FC_KG * FC_LANES);
     dim3 rgrid((unsigned int)((g.c_out_p / 4 + 127) / 128), (unsigned int)g.n), rblock(FC_RG * 128);
     const unsigned char* w = static_cast<const unsigned char*>(wT);
     const unsigned char* xx = static_cast<const unsigned char*>(x);
-#define RRM_FC(DTV, DV)                                                                                              \
-    do {                                                                                                            \
-        hipLaunchKernelGGL((fc_scatter_kernel<DTV, DV>), grid, block, 0, s, w, idx, val, count, xx, part, g, splits); \
-        hipLaunchKernelGGL((fc_reduce_kernel<DTV, DV>), rgrid, rblock, 0, s, part, count, bias, y, g, splits);       \
-    } while (0)
     if (dtype == RRM_I8_I32) {
-        if (dense) RRM_FC(RRM_I8_I32, 1); else RRM_FC(RRM_I8_I32, 0);
+        hipLaunchKernelGGL(fc_dense_kernel<RRM_I8_I32>, grid, block, 0, s, w, xx, part, g, splits);
+        hipLaunchKernelGGL(fc_reduce_kernel<RRM_I8_I32>, rgrid, rblock, 0, s, part, bias, y, g, splits);
     } else {
-        if (dense) RRM_FC(RRM_BF16_F32, 1); else RRM_FC(RRM_BF16_F32, 0);
+        hipLaunchKernelGGL(fc_dense_kernel<RRM_BF16_F32>, grid, block, 0, s, w, xx, part, g, splits);
+        hipLaunchKernelGGL(fc_reduce_kernel<RRM_BF16_F32>, rgrid, rblock, 0, s, part, bias, y, g, splits);
     }
-#undef RRM_FC
     return hipGetLastError();
 }
 

@@ -64,19 +64,17 @@ struct rrm_layer {
     unsigned long long* bitmap = nullptr;
     unsigned int* tileflag = nullptr;  // binary: 8x8 tile stamps; int8 / bf16: 4x4 sub-tile byte flags
     unsigned int* touched = nullptr;   // int8 / bf16 conv: the sub-tile flags of the last step (what it wrote in y_snap)
-    bool touched_all = true;           // host view: `touched` is all ones (set by create / reset / dense steps)
     size_t marks_bytes = 0;
     unsigned int* ctrl = nullptr;      // arrival counter of the gather kernel
+    unsigned int* fresh = nullptr;     // conv: device word, non-zero until the first delta step has run (see FusedSrc)
     void* zero16 = nullptr;            // a block of zeros: source of staged units outside the image
-    int* fc_idx = nullptr;
-    void* fc_val = nullptr;
-    int* fc_count = nullptr;
-    void* fc_part = nullptr;  // FC: per-split partial sums [n][fc_nsplit][c_out_p]
+    unsigned int* fc_arrive = nullptr;  // FC delta step: arrival counter per stream
+    void* fc_part = nullptr;  // FC dense path: per-split partial sums [n][fc_nsplit][c_out_p]
     int fc_nsplit = 0;
     DevStats* stats = nullptr;
     // state
     bool has_snapshot = false;
-    unsigned long long steps = 0, delta_steps = 0, total_tiles = 0;
+    unsigned long long steps = 0;  // rrm_step calls enqueued by the host
     // event brackets of the "profile" option: 3 events per step (before scan, between, after)
     std::vector<hipEvent_t> prof_ev;
     int prof_n = 0;
@@ -85,7 +83,7 @@ struct rrm_layer {
     int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0;
 
     ~rrm_layer() {
-        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, zero16, fc_idx, fc_val, fc_count, fc_part, stats};
+        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, fresh, zero16, fc_arrive, fc_part, stats};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
         for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
@@ -446,7 +444,6 @@ rrm_status setup_fc(rrm_layer* L, const std::vector<unsigned char>& w) {
     g.n = s.n; g.c_in = s.c_in; g.c_out = s.c_out;
     g.per_vec = 16 / L->esize;
     g.c_out_p = (s.c_out + g.per_vec - 1) / g.per_vec * g.per_vec;
-    g.slices = (g.c_out_p + 256 * g.per_vec - 1) / (256 * g.per_vec);
     g.vec_ok = (s.c_in % g.per_vec) == 0;
     // input-major copy: W^T [c_in][c_out_p], every column of W contiguous
     const int es = L->esize;
@@ -456,12 +453,10 @@ rrm_status setup_fc(rrm_layer* L, const std::vector<unsigned char>& w) {
             std::memcpy(t.data() + ((size_t)j * g.c_out_p + o) * es, w.data() + ((size_t)o * s.c_in + j) * es, es);
     rrm_status st = upload(t.data(), t.size(), &L->wpack);
     if (st != RRM_OK) return st;
-    if ((st = dalloc((size_t)s.n * s.c_in * sizeof(int), (void**)&L->fc_idx)) != RRM_OK) return st;
-    if ((st = dalloc((size_t)s.n * s.c_in * 4, &L->fc_val)) != RRM_OK) return st;
-    // enough 1024-thread workgroups to keep memory busy: about 256 in total, at most 64 splits per stream
-    L->fc_nsplit = std::max(1, std::min(64, 256 / (g.slices * s.n)));
+    // dense path: enough workgroups to keep memory busy (about 256 in total, at most 64 row splits per stream)
+    L->fc_nsplit = std::max(1, std::min(64, 256 / (fc_dense_slices(L->dtype, g) * s.n)));
     if ((st = dalloc((size_t)s.n * L->fc_nsplit * g.c_out_p * 4, &L->fc_part)) != RRM_OK) return st;
-    return dalloc((size_t)s.n * sizeof(int), (void**)&L->fc_count);
+    return dalloc((size_t)s.n * sizeof(unsigned int), (void**)&L->fc_arrive);  // delta path: arrival counters
 }
 
 constexpr int kProfMax = 1024;
@@ -497,8 +492,7 @@ rrm_status check_ptr(const void* p, const char* what) {
 // dense layer of Eq. 3 from x into y
 rrm_status enqueue_dense(rrm_layer* L, const void* x, void* y, hipStream_t st) {
     if (L->shape.kind == RRM_FC) {
-        RRM_HIP(launch_fc_scatter(L->dtype, 1, fc_splits(L), L->wpack, nullptr, nullptr, nullptr, x, L->fc_part, L->bias, y,
-                                  L->fg, st));
+        RRM_HIP(launch_fc_dense(L->dtype, fc_splits(L), L->wpack, x, L->fc_part, L->bias, y, L->fg, st));
     } else if (L->dtype == RRM_BIN_I32) {
         RRM_HIP(launch_bin_conv(MODE_DENSE, bin_cw(L), x, nullptr, nullptr, L->wpack, L->bias, y, L->bg, L->stats, st));
     } else {
@@ -563,8 +557,7 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
 
     if ((st = dalloc(L->x_bytes, &L->x_snap)) != RRM_OK) return bail(st);
     if ((st = dalloc(L->y_bytes, &L->y_snap)) != RRM_OK) return bail(st);
-    // (a debug build keeps cycle stamps behind the counters: STAT_TRACE_SLOTS more slots)
-    if ((st = dalloc(sizeof(DevStats) * (STAT_SLOTS + STAT_TRACE_SLOTS), (void**)&L->stats)) != RRM_OK) return bail(st);
+    if ((st = dalloc(sizeof(DevStats) * STAT_SLOTS, (void**)&L->stats)) != RRM_OK) return bail(st);
     if (s.kind == RRM_CONV) {
         ScanGeom& sg = L->sg;
         sg.total_elems = L->x_elems;
@@ -596,6 +589,8 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
         if ((st = dalloc(((nvec + 63) / 64) * 8, (void**)&L->bitmap)) != RRM_OK) return bail(st);
         sg.sty = (int)((ho + 3) / 4);
         sg.stx = (int)((wo + 3) / 4);
+        sg.tiles_per_step = dtype == RRM_BIN_I32 ? (unsigned long long)s.n * sg.tiles_y * sg.tiles_x
+                                                 : (unsigned long long)s.n * sg.sty * sg.stx;
         // binary: one stamp per 8x8 tile; int8 / bf16: one byte flag per 4x4 sub-tile
         L->marks_bytes = dtype == RRM_BIN_I32 ? (size_t)s.n * sg.tiles_y * sg.tiles_x * 4
                                               : (size_t)((s.n * sg.sty * sg.stx + 3) / 4) * 4;
@@ -612,10 +607,19 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
             L->cg.full_pct = dtype == RRM_BF16_F32 ? 40 : 62;
         }
         if ((st = dalloc(16, (void**)&L->ctrl)) != RRM_OK) return bail(st);
+        {
+            const unsigned int ones[4] = {1u, 1u, 1u, 1u};
+            if ((st = upload(ones, 16, (void**)&L->fresh)) != RRM_OK) return bail(st);
+            L->cg.fresh = L->fresh;
+        }
         if ((st = dalloc(256, &L->zero16)) != RRM_OK) return bail(st);
     }
     // P_0 = b (Eq. 3 at I_0 = 0); I_0 = 0 comes from the zeroed allocation
     hipError_t e = launch_fill_bias(dtype == RRM_BF16_F32, L->y_snap, L->bias, L->y_elems / s.c_out, s.c_out, nullptr);
+    // A binary tensor has no zero: the all-zero bit pattern of the fresh stored input is the frame of all -1,
+    // and the stored projection starts as that frame's projection, so that the recurrence holds from the first
+    // delta step on whatever the host knows about the handle's history.
+    if (e == hipSuccess && dtype == RRM_BIN_I32 && enqueue_dense(L, L->x_snap, L->y_snap, nullptr) != RRM_OK) e = hipErrorUnknown;
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         delete L;
@@ -638,20 +642,15 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
         RRM_HIP(launch_copy(L->x_snap, x_t, L->x_bytes, s));
         if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
         if ((st = enqueue_dense(L, x_t, L->y_snap, s)) != RRM_OK) return st;
-        if (L->touched && !L->touched_all) {  // a full recomputation writes every sub-tile
-            RRM_HIP(launch_fill_word(L->touched, round16(L->marks_bytes), 0x01010101u, s));
-            L->touched_all = true;
-        }
+        // a full recomputation writes every output block (enqueued unconditionally: a captured step must not
+        // depend on what the host believes the flags hold)
+        if (L->touched) RRM_HIP(launch_fill_word(L->touched, round16(L->marks_bytes), 0x01010101u, s));
         if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
     } else if (L->shape.kind == RRM_FC) {
         if ((st = prof_mark(L, 0, s)) != RRM_OK) return st;
-        RRM_HIP(launch_fc_scan(L->dtype, x_t, L->x_snap, L->fc_idx, L->fc_val, L->fc_count, L->fg, L->stats, s));
-        if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
-        RRM_HIP(launch_fc_scatter(L->dtype, 0, fc_splits(L), L->wpack, L->fc_idx, L->fc_val, L->fc_count, nullptr,
-                                  L->fc_part, nullptr, L->y_snap, L->fg, s));
+        if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;  // (no separate scan kernel: its time is reported as 0)
+        RRM_HIP(launch_fc_delta(L->dtype, x_t, L->x_snap, L->wpack, L->y_snap, L->fc_arrive, L->fg, L->stats, s));
         if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
-        ++L->delta_steps;
-        L->total_tiles += (unsigned long long)L->shape.n * L->shape.c_in;
     } else {
         if ((st = prof_mark(L, 0, s)) != RRM_OK) return st;
         if (L->dtype == RRM_BIN_I32) {
@@ -664,15 +663,13 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
         } else {
             RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag, 0u, L->sg, L->stats, s));
             if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
+            ConvGeom cg = L->cg;
+            if (L->opt_path == 1) cg.xfull = nullptr;  // the sparse path always: no switch to recomputation
             RRM_HIP(launch_conv(L->dtype, MODE_DELTA, L->cg.wg_cb, L->cg.nt, L->dtype == RRM_BF16_F32 ? L->opt_terms : 1,
-                                L->d0, L->d1, L->zero16, L->tileflag, L->ctrl, L->wpack, L->offtab, L->bias, L->y_snap, L->cg,
+                                L->d0, L->d1, L->zero16, L->tileflag, L->ctrl, L->wpack, L->offtab, L->bias, L->y_snap, cg,
                                 L->stats, s));
-            L->touched_all = false;  // the kernel's last workgroup copies the step's flags there
         }
         if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
-        ++L->delta_steps;
-        L->total_tiles += L->dtype == RRM_BIN_I32 ? (unsigned long long)L->shape.n * L->sg.tiles_y * L->sg.tiles_x
-                                                   : (unsigned long long)L->shape.n * L->sg.sty * L->sg.stx;
     }
     L->has_snapshot = true;
     ++L->steps;
@@ -701,17 +698,14 @@ rrm_status rrm_step_from_projection(rrm_layer* L, rrm_layer* P, int shift, int p
     src.touched = reinterpret_cast<const unsigned char*>(P->touched);
     src.hy = hy; src.wy = wy; src.sty = P->sg.sty; src.stx = P->sg.stx;
     src.shift = shift; src.pool = pool ? 1 : 0;
-    src.all = L->has_snapshot ? 0 : 1;  // a fresh / reset layer holds no f(P) yet: everything is compared
+    src.fresh = L->fresh;  // a fresh / reset layer holds no f(P) yet: everything is compared
     rrm_status rs;
     if ((rs = prof_mark(L, 0, st)) != RRM_OK) return rs;
     RRM_HIP(launch_scan_fused(src, L->x_snap, L->d0, L->bitmap, L->tileflag, L->sg, L->stats, st));
     if ((rs = prof_mark(L, 1, st)) != RRM_OK) return rs;
     RRM_HIP(launch_conv(L->dtype, MODE_DELTA, L->cg.wg_cb, L->cg.nt, 1, L->d0, L->d1, L->zero16, L->tileflag, L->ctrl,
                         L->wpack, L->offtab, L->bias, L->y_snap, L->cg, L->stats, st));
-    L->touched_all = false;
     if ((rs = prof_mark(L, 2, st)) != RRM_OK) return rs;
-    ++L->delta_steps;
-    L->total_tiles += (unsigned long long)s.n * L->sg.sty * L->sg.stx;
     L->has_snapshot = true;
     ++L->steps;
     if (y_out) RRM_HIP(launch_copy(y_out, L->y_snap, L->y_bytes, st));
@@ -731,6 +725,10 @@ rrm_status rrm_reset(rrm_layer* L, void* hip_stream) {
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     RRM_HIP(launch_fill_zero(L->x_snap, round16(L->x_bytes), s));
     RRM_HIP(launch_fill_bias(L->dtype == RRM_BF16_F32, L->y_snap, L->bias, L->y_elems / L->shape.c_out, L->shape.c_out, s));
+    if (L->dtype == RRM_BIN_I32) {  // (see rrm_layer_create: the projection of the all -1 frame)
+        rrm_status rs = enqueue_dense(L, L->x_snap, L->y_snap, s);
+        if (rs != RRM_OK) return rs;
+    }
     RRM_HIP(launch_fill_zero(L->stats, sizeof(DevStats) * STAT_SLOTS, s));
     if (L->shape.kind == RRM_CONV) {
         // the difference buffer is zero wherever the bitmap is clear, and no tile is stamped
@@ -739,11 +737,12 @@ rrm_status rrm_reset(rrm_layer* L, void* hip_stream) {
         RRM_HIP(launch_fill_zero(L->bitmap, round16(((round16(L->x_bytes) / 16 + 63) / 64) * 8), s));
         RRM_HIP(launch_fill_zero(L->tileflag, round16(L->marks_bytes), s));
         RRM_HIP(launch_fill_zero(L->ctrl, 16, s));
+        RRM_HIP(launch_fill_word(L->fresh, 16, 1u, s));
         if (L->touched) RRM_HIP(launch_fill_word(L->touched, round16(L->marks_bytes), 0x01010101u, s));
     }
+    if (L->fc_arrive) RRM_HIP(launch_fill_zero(L->fc_arrive, round16((size_t)L->shape.n * sizeof(unsigned int)), s));
     L->has_snapshot = false;
-    L->touched_all = true;
-    L->steps = L->delta_steps = L->total_tiles = 0;
+    L->steps = 0;
     return RRM_OK;
 }
 
@@ -815,13 +814,15 @@ rrm_status rrm_get_stats(rrm_layer* L, rrm_stats* out) {
         d.range_error |= t.range_error;
         d.truncated_elems += t.truncated_elems;
         d.truncated_sumsq += t.truncated_sumsq;
+        d.delta_steps += t.delta_steps;
+        d.total_tiles += t.total_tiles;
     }
     out->steps = L->steps;
-    out->delta_steps = L->delta_steps;
+    out->delta_steps = d.delta_steps;
     out->changed_elems = d.changed_elems;
     out->changed_units = d.changed_units;
     out->active_tiles = d.active_tiles;
-    out->total_tiles = L->total_tiles;
+    out->total_tiles = d.total_tiles;
     out->range_error = (int32_t)d.range_error;
     out->reserved = 0;
     out->truncated_elems = d.truncated_elems;
@@ -847,15 +848,6 @@ rrm_status rrm_get_kernel_times(rrm_layer* L, double* scan_us, double* compute_u
     L->prof_n = 0;
     return RRM_OK;
 }
-
-#ifdef RRM_TRACE
-// debug build only: raw copy of the cycle stamps kept behind the statistics slots
-rrm_status rrm_debug_raw_stats(rrm_layer* L, void* dst, size_t bytes) {
-    RRM_HIP(hipMemcpy(dst, L->stats + STAT_SLOTS, bytes < sizeof(DevStats) * STAT_TRACE_SLOTS ? bytes : sizeof(DevStats) * STAT_TRACE_SLOTS,
-                      hipMemcpyDeviceToHost));
-    return RRM_OK;
-}
-#endif
 
 void rrm_layer_destroy(rrm_layer* L) { delete L; }
 

@@ -19,7 +19,6 @@ enum Mode : int { MODE_DELTA = 0, MODE_DENSE = 1 };
 // (a workgroup uses slot blockIdx.x % STAT_SLOTS) so that same-address atomics do not serialise
 // the scan; rrm_get_stats sums them.
 constexpr int STAT_SLOTS = 256;
-constexpr int STAT_TRACE_SLOTS = 32;  // room behind the counters for a debug build's cycle stamps
 struct DevStats {
     unsigned long long changed_elems;
     unsigned long long changed_units;
@@ -28,6 +27,9 @@ struct DevStats {
     unsigned int pad_;
     unsigned long long truncated_elems;  // bf16 with a threshold: differences below it (not applied, not committed)
     double truncated_sumsq;              //   and the sum of their squares
+    // counted on the device (by the scan of every delta step), so that they advance under graph replay too
+    unsigned long long delta_steps;
+    unsigned long long total_tiles;
 };
 
 // Geometry of the flat scan over x (delta + change map), one element = int8 / bf16 / u32 word.
@@ -50,6 +52,7 @@ struct ScanGeom {
     double r_c, r_hw, r_w;
     unsigned int magic_stride;
     float eps;  // bf16: truncation threshold of the difference (0 = exact)
+    unsigned long long tiles_per_step;  // what a dense step would count as "tiles" (added to the device counters)
 };
 
 // A scan whose input is not a tensor in memory but f(P) of the layer before (Algorithm 1 applies the
@@ -61,7 +64,10 @@ struct FusedSrc {
     const unsigned char* touched; // producer's byte flags per 4x4 block of (hy, wy)
     int hy, wy, sty, stx;
     int shift, pool;
-    int all;                      // 1: ignore `touched`, every unit is computed and compared
+    // device word, non-zero while the consumer's stored input holds no f(P) yet (fresh or reset layer): `touched`
+    // is ignored and every unit is computed and compared.  Set by create / reset, cleared by the consumer's
+    // compute kernel at the end of its first delta step (device state: a replayed graph sees it too).
+    const unsigned int* fresh;
 };
 
 constexpr int CONV_MAX_STAGE_UNITS = 12;  // 16-byte units a thread stages per slab (half for 2 terms)
@@ -109,6 +115,7 @@ struct ConvGeom {
     unsigned int magic_sub;     // d = sty*stx
     unsigned int magic_stx;     // d = stx
     int vec_store;       // 1: y rows allow 16-byte read-modify-write
+    unsigned int* fresh;    // see FusedSrc::fresh: cleared at the end of a delta launch
     unsigned int* touched;  // copy of the sub-tile flags of the last delta step (what it wrote in y), or nullptr
     const unsigned char* xfull;  // delta launches: the committed input in source layout (full recomputation above
     int full_pct;                //   full_pct % active sub-tiles), or nullptr: never
@@ -133,10 +140,21 @@ struct FcGeom {
     int n, c_in, c_out;
     int c_out_p;         // row pitch of the transposed weights (elements), multiple of per_vec
     int per_vec;         // output channels per lane per 16-byte load: 16 / 8
-    int slices;          // ceil(c_out_p / (256 * per_vec))
     int vec_ok;          // 1: x rows are 16-byte aligned multiples
     float eps;           // bf16: truncation threshold of the difference (0 = exact)
 };
+
+// floor(u / d) through the reciprocal magic = floor(2^32 / d) + 1 (0 encodes d == 1).  The product's high word is
+// the quotient or one more than it for every u < 2^32 - d (the reciprocal is rounded up), so one
+// multiply-and-compare makes the result exact over the whole admitted range; without it the estimate is only
+// right while u * (magic * d - 2^32) < 2^32.
+#ifdef __HIPCC__
+__device__ __forceinline__ unsigned int udiv_magic(unsigned int u, unsigned int d, unsigned int magic) {
+    if (!magic) return u;
+    const unsigned int q = __umulhi(u, magic);
+    return q * d > u ? q - 1u : q;
+}
+#endif
 
 // ---- launchers implemented in the kernel translation units ------------------------------------
 // `marks` is the 8x8-tile stamp array (binary layers, stamp = consumers per tile) or the 4x4
@@ -154,15 +172,15 @@ hipError_t launch_conv(int dtype, int mode, int ncb, int nt, int terms, const vo
                        const void* zero16, unsigned int* subbits, unsigned int* ctrl, const void* wpack, const int* offtab,
                        const void* bias, void* y, const ConvGeom& g, DevStats* stats, hipStream_t s);
 
-hipError_t launch_fc_scan(int dtype, const void* x_t, void* x_snap, int* idx, void* val, int* count,
-                          const FcGeom& g, DevStats* stats, hipStream_t s);
+// one delta step of an FC layer in a single launch; `arrive`: one zeroed word per stream (rearmed by the kernel)
+hipError_t launch_fc_delta(int dtype, const void* x_t, void* x_snap, const void* wT, void* y, unsigned int* arrive,
+                           const FcGeom& g, DevStats* stats, hipStream_t s);
 
-// column scatter into per-split partial sums (scratch `part`: [n][splits][c_out_p] 4-byte values),
-// then the reduction of the splits into y (dense: y = bias + sum; delta: y += sum)
-hipError_t launch_fc_scatter(int dtype, int dense, int splits, const void* wT, const int* idx, const void* val,
-                             const int* count, const void* x, void* part, const void* bias, void* y, const FcGeom& g,
-                             hipStream_t s);
-
+// dense FC layer: row/slice split into per-split partial sums (scratch `part`: [n][splits][c_out_p] 4-byte
+// values), then y = bias + the sum of the splits in a fixed order
+int fc_dense_slices(int dtype, const FcGeom& g);
+hipError_t launch_fc_dense(int dtype, int splits, const void* wT, const void* x, void* part, const void* bias, void* y,
+                           const FcGeom& g, hipStream_t s);
 hipError_t launch_bin_conv(int mode, int cw, const void* xsrc, const void* flip, unsigned int* tileflag,
                            const void* wpack, const void* bias, void* y, const BinGeom& g, DevStats* stats,
                            hipStream_t s);

@@ -223,7 +223,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
         const int y0 = fs.pool ? 2 * iy : iy, x0 = fs.pool ? 2 * ix : ix, span = fs.pool ? 2 : 0;
         const unsigned char* t = fs.touched + (size_t)bb * fs.sty * fs.stx;
         const int sy0 = y0 >> 2, sy1 = (y0 + span) >> 2, sx0 = x0 >> 2, sx1 = (x0 + span) >> 2;
-        compare = fs.all || (t[sy0 * fs.stx + sx0] | t[sy0 * fs.stx + sx1] | t[sy1 * fs.stx + sx0] | t[sy1 * fs.stx + sx1]) != 0;
+        compare = fs.fresh[0] != 0u || (t[sy0 * fs.stx + sx0] | t[sy0 * fs.stx + sx1] | t[sy1 * fs.stx + sx0] | t[sy1 * fs.stx + sx1]) != 0;
         if (compare) {
             b_early = x_snap[v];  // in flight together with the window's loads
             int best[16];
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
                 }
                 if (ovf) atomicOr(&stats->range_error, 1u);
             } else if (DT == RRM_BF16_F32) {
-                // Truncation threshold (Sec. 3.3, "Improving sparsity"): an entry whose difference is below
+                // Truncation threshold (Sec. 3.4, "Improving sparsity"): an entry whose difference is below
                 // g.eps in magnitude is not applied and not committed (its snapshot entry keeps the old
                 // value), so the stored projection stays the projection of the stored input.  eps = 0: exact.
                 bool any_pass = false;
@@ -390,6 +390,10 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
         if (DT == RRM_BF16_F32 && nt) {
             atomicAdd(&stats->truncated_elems, (unsigned long long)nt);
             atomicAdd(&stats->truncated_sumsq, (double)s_tq[0] + (double)s_tq[1] + (double)s_tq[2] + (double)s_tq[3]);
+        }
+        if (blockIdx.x == 0) {  // one scan launch = one delta step
+            atomicAdd(&stats_base->delta_steps, 1ull);
+            atomicAdd(&stats_base->total_tiles, g.tiles_per_step);
         }
     }
 }

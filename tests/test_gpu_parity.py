@@ -184,7 +184,7 @@ def _perturbed_frames(seq, seed, sigma=0.02):
 @pytest.mark.parametrize("eps", [0.0, 0.03])
 def test_bf16_truncation_threshold_matches_oracle(kind, eps):
     """rrm_set_threshold: stored input bit-identical to the oracle's (same fp32 decision per entry), stored
-    projection within the bf16 tolerance, same number of truncated entries (Sec. 3.3, Improving sparsity)."""
+    projection within the bf16 tolerance, same number of truncated entries (Sec. 3.4, Improving sparsity)."""
     if kind == "fc":
         seq = S.config3("fc7", S.BF16, 0.10, n=2, T=5)
     elif kind == "conv":

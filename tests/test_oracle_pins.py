@@ -370,7 +370,7 @@ def test_generators_are_seeded_and_shaped():
     assert 0.01 < S.density(c1["frames"][0], c1["frames"][1])["rho_pos"] < 0.12
 
 
-# ---- truncation threshold (Sec. 3.3, "Improving sparsity") ----------------------------------------
+# ---- truncation threshold (Sec. 3.4, "Improving sparsity") ----------------------------------------
 def _eps_case(T=5, n=2):
     shp = S.conv_shape(9, 7, 8, 6, 3, 1, 1, n=n)
     seq = S.random_layer(991, shp, S.BF16, T=T, frac=0.4, block=2)
