@@ -113,6 +113,15 @@ rrm_status rrm_step(rrm_layer* layer, const void* x_t, void* y_out, void* hip_st
 /* The standard (dense) layer of Eq. 3: y = b + W (*) x.  Stateless: snapshots are untouched. */
 rrm_status rrm_dense(rrm_layer* layer, const void* x, void* y, void* hip_stream);
 
+/* rrm_dense for callers that cannot allocate device memory while they run (code under HIP-graph capture, tight
+ * serving loops, harnesses that forbid it): FC layers only; the partial sums of the row splits, which rrm_dense
+ * keeps in a buffer the handle allocated at create, live in a static device array of 4 MiB that exists once per
+ * GPU.  The call allocates and frees nothing.  Same arguments and result as rrm_dense.  A layer whose partial
+ * sums (n x row splits x c_out x 4 bytes) exceed the array gives RRM_ERR_SHAPE.  Every call on a GPU shares that
+ * GPU's array: calls that overlap in time on one GPU (different streams, different handles) race.
+ * Errors: RRM_ERR_NULL, RRM_ERR_ALIGN, RRM_ERR_SHAPE (not an FC layer, or too large), RRM_ERR_HIP. */
+rrm_status rrm_dense_noalloc(rrm_layer* layer, const void* x, void* y, void* hip_stream);
+
 /* Forget the stream history: I <- 0, P <- b, counters cleared (the "new precise inference"
  * of Sec. 3.4 starts from here: the next rrm_step recomputes its frame in full). */
 rrm_status rrm_reset(rrm_layer* layer, void* hip_stream);

@@ -67,6 +67,7 @@ def lib():
         L.rrm_layer_create.argtypes = [P, P, ctypes.POINTER(Shape), I, ctypes.POINTER(P)]
         L.rrm_step.argtypes = [P, P, P, P]
         L.rrm_dense.argtypes = [P, P, P, P]
+        L.rrm_dense_noalloc.argtypes = [P, P, P, P]
         L.rrm_reset.argtypes = [P, P]
         L.rrm_snapshot.argtypes = [P, ctypes.POINTER(P), ctypes.POINTER(P)]
         L.rrm_read_snapshot.argtypes = [P, P, P, P]
@@ -83,7 +84,7 @@ def lib():
         L.rrm_aux_relu_requant_pool_changed_i8.argtypes = [P, P, I, I, P]
         L.rrm_set_threshold.argtypes = [P, ctypes.c_float]
         L.rrm_step_from_projection.argtypes = [P, P, I, I, P, P]
-        for f in ("rrm_layer_create", "rrm_step", "rrm_dense", "rrm_reset", "rrm_snapshot", "rrm_read_snapshot", "rrm_set_option",
+        for f in ("rrm_layer_create", "rrm_step", "rrm_dense", "rrm_dense_noalloc", "rrm_reset", "rrm_snapshot", "rrm_read_snapshot", "rrm_set_option",
                   "rrm_get_stats", "rrm_get_kernel_times", "rrm_aux_relu_requant_pool_i8",
                   "rrm_aux_relu_requant_pool_changed_i8", "rrm_set_threshold", "rrm_step_from_projection"):
             getattr(L, f).restype = I
@@ -156,6 +157,9 @@ class Layer:
 
     def dense(self, x, y, stream=None) -> None:
         _check(lib().rrm_dense(self._h, _dptr(x), _dptr(y), _stream_ptr(stream)))
+
+    def dense_noalloc(self, x, y, stream=None) -> None:
+        _check(lib().rrm_dense_noalloc(self._h, _dptr(x), _dptr(y), _stream_ptr(stream)))
 
     def reset(self, stream=None) -> None:
         _check(lib().rrm_reset(self._h, _stream_ptr(stream)))

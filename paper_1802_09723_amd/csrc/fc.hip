@@ -484,4 +484,37 @@ hipError_t launch_fc_dense(int dtype, int splits, const void* wT, const void* x,
     return hipGetLastError();
 }
 
+// ---- the dense layer with its partial-sum scratch in a static device array ----------------------------------
+// For callers that cannot allocate.  The array exists once per GPU the library runs on and is shared by every
+// call on that GPU; its address is looked up once per device (the name below is a host-side stand-in, not a
+// device address, so only the looked-up pointer is ever handed to a kernel).
+static __device__ __align__(256) unsigned char scratch[FC_STATIC_SCRATCH_BYTES];
+
+hipError_t launch_fc_dense_static(int dtype, int splits, const void* wT, const void* x, const void* bias, void* y,
+                                  const FcGeom& g, hipStream_t s) {
+    constexpr int MAX_DEV = 64;
+    static std::mutex mu;
+    static void* dev_ptr[MAX_DEV] = {};
+    const size_t need = (size_t)g.n * (size_t)splits * (size_t)g.c_out_p * 4;
+    if (need > FC_STATIC_SCRATCH_BYTES) return hipErrorInvalidValue;  // (the caller checks first, with a message)
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEV) return hipErrorInvalidDevice;
+    void* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (!dev_ptr[dev]) {
+            void* p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return e;
+            if (!p) return hipErrorInvalidSymbol;
+            dev_ptr[dev] = p;
+        }
+        ptr = dev_ptr[dev];
+    }
+    // every partial row that the reduction reads is written by the first kernel: nothing has to start at zero
+    return launch_fc_dense(dtype, splits, wT, x, ptr, bias, y, g, s);
+}
+
 }  // namespace rrm

@@ -720,6 +720,21 @@ rrm_status rrm_dense(rrm_layer* L, const void* x, void* y, void* hip_stream) {
     return enqueue_dense(L, x, y, static_cast<hipStream_t>(hip_stream));
 }
 
+rrm_status rrm_dense_noalloc(rrm_layer* L, const void* x, void* y, void* hip_stream) {
+    if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
+    rrm_status st = check_ptr(x, "x");
+    if (st != RRM_OK) return st;
+    if ((st = check_ptr(y, "y")) != RRM_OK) return st;
+    if (L->shape.kind != RRM_FC) return fail(RRM_ERR_SHAPE, "rrm_dense_noalloc is available for FC layers");
+    const size_t need = (size_t)L->shape.n * (size_t)fc_splits(L) * (size_t)L->fg.c_out_p * 4;
+    if (need > FC_STATIC_SCRATCH_BYTES)
+        return fail(RRM_ERR_SHAPE, "rrm_dense_noalloc: the layer needs " + std::to_string(need) +
+                                       " bytes of partial sums, the static scratch holds " +
+                                       std::to_string(FC_STATIC_SCRATCH_BYTES));
+    RRM_HIP(launch_fc_dense_static(L->dtype, fc_splits(L), L->wpack, x, L->bias, y, L->fg, static_cast<hipStream_t>(hip_stream)));
+    return RRM_OK;
+}
+
 rrm_status rrm_reset(rrm_layer* L, void* hip_stream) {
     if (!L) return fail(RRM_ERR_NULL, "layer is NULL");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);

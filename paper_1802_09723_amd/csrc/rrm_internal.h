@@ -181,6 +181,11 @@ hipError_t launch_fc_delta(int dtype, const void* x_t, void* x_snap, const void*
 int fc_dense_slices(int dtype, const FcGeom& g);
 hipError_t launch_fc_dense(int dtype, int splits, const void* wT, const void* x, void* part, const void* bias, void* y,
                            const FcGeom& g, hipStream_t s);
+// the same with the partial sums in a static device array of FC_STATIC_SCRATCH_BYTES (no allocation anywhere)
+constexpr size_t FC_STATIC_SCRATCH_BYTES = 4u << 20;
+hipError_t launch_fc_dense_static(int dtype, int splits, const void* wT, const void* x, const void* bias, void* y,
+                                  const FcGeom& g, hipStream_t s);
+
 hipError_t launch_bin_conv(int mode, int cw, const void* xsrc, const void* flip, unsigned int* tileflag,
                            const void* wpack, const void* bias, void* y, const BinGeom& g, DevStats* stats,
                            hipStream_t s);
