@@ -18,7 +18,7 @@ namespace rrm {
 namespace {
 
 constexpr int FCD_THREADS = 1024;  // 16 wavefronts
-constexpr int FCD_CH = 8192;        // inputs compared per round = capacity of the changed-column list in LDS
+constexpr int FCD_CH = 8192;        // inputs of one compare round = capacity of the changed-column list in LDS
 constexpr int FCD_UN = 8;           // columns in flight per lane
 constexpr int FCD_SEG = 64;         // bytes of a weight column one workgroup owns (4 lanes of 16 bytes)
 
@@ -60,73 +60,74 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
     unsigned int ntrunc = 0, total = 0;
     float tsq = 0.f;
 
-    // difference of one 16-byte unit (PV entries from element e0 of the row): mask of entries to apply, values
-    auto diff_unit = [&](int e0, val_t (&dv)[PV], unsigned int& mask, uint4& a_out, uint4& n_out, bool count) {
-        mask = 0;
+    // the two copies of one 16-byte unit (PV entries from element e0 of the row); rows that are not 16-byte
+    // multiples are gathered element by element (zeros beyond the row's end)
+    auto load_unit = [&](int e0, uint4& a, uint4& s) {
         if (g.vec_ok) {
-            const uint4 a = *reinterpret_cast<const uint4*>(x_t + (row + e0) * ESIZE);
-            const uint4 s = *reinterpret_cast<const uint4*>(x_snap + (row + e0) * ESIZE);
-            a_out = a;
-            n_out = a;
-            if (!((a.x ^ s.x) | (a.y ^ s.y) | (a.z ^ s.z) | (a.w ^ s.w))) return;
-            const unsigned int aw[4] = {a.x, a.y, a.z, a.w}, sw[4] = {s.x, s.y, s.z, s.w};
-            unsigned int nw[4] = {a.x, a.y, a.z, a.w};  // the unit's new snapshot
+            a = *reinterpret_cast<const uint4*>(x_t + (row + e0) * ESIZE);
+            s = *reinterpret_cast<const uint4*>(x_snap + (row + e0) * ESIZE);
+            return;
+        }
+        unsigned int aw[4] = {0u, 0u, 0u, 0u}, sw[4] = {0u, 0u, 0u, 0u};
+        for (int e = 0; e < PV; ++e) {
+            if (e0 + e >= g.c_in) break;
+            if (DT == RRM_I8_I32) {
+                aw[e >> 2] |= (unsigned int)x_t[row + e0 + e] << (8 * (e & 3));
+                sw[e >> 2] |= (unsigned int)x_snap[row + e0 + e] << (8 * (e & 3));
+            } else {
+                aw[e >> 1] |= (unsigned int)reinterpret_cast<const unsigned short*>(x_t)[row + e0 + e] << (16 * (e & 1));
+                sw[e >> 1] |= (unsigned int)reinterpret_cast<const unsigned short*>(x_snap)[row + e0 + e] << (16 * (e & 1));
+            }
+        }
+        a = make_uint4(aw[0], aw[1], aw[2], aw[3]);
+        s = make_uint4(sw[0], sw[1], sw[2], sw[3]);
+    };
+    // difference of a unit: mask of the entries to apply, their values, and the unit's new snapshot
+    auto diff_unit = [&](const uint4& a, const uint4& s, val_t (&dv)[PV], unsigned int& mask, uint4& n_out) {
+        mask = 0;
+        n_out = a;
+        if (!((a.x ^ s.x) | (a.y ^ s.y) | (a.z ^ s.z) | (a.w ^ s.w))) return;
+        const unsigned int aw[4] = {a.x, a.y, a.z, a.w}, sw[4] = {s.x, s.y, s.z, s.w};
+        unsigned int nw[4] = {a.x, a.y, a.z, a.w};
 #pragma unroll
-            for (int e = 0; e < PV; ++e) {
-                if (DT == RRM_I8_I32) {
-                    const int xa = (int)(signed char)(aw[e >> 2] >> (8 * (e & 3)));
-                    const int xb = (int)(signed char)(sw[e >> 2] >> (8 * (e & 3)));
-                    dv[e] = (val_t)(xa - xb);
-                    if (xa != xb) mask |= 1u << e;
-                } else {
-                    // (truncation threshold, Sec. 3.4 "Improving sparsity": a difference below g.eps is
-                    // neither applied nor committed; eps = 0 is the exact method)
-                    const unsigned int xa = (aw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-                    const unsigned int xb = (sw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-                    const float d = bf16_to_f32(xa) - bf16_to_f32(xb);
-                    dv[e] = (val_t)d;
-                    if (xa != xb) {
-                        if (fabsf(d) < g.eps) {
-                            if (count) {
-                                ++ntrunc;
-                                tsq += d * d;
-                            }
-                            nw[e >> 1] = (nw[e >> 1] & ~(0xFFFFu << (16 * (e & 1)))) | (xb << (16 * (e & 1)));
-                        } else {
-                            mask |= 1u << e;
-                        }
-                    }
-                }
-            }
-            n_out = make_uint4(nw[0], nw[1], nw[2], nw[3]);
-        } else {
-            for (int e = 0; e < PV; ++e) {
-                dv[e] = 0;
-                if (e0 + e >= g.c_in) continue;
-                if (DT == RRM_I8_I32) {
-                    const signed char xa = (signed char)x_t[row + e0 + e];
-                    const signed char xb = (signed char)x_snap[row + e0 + e];
-                    if (xa != xb) {
+        for (int e = 0; e < PV; ++e) {
+            if (DT == RRM_I8_I32) {
+                const int xa = (int)(signed char)(aw[e >> 2] >> (8 * (e & 3)));
+                const int xb = (int)(signed char)(sw[e >> 2] >> (8 * (e & 3)));
+                dv[e] = (val_t)(xa - xb);
+                if (xa != xb) mask |= 1u << e;
+            } else {
+                // (truncation threshold, Sec. 3.4 "Improving sparsity": a difference below g.eps is neither
+                // applied nor committed; eps = 0 is the exact method)
+                const unsigned int xa = (aw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                const unsigned int xb = (sw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                const float d = bf16_to_f32(xa) - bf16_to_f32(xb);
+                dv[e] = (val_t)d;
+                if (xa != xb) {
+                    if (fabsf(d) < g.eps) {
+                        ++ntrunc;
+                        tsq += d * d;
+                        nw[e >> 1] = (nw[e >> 1] & ~(0xFFFFu << (16 * (e & 1)))) | (xb << (16 * (e & 1)));
+                    } else {
                         mask |= 1u << e;
-                        dv[e] = (val_t)((int)xa - (int)xb);
-                    }
-                } else {
-                    const unsigned short xa = reinterpret_cast<const unsigned short*>(x_t)[row + e0 + e];
-                    const unsigned short xb = reinterpret_cast<const unsigned short*>(x_snap)[row + e0 + e];
-                    if (xa != xb) {
-                        const float d = bf16_to_f32(xa) - bf16_to_f32(xb);
-                        if (fabsf(d) < g.eps) {
-                            if (count) {
-                                ++ntrunc;
-                                tsq += d * d;
-                            }
-                        } else {
-                            mask |= 1u << e;
-                            dv[e] = (val_t)d;
-                        }
                     }
                 }
             }
+        }
+        n_out = make_uint4(nw[0], nw[1], nw[2], nw[3]);
+    };
+    auto store_unit = [&](int e0, const uint4& nw) {  // commit a unit's new snapshot
+        if (g.vec_ok) {
+            *reinterpret_cast<uint4*>(x_snap + (row + e0) * ESIZE) = nw;
+            return;
+        }
+        const unsigned int w[4] = {nw.x, nw.y, nw.z, nw.w};
+        for (int e = 0; e < PV; ++e) {
+            if (e0 + e >= g.c_in) break;
+            if (DT == RRM_I8_I32)
+                x_snap[row + e0 + e] = (unsigned char)(w[e >> 2] >> (8 * (e & 3)));
+            else
+                reinterpret_cast<unsigned short*>(x_snap)[row + e0 + e] = (unsigned short)(w[e >> 1] >> (16 * (e & 1)));
         }
     };
     auto fma16 = [&](const uint4& w, val_t d) {
@@ -140,19 +141,44 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
         }
     };
 
-    const int nchunk = (g.c_in + FCD_CH - 1) / FCD_CH;
+    // One compare round covers FCD_CH inputs, at most one 16-byte unit per thread: the loads of round c + 1 are
+    // issued before round c's columns are streamed, and the first KEEP rounds' new snapshots stay in registers for
+    // the commit.
+    constexpr int CHU = FCD_CH;
+    static_assert(CHU / PV <= FCD_THREADS, "one unit per thread and round");
+    constexpr int KEEP = 2;
+    const int nchunk = (g.c_in + CHU - 1) / CHU;
+    uint4 keep_nw[KEEP];
+    unsigned int keep_mask[KEEP];
+#pragma unroll
+    for (int i = 0; i < KEEP; ++i) keep_mask[i] = 0;
+    // this workgroup's channels of the stored projection, fetched now and needed at the end
+    const int co_y = r * (FCD_SEG / ESIZE) + tid;
+    val_t y_old = 0;
+    if (tid < 4 * PV && co_y < g.c_out) y_old = static_cast<const val_t*>(y_v)[(long long)b * g.c_out + co_y];
+    uint4 cur_a = make_uint4(0, 0, 0, 0), cur_s = cur_a;
+    if (tid * PV < min(CHU, g.c_in)) load_unit(tid * PV, cur_a, cur_s);
     for (int ch = 0; ch < nchunk; ++ch) {
-        const int base = ch * FCD_CH;
-        const int n_in = min(FCD_CH, g.c_in - base);
+        const int base = ch * CHU;
+        const int n_in = min(CHU, g.c_in - base);
         const int nunits = (n_in + PV - 1) / PV;
         // ---- compare + ordered compaction of this round's inputs ------------------------------------------
         int running = 0;
-        for (int u0 = 0; u0 < nunits; u0 += FCD_THREADS) {
-            const int u = u0 + tid;
+        {
+            const int u = tid;
             val_t dv[PV];
             unsigned int mask = 0;
-            uint4 a, nw;
-            if (u < nunits) diff_unit(base + u * PV, dv, mask, a, nw, true);
+            uint4 nw = cur_a;
+            if (u < nunits) diff_unit(cur_a, cur_s, dv, mask, nw);
+#pragma unroll
+            for (int i = 0; i < KEEP; ++i)
+                if (ch == i) {
+                    keep_nw[i] = nw;
+                    keep_mask[i] = mask;
+                }
+            // the next round's units are on their way while this round's columns are streamed
+            if (ch + 1 < nchunk && tid * PV < CHU && base + CHU + tid * PV < g.c_in)
+                load_unit(base + CHU + tid * PV, cur_a, cur_s);
             const int cnt = __popc(mask);
             int incl = cnt;
 #pragma unroll
@@ -168,7 +194,7 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
                 if (w < wave) wbase += t;
                 btot += t;
             }
-            int pos = running + wbase + incl - cnt;
+            int pos = wbase + incl - cnt;
             if (mask) {
 #pragma unroll
                 for (int e = 0; e < PV; ++e)
@@ -178,7 +204,7 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
                         ++pos;
                     }
             }
-            running += btot;
+            running = btot;
             __syncthreads();  // the list is published (and wave_tot may be rewritten)
         }
         const int cnt = running;
@@ -243,11 +269,7 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
             val_t sum = 0;
 #pragma unroll
             for (int w = 0; w < FCD_THREADS / 64; ++w) sum += red[w][tid / PV][tid % PV];
-            const int co = r * (FCD_SEG / ESIZE) + tid;
-            if (co < g.c_out) {
-                val_t* y = static_cast<val_t*>(y_v) + (long long)b * g.c_out + co;
-                *y += sum;
-            }
+            if (co_y < g.c_out) static_cast<val_t*>(y_v)[(long long)b * g.c_out + co_y] = y_old + sum;
         }
     }
     // ---- statistics (one workgroup per stream) ----------------------------------------------------------
@@ -278,25 +300,22 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
     // ---- commit: the workgroup that finished comparing last snapshots the input (applied entries only) -------
     __syncthreads();  // (s_prev was written by thread 0 after the last round's barrier)
     if (s_prev == gridDim.x - 1u) {
-        const int nunits = (g.c_in + PV - 1) / PV;
-        for (int u = tid; u < nunits; u += FCD_THREADS) {
+#pragma unroll
+        for (int i = 0; i < KEEP; ++i)
+            if (i < nchunk && keep_mask[i]) store_unit(i * CHU + tid * PV, keep_nw[i]);
+        for (int ch = KEEP; ch < nchunk; ++ch) {  // (long rows: compare again)
+            const int e0 = ch * CHU + tid * PV;
+            if (tid * PV >= CHU || e0 >= g.c_in) continue;
+            uint4 a, s, nw;
             val_t dv[PV];
             unsigned int mask = 0;
-            uint4 a, nw;
-            diff_unit(u * PV, dv, mask, a, nw, false);
-            if (!mask) continue;
-            if (g.vec_ok) {
-                *reinterpret_cast<uint4*>(x_snap + (row + u * PV) * ESIZE) = nw;
-            } else {
-                for (int e = 0; e < PV; ++e)
-                    if (mask & (1u << e)) {
-                        if (DT == RRM_I8_I32)
-                            x_snap[row + u * PV + e] = x_t[row + u * PV + e];
-                        else
-                            reinterpret_cast<unsigned short*>(x_snap)[row + u * PV + e] =
-                                reinterpret_cast<const unsigned short*>(x_t)[row + u * PV + e];
-                    }
-            }
+            load_unit(e0, a, s);
+            const unsigned int nt0 = ntrunc;
+            const float tq0 = tsq;
+            diff_unit(a, s, dv, mask, nw);
+            ntrunc = nt0;  // (already counted)
+            tsq = tq0;
+            if (mask) store_unit(e0, nw);
         }
         if (tid == 0) arrive[b] = 0u;
     }
