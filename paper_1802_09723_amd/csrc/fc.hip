@@ -8,6 +8,7 @@
 // layer is memory bound: bytes moved are (changed columns) x c_out x element size.
 // The dense layer streams all of W^T, split over rows and output-channel slices (fc_dense_kernel), and adds the
 // splits' partial sums in a fixed order (fc_reduce_kernel): no atomics, bit-reproducible for fp32.
+#include <algorithm>
 #include <mutex>
 #include <type_traits>
 
@@ -17,7 +18,7 @@ namespace rrm {
 
 namespace {
 
-constexpr int FCD_THREADS = 1024;  // 16 wavefronts
+constexpr int FCD_THREADS = 512;   // 8 wavefronts (up to 256 registers each: nothing spills)
 constexpr int FCD_CH = 8192;        // inputs of one compare round = capacity of the changed-column list in LDS
 constexpr int FCD_UN = 8;           // columns in flight per lane
 constexpr int FCD_SEG = 64;         // bytes of a weight column one workgroup owns (4 lanes of 16 bytes)
@@ -48,6 +49,9 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
     __shared__ int wave_tot[FCD_THREADS / 64];
     __shared__ unsigned int s_prev;
     const int r = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // integer layers split long lists over gridDim.z workgroups, pass by pass (pass p of NCG * FCD_UN columns goes
+    // to workgroup p % gridDim.z), and add with integer atomics: exact in any order
+    const int ks = blockIdx.z, nks = gridDim.z;
     const int sub = tid & 3, cgid = tid >> 2;
     const long long row = (long long)b * g.c_in;
     const int co0 = r * (FCD_SEG / ESIZE) + sub * PV;  // this lane's first output channel
@@ -144,8 +148,8 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
     // One compare round covers FCD_CH inputs, at most one 16-byte unit per thread: the loads of round c + 1 are
     // issued before round c's columns are streamed, and the first KEEP rounds' new snapshots stay in registers for
     // the commit.
-    constexpr int CHU = FCD_CH;
-    static_assert(CHU / PV <= FCD_THREADS, "one unit per thread and round");
+    constexpr int CHU = FCD_THREADS * PV < FCD_CH ? FCD_THREADS * PV : FCD_CH;
+    static_assert(CHU / PV <= FCD_THREADS && CHU <= FCD_CH, "one unit per thread and round; the list holds a round");
     constexpr int KEEP = 2;
     const int nchunk = (g.c_in + CHU - 1) / CHU;
     uint4 keep_nw[KEEP];
@@ -155,7 +159,7 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
     // this workgroup's channels of the stored projection, fetched now and needed at the end
     const int co_y = r * (FCD_SEG / ESIZE) + tid;
     val_t y_old = 0;
-    if (tid < 4 * PV && co_y < g.c_out) y_old = static_cast<const val_t*>(y_v)[(long long)b * g.c_out + co_y];
+    if (nks == 1 && tid < 4 * PV && co_y < g.c_out) y_old = static_cast<const val_t*>(y_v)[(long long)b * g.c_out + co_y];
     uint4 cur_a = make_uint4(0, 0, 0, 0), cur_s = cur_a;
     if (tid * PV < min(CHU, g.c_in)) load_unit(tid * PV, cur_a, cur_s);
     for (int ch = 0; ch < nchunk; ++ch) {
@@ -213,34 +217,30 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
         if (ch == nchunk - 1 && tid == 0) s_prev = atomicAdd(&arrive[b], 1u);
         // ---- this workgroup's 64 bytes of every listed column ------------------------------------------------
         if (live) {
-            int k = cgid;
-            for (; k + (FCD_UN - 1) * NCG < cnt; k += FCD_UN * NCG) {
+            for (int k0 = ks * (FCD_UN * NCG); k0 < cnt; k0 += nks * (FCD_UN * NCG)) {
+                const int k = k0 + cgid;
                 int j[FCD_UN];
                 val_t d[FCD_UN];
                 uint4 w[FCD_UN];
+                if (k0 + FCD_UN * NCG <= cnt) {  // a full pass (the same branch in every thread)
 #pragma unroll
-                for (int u = 0; u < FCD_UN; ++u) {
-                    j[u] = base + l_idx[k + u * NCG];
-                    d[u] = l_val[k + u * NCG];
+                    for (int u = 0; u < FCD_UN; ++u) {
+                        j[u] = base + l_idx[k + u * NCG];
+                        d[u] = l_val[k + u * NCG];
+                    }
+#pragma unroll
+                    for (int u = 0; u < FCD_UN; ++u) w[u] = *reinterpret_cast<const uint4*>(wcol + j[u] * pitch);
+                } else {  // the list's tail: whatever is there, in flight together
+#pragma unroll
+                    for (int u = 0; u < FCD_UN; ++u) {
+                        const bool ok = k + u * NCG < cnt;
+                        j[u] = ok ? base + l_idx[k + u * NCG] : 0;
+                        d[u] = ok ? l_val[k + u * NCG] : (val_t)0;
+                    }
+#pragma unroll
+                    for (int u = 0; u < FCD_UN; ++u)
+                        w[u] = k + u * NCG < cnt ? *reinterpret_cast<const uint4*>(wcol + j[u] * pitch) : uint4{0u, 0u, 0u, 0u};
                 }
-#pragma unroll
-                for (int u = 0; u < FCD_UN; ++u) w[u] = *reinterpret_cast<const uint4*>(wcol + j[u] * pitch);
-#pragma unroll
-                for (int u = 0; u < FCD_UN; ++u) fma16(w[u], d[u]);
-            }
-            if (k < cnt) {  // the rest of this group's columns (fewer than FCD_UN), in flight together
-                int j[FCD_UN];
-                val_t d[FCD_UN];
-                uint4 w[FCD_UN];
-#pragma unroll
-                for (int u = 0; u < FCD_UN; ++u) {
-                    const bool ok = k + u * NCG < cnt;
-                    j[u] = ok ? base + l_idx[k + u * NCG] : 0;
-                    d[u] = ok ? l_val[k + u * NCG] : (val_t)0;
-                }
-#pragma unroll
-                for (int u = 0; u < FCD_UN; ++u)
-                    w[u] = k + u * NCG < cnt ? *reinterpret_cast<const uint4*>(wcol + j[u] * pitch) : uint4{0u, 0u, 0u, 0u};
 #pragma unroll
                 for (int u = 0; u < FCD_UN; ++u) fma16(w[u], d[u]);
             }
@@ -269,11 +269,22 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
             val_t sum = 0;
 #pragma unroll
             for (int w = 0; w < FCD_THREADS / 64; ++w) sum += red[w][tid / PV][tid % PV];
-            if (co_y < g.c_out) static_cast<val_t*>(y_v)[(long long)b * g.c_out + co_y] = y_old + sum;
+            if (co_y < g.c_out) {
+                val_t* yp = static_cast<val_t*>(y_v) + (long long)b * g.c_out + co_y;
+                if constexpr (DT == RRM_I8_I32) {
+                    if (nks > 1) {
+                        if (sum != 0) atomicAdd(yp, sum);
+                    } else {
+                        *yp = y_old + sum;
+                    }
+                } else {
+                    *yp = y_old + sum;
+                }
+            }
         }
     }
     // ---- statistics (one workgroup per stream) ----------------------------------------------------------
-    if (r == 0) {
+    if (r == 0 && ks == 0) {
         if (DT == RRM_BF16_F32) {
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) {
@@ -299,7 +310,7 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
     }
     // ---- commit: the workgroup that finished comparing last snapshots the input (applied entries only) -------
     __syncthreads();  // (s_prev was written by thread 0 after the last round's barrier)
-    if (s_prev == gridDim.x - 1u) {
+    if (s_prev == gridDim.x * gridDim.z - 1u) {
 #pragma unroll
         for (int i = 0; i < KEEP; ++i)
             if (i < nchunk && keep_mask[i]) store_unit(i * CHU + tid * PV, keep_nw[i]);
@@ -323,7 +334,6 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
 
 constexpr int FC_LANES = 64;      // lanes of a dense workgroup along the output channels (16 bytes each)
 constexpr int FC_KG = 8;          // row groups of a dense workgroup (512 threads = 8 wavefronts)
-constexpr int FC_RG = 8;          // split groups of a reduce workgroup (1024 threads = 8 x 128 lanes)
 constexpr int FC_MAX_SPLITS = 64;
 
 // Dense layer (Eq. 3, FC form), first of two kernels.  Workgroup (slice, split s, stream): 64 lanes of 16 bytes
@@ -421,38 +431,28 @@ __global__ __launch_bounds__(FC_KG * FC_LANES) void fc_dense_kernel(const unsign
     }
 }
 
-// Second kernel of the dense layer.  Workgroup (block of 512 channels, stream): 128 lanes of 4 channels each,
-// times FC_RG split groups; group rg adds the partial rows rg, rg + FC_RG, ... (all loads in flight together),
-// the groups' sums are added through LDS in group order, and group 0 writes y = bias + sum.
+// Second kernel of the dense layer.  Workgroup (block of 64 channels, stream): 16 lanes of 4 channels each times
+// 64 split groups, one partial row per group (all loads in flight at once); the groups' values meet in LDS and 16
+// threads add them in split order and write y = bias + sum.
 template <int DT>
-__global__ __launch_bounds__(FC_RG * 128) void fc_reduce_kernel(const void* __restrict__ part_v,
-                                                                const void* __restrict__ bias_v, void* __restrict__ y_v,
-                                                                FcGeom g, int splits) {
+__global__ __launch_bounds__(FC_MAX_SPLITS * 16) void fc_reduce_kernel(const void* __restrict__ part_v,
+                                                                       const void* __restrict__ bias_v,
+                                                                       void* __restrict__ y_v, FcGeom g, int splits) {
     typedef typename std::conditional<DT == RRM_I8_I32, int, float>::type val_t;
     typedef typename std::conditional<DT == RRM_I8_I32, int4, float4>::type vec_t;
-    constexpr int PER = FC_MAX_SPLITS / FC_RG;  // partial rows per thread at most
-    __shared__ vec_t red[FC_RG - 1][128];
+    __shared__ vec_t red[FC_MAX_SPLITS][16];
     const int b = blockIdx.y;
-    const int lane = threadIdx.x & 127, rg = threadIdx.x >> 7;
-    const int co = (blockIdx.x * 128 + lane) * 4;
+    const int lane = threadIdx.x & 15, sg = threadIdx.x >> 4;
+    const int co = (blockIdx.x * 16 + lane) * 4;
     const bool live = co < g.c_out_p;  // (c_out_p is a multiple of 4)
-    const val_t* part = static_cast<const val_t*>(part_v) + (long long)b * splits * g.c_out_p + (live ? co : 0);
-    vec_t v[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-        const int s = rg + i * FC_RG;
-        v[i] = (live && s < splits) ? *reinterpret_cast<const vec_t*>(part + (long long)s * g.c_out_p) : vec_t{0, 0, 0, 0};
-    }
-    vec_t sum = v[0];
-#pragma unroll
-    for (int i = 1; i < PER; ++i) {
-        sum.x += v[i].x; sum.y += v[i].y; sum.z += v[i].z; sum.w += v[i].w;
-    }
-    if (rg > 0) red[rg - 1][lane] = sum;
+    if (sg < splits)
+        red[sg][lane] = live ? *reinterpret_cast<const vec_t*>(static_cast<const val_t*>(part_v) +
+                                                               ((long long)b * splits + sg) * g.c_out_p + co)
+                             : vec_t{0, 0, 0, 0};
     __syncthreads();
-    if (rg != 0 || !live) return;
-#pragma unroll
-    for (int q = 0; q < FC_RG - 1; ++q) {
+    if (sg != 0 || !live) return;
+    vec_t sum = red[0][lane];
+    for (int q = 1; q < splits; ++q) {
         const vec_t o = red[q][lane];
         sum.x += o.x; sum.y += o.y; sum.z += o.z; sum.w += o.w;
     }
@@ -471,7 +471,12 @@ __global__ __launch_bounds__(FC_RG * 128) void fc_reduce_kernel(const void* __re
 hipError_t launch_fc_delta(int dtype, const void* x_t, void* x_snap, const void* wT, void* y, unsigned int* arrive,
                            const FcGeom& g, DevStats* stats, hipStream_t s) {
     const int esize = dtype == RRM_I8_I32 ? 1 : 2;
-    dim3 grid((unsigned int)((g.c_out_p * esize + FCD_SEG - 1) / FCD_SEG), (unsigned int)g.n), block(FCD_THREADS);
+    const int ranges = (g.c_out_p * esize + FCD_SEG - 1) / FCD_SEG;
+    // integer layers with long input vectors: up to four list splits while that fills more of the chip's 256
+    // compute units (measured: pays off from about a thousand changed columns; short vectors lose to the extra
+    // workgroups' compare)
+    const int nks = dtype == RRM_I8_I32 && g.c_in >= 8192 ? std::max(1, std::min(4, 256 / (ranges * g.n))) : 1;
+    dim3 grid((unsigned int)ranges, (unsigned int)g.n, (unsigned int)nks), block(FCD_THREADS);
     if (dtype == RRM_I8_I32)
         hipLaunchKernelGGL(fc_delta_kernel<RRM_I8_I32>, grid, block, 0, s, (const unsigned char*)x_t,
                            (unsigned char*)x_snap, (const unsigned char*)wT, y, arrive, g, stats);
@@ -490,7 +495,7 @@ hipError_t launch_fc_dense(int dtype, int splits, const void* wT, const void* x,
                            const FcGeom& g, hipStream_t s) {
     if (splits < 1 || splits > FC_MAX_SPLITS) return hipErrorInvalidValue;
     dim3 grid((unsigned int)fc_dense_slices(dtype, g), (unsigned int)splits, (unsigned int)g.n), block(FC_KG * FC_LANES);
-    dim3 rgrid((unsigned int)((g.c_out_p / 4 + 127) / 128), (unsigned int)g.n), rblock(FC_RG * 128);
+    dim3 rgrid((unsigned int)((g.c_out_p / 4 + 15) / 16), (unsigned int)g.n), rblock(FC_MAX_SPLITS * 16);
     const unsigned char* w = static_cast<const unsigned char*>(wT);
     const unsigned char* xx = static_cast<const unsigned char*>(x);
     if (dtype == RRM_I8_I32) {
