@@ -185,22 +185,35 @@ class Stack:
             L.set_option("profile", 0)
             b = L.stats()
             d = {k: b[k] - a[k] for k in ("changed_elems", "changed_units", "active_tiles", "total_tiles", "delta_steps")}
-            out.append({"scan_us": scan_us / max(n, 1), "compute_us": comp_us / max(n, 1), "steps": n, **d})
+            out.append({"scan_us": scan_us / max(n, 1), "compute_us": comp_us / max(n, 1), "steps": n,
+                        "tile_positions": b["tile_positions"], **d})
         return out
 
 
-def conv_alg_bytes(shape, esize, changed_units_per_step, active_tiles_per_step, terms=1):
+def conv_alg_bytes(shape, esize, changed_units_per_step, active_positions_per_step, terms=1):
     """Algorithmic HBM bytes of one delta step of a conv layer, split by kernel.
     scan: both copies of x are read once; changed 16-byte units write their difference (terms
           buffers) and the snapshot.
     tile: the changed difference units are read once, the weights once (if anything changed),
-          and the touched 4x4 output sub-tiles are read and written once (4-byte outputs)."""
+          and the output positions whose receptive field changed are read and written once (4-byte
+          outputs).  `active_positions_per_step` counts real output positions (clipped blocks of the
+          window-tile kernel are counted by the caller as what lies inside the map)."""
     xb = shape.n * shape.h * shape.w * shape.c_in * esize
     wb = shape.c_out * shape.kh * shape.kw * (shape.c_in // shape.groups) * esize
-    tile_y = 16 * shape.c_out * 4
     scan = 2 * xb + changed_units_per_step * 16 * (1 + terms)
-    tile = changed_units_per_step * 16 * terms + 2 * active_tiles_per_step * tile_y + (wb if active_tiles_per_step > 0 else 0)
+    tile = changed_units_per_step * 16 * terms + 2 * active_positions_per_step * shape.c_out * 4 + (wb if active_positions_per_step > 0 else 0)
     return scan, tile
+
+
+def active_positions(shape, stats_row, tiles_per_step):
+    """Output positions under the active tiles of a step: exact for the position-gather kernel; for 4x4 (8x8)
+    blocks the blocks' share of the map (clipped border blocks hold fewer positions)."""
+    tp = stats_row.get("tile_positions", 16) or 1
+    if tp == 1:
+        return tiles_per_step
+    side = int(round(tp ** 0.5))
+    blocks = shape.n * -(-shape.h_out // side) * -(-shape.w_out // side)
+    return tiles_per_step / blocks * shape.n * shape.h_out * shape.w_out
 
 
 COPY_BYTES = 64 << 20
@@ -239,6 +252,13 @@ def run_stack(args):
     import torch
     calibration_copy()
     st = Stack(args.streams, fuse=not args.no_fuse)
+    if args.conv_kernel:
+        for L in st.layers:
+            try:
+                L.set_option("conv_kernel", args.conv_kernel)
+            except Exception:  # (a layer the position-gather kernel does not take keeps its kernel)
+                pass
+            L.reset()
     B = st.B
     shapes = [l["shape"] for l in st.cfg["layers"]]
     names = [l["name"] for l in st.cfg["layers"]]
@@ -264,14 +284,15 @@ def run_stack(args):
     prev = None  # (shape, active sub-tiles per step) of the layer before
     for nm, sh, p, pd in zip(names, shapes, prof, prof_dense):
         n = max(p["steps"], 1)
-        cu, at = p["changed_units"] / n, p["active_tiles"] / n
+        cu = p["changed_units"] / n
+        at = active_positions(sh, p, p["active_tiles"] / n)  # output positions written per step
         scan_b, tile_b = conv_alg_bytes(sh, 1, cu, at)
         if prev is not None and st.fuse:
-            # fused scan: the producer's written 4x4 blocks are read once (int32), the stored input is read
+            # fused scan: the producer's written positions are read once (int32), the stored input is read
             # only under them (about the same share of it), changed units are written twice
             psh, pat = prev
-            share = pat / (psh.n * ((psh.h_out + 3) // 4) * ((psh.w_out + 3) // 4))
-            scan_b = pat * 16 * psh.c_out * 4 + share * sh.n * sh.h * sh.w * sh.c_in + cu * 32
+            share = pat / (psh.n * psh.h_out * psh.w_out)
+            scan_b = pat * psh.c_out * 4 + share * sh.n * sh.h * sh.w * sh.c_in + cu * 32
         prev = (sh, at)
         rho_elem = p["changed_elems"] / n / (sh.n * sh.h * sh.w * sh.c_in)
         rho_tile = p["active_tiles"] / max(p["total_tiles"], 1)
@@ -552,6 +573,7 @@ def main():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--no-fuse", action="store_true",
                     help="delta path: write every layer's input to memory (separate f kernel) instead of rrm_step_from_projection")
+    ap.add_argument("--conv-kernel", type=int, default=0, help="0 automatic, 1 window-tile, 2 position-gather (where eligible)")
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--sweep-streams", type=int, default=64,
                     help="--sweep times every layer at 1 stream (the configs' batch) and at this many streams")

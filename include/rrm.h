@@ -82,12 +82,13 @@ typedef struct {
     uint64_t delta_steps;     /* steps executed on the sparse delta path */
     uint64_t changed_elems;   /* input elements (binary: bits) that differed from the snapshot */
     uint64_t changed_units;   /* 16-byte input units with any difference (FC: = changed_elems) */
-    uint64_t active_tiles;    /* int8 / bf16 conv: 4x4 output sub-tiles recomputed; binary conv: 8x8 output
+    uint64_t active_tiles;    /* int8 / bf16 conv: output blocks recomputed (4x4 positions for the window-tile
+                                 kernel, single positions for the position-gather kernel); binary conv: 8x8 output
                                  tiles recomputed; FC: columns streamed */
     uint64_t total_tiles;     /* the same unit, counted as a dense step would, summed over delta steps
                                  (FC: c_in per step) */
     int32_t range_error;      /* non-zero once an int8 difference overflowed */
-    int32_t reserved;
+    int32_t tile_positions;   /* output positions per tile of active_tiles / total_tiles: 16, 1, 64; FC: 0 */
     uint64_t truncated_elems; /* BF16 with a threshold: differences below it (neither applied nor committed) */
     double truncated_sumsq;   /* and the sum of their squares: sum over steps of l2(u)^2 of Eq. 7's truncated maps */
 } rrm_stats;
@@ -141,7 +142,13 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
  *   "bf16_terms"  BF16 conv: 2 = difference carried as hi+lo bf16 pair (default), 1 = hi only
  *   "dense_switch_pct"  INT8 / BF16 conv: a delta step whose changes touch more than this percentage of the
  *                 4x4 output blocks recomputes the whole projection (same result; cheaper than reading and
- *                 re-writing most of it); 1..100, default 62 (int8) / 40 (bf16), 100 = never
+ *                 re-writing most of it); 1..100, 100 = never; defaults 62 (int8) / 40 (bf16) for the window-tile
+ *                 kernel, which decides per launch, and 90 / 50 for the position-gather kernel, which decides per
+ *                 work unit
+ *   "conv_kernel" INT8 / BF16 conv: 0 = automatic, 1 = window-tile kernel (4x4 output blocks with their input windows
+ *                 gathered into LDS; any stride), 2 = position-gather kernel (single active output positions as
+ *                 columns of the product; stride 1 and channel runs of 16-byte multiples).  Set it before the
+ *                 first rrm_step, or follow it with rrm_reset: the two kernels keep their change flags differently.
  *   "bin_cout_per_wave"  binary conv: output channels per wavefront, 8 / 16 (0 = heuristic)
  *   "profile"     1 = bracket every kernel of the following rrm_step calls with HIP events on the
  *                 caller's stream (see rrm_get_kernel_times; not for use under graph capture), 0 = off */

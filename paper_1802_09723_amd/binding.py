@@ -34,11 +34,11 @@ class Stats(ctypes.Structure):
     """``rrm_stats``"""
     _fields_ = [("steps", ctypes.c_uint64), ("delta_steps", ctypes.c_uint64), ("changed_elems", ctypes.c_uint64),
                 ("changed_units", ctypes.c_uint64), ("active_tiles", ctypes.c_uint64), ("total_tiles", ctypes.c_uint64),
-                ("range_error", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("range_error", ctypes.c_int32), ("tile_positions", ctypes.c_int32),
                 ("truncated_elems", ctypes.c_uint64), ("truncated_sumsq", ctypes.c_double)]
 
     def as_dict(self):
-        return {k: (float if k == "truncated_sumsq" else int)(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
+        return {k: (float if k == "truncated_sumsq" else int)(getattr(self, k)) for k, _ in self._fields_}
 
 
 class RRMError(RuntimeError):

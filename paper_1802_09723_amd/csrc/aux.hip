@@ -59,13 +59,13 @@ __global__ void relu_requant_pool_kernel(const int* __restrict__ y, signed char*
 }
 
 // The same map, four channels per thread (16-byte loads of y), one workgroup row per output row.  With
-// CHANGED, an output is recomputed only if one of the 4x4 sub-tiles of y under its window was written by
-// the layer's last step (byte flags `touched`, [n][ceil(h/4)][ceil(w/4)]); the rest of `out` keeps its
-// value from the previous call.
+// CHANGED, an output is recomputed only if one of the blocks of y under its window was written by the layer's
+// last step (byte flags `touched`, one per block of (1 << tshift)^2 positions); the rest of `out` keeps its value
+// from the previous call.
 template <bool CHANGED>
 __global__ __launch_bounds__(256) void relu_requant_pool4_kernel(const int4* __restrict__ y, unsigned int* __restrict__ out,
-                                                                 const unsigned char* __restrict__ touched, int h, int w,
-                                                                 int c4, int ho, int wo, int shift, int pool,
+                                                                 const unsigned char* __restrict__ touched, int tshift,
+                                                                 int h, int w, int c4, int ho, int wo, int shift, int pool,
                                                                  unsigned int magic_c4, unsigned int magic_ho) {
     const int row = (int)blockIdx.x;  // b*ho + oy
     const int idx = (int)(blockIdx.y * blockDim.x + threadIdx.x);
@@ -77,10 +77,13 @@ __global__ __launch_bounds__(256) void relu_requant_pool4_kernel(const int4* __r
     const int y0 = pool ? 2 * oy : oy, x0 = pool ? 2 * ox : ox;
     const int span = pool ? 2 : 0;
     if (CHANGED) {
-        const int sty = (h + 3) >> 2, stx = (w + 3) >> 2;
+        const int rnd = (1 << tshift) - 1;
+        const int sty = (h + rnd) >> tshift, stx = (w + rnd) >> tshift;
         const unsigned char* t = touched + (size_t)b * sty * stx;
-        const int sy0 = y0 >> 2, sy1 = (y0 + span) >> 2, sx0 = x0 >> 2, sx1 = (x0 + span) >> 2;
-        const unsigned int any = t[sy0 * stx + sx0] | t[sy0 * stx + sx1] | t[sy1 * stx + sx0] | t[sy1 * stx + sx1];
+        const int sy0 = y0 >> tshift, sy1 = (y0 + span) >> tshift, sx0 = x0 >> tshift, sx1 = (x0 + span) >> tshift;
+        unsigned int any = 0;
+        for (int sy = sy0; sy <= sy1; ++sy)
+            for (int sx = sx0; sx <= sx1; ++sx) any |= t[sy * stx + sx];
         if (!any) return;
     }
     int4 best = make_int4(0, 0, 0, 0);
@@ -129,8 +132,8 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) 
     return hipGetLastError();
 }
 
-hipError_t launch_relu_requant_pool(const void* y, void* out, const void* touched, int n, int h, int w, int c, int shift,
-                                    int pool, hipStream_t s) {
+hipError_t launch_relu_requant_pool(const void* y, void* out, const void* touched, int tshift, int n, int h, int w, int c,
+                                    int shift, int pool, hipStream_t s) {
     const int ho = pool ? (h - 3) / 2 + 1 : h, wo = pool ? (w - 3) / 2 + 1 : w;
     const long long total = (long long)n * ho * wo * c;
     if (total <= 0) return hipSuccess;
@@ -140,10 +143,10 @@ hipError_t launch_relu_requant_pool(const void* y, void* out, const void* touche
         dim3 grid((unsigned int)(n * ho), (unsigned int)((wo * c4 + 255) / 256));
         if (touched)
             hipLaunchKernelGGL(relu_requant_pool4_kernel<true>, grid, dim3(256), 0, s, (const int4*)y, (unsigned int*)out,
-                               (const unsigned char*)touched, h, w, c4, ho, wo, shift, pool, magic(c4), magic(ho));
+                               (const unsigned char*)touched, tshift, h, w, c4, ho, wo, shift, pool, magic(c4), magic(ho));
         else
             hipLaunchKernelGGL(relu_requant_pool4_kernel<false>, grid, dim3(256), 0, s, (const int4*)y, (unsigned int*)out,
-                               (const unsigned char*)nullptr, h, w, c4, ho, wo, shift, pool, magic(c4), magic(ho));
+                               (const unsigned char*)nullptr, 0, h, w, c4, ho, wo, shift, pool, magic(c4), magic(ho));
         return hipGetLastError();
     }
     if (touched) return hipErrorInvalidValue;  // the incremental form needs channel counts in fours

@@ -186,7 +186,6 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     const int n_vec = (g.n_words + 3) >> 2;
     const int n_grp = (n_vec + 3) >> 2;
     const int gpt = (n_grp + CONV_THREADS - 1) / CONV_THREADS;
-    const int g_lo = tid * gpt;
     auto load_group = [&](int gi) {
         uint4 v[4];
 #pragma unroll

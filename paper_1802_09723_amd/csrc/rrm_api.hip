@@ -50,6 +50,12 @@ struct rrm_layer {
     size_t d_bytes = 0;     // bytes of one difference buffer
     ScanGeom sg{};
     ConvGeom cg{};
+    PosGeom pg{};           // position-gather kernel (stride-1 layers with 16-byte channel runs)
+    bool pos_ok = false;    // the layer can run on the position-gather kernel
+    bool use_pos = false;   // ... and does
+    int tshift = 2;         // log2 of the side of the output blocks that `touched` flags: 2 (4x4) or 0 (positions)
+    void* wpos = nullptr;   // weights packed for the position-gather kernel
+    size_t touched_bytes = 0;
     BinGeom bg{};
     FcGeom fg{};
     // device memory
@@ -83,7 +89,7 @@ struct rrm_layer {
     int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0;
 
     ~rrm_layer() {
-        void* ptrs[] = {wpack, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, fresh, zero16, fc_arrive, fc_part, stats};
+        void* ptrs[] = {wpack, wpos, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, fresh, zero16, fc_arrive, fc_part, stats};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
         for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
@@ -402,6 +408,53 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     return pack_conv(L, w);
 }
 
+// Position-gather kernel: eligibility, work-unit shape, weights in per-lane MFMA order
+// [group][block of POS_NCB x 32 channels][slab of 2 chunks][tap][32-channel block][lane] x 16 bytes, lane l ->
+// output channel l % 32 of the block, chunk 2 * slab + l / 32 of the tap.  Padded channels and chunks are zero.
+rrm_status setup_pos(rrm_layer* L, const std::vector<unsigned char>& w) {
+    const rrm_shape& s = L->shape;
+    PosGeom& g = L->pg;
+    L->pos_ok = false;
+    const int es = L->esize;
+    if (!pos_choose_shape(s, es, L->dtype == RRM_BF16_F32 ? 2 : 1, g)) return RRM_OK;
+    const int cg = g.cg, og = g.og;
+
+    const int real_taps = s.kh * s.kw;
+    std::vector<unsigned char> pack((size_t)s.groups * g.ncg * g.nslab * g.ntaps * POS_NCB * 1024, 0);
+    const int per_vec = 16 / es;
+    for (int grp = 0; grp < s.groups; ++grp)
+        for (int cgp = 0; cgp < g.ncg; ++cgp)
+            for (int slab = 0; slab < g.nslab; ++slab)
+                for (int tap = 0; tap < g.ntaps; ++tap)
+                    for (int cb = 0; cb < POS_NCB; ++cb)
+                        for (int lane = 0; lane < 64; ++lane) {
+                            const int co = (cgp * POS_NCB + cb) * 32 + (lane & 31);
+                            const int chunk = 2 * slab + (lane >> 5);
+                            if (co >= og || chunk >= g.chunks) continue;
+                            const size_t frag = ((((size_t)(grp * g.ncg + cgp) * g.nslab + slab) * g.ntaps + tap) * POS_NCB + cb);
+                            unsigned char* dst = pack.data() + (frag * 64 + lane) * 16;
+                            const size_t wrow = (size_t)(grp * og + co) * real_taps + tap;
+                            std::memcpy(dst, w.data() + (wrow * cg + (size_t)chunk * per_vec) * es, 16);
+                        }
+    rrm_status st = upload(pack.data(), pack.size(), &L->wpos);
+    if (st != RRM_OK) return st;
+    L->pos_ok = true;
+    return RRM_OK;
+}
+
+// choose the convolution kernel of an int8 / bf16 layer: 0 = automatic, 1 = window-tile, 2 = position-gather
+rrm_status select_conv_kernel(rrm_layer* L, int which) {
+    if (which == 2 && !L->pos_ok) return fail(RRM_ERR_OPTION, "the position-gather kernel needs stride 1 and 16-byte channel runs");
+    L->use_pos = which == 2 || (which == 0 && L->pos_ok);
+    L->tshift = L->use_pos ? 0 : 2;
+    ScanGeom& sg = L->sg;
+    sg.sty = L->use_pos ? 0 : L->cg.sty;  // (no sub-tile flags for the position-gather kernel: it reads the bitmap)
+    sg.stx = L->use_pos ? 0 : L->cg.stx;
+    sg.tiles_per_step = L->use_pos ? (unsigned long long)L->shape.n * L->cg.ho * L->cg.wo
+                                   : (unsigned long long)L->shape.n * L->cg.sty * L->cg.stx;
+    return RRM_OK;
+}
+
 rrm_status setup_bin(rrm_layer* L, const std::vector<unsigned char>& w) {
     const rrm_shape& s = L->shape;
     BinGeom& g = L->bg;
@@ -496,6 +549,11 @@ rrm_status enqueue_dense(rrm_layer* L, const void* x, void* y, hipStream_t st) {
     } else if (L->dtype == RRM_BIN_I32) {
         RRM_HIP(launch_bin_conv(MODE_DENSE, bin_cw(L), x, nullptr, nullptr, L->wpack, L->bias, y, L->bg, L->stats, st));
     } else {
+        if (L->use_pos) {
+            RRM_HIP(launch_conv_pos(L->dtype, MODE_DENSE, 1, x, nullptr, L->zero16, nullptr, L->ctrl, L->wpos, L->bias, y, L->pg,
+                                    L->stats, st));
+            return RRM_OK;
+        }
         const void* src = x;
         if (!L->cg.aligned) {  // bring x into the 16-byte-chunk layout first (its pad elements stay zero)
             RRM_HIP(launch_repack(L->esize, x, L->xpad, L->sg, st));
@@ -551,8 +609,10 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
         st = setup_fc(L, hw);
     else if (dtype == RRM_BIN_I32)
         st = setup_bin(L, hw);
-    else
+    else {
         st = setup_conv(L, hw);
+        if (st == RRM_OK) st = setup_pos(L, hw);
+    }
     if (st != RRM_OK) return bail(st);
 
     if ((st = dalloc(L->x_bytes, &L->x_snap)) != RRM_OK) return bail(st);
@@ -597,20 +657,27 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
         if ((st = dalloc(L->marks_bytes, (void**)&L->tileflag)) != RRM_OK) return bail(st);
         if (dtype != RRM_BIN_I32) {
             // everything counts as written until the first step has run (y_snap = bias everywhere)
-            if ((st = dalloc(L->marks_bytes, (void**)&L->touched)) != RRM_OK) return bail(st);
-            if (hipMemset(L->touched, 1, round16(L->marks_bytes)) != hipSuccess) return bail(fail(RRM_ERR_HIP, "hipMemset failed"));
+            // (one byte per 4x4 block for the window-tile kernel, per output position for the position-gather kernel)
+            L->touched_bytes = L->pos_ok ? std::max(L->marks_bytes, (size_t)s.n * (size_t)ho * (size_t)wo) : L->marks_bytes;
+            if ((st = dalloc(L->touched_bytes, (void**)&L->touched)) != RRM_OK) return bail(st);
+            if (hipMemset(L->touched, 1, round16(L->touched_bytes)) != hipSuccess) return bail(fail(RRM_ERR_HIP, "hipMemset failed"));
             L->cg.touched = L->touched;
+            L->pg.touched = reinterpret_cast<unsigned char*>(L->touched);
             // Above this share of active sub-tiles a delta step recomputes the layer instead (the stored
             // input, equal to x_t after the scan, is the source: only layers whose x layout is the kernel's)
             L->cg.xfull = L->cg.aligned ? static_cast<const unsigned char*>(L->x_snap) : nullptr;
             // (a bf16 delta multiplies two terms, a recomputation one: it pays off earlier)
             L->cg.full_pct = dtype == RRM_BF16_F32 ? 40 : 62;
+            L->pg.xfull = static_cast<const unsigned char*>(L->x_snap);  // (its layers are always in x's layout)
+            L->pg.full_pct = dtype == RRM_BF16_F32 ? 50 : 90;
+            if ((st = select_conv_kernel(L, 0)) != RRM_OK) return bail(st);
         }
         if ((st = dalloc(16, (void**)&L->ctrl)) != RRM_OK) return bail(st);
         {
             const unsigned int ones[4] = {1u, 1u, 1u, 1u};
             if ((st = upload(ones, 16, (void**)&L->fresh)) != RRM_OK) return bail(st);
             L->cg.fresh = L->fresh;
+            L->pg.fresh = L->fresh;
         }
         if ((st = dalloc(256, &L->zero16)) != RRM_OK) return bail(st);
     }
@@ -644,7 +711,7 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
         if ((st = enqueue_dense(L, x_t, L->y_snap, s)) != RRM_OK) return st;
         // a full recomputation writes every output block (enqueued unconditionally: a captured step must not
         // depend on what the host believes the flags hold)
-        if (L->touched) RRM_HIP(launch_fill_word(L->touched, round16(L->marks_bytes), 0x01010101u, s));
+        if (L->touched) RRM_HIP(launch_fill_word(L->touched, round16(L->touched_bytes), 0x01010101u, s));
         if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
     } else if (L->shape.kind == RRM_FC) {
         if ((st = prof_mark(L, 0, s)) != RRM_OK) return st;
@@ -663,11 +730,18 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
         } else {
             RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag, 0u, L->sg, L->stats, s));
             if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
+            if (L->use_pos) {
+                PosGeom pg = L->pg;
+                if (L->opt_path == 1) pg.xfull = nullptr;  // the sparse path always: no switch to recomputation
+                RRM_HIP(launch_conv_pos(L->dtype, MODE_DELTA, L->dtype == RRM_BF16_F32 ? L->opt_terms : 1, L->d0, L->d1,
+                                        L->zero16, L->bitmap, L->ctrl, L->wpos, L->bias, L->y_snap, pg, L->stats, s));
+            } else {
             ConvGeom cg = L->cg;
             if (L->opt_path == 1) cg.xfull = nullptr;  // the sparse path always: no switch to recomputation
             RRM_HIP(launch_conv(L->dtype, MODE_DELTA, L->cg.wg_cb, L->cg.nt, L->dtype == RRM_BF16_F32 ? L->opt_terms : 1,
                                 L->d0, L->d1, L->zero16, L->tileflag, L->ctrl, L->wpack, L->offtab, L->bias, L->y_snap, cg,
                                 L->stats, s));
+            }
         }
         if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
     }
@@ -696,15 +770,22 @@ rrm_status rrm_step_from_projection(rrm_layer* L, rrm_layer* P, int shift, int p
     FusedSrc src{};
     src.y = static_cast<const int*>(P->y_snap);
     src.touched = reinterpret_cast<const unsigned char*>(P->touched);
-    src.hy = hy; src.wy = wy; src.sty = P->sg.sty; src.stx = P->sg.stx;
+    src.hy = hy; src.wy = wy;
+    src.tshift = P->tshift;
+    src.sty = P->tshift ? P->cg.sty : hy;
+    src.stx = P->tshift ? P->cg.stx : wy;
     src.shift = shift; src.pool = pool ? 1 : 0;
     src.fresh = L->fresh;  // a fresh / reset layer holds no f(P) yet: everything is compared
     rrm_status rs;
     if ((rs = prof_mark(L, 0, st)) != RRM_OK) return rs;
     RRM_HIP(launch_scan_fused(src, L->x_snap, L->d0, L->bitmap, L->tileflag, L->sg, L->stats, st));
     if ((rs = prof_mark(L, 1, st)) != RRM_OK) return rs;
-    RRM_HIP(launch_conv(L->dtype, MODE_DELTA, L->cg.wg_cb, L->cg.nt, 1, L->d0, L->d1, L->zero16, L->tileflag, L->ctrl,
-                        L->wpack, L->offtab, L->bias, L->y_snap, L->cg, L->stats, st));
+    if (L->use_pos)
+        RRM_HIP(launch_conv_pos(L->dtype, MODE_DELTA, 1, L->d0, L->d1, L->zero16, L->bitmap, L->ctrl, L->wpos, L->bias,
+                                L->y_snap, L->pg, L->stats, st));
+    else
+        RRM_HIP(launch_conv(L->dtype, MODE_DELTA, L->cg.wg_cb, L->cg.nt, 1, L->d0, L->d1, L->zero16, L->tileflag, L->ctrl,
+                            L->wpack, L->offtab, L->bias, L->y_snap, L->cg, L->stats, st));
     if ((rs = prof_mark(L, 2, st)) != RRM_OK) return rs;
     L->has_snapshot = true;
     ++L->steps;
@@ -753,7 +834,7 @@ rrm_status rrm_reset(rrm_layer* L, void* hip_stream) {
         RRM_HIP(launch_fill_zero(L->tileflag, round16(L->marks_bytes), s));
         RRM_HIP(launch_fill_zero(L->ctrl, 16, s));
         RRM_HIP(launch_fill_word(L->fresh, 16, 1u, s));
-        if (L->touched) RRM_HIP(launch_fill_word(L->touched, round16(L->marks_bytes), 0x01010101u, s));
+        if (L->touched) RRM_HIP(launch_fill_word(L->touched, round16(L->touched_bytes), 0x01010101u, s));
     }
     if (L->fc_arrive) RRM_HIP(launch_fill_zero(L->fc_arrive, round16((size_t)L->shape.n * sizeof(unsigned int)), s));
     L->has_snapshot = false;
@@ -794,6 +875,11 @@ rrm_status rrm_set_option(rrm_layer* L, const char* key, long value) {
     } else if (k == "dense_switch_pct") {
         if (value < 1 || value > 100) return fail(RRM_ERR_OPTION, "dense_switch_pct must be in [1, 100]");
         L->cg.full_pct = (int)value;
+        L->pg.full_pct = (int)value;
+    } else if (k == "conv_kernel") {
+        if (L->shape.kind != RRM_CONV || L->dtype == RRM_BIN_I32 || value < 0 || value > 2)
+            return fail(RRM_ERR_OPTION, "conv_kernel is 0, 1 or 2, for int8 / bf16 convolution layers");
+        return select_conv_kernel(L, (int)value);
     } else if (k == "profile") {
         if (value != 0 && value != 1) return fail(RRM_ERR_OPTION, "profile must be 0 or 1");
         L->prof_on = value != 0;
@@ -839,7 +925,7 @@ rrm_status rrm_get_stats(rrm_layer* L, rrm_stats* out) {
     out->active_tiles = d.active_tiles;
     out->total_tiles = d.total_tiles;
     out->range_error = (int32_t)d.range_error;
-    out->reserved = 0;
+    out->tile_positions = L->shape.kind == RRM_FC ? 0 : (L->dtype == RRM_BIN_I32 ? TILE * TILE : (L->use_pos ? 1 : 16));
     out->truncated_elems = d.truncated_elems;
     out->truncated_sumsq = d.truncated_sumsq;
     if (d.range_error) return fail(RRM_ERR_RANGE, "an int8 input difference did not fit int8");
@@ -889,7 +975,7 @@ rrm_status rrm_aux_relu_requant_pool_i8(const void* y, void* out, int n, int h, 
     if (!y || !out) return fail(RRM_ERR_NULL, "y / out is NULL");
     if (n < 1 || h < 1 || w < 1 || c < 1 || shift < 0 || shift > 31 || (pool && (h < 3 || w < 3)))
         return fail(RRM_ERR_SHAPE, "bad shape for relu_requant_pool");
-    RRM_HIP(launch_relu_requant_pool(y, out, nullptr, n, h, w, c, shift, pool, static_cast<hipStream_t>(hip_stream)));
+    RRM_HIP(launch_relu_requant_pool(y, out, nullptr, 0, n, h, w, c, shift, pool, static_cast<hipStream_t>(hip_stream)));
     return RRM_OK;
 }
 
@@ -901,7 +987,7 @@ rrm_status rrm_aux_relu_requant_pool_changed_i8(rrm_layer* L, void* out, int shi
     const int ho = L->cg.ho, wo = L->cg.wo;
     if (shift < 0 || shift > 31 || (pool && (ho < 3 || wo < 3))) return fail(RRM_ERR_SHAPE, "bad shape for relu_requant_pool");
     if (reinterpret_cast<uintptr_t>(out) & 3) return fail(RRM_ERR_ALIGN, "out must be 4-byte aligned");
-    RRM_HIP(launch_relu_requant_pool(L->y_snap, out, L->touched, s.n, ho, wo, s.c_out, shift, pool,
+    RRM_HIP(launch_relu_requant_pool(L->y_snap, out, L->touched, L->tshift, s.n, ho, wo, s.c_out, shift, pool,
                                      static_cast<hipStream_t>(hip_stream)));
     return RRM_OK;
 }

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "rrm.h"
+#include "pos_shape.h"
 
 namespace rrm {
 
@@ -61,8 +62,9 @@ struct ScanGeom {
 // only under the 4x4 blocks of the projection that the producer's last step wrote.
 struct FusedSrc {
     const int* y;                 // producer's stored projection [n][hy][wy][c], c = this layer's c_in
-    const unsigned char* touched; // producer's byte flags per 4x4 block of (hy, wy)
-    int hy, wy, sty, stx;
+    const unsigned char* touched; // producer's byte flags per block of (1 << tshift)^2 positions of (hy, wy)
+    int hy, wy, sty, stx;         // sty x stx blocks per image
+    int tshift;                   // 2: 4x4 blocks (window-tile kernel), 0: single positions (position-gather kernel)
     int shift, pool;
     // device word, non-zero while the consumer's stored input holds no f(P) yet (fresh or reset layer): `touched`
     // is ignored and every unit is computed and compared.  Set by create / reset, cleared by the consumer's
@@ -172,6 +174,11 @@ hipError_t launch_conv(int dtype, int mode, int ncb, int nt, int terms, const vo
                        const void* zero16, unsigned int* subbits, unsigned int* ctrl, const void* wpack, const int* offtab,
                        const void* bias, void* y, const ConvGeom& g, DevStats* stats, hipStream_t s);
 
+// `bitmap`: the scan's changed-unit bitmap (delta mode); ctrl: 4 zeroed words (rearmed by the kernel)
+hipError_t launch_conv_pos(int dtype, int mode, int terms, const void* src0, const void* src1, const void* zero16,
+                           const unsigned long long* bitmap, unsigned int* ctrl, const void* wpack, const void* bias, void* y,
+                           const PosGeom& g, DevStats* stats, hipStream_t s);
+
 // one delta step of an FC layer in a single launch; `arrive`: one zeroed word per stream (rearmed by the kernel)
 hipError_t launch_fc_delta(int dtype, const void* x_t, void* x_snap, const void* wT, void* y, unsigned int* arrive,
                            const FcGeom& g, DevStats* stats, hipStream_t s);
@@ -197,8 +204,9 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 // x (caller layout) -> the padded / folded source layout described by g (pad elements are left untouched)
 hipError_t launch_repack(int esize, const void* x, void* dst, const ScanGeom& g, hipStream_t s);
 hipError_t launch_fill_word(void* p, size_t bytes, unsigned int word, hipStream_t s);
-// touched: nullptr = every output; else byte flags per 4x4 sub-tile of y, only outputs under a set flag
-hipError_t launch_relu_requant_pool(const void* y, void* out, const void* touched, int n, int h, int w, int c, int shift,
-                                    int pool, hipStream_t s);
+// touched: nullptr = every output; else byte flags per block of (1 << tshift)^2 positions of y, only outputs under
+// a set flag
+hipError_t launch_relu_requant_pool(const void* y, void* out, const void* touched, int tshift, int n, int h, int w, int c,
+                                    int shift, int pool, hipStream_t s);
 
 }  // namespace rrm

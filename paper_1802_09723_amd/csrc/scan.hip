@@ -222,8 +222,11 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
         const int iy = (int)udiv_big(r, g.r_w), ix = (int)r - iy * g.w;
         const int y0 = fs.pool ? 2 * iy : iy, x0 = fs.pool ? 2 * ix : ix, span = fs.pool ? 2 : 0;
         const unsigned char* t = fs.touched + (size_t)bb * fs.sty * fs.stx;
-        const int sy0 = y0 >> 2, sy1 = (y0 + span) >> 2, sx0 = x0 >> 2, sx1 = (x0 + span) >> 2;
-        compare = fs.fresh[0] != 0u || (t[sy0 * fs.stx + sx0] | t[sy0 * fs.stx + sx1] | t[sy1 * fs.stx + sx0] | t[sy1 * fs.stx + sx1]) != 0;
+        const int sy0 = y0 >> fs.tshift, sy1 = (y0 + span) >> fs.tshift, sx0 = x0 >> fs.tshift, sx1 = (x0 + span) >> fs.tshift;
+        unsigned int any = 0;
+        for (int sy = sy0; sy <= sy1; ++sy)
+            for (int sx = sx0; sx <= sx1; ++sx) any |= t[sy * fs.stx + sx];
+        compare = fs.fresh[0] != 0u || any != 0u;
         if (compare) {
             b_early = x_snap[v];  // in flight together with the window's loads
             int best[16];
@@ -355,7 +358,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
     // mark the output blocks that see the changed positions
     if (DT == RRM_BIN_I32) {
         for (int p = p0; p <= p1; ++p) mark_tiles(g, p, tileflag, stamp);
-    } else {
+    } else if (g.sty > 0) {  // (layers on the position-gather kernel read the bitmap instead: no flags)
         for (int p = p0; p <= p1; ++p) mark_subtiles(g, (unsigned int)p, reinterpret_cast<unsigned char*>(tileflag));
     }
     const unsigned long long mask = __ballot(changed);

@@ -35,3 +35,44 @@ def test_reciprocal_division_is_exact_over_the_admitted_range():
     d = 16384
     u = 17 * d - 1
     assert ((u * _magic(d)) >> 32) != u // d and _udiv_magic(u, d, _magic(d)) == u // d
+
+
+def test_position_kernel_unit_shapes_terminate_and_fit(tmp_path):
+    """The work-unit choice of the position-gather kernel (pure host code): compiled alone and run over the
+    benchmark shapes and a sweep; it must end, and what it picks must respect the kernel's limits (staged units
+    and output positions per thread, LDS budget) and cover every output row and stream."""
+    import os
+    import re
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = tmp_path / "pos_shape_test"
+    subprocess.run(["g++", "-std=c++17", "-O1", "-I", os.path.join(root, "include"), "-I",
+                    os.path.join(root, "paper_1802_09723_amd", "csrc"), os.path.join(root, "tests", "host", "pos_shape_test.cpp"),
+                    "-o", str(exe)], check=True)
+    cases = [(1, 32, 32, 16, 16, 3, 1, 1, 1, 1), (512, 13, 13, 384, 384, 3, 1, 1, 1, 1), (512, 27, 27, 96, 256, 5, 2, 2, 1, 1),
+             (257, 256, 256, 16, 4, 3, 1, 1, 1, 1), (3, 100, 100, 32, 8, 1, 0, 1, 1, 1)]
+    for n in (1, 2, 64):
+        for hw, c in ((56, 64), (28, 128), (14, 256), (7, 512)):
+            cases.append((n, hw, hw, c, c, 3, 1, 1, 2, 2))
+    rng = np.random.default_rng(9)
+    for _ in range(60):
+        k = int(rng.choice([1, 3, 5, 7]))
+        hw = int(rng.integers(k, 80))
+        grp = int(rng.choice([1, 2]))
+        cases.append((int(rng.integers(1, 600)), hw, int(rng.integers(k, 80)), 16 * grp * int(rng.integers(1, 9)),
+                      4 * grp * int(rng.integers(1, 70)), k, int(rng.integers(0, k)), grp, int(rng.choice([1, 2])), int(rng.choice([1, 2]))))
+    eligible = 0
+    for cse in cases:
+        out = subprocess.run([str(exe)] + [str(v) for v in cse], check=True, capture_output=True, text=True, timeout=10).stdout
+        if out.strip() == "no":
+            continue
+        eligible += 1
+        f = {k: int(v) for k, v in re.findall(r"(\w+)=(\d+)", out)}
+        n, h, w, ci, co, k, pad, grp, es, terms = cse
+        ho, wo = h + 2 * pad - k + 1, w + 2 * pad - k + 1
+        assert f["npos"] * 2 <= 256 * 8 and f["G"] * f["R"] * wo <= 256 * 4, (cse, f)
+        assert f["lds"] <= 80 * 1024 - 512, (cse, f)
+        assert f["nbands"] * f["R"] >= ho and f["nsg"] * f["G"] >= n, (cse, f)
+        assert f["units"] == f["nsg"] * f["nbands"] * grp * f["ncg"], (cse, f)
+        assert f["RB"] == f["R"] + k - 1 and f["WP"] == w + pad and f["npos"] == f["G"] * f["RB"] * f["WP"] + pad
+    assert eligible >= 20
