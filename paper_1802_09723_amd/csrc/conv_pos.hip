@@ -18,14 +18,14 @@
 //     positions are also written out for the next layer ("touched"); every position is written by exactly one
 //     workgroup in every step, so nothing has to be cleared.
 //   * The columns are multiplied 32 at a time: v_mfma_i32_32x32x32_i8 / v_mfma_f32_32x32x16_bf16 with M = 32
-//     output channels, N = 32 gathered positions, K = 2 chunks of one tap.  A wavefront owns 4 channel blocks x 2
-//     column tiles (one weight fragment feeds 2 products, one window fragment 4), a workgroup of four wavefronts
-//     256 columns; longer lists take several passes.  Weights are packed at create time in per-lane fragment
-//     order, one contiguous run per (slab, tap group), double-buffered in LDS like the bands.
+//     output channels, N = 32 gathered positions, K = 2 chunks of one tap.  A consumer wavefront owns 4 channel
+//     blocks x 2 column tiles (one weight fragment feeds 2 products, one window fragment 4), the four consumers of
+//     a workgroup 256 columns; longer lists take several passes.  Weights are packed at create time in per-lane
+//     fragment order, one contiguous run per (slab, tap group), double-buffered in LDS like the bands.
 //   * The accumulators start from the stored projection (delta) or the bias (dense) and are stored back: one owner
 //     per output element, no atomics, results reproducible run to run.
-// Two workgroups fit a compute unit (80 KB of LDS and 256 registers each): while one waits for its stored
-// projections or writes them back, the other multiplies.  Work units are handed out by an atomic counter (their
+// A workgroup has eight wavefronts in two roles (see the kernel): four only copy into LDS, one stage ahead, four
+// only multiply; the roles meet at one barrier per stage.  Work units are handed out by an atomic counter (their
 // cost varies with the number of active columns); the last workgroup to leave rearms the counters, so a step
 // needs no host-side state and can be replayed in a HIP graph.
 #include <algorithm>
@@ -77,24 +77,44 @@ __device__ __forceinline__ void sched_interleave() {
     }
 }
 
+// Wait until at most n of this wavefront's vector-memory operations are outstanding (they complete in order, so
+// everything but the n youngest has landed).  The count is an immediate of the instruction, hence the switch; LDS
+// and scalar counters are not waited for.
+__device__ __forceinline__ void wait_vmcnt(int n) {
+#define RRM_VM(N) \
+    case N:       \
+        __builtin_amdgcn_s_waitcnt(((N) & 15) | (((N) >> 4) << 14) | (7 << 4) | (15 << 8)); \
+        break;
+    switch (n) {
+        RRM_VM(0) RRM_VM(1) RRM_VM(2) RRM_VM(3) RRM_VM(4) RRM_VM(5) RRM_VM(6) RRM_VM(7) RRM_VM(8) RRM_VM(9) RRM_VM(10)
+        RRM_VM(11) RRM_VM(12) RRM_VM(13) RRM_VM(14) RRM_VM(15) RRM_VM(16) RRM_VM(17) RRM_VM(18) RRM_VM(19) RRM_VM(20)
+        RRM_VM(21) RRM_VM(22) RRM_VM(23) RRM_VM(24)
+        default:
+            __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8));
+            break;
+    }
+#undef RRM_VM
+}
+
 typedef const void __attribute__((address_space(1))) * gptr_t;
 typedef void __attribute__((address_space(3))) * lptr_t;
 
 constexpr int PT = POS_THREADS;
+constexpr int PP = POS_PROD;
 constexpr int NCB = POS_NCB;
 
 template <int DT, int MODE, int TERMS>
-__global__ __launch_bounds__(PT, 2) void conv_pos_kernel(const unsigned char* __restrict__ src0,
-                                                         const unsigned char* __restrict__ src1,
-                                                         const unsigned char* __restrict__ zero16,
-                                                         const unsigned long long* __restrict__ bitmap,
-                                                         unsigned int* ctrl, const unsigned char* __restrict__ wpack,
-                                                         const void* __restrict__ bias_v, void* y_v, PosGeom g,
-                                                         DevStats* __restrict__ stats) {
+__global__ __launch_bounds__(PT) void conv_pos_kernel(const unsigned char* __restrict__ src0,
+                                                      const unsigned char* __restrict__ src1,
+                                                      const unsigned char* __restrict__ zero16,
+                                                      const unsigned long long* __restrict__ bitmap,
+                                                      unsigned int* ctrl, const unsigned char* __restrict__ wpack,
+                                                      const void* __restrict__ bias_v, void* y_v, PosGeom g,
+                                                      DevStats* __restrict__ stats) {
     typedef typename Acc<DT>::type acc_t;
     typedef typename Acc<DT>::vec vec_t;
     typedef typename Acc<DT>::scalar sc_t;
-    constexpr int NP = 2;  // column tiles per wavefront and pass
+    constexpr int NP = 2;  // column tiles per consumer wavefront and pass
 
     // LDS: [weights x 2][bands (TERMS planes) x 2][input-position flags][column list: band position, y position]
     extern __shared__ uint4 smem[];
@@ -103,25 +123,30 @@ __global__ __launch_bounds__(PT, 2) void conv_pos_kernel(const unsigned char* __
     const int plane = g.b_plane_bytes;
     const int b_bytes = TERMS * plane;
     unsigned char* abase = lds;
-    unsigned char* bbase = lds + 2 * a_bytes;
+    unsigned char* bbase = lds + POS_ABUF * a_bytes;
     unsigned char* in_act = bbase + 2 * b_bytes;
     unsigned short* s_colq = reinterpret_cast<unsigned short*>(in_act + g.act_bytes);
     unsigned int* s_coly = reinterpret_cast<unsigned int*>(s_colq + g.col_cap);
     __shared__ int s_cnt[POS_MAXO][PT / 64];
     __shared__ int s_next;
-    __shared__ int s_last;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // Two roles.  Wavefronts 0-3 ("consumers", one per SIMD) only multiply and write results; wavefronts 4-7
+    // ("producers") only copy weights and bands into LDS.  An LDS-direct copy occupies its wavefront's issue slot
+    // for a hundred cycles or more; issued by a wavefront of its own it runs in the shadow of the matrix
+    // instructions of the consumer on the same SIMD instead of delaying them.
+    const bool producer = wave >= 4;
+    const int ptid = tid - PP;  // producer thread index
     const int khalf = lane >> 5;
     sc_t* y = static_cast<sc_t*>(y_v);
     const sc_t* bias = static_cast<const sc_t*>(bias_v);
 
-    // Slots of a thread (the same decomposition for every unit, divided out again per unit: a handful of
-    // divisions against a unit's thousands of matrix instructions):
-    //   staged unit v = tid + PT*i: 16 bytes (chunk v & 1 of the slab) of band position q = v >> 1,
-    //     q = (stream * RB + row) * WP + column (column < pad: the zeros between rows);
+    // Slots of a thread (the same decomposition for every unit, divided out again per unit: a handful of divisions
+    // against a unit's thousands of matrix instructions):
+    //   staged unit v = ptid + PP*i of a producer thread: 16 bytes (chunk v & 1 of the slab) of band position
+    //     q = v >> 1, q = (stream * RB + row) * WP + column (column < pad: the zeros between rows);
     //   output position lo = tid + PT*i of a unit: (stream * R + row) * wo + column.
     const int band_pos = g.G * g.RB * g.WP;
     const int upos = g.pos_bytes >> 4;  // bitmap bits (16-byte units) per input position
@@ -142,33 +167,43 @@ __global__ __launch_bounds__(PT, 2) void conv_pos_kernel(const unsigned char* __
         const int rows_here = min(g.R, g.ho - r0);
         const bool flag_owner = grp == 0 && cgrp == 0;
 
-        // ---- source offsets of this thread's staged units; flags of the band's input positions ----------------
-        unsigned int uoff[POS_MAXU];  // byte offset at slab 0, 0xFFFFFFFF = zeros
-#pragma unroll
-        for (int i = 0; i < POS_MAXU; ++i) {
-            const int q0 = (tid + PT * i) >> 1;
-            const int gg = q0 / (g.RB * g.WP), rem = q0 - gg * (g.RB * g.WP);
-            const int row = rem / g.WP, col = rem - row * g.WP;
-            const int b = b0 + gg, iy = r0 - g.pad + row;
-            const bool ok = q0 < band_pos && col >= g.pad && b < g.n && iy >= 0 && iy < g.h;
-            const unsigned int p = (unsigned int)((b * g.h + iy) * g.w + col - g.pad);
-            uoff[i] = ok ? p * (unsigned int)g.pos_bytes + (unsigned int)(grp * g.grp_bytes) + ((tid & 1) ? 16u : 0u)
-                         : 0xFFFFFFFFu;
-            if (MODE == MODE_DELTA && !(tid & 1)) {
-                const int q = (tid + PT * i) >> 1;
-                if (q < g.npos) {
-                    unsigned char f = 0;
-                    if (ok) {  // any changed 16-byte unit among this position's?
-                        const unsigned int lo = p * (unsigned int)upos, hi = lo + (unsigned int)upos;
-                        for (unsigned int wd = lo >> 6; wd <= (hi - 1u) >> 6; ++wd) {
-                            unsigned long long m = bitmap[wd];
-                            if (wd == lo >> 6) m &= ~0ull << (lo & 63u);
-                            if (wd == (hi - 1u) >> 6 && (hi & 63u)) m &= ~0ull >> (64u - (hi & 63u));
-                            if (m) f = 1;
-                        }
+        // ---- flags of the band's input positions (all threads); source offsets of the producers' units ---------
+        if (MODE == MODE_DELTA) {
+            for (int q = tid; q < g.npos; q += PT) {
+                const int gg = q / (g.RB * g.WP), rem = q - gg * (g.RB * g.WP);
+                const int row = rem / g.WP, col = rem - row * g.WP;
+                const int b = b0 + gg, iy = r0 - g.pad + row;
+                unsigned char f = 0;
+                if (q < band_pos && col >= g.pad && b < g.n && iy >= 0 && iy < g.h) {
+                    // any changed 16-byte unit among this position's?
+                    const unsigned int p = (unsigned int)((b * g.h + iy) * g.w + col - g.pad);
+                    const unsigned int lo = p * (unsigned int)upos, hi = lo + (unsigned int)upos;
+                    for (unsigned int wd = lo >> 6; wd <= (hi - 1u) >> 6; ++wd) {
+                        unsigned long long m = bitmap[wd];
+                        if (wd == lo >> 6) m &= ~0ull << (lo & 63u);
+                        if (wd == (hi - 1u) >> 6 && (hi & 63u)) m &= ~0ull >> (64u - (hi & 63u));
+                        if (m) f = 1;
                     }
-                    in_act[q] = f;
                 }
+                in_act[q] = f;
+            }
+        }
+        unsigned int uoff[POS_MAXU];  // producers: byte offset at slab 0, 0xFFFFFFFF = zeros
+        unsigned int odd_chunk = 0;   // bit i: unit i holds the slab's second chunk
+        if (producer) {
+#pragma unroll
+            for (int i = 0; i < POS_MAXU; ++i) {
+                const int q0 = (ptid + PP * i) >> 1;
+                const int gg = q0 / (g.RB * g.WP), rem = q0 - gg * (g.RB * g.WP);
+                const int row = rem / g.WP, col = rem - row * g.WP;
+                const int b = b0 + gg, iy = r0 - g.pad + row;
+                const bool ok = q0 < band_pos && col >= g.pad && b < g.n && iy >= 0 && iy < g.h;
+                const unsigned int p = (unsigned int)((b * g.h + iy) * g.w + col - g.pad);
+                // (the two chunks of a position swap places with bits 2 and 3 of the position index: the operand
+                // reads of consecutive positions then fall into different LDS banks)
+                const unsigned int chunk = (unsigned int)((ptid ^ (q0 >> 2) ^ (q0 >> 3)) & 1);
+                uoff[i] = ok ? p * (unsigned int)g.pos_bytes + (unsigned int)(grp * g.grp_bytes) + chunk * 16u : 0xFFFFFFFFu;
+                if (chunk) odd_chunk |= 1u << i;
             }
         }
         __syncthreads();
@@ -249,190 +284,222 @@ __global__ __launch_bounds__(PT, 2) void conv_pos_kernel(const unsigned char* __
         const bool from_y = MODE == MODE_DELTA && !full;
         const unsigned char* s0 = full ? g.xfull : src0;
         const bool two = TERMS == 2 && !full;
-
-        // ---- staging ----------------------------------------------------------------------------------------------
-        const unsigned char* wsrc = wpack + (size_t)(grp * g.ncg + cgrp) * g.nslab * g.ntaps * (NCB * 1024);
-        auto stage_a = [&](int slab, int tg, int buf) {
-            const int t0 = tg * g.ts, nt = min(g.ts, g.ntaps - t0);
-            const unsigned char* src = wsrc + (size_t)(slab * g.ntaps + t0) * (NCB * 1024) + tid * 16;
-            unsigned char* dst = abase + buf * a_bytes + wave * 1024;
-            for (int t = 0; t < nt; ++t)  // (NCB * 1024 bytes = one round of the workgroup)
-                __builtin_amdgcn_global_load_lds((gptr_t)(src + t * (NCB * 1024)), (lptr_t)(dst + t * (NCB * 1024)), 16, 0, 0);
-        };
-        auto stage_b = [&](int slab, int buf) {
-            unsigned char* dst = bbase + buf * b_bytes;
-            // (a chunk beyond the group's channels is a copy of zeros: odd chunk counts are padded)
-            const bool chunk_ok = 2 * slab + (tid & 1) < g.chunks;
-#pragma unroll
-            for (int i = 0; i < POS_MAXU; ++i) {
-                if ((tid + PT * i) >> 1 >= g.npos) break;
-                const bool real = uoff[i] != 0xFFFFFFFFu && chunk_ok;
-                const unsigned int o = uoff[i] + (unsigned int)slab * 32u;
-                unsigned char* d = dst + (i * PT + wave * 64) * 16;  // wave-uniform; the lane adds 16 * lane
-                __builtin_amdgcn_global_load_lds((gptr_t)(real ? s0 + o : zero16), (lptr_t)d, 16, 0, 0);
-                if (TERMS == 2 && two)
-                    __builtin_amdgcn_global_load_lds((gptr_t)(real ? src1 + o : zero16), (lptr_t)(d + plane), 16, 0, 0);
-            }
-        };
-
         const int nst = g.nslab * g.nstage;
-        for (int p0 = 0; p0 < ncols; p0 += POS_COLS) {
-            // ---- this wavefront's column tiles of the pass: tiles wave and wave + 4 ------------------------------
-            const int ntile = min(POS_COLS / 32, (ncols - p0 + 31) >> 5);
-            const int nact = (ntile > wave ? 1 : 0) + (ntile > wave + 4 ? 1 : 0);
-            bool cv[NP];
-            unsigned int boff[NP], ybase[NP];
-#pragma unroll
-            for (int j = 0; j < NP; ++j) {
-                const int cidx = p0 + (wave + 4 * j) * 32 + (lane & 31);
-                cv[j] = j < nact && cidx < ncols;
-                boff[j] = (cv[j] ? (unsigned int)s_colq[cidx] : 0u) * 32u + (unsigned int)khalf * 16u;
-                ybase[j] = (cv[j] ? s_coly[cidx] : 0u) * (unsigned int)g.c_out + (unsigned int)(grp * g.og);
-            }
-            // channel (within the filter group) of register 4*gq of block c; the 4 registers are consecutive channels
-            auto chan = [&](int c, int gq) { return (cgrp * NCB + c) * 32 + 8 * gq + 4 * khalf; };
-            // accumulators start from what the result is added to
-            acc_t acc[NCB][NP];
-#pragma unroll
-            for (int c = 0; c < NCB; ++c)
-#pragma unroll
-                for (int gq = 0; gq < 4; ++gq) {
-                    const int co = chan(c, gq);
-                    const bool ch_ok = co < g.og;
-                    vec_t bv = vec_t{0, 0, 0, 0};
-                    if (!from_y && ch_ok && bias) bv = *reinterpret_cast<const vec_t*>(bias + grp * g.og + co);
-#pragma unroll
-                    for (int j = 0; j < NP; ++j) {
-                        vec_t v = bv;
-                        if (from_y && ch_ok && cv[j]) v = *reinterpret_cast<const vec_t*>(y + (ybase[j] + (unsigned int)co));
-                        acc[c][j][4 * gq + 0] = v.x;
-                        acc[c][j][4 * gq + 1] = v.y;
-                        acc[c][j][4 * gq + 2] = v.z;
-                        acc[c][j][4 * gq + 3] = v.w;
-                    }
-                }
+        // Every unit walks the slabs in a rotated order of its own, so that at any moment the workgroups of the chip
+        // read different parts of the packed weights.  The rotation is a fixed function of the unit: results repeat
+        // from run to run.
+        const int rot = (unit * 5 + (unit >> 3)) % g.nslab;
+        auto phys = [&](int sl) {
+            const int p2 = sl + rot;
+            return p2 >= g.nslab ? p2 - g.nslab : p2;
+        };
 
-            // K loop of one stage (the taps t0 .. t0 + nt - 1 of one slab), in half taps: two of the four channel
-            // blocks at a time, so that the operand registers stay few.  The weight fragments of half tap k + 1 (and,
-            // at a tap's end, the window fragments of the next tap) are read from LDS while half tap k multiplies.
-            auto k_loop = [&]<int NPA, int T>(const unsigned char* aw, const unsigned char* bw, int t0, int nt) {
-                constexpr int NB1 = T == 2 ? NPA : 1;
-                struct OpsA {
-                    uint4 a[2];
-                };
-                struct OpsB {
-                    uint4 b0[NPA], b1[NB1];
-                };
-                constexpr int N_MFMA = 2 * NPA * T;
-                int ky = t0 / g.kw, kx = t0 - ky * g.kw;
-                auto fetch_a = [&](int i, int half, OpsA& o) {
+        if (producer) {
+            // ================= producers: copies into LDS, one stage ahead of the consumers =======================
+            const unsigned char* wsrc = wpack + (size_t)(grp * g.ncg + cgrp) * g.nslab * g.ntaps * (NCB * 1024);
+            auto stage_a = [&](int slab, int tg, int buf) {
+                const int t0 = tg * g.ts, nt = min(g.ts, g.ntaps - t0);
+                const unsigned char* src = wsrc + (size_t)(slab * g.ntaps + t0) * (NCB * 1024) + ptid * 16;
+                unsigned char* dst = abase + buf * a_bytes + (wave - 4) * 1024;
+                for (int t = 0; t < nt; ++t)  // (NCB * 1024 bytes = one round of the 256 producer threads)
+                    __builtin_amdgcn_global_load_lds((gptr_t)(src + t * (NCB * 1024)), (lptr_t)(dst + t * (NCB * 1024)), 16, 0, 0);
+            };
+            auto stage_b = [&](int slab, int buf) {
+                unsigned char* dst = bbase + buf * b_bytes;
 #pragma unroll
-                    for (int c = 0; c < 2; ++c) o.a[c] = *reinterpret_cast<const uint4*>(aw + (i * NCB + 2 * half + c) * 1024);
-                };
-                auto fetch_b = [&](OpsB& o) {  // (taps in order: the window offset steps along)
-                    const unsigned int tapoff = (unsigned int)((ky * g.WP + kx) * 32);
-                    if (++kx == g.kw) {
-                        kx = 0;
-                        ++ky;
-                    }
-#pragma unroll
-                    for (int j = 0; j < NPA; ++j) {
-                        o.b0[j] = *reinterpret_cast<const uint4*>(bw + (boff[j] + tapoff));
-                        if (T == 2) o.b1[j] = *reinterpret_cast<const uint4*>(bw + plane + (boff[j] + tapoff));
-                    }
-                };
-                auto multiply = [&]<int HALF>(const OpsA& oa, const OpsB& ob) {
-#pragma unroll
-                    for (int t = 0; t < T; ++t)
-#pragma unroll
-                        for (int c = 0; c < 2; ++c)
-#pragma unroll
-                            for (int j = 0; j < NPA; ++j)
-                                acc[2 * HALF + c][j] = mma(oa.a[c], t == 0 ? ob.b0[j] : ob.b1[j < NB1 ? j : 0], acc[2 * HALF + c][j]);
-                };
-                OpsA ae, ao;
-                OpsB bx, by;
-                fetch_b(bx);
-                fetch_a(0, 0, ae);
-                for (int i = 0; i < nt; i += 2) {
-                    fetch_a(i, 1, ao);
-                    multiply.template operator()<0>(ae, bx);
-                    sched_interleave<0, N_MFMA, 2>();
-                    if (i + 1 < nt) {
-                        fetch_a(i + 1, 0, ae);
-                        fetch_b(by);
-                    }
-                    multiply.template operator()<1>(ao, bx);
-                    sched_interleave<0, N_MFMA, 2 + NPA * T>();
-                    if (i + 1 < nt) {
-                        fetch_a(i + 1, 1, ao);
-                        multiply.template operator()<0>(ae, by);
-                        sched_interleave<0, N_MFMA, 2>();
-                        if (i + 2 < nt) {
-                            fetch_a(i + 2, 0, ae);
-                            fetch_b(bx);
-                        }
-                        multiply.template operator()<1>(ao, by);
-                        sched_interleave<0, N_MFMA, 2 + NPA * T>();
-                    }
+                for (int i = 0; i < POS_MAXU; ++i) {
+                    if ((ptid + PP * i) >> 1 >= g.npos) break;
+                    // (a chunk beyond the group's channels is a copy of zeros: odd chunk counts are padded)
+                    const bool real = uoff[i] != 0xFFFFFFFFu && 2 * slab + (int)((odd_chunk >> i) & 1u) < g.chunks;
+                    const unsigned int o = uoff[i] + (unsigned int)slab * 32u;
+                    unsigned char* d = dst + (i * PP + (wave - 4) * 64) * 16;  // wave-uniform; the lane adds 16 * lane
+                    __builtin_amdgcn_global_load_lds((gptr_t)(real ? s0 + o : zero16), (lptr_t)d, 16, 0, 0);
+                    if (TERMS == 2 && two)
+                        __builtin_amdgcn_global_load_lds((gptr_t)(real ? src1 + o : zero16), (lptr_t)(d + plane), 16, 0, 0);
                 }
             };
-
-            // ---- stages: (slab, tap group), weights double-buffered per stage, bands per slab -------------------
-            stage_a(0, 0, 0);
-            stage_b(0, 0);
-            int slab = 0, tg = 0;
-            for (int s = 0; s < nst; ++s) {
-                __builtin_amdgcn_s_waitcnt(0);  // this thread's copies for stage s have landed
-                __syncthreads();                // everybody's have; everybody is done with stage s - 1
-                int nslab_n = slab, ntg = tg + 1;
-                if (ntg == g.nstage) {
-                    ntg = 0;
-                    ++nslab_n;
-                }
-                if (s + 1 < nst) stage_a(nslab_n, ntg, (s + 1) & 1);
-                if (tg == 0 && slab + 1 < g.nslab) stage_b(slab + 1, (slab + 1) & 1);
-                const unsigned char* aw = abase + (s & 1) * a_bytes + lane * 16;
-                const unsigned char* bw = bbase + (slab & 1) * b_bytes;
-                const int t0 = tg * g.ts, nt = min(g.ts, g.ntaps - t0);
-                if (two) {
-                    if (nact > 1) {
-                        if constexpr (TERMS == 2) k_loop.template operator()<2, 2>(aw, bw, t0, nt);
-                    } else if (nact > 0) {
-                        if constexpr (TERMS == 2) k_loop.template operator()<1, 2>(aw, bw, t0, nt);
+            for (int p0 = 0; p0 < ncols; p0 += POS_COLS) {
+                stage_a(phys(0), 0, 0);
+                stage_b(phys(0), 0);
+                int slab = 0, tg = 0;
+                for (int s = 0; s < nst; ++s) {
+                    __builtin_amdgcn_s_waitcnt(0);  // this wavefront's copies for stage s have landed
+                    __syncthreads();                // stage s is published; the consumers are done with stage s - 1
+                    int sl1 = slab, tg1 = tg + 1;
+                    if (tg1 == g.nstage) {
+                        tg1 = 0;
+                        ++sl1;
                     }
-                } else if (nact > 1) {
-                    k_loop.template operator()<2, 1>(aw, bw, t0, nt);
-                } else if (nact > 0) {
-                    k_loop.template operator()<1, 1>(aw, bw, t0, nt);
+                    if (s + 1 < nst) {
+                        stage_a(phys(sl1), tg1, (s + 1) & 1);
+                        if (tg1 == 0) stage_b(phys(sl1), sl1 & 1);
+                    }
+                    slab = sl1;
+                    tg = tg1;
                 }
-                slab = nslab_n;
-                tg = ntg;
+                __syncthreads();  // the consumers are done with the last stage: its buffers are free
             }
-
-            // ---- results back -----------------------------------------------------------------------------------
+        } else {
+            // ================= consumers: the matrix products ==========================================================
+            for (int p0 = 0; p0 < ncols; p0 += POS_COLS) {
+                // ---- this wavefront's column tiles of the pass: tiles wave and wave + 4 --------------------------
+                const int ntile = min(POS_COLS / 32, (ncols - p0 + 31) >> 5);
+                const int nact = (ntile > wave ? 1 : 0) + (ntile > wave + 4 ? 1 : 0);
+                bool cv[NP];
+                unsigned int boff[NP], ybase[NP];
 #pragma unroll
-            for (int c = 0; c < NCB; ++c)
-#pragma unroll
-                for (int gq = 0; gq < 4; ++gq) {
-                    const int co = chan(c, gq);
-                    if (co >= g.og) continue;
-#pragma unroll
-                    for (int j = 0; j < NP; ++j) {
-                        if (!cv[j]) continue;
-                        vec_t o;
-                        o.x = acc[c][j][4 * gq + 0];
-                        o.y = acc[c][j][4 * gq + 1];
-                        o.z = acc[c][j][4 * gq + 2];
-                        o.w = acc[c][j][4 * gq + 3];
-                        *reinterpret_cast<vec_t*>(y + (ybase[j] + (unsigned int)co)) = o;
-                    }
+                for (int j = 0; j < NP; ++j) {
+                    const int cidx = p0 + (wave + 4 * j) * 32 + (lane & 31);
+                    cv[j] = j < nact && cidx < ncols;
+                    boff[j] = cv[j] ? (unsigned int)s_colq[cidx] : 0u;  // band position of the column (tap 0, 0)
+                    ybase[j] = (cv[j] ? s_coly[cidx] : 0u) * (unsigned int)g.c_out + (unsigned int)(grp * g.og);
                 }
-            __syncthreads();  // the last stage's buffers are free for the next pass / unit
+                // channel (within the filter group) of register 4*gq of block c; the 4 registers are consecutive channels
+                auto chan = [&](int c, int gq) { return (cgrp * NCB + c) * 32 + 8 * gq + 4 * khalf; };
+                // accumulators start from what the result is added to
+                acc_t acc[NCB][NP];
+#pragma unroll
+                for (int c = 0; c < NCB; ++c)
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq) {
+                        const int co = chan(c, gq);
+                        const bool ch_ok = co < g.og;
+                        vec_t bv = vec_t{0, 0, 0, 0};
+                        if (!from_y && ch_ok && bias) bv = *reinterpret_cast<const vec_t*>(bias + grp * g.og + co);
+#pragma unroll
+                        for (int j = 0; j < NP; ++j) {
+                            vec_t v = bv;
+                            if (from_y && ch_ok && cv[j]) v = *reinterpret_cast<const vec_t*>(y + (ybase[j] + (unsigned int)co));
+                            acc[c][j][4 * gq + 0] = v.x;
+                            acc[c][j][4 * gq + 1] = v.y;
+                            acc[c][j][4 * gq + 2] = v.z;
+                            acc[c][j][4 * gq + 3] = v.w;
+                        }
+                    }
+
+                // K loop of one stage (the taps t0 .. t0 + NT - 1 of one slab), unrolled over the taps: the operands
+                // of tap i + 1 are read from LDS into a second register set while tap i multiplies, the reads issued
+                // one by one between the matrix instructions.  NT = 0: any number of taps (nt), one after the other.
+                auto k_loop = [&]<int NPA, int T, int NT>(const unsigned char* aw, const unsigned char* bw, int t0, int nt) {
+                    constexpr int NB1 = T == 2 ? NPA : 1;
+                    struct Ops {
+                        uint4 a[NCB], b0[NPA], b1[NB1];
+                    };
+                    constexpr int N_MFMA = NCB * NPA * T;
+                    constexpr int N_READ = NCB + NPA * T;
+                    int ky = t0 / g.kw, kx = t0 - ky * g.kw;
+                    auto fetch = [&](int i, Ops& o) {  // (taps in order: the window offset steps along)
+                        const unsigned int tapq = (unsigned int)(ky * g.WP + kx);
+                        if (++kx == g.kw) {
+                            kx = 0;
+                            ++ky;
+                        }
+#pragma unroll
+                        for (int c = 0; c < NCB; ++c) o.a[c] = *reinterpret_cast<const uint4*>(aw + (i * NCB + c) * 1024);
+#pragma unroll
+                        for (int j = 0; j < NPA; ++j) {
+                            // (the position's two chunks are stored swapped according to bits 2 and 3 of its index)
+                            const unsigned int q = boff[j] + tapq;
+                            const unsigned int off = q * 32u + (((unsigned int)khalf ^ (q >> 2) ^ (q >> 3)) & 1u) * 16u;
+                            o.b0[j] = *reinterpret_cast<const uint4*>(bw + off);
+                            if (T == 2) o.b1[j] = *reinterpret_cast<const uint4*>(bw + plane + off);
+                        }
+                    };
+                    auto multiply = [&](const Ops& o) {
+#pragma unroll
+                        for (int t = 0; t < T; ++t)
+#pragma unroll
+                            for (int c = 0; c < NCB; ++c)
+#pragma unroll
+                                for (int j = 0; j < NPA; ++j)
+                                    acc[c][j] = mma(o.a[c], t == 0 ? o.b0[j] : o.b1[j < NB1 ? j : 0], acc[c][j]);
+                    };
+                    if constexpr (NT > 0) {
+                        Ops o[2];
+                        fetch(0, o[0]);
+#pragma unroll
+                        for (int i = 0; i < NT; ++i) {
+                            if (i + 1 < NT) fetch(i + 1, o[(i + 1) & 1]);
+                            multiply(o[i & 1]);
+                            if (i + 1 < NT) sched_interleave<0, N_MFMA, N_READ>();
+                        }
+                    } else {
+                        for (int i = 0; i < nt; ++i) {
+                            Ops o;
+                            fetch(i, o);
+                            multiply(o);
+                        }
+                    }
+                };
+
+                // ---- stages: (slab, tap group).  The loop is compiled per (column tiles in use, terms, taps per
+                // stage): a variant's accumulators never change registers.
+                auto run_stages = [&]<int NPA, int T, int NT>() {
+                    int slab = 0, tg = 0;
+                    for (int s = 0; s < nst; ++s) {
+                        // Stage s is staged.  A bare barrier: the producers waited for their copies before they
+                        // arrived, and this wavefront's own loads of stored projections and its stores need not
+                        // have completed.
+                        asm volatile("s_barrier" ::: "memory");
+                        if constexpr (NPA > 0) {
+                            const unsigned char* aw = abase + (s & 1) * a_bytes + lane * 16;
+                            const unsigned char* bw = bbase + (slab & 1) * b_bytes;
+                            const int t0 = tg * g.ts;
+                            k_loop.template operator()<(NPA > 0 ? NPA : 1), T, NT>(aw, bw, t0, min(g.ts, g.ntaps - t0));
+                        }
+                        if (++tg == g.nstage) {
+                            tg = 0;
+                            ++slab;
+                        }
+                    }
+                    // every LDS read of the last stage has been consumed by a matrix instruction issued above
+                    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                };
+                // (stages of exactly ts taps get the unrolled loop: 1, 3, 5 and 9 taps, when ts divides the tap count)
+                const int nt_fixed = (g.ntaps % g.ts == 0 && (g.ts == 1 || g.ts == 3 || g.ts == 5 || g.ts == 9)) ? g.ts : 0;
+                auto run_tiles = [&]<int T>() {
+#define RRM_POS_RUN(NPA)                                                     \
+    do {                                                                     \
+        if (nt_fixed == 9) run_stages.template operator()<NPA, T, 9>();      \
+        else if (nt_fixed == 3) run_stages.template operator()<NPA, T, 3>(); \
+        else if (nt_fixed == 5) run_stages.template operator()<NPA, T, 5>(); \
+        else if (nt_fixed == 1) run_stages.template operator()<NPA, T, 1>(); \
+        else run_stages.template operator()<NPA, T, 0>();                    \
+    } while (0)
+                    if (nact > 1) RRM_POS_RUN(2);
+                    else if (nact > 0) RRM_POS_RUN(1);
+                    else run_stages.template operator()<0, T, 0>();  // (no column tile: barriers only)
+#undef RRM_POS_RUN
+                };
+                if (two) {
+                    if constexpr (TERMS == 2) run_tiles.template operator()<2>();
+                } else {
+                    run_tiles.template operator()<1>();
+                }
+
+                // ---- results back (while the producers stage the next pass / unit) ----------------------------------
+#pragma unroll
+                for (int c = 0; c < NCB; ++c)
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq) {
+                        const int co = chan(c, gq);
+                        if (co >= g.og) continue;
+#pragma unroll
+                        for (int j = 0; j < NP; ++j) {
+                            if (!cv[j]) continue;
+                            vec_t o;
+                            o.x = acc[c][j][4 * gq + 0];
+                            o.y = acc[c][j][4 * gq + 1];
+                            o.z = acc[c][j][4 * gq + 2];
+                            o.w = acc[c][j][4 * gq + 3];
+                            *reinterpret_cast<vec_t*>(y + (ybase[j] + (unsigned int)co)) = o;
+                        }
+                    }
+            }
         }
 
         if (tid == 0) s_next = (int)gridDim.x + (int)nxt_pending;
-        __syncthreads();
+        __syncthreads();  // (also: both roles are done with this unit's lists)
         unit = s_next;
         __syncthreads();  // (s_next is rewritten at the end of the next unit; the lists at its start)
     }
@@ -446,7 +513,6 @@ __global__ __launch_bounds__(PT, 2) void conv_pos_kernel(const unsigned char* __
             if (MODE == MODE_DELTA && g.fresh) g.fresh[0] = 0u;  // the stored input now holds this step's input
         }
     }
-    (void)s_last;
 }
 
 template <int DT, int MODE, int TERMS>
@@ -454,7 +520,7 @@ hipError_t launch_one(const void* src0, const void* src1, const void* zero16, co
                       unsigned int* ctrl, const void* wpack, const void* bias, void* y, const PosGeom& g, DevStats* stats,
                       hipStream_t s) {
     const size_t lds = conv_pos_lds_bytes(g, TERMS);
-    const int gx = std::min(g.total_units, 2 * NUM_CU);
+    const int gx = std::min(g.total_units, NUM_CU);  // (one workgroup per compute unit; it loops over units)
     auto kern = conv_pos_kernel<DT, MODE, TERMS>;
     if (lds > 64 * 1024) {
         static std::mutex mu;  // one per instantiation, shared by every handle and thread of the process

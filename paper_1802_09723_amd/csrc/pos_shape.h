@@ -8,14 +8,16 @@
 namespace rrm {
 
 constexpr int POS_NUM_CU = 256;  // compute units of the MI355X
-constexpr int POS_LDS_BUDGET = 80 * 1024 - 512;  // dynamic LDS of a workgroup: half a compute unit's, minus statics
+constexpr int POS_LDS_BUDGET = 160 * 1024 - 1024;  // dynamic LDS of a workgroup: a compute unit's, minus statics
 
 // Geometry of the position-gather convolution (conv_pos.hip): stride 1, channel runs of 16-byte multiples.
-constexpr int POS_THREADS = 256;
+constexpr int POS_THREADS = 512;  // 4 consumer + 4 producer wavefronts
+constexpr int POS_PROD = 256;     // producer threads
 constexpr int POS_NCB = 4;     // 32-channel blocks per workgroup
-constexpr int POS_MAXU = 8;    // staged 16-byte units per thread and slab
-constexpr int POS_MAXO = 4;    // output positions per thread and work unit
+constexpr int POS_MAXU = 10;   // staged 16-byte units per producer thread and slab
+constexpr int POS_MAXO = 2;    // output positions per thread and work unit
 constexpr int POS_COLS = 256;  // columns (output positions) per pass of a workgroup
+constexpr int POS_ABUF = 2;    // weight stages in LDS: copies run one stage ahead of the multiplications
 struct PosGeom {
     int n, h, w, c_out, kh, kw, pad, groups;
     int ho, wo, og, cg;
@@ -45,7 +47,7 @@ struct PosGeom {
 
 // dynamic LDS of the position-gather kernel
 inline size_t conv_pos_lds_bytes(const PosGeom& g, int terms) {
-    return 2 * (size_t)g.a_stage_bytes + 2 * (size_t)terms * g.b_plane_bytes + (size_t)g.act_bytes + (size_t)g.col_cap * 6;
+    return POS_ABUF * (size_t)g.a_stage_bytes + 2 * (size_t)terms * g.b_plane_bytes + (size_t)g.act_bytes + (size_t)g.col_cap * 6;
 }
 
 // Fill the geometry of a layer (esize = bytes per input element, terms = difference planes staged per band);
@@ -62,25 +64,38 @@ inline bool pos_choose_shape(const rrm_shape& s, int esize, int terms, PosGeom& 
     g.chunks = g.grp_bytes / 16;
     g.nslab = (g.chunks + 1) / 2;
     g.ntaps = s.kh * s.kw;
-    g.ts = s.kw <= 5 ? s.kw : 4;
+    // taps per stage: the whole window if its weights (POS_NCB KiB per tap) stay within 36 KiB, else a filter row
+    g.ts = g.ntaps <= 9 ? g.ntaps : (s.kw <= 5 ? s.kw : 4);
     g.nstage = (g.ntaps + g.ts - 1) / g.ts;
     g.a_stage_bytes = g.ts * POS_NCB * 1024;
     g.WP = s.w + s.pad;
     g.ncg = (og + POS_NCB * 32 - 1) / (POS_NCB * 32);
     if (s.kh > 64 || g.WP > 32000 || g.ho < 1 || g.wo < 1) return false;
-    const long long budget = (long long)POS_LDS_BUDGET - 2ll * g.a_stage_bytes;
+    const long long budget = (long long)POS_LDS_BUDGET - (long long)POS_ABUF * g.a_stage_bytes;
     // per staged position: two buffers x terms x 32 bytes and one flag; per output position: 6 bytes of column list
     auto fits = [&](int G, int R) {
         const long long RB = R + s.kh - 1, npos = (long long)G * RB * g.WP + s.pad, ncol = (long long)G * R * g.wo;
-        if (npos * 2 > (long long)POS_THREADS * POS_MAXU || ncol > (long long)POS_THREADS * POS_MAXO || G > 255 || RB > 255)
+        if (npos * 2 > (long long)POS_PROD * POS_MAXU || ncol > (long long)POS_THREADS * POS_MAXO || G > 255 || RB > 255)
             return false;
         return npos * (2 * terms * 32) + 32 * terms + npos + 16 + (ncol + 8) * 6 <= budget;
     };
     const long long chan_units = (long long)s.groups * g.ncg;
     int G = 1, R = 0;
-    if (fits(1, g.ho)) {  // whole maps: as many streams per unit as fit, while enough units remain to fill the chip
+    if (fits(1, g.ho)) {
+        // Whole maps, G streams per unit: the G that needs the fewest rounds of the chip's compute units per stream
+        // (a unit costs about G; rounds = ceil(units / compute units)).
         R = g.ho;
-        while (G < s.n && fits(G + 1, R) && ((s.n + G) / (G + 1)) * chan_units >= 2 * POS_NUM_CU) ++G;
+        long long best = -1;
+        for (int c = 1; c <= s.n && fits(c, R); ++c) {
+            const long long units = (long long)((s.n + c - 1) / c) * chan_units;
+            const long long cost = ((units + POS_NUM_CU - 1) / POS_NUM_CU) * c;
+            // (ties: the largest G whose unit still holds at most one and a half passes of columns: more, smaller
+            // units balance better when their costs differ, fuller passes multiply better)
+            if (best < 0 || cost < best || (cost == best && (long long)c * R * g.wo <= POS_COLS + POS_COLS / 2)) {
+                best = cost;
+                G = c;
+            }
+        }
     } else {
         int rmax = 0;
         for (int r = 1; r <= g.ho && fits(1, r); ++r) rmax = r;

@@ -445,7 +445,12 @@ rrm_status setup_pos(rrm_layer* L, const std::vector<unsigned char>& w) {
 // choose the convolution kernel of an int8 / bf16 layer: 0 = automatic, 1 = window-tile, 2 = position-gather
 rrm_status select_conv_kernel(rrm_layer* L, int which) {
     if (which == 2 && !L->pos_ok) return fail(RRM_ERR_OPTION, "the position-gather kernel needs stride 1 and 16-byte channel runs");
-    L->use_pos = which == 2 || (which == 0 && L->pos_ok);
+    // Automatic: the position-gather kernel where it measured faster, int8 layers on small maps with enough streams
+    // to give every compute unit several work units; elsewhere (large maps, whose 4x4 blocks waste little; bf16,
+    // whose second difference term doubles its staging; few streams, where its per-unit set-up is not amortised)
+    // the window-tile kernel.
+    const bool pos_pays = L->pos_ok && L->dtype == RRM_I8_I32 && L->pg.ho * L->pg.wo <= 256 && L->pg.total_units >= 2 * NUM_CU;
+    L->use_pos = which == 2 || (which == 0 && pos_pays);
     L->tshift = L->use_pos ? 0 : 2;
     ScanGeom& sg = L->sg;
     sg.sty = L->use_pos ? 0 : L->cg.sty;  // (no sub-tile flags for the position-gather kernel: it reads the bitmap)

@@ -23,9 +23,17 @@ def boundary_weights(seq):
 
 
 def make_layer(seq, **opts):
+    """A layer handle with the given options.  "conv_kernel" = 2 (the position-gather kernel) is dropped for layers
+    that kernel does not take (stride > 1, channel runs that are not 16-byte multiples, FC, binary)."""
     import paper_1802_09723_amd as rrm
     layer = rrm.Layer(seq.shape, seq.dtype, boundary_weights(seq), seq.bias)
     for k, v in opts.items():
+        if k == "conv_kernel":
+            try:
+                layer.set_option(k, v)
+            except rrm.binding.RRMError:
+                pass
+            continue
         layer.set_option(k, v)
     return layer
 

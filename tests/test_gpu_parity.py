@@ -25,6 +25,21 @@ def test_config0_batched_streams():
     run_sequence(S.config0(n=3, T=4))
 
 
+def _pos_kernel_takes(shp, dt):
+    """the position-gather kernel's conditions (stride 1, channel runs of 16-byte multiples, outputs in fours)"""
+    es = 1 if dt == S.I8 else 2
+    return (shp.stride == 1 and (shp.c_in // shp.groups * es) % 16 == 0 and (shp.c_out // shp.groups) % 4 == 0
+            and shp.c_out % 4 == 0)
+
+
+def _kernel_opts(shp, dt, kern):
+    """options that select the convolution kernel under test: 1 window-tile, 2 position-gather (skipped where that
+    kernel does not apply)"""
+    if kern == 2 and not _pos_kernel_takes(shp, dt):
+        pytest.skip("layer not eligible for the position-gather kernel")
+    return {"conv_kernel": kern}
+
+
 SMALL_CONV = [
     # odd sizes, strides, pads, groups, channel counts off the 16-byte chunk
     S.conv_shape(9, 11, 6, 10, 3, 1, 1, 1, n=2),
@@ -43,9 +58,10 @@ SMALL_CONV = [
 
 @pytest.mark.parametrize("shp", SMALL_CONV)
 @pytest.mark.parametrize("dt", [S.I8, S.BF16])
-def test_small_conv_shapes(shp, dt):
+@pytest.mark.parametrize("kern", [1, 2])
+def test_small_conv_shapes(shp, dt, kern):
     seq = S.random_layer(4000 + shp.h * 7 + shp.c_in, shp, dt, T=4, frac=0.2, block=2)
-    run_sequence(seq, check_dense=(0, 2))
+    run_sequence(seq, check_dense=(0, 2), **_kernel_opts(shp, dt, kern))
 
 
 SMALL_FC = [S.fc_shape(67, 29, n=2), S.fc_shape(256, 128), S.fc_shape(1000, 515, n=3), S.fc_shape(48, 4100)]
@@ -245,7 +261,35 @@ def test_random_conv_shapes(idx):
     shp = _random_conv_shapes(24, 20240)[idx]
     dt = S.I8 if idx % 2 == 0 else S.BF16
     seq = S.random_layer(8100 + idx, shp, dt, T=4, frac=0.25, block=2)
-    run_sequence(seq, check_dense=(0, 3))
+    run_sequence(seq, check_dense=(0, 3), conv_kernel=1)
+
+
+def _random_pos_shapes(count, seed):
+    """Seeded random shapes the position-gather kernel takes: stride 1, kernels 1..5 (also non-square), pads 0..2,
+    groups 1..2, channel runs of 16-byte multiples (odd chunk counts too), outputs in fours, 1..40 streams."""
+    rng = S.rng_for(seed)
+    out = []
+    while len(out) < count:
+        dt = S.I8 if len(out) % 2 == 0 else S.BF16
+        groups = int(rng.choice([1, 1, 2]))
+        cg = (16 if dt == S.I8 else 8) * int(rng.choice([1, 2, 3, 4, 5, 8]))
+        og = 4 * int(rng.choice([1, 2, 5, 8, 16, 33, 40]))
+        kh, kw = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        pad = int(rng.integers(0, 3))
+        h, w = int(rng.integers(max(kh - 2 * pad, 1) + 1, 30)), int(rng.integers(max(kw - 2 * pad, 1) + 1, 30))
+        n = int(rng.choice([1, 2, 3, 7, 40]))
+        shp = S.LayerShape(S.CONV, n, h, w, cg * groups, og * groups, kh, kw, 1, pad, groups)
+        if shp.h_out < 1 or shp.w_out < 1 or n * shp.h_out * shp.w_out * cg * groups * og * kh * kw > 6e8:
+            continue
+        out.append((shp, dt))
+    return out
+
+
+@pytest.mark.parametrize("idx", range(20))
+def test_random_shapes_on_the_position_kernel(idx):
+    shp, dt = _random_pos_shapes(20, 20250)[idx]
+    seq = S.random_layer(8300 + idx, shp, dt, T=4, frac=0.25, block=2)
+    run_sequence(seq, check_dense=(0, 3), conv_kernel=2)
 
 
 def _random_bin_shapes(count, seed):
@@ -289,7 +333,8 @@ def test_random_fc_shapes(idx):
     (13, 64, 64, 3, 1, 16, 0.30), (13, 64, 64, 3, 1, 256, 0.10),
 ])
 @pytest.mark.parametrize("dt", [S.I8, S.BF16])
-def test_many_streams_mid_size(case, dt):
+@pytest.mark.parametrize("kern", [1, 2])
+def test_many_streams_mid_size(case, dt, kern):
     h, ci, co, k, groups, n, frac = case
     shp = S.conv_shape(h, h, ci, co, k, 1, k // 2, groups, n=n)
     rng = S.rng_for(8500 + n + h)
@@ -305,4 +350,4 @@ def test_many_streams_mid_size(case, dt):
             f = draw(rng, shp.x_shape)
         frames.append(f)
     seq = S.Sequence_(shp, dt, w, None, frames, "mid")
-    run_sequence(seq, check_dense=(1,), check_x=False)
+    run_sequence(seq, check_dense=(1,), check_x=False, conv_kernel=kern)
