@@ -136,7 +136,12 @@ rrm_status rrm_snapshot(rrm_layer* layer, const void** x_snap, const void** y_sn
 rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* hip_stream);
 
 /* Options (value semantics per key):
- *   "path"        0 auto, 1 sparse delta path always, 2 recompute densely every step
+ *   "path"        0 auto, 1 sparse delta path always (scan + tile kernel, no switch to recomputation), 2 recompute
+ *                 densely every step, 3 INT8 / BF16 conv: the single-launch scatter path always (one kernel compares,
+ *                 multiplies the changed input positions and adds the products into the stored projection with
+ *                 atomic adds: work proportional to the changed input positions; fp32 results then depend on the
+ *                 order of the adds within the layer's tolerance).  Automatic mode takes path 3 for layers with few
+ *                 positions in all (one stream of a small map), where two dependent launches cost more than the work.
  *   "fc_splits"   FC, dense path: number of row splits of the weight matrix, in [1, the default chosen at
  *                 create] (the partial-sum scratch is sized for the default)
  *   "bf16_terms"  BF16 conv: 2 = difference carried as hi+lo bf16 pair (default), 1 = hi only

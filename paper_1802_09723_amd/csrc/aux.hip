@@ -64,7 +64,8 @@ __global__ void relu_requant_pool_kernel(const int* __restrict__ y, signed char*
 // from the previous call.
 template <bool CHANGED>
 __global__ __launch_bounds__(256) void relu_requant_pool4_kernel(const int4* __restrict__ y, unsigned int* __restrict__ out,
-                                                                 const unsigned char* __restrict__ touched, int tshift,
+                                                                 const unsigned char* __restrict__ touched,
+                                                                 const unsigned int* __restrict__ touched_all, int tshift,
                                                                  int h, int w, int c4, int ho, int wo, int shift, int pool,
                                                                  unsigned int magic_c4, unsigned int magic_ho) {
     const int row = (int)blockIdx.x;  // b*ho + oy
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(256) void relu_requant_pool4_kernel(const int4* __r
     const int cv = idx - ox * c4;
     const int y0 = pool ? 2 * oy : oy, x0 = pool ? 2 * ox : ox;
     const int span = pool ? 2 : 0;
-    if (CHANGED) {
+    if (CHANGED && touched_all[0] == 0u) {
         const int rnd = (1 << tshift) - 1;
         const int sty = (h + rnd) >> tshift, stx = (w + rnd) >> tshift;
         const unsigned char* t = touched + (size_t)b * sty * stx;
@@ -132,8 +133,8 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) 
     return hipGetLastError();
 }
 
-hipError_t launch_relu_requant_pool(const void* y, void* out, const void* touched, int tshift, int n, int h, int w, int c,
-                                    int shift, int pool, hipStream_t s) {
+hipError_t launch_relu_requant_pool(const void* y, void* out, const void* touched, const unsigned int* touched_all,
+                                    int tshift, int n, int h, int w, int c, int shift, int pool, hipStream_t s) {
     const int ho = pool ? (h - 3) / 2 + 1 : h, wo = pool ? (w - 3) / 2 + 1 : w;
     const long long total = (long long)n * ho * wo * c;
     if (total <= 0) return hipSuccess;
@@ -143,10 +144,10 @@ hipError_t launch_relu_requant_pool(const void* y, void* out, const void* touche
         dim3 grid((unsigned int)(n * ho), (unsigned int)((wo * c4 + 255) / 256));
         if (touched)
             hipLaunchKernelGGL(relu_requant_pool4_kernel<true>, grid, dim3(256), 0, s, (const int4*)y, (unsigned int*)out,
-                               (const unsigned char*)touched, tshift, h, w, c4, ho, wo, shift, pool, magic(c4), magic(ho));
+                               (const unsigned char*)touched, touched_all, tshift, h, w, c4, ho, wo, shift, pool, magic(c4), magic(ho));
         else
             hipLaunchKernelGGL(relu_requant_pool4_kernel<false>, grid, dim3(256), 0, s, (const int4*)y, (unsigned int*)out,
-                               (const unsigned char*)nullptr, 0, h, w, c4, ho, wo, shift, pool, magic(c4), magic(ho));
+                               (const unsigned char*)nullptr, (const unsigned int*)nullptr, 0, h, w, c4, ho, wo, shift, pool, magic(c4), magic(ho));
         return hipGetLastError();
     }
     if (touched) return hipErrorInvalidValue;  // the incremental form needs channel counts in fours

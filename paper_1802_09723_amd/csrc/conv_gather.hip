@@ -313,6 +313,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             if (tid == 0) {
                 ctrl[0] = 0u;
                 if (g.fresh) g.fresh[0] = 0u;  // the stored input now holds this step's input
+                if (g.touched_all) g.touched_all[0] = 0u;  // `touched` describes this step
                 if (n_flagged && !own_group) atomicAdd(&stats[0].active_tiles, (unsigned long long)n_flagged);
             }
         }

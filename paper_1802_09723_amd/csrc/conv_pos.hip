@@ -511,6 +511,7 @@ __global__ __launch_bounds__(PT) void conv_pos_kernel(const unsigned char* __res
             ctrl[0] = 0u;
             ctrl[2] = 0u;
             if (MODE == MODE_DELTA && g.fresh) g.fresh[0] = 0u;  // the stored input now holds this step's input
+            if (MODE == MODE_DELTA && g.touched_all) g.touched_all[0] = 0u;  // `touched` describes this step
         }
     }
 }

@@ -42,6 +42,7 @@ struct PosGeom {
     int full_pct;        // delta launches: units with more than this percentage of active positions recompute
     const unsigned char* xfull;  //   their band from the committed input (nullptr: never)
     unsigned int* fresh;         // see FusedSrc::fresh: cleared at the end of a delta launch
+    unsigned int* touched_all;   // see FusedSrc::touched_all: cleared at the end of a delta launch
     unsigned char* touched;      // one byte per output position: written by the last delta step (or nullptr)
 };
 

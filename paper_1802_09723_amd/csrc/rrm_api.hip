@@ -55,6 +55,11 @@ struct rrm_layer {
     bool use_pos = false;   // ... and does
     int tshift = 2;         // log2 of the side of the output blocks that `touched` flags: 2 (4x4) or 0 (positions)
     void* wpos = nullptr;   // weights packed for the position-gather kernel
+    ScatGeom sc{};          // single-launch scatter path
+    bool scat_ok = false;   // the layer can run on it
+    bool scat_auto = false; // ... and does when "path" is automatic
+    void* wsc = nullptr;    // weights packed for it
+    unsigned int* sc_arrive = nullptr;  // its arrival counters (one per position block)
     size_t touched_bytes = 0;
     BinGeom bg{};
     FcGeom fg{};
@@ -89,7 +94,7 @@ struct rrm_layer {
     int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0;
 
     ~rrm_layer() {
-        void* ptrs[] = {wpack, wpos, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, fresh, zero16, fc_arrive, fc_part, stats};
+        void* ptrs[] = {wpack, wpos, wsc, sc_arrive, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, fresh, zero16, fc_arrive, fc_part, stats};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
         for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
@@ -442,6 +447,61 @@ rrm_status setup_pos(rrm_layer* L, const std::vector<unsigned char>& w) {
     return RRM_OK;
 }
 
+// Single-launch scatter path: eligibility, block shape, weights in per-lane MFMA order
+// [(group, 32-channel block)][tap][K step][lane] x 16 bytes, lane l -> output channel l % 32 of the block, unit
+// 2 * step + l / 32 of the group's channels at that tap.  Padded channels and units are zero.
+rrm_status setup_scatter(rrm_layer* L, const std::vector<unsigned char>& w) {
+    const rrm_shape& s = L->shape;
+    ScatGeom& g = L->sc;
+    L->scat_ok = false;
+    const int es = L->esize;
+    const int cg = s.c_in / s.groups, og = s.c_out / s.groups;
+    if ((cg * es) % 16 != 0) return RRM_OK;
+    g.n = s.n; g.h = s.h; g.w = s.w; g.c_out = s.c_out; g.kh = s.kh; g.kw = s.kw; g.stride = s.stride; g.pad = s.pad;
+    g.groups = s.groups;
+    g.ho = (s.h + 2 * s.pad - s.kh) / s.stride + 1;
+    g.wo = (s.w + 2 * s.pad - s.kw) / s.stride + 1;
+    g.og = og;
+    g.U = s.c_in * es / 16;
+    g.ug = cg * es / 16;
+    g.nk = (g.ug + 1) / 2;
+    g.ncb = (og + 31) / 32;
+    g.npair = s.groups * g.ncb;
+    g.ntaps = s.kh * s.kw;
+    g.npos_total = (long long)s.n * s.h * s.w;
+    const int terms = L->dtype == RRM_BF16_F32 ? 2 : 1;
+    // positions per block: the block's units fit the threads' registers (SCAT_UPT each) and, times the terms, 64 KB
+    g.PB = 0;
+    for (int pb : {64, 32, 16, 8})
+        if (pb * g.U <= 256 * SCAT_UPT && terms * pb * g.U <= 4000) {
+            g.PB = pb;
+            break;
+        }
+    if (g.PB == 0) return RRM_OK;
+    const long long nblk = (g.npos_total + g.PB - 1) / g.PB;
+    // few position blocks: split the output channels over more workgroups, up to about two per compute unit
+    g.cs = (int)std::max(1ll, std::min((long long)g.npair, (2ll * NUM_CU + nblk - 1) / nblk));
+    std::vector<unsigned char> pack((size_t)g.npair * g.ntaps * g.nk * 64 * 16, 0);
+    const int per_vec = 16 / es;
+    for (int pair = 0; pair < g.npair; ++pair)
+        for (int tap = 0; tap < g.ntaps; ++tap)
+            for (int k = 0; k < g.nk; ++k)
+                for (int lane = 0; lane < 64; ++lane) {
+                    const int grp = pair / g.ncb, cb = pair % g.ncb;
+                    const int co = cb * 32 + (lane & 31), unit = 2 * k + (lane >> 5);
+                    if (co >= og || unit >= g.ug) continue;
+                    unsigned char* dst = pack.data() + ((((size_t)pair * g.ntaps + tap) * g.nk + k) * 64 + lane) * 16;
+                    const size_t wrow = (size_t)(grp * og + co) * g.ntaps + tap;
+                    std::memcpy(dst, w.data() + (wrow * cg + (size_t)unit * per_vec) * es, 16);
+                }
+    rrm_status st = upload(pack.data(), pack.size(), &L->wsc);
+    if (st != RRM_OK) return st;
+    if ((st = dalloc((size_t)nblk * sizeof(unsigned int), (void**)&L->sc_arrive)) != RRM_OK) return st;
+    g.arrive = L->sc_arrive;
+    L->scat_ok = true;
+    return RRM_OK;
+}
+
 // choose the convolution kernel of an int8 / bf16 layer: 0 = automatic, 1 = window-tile, 2 = position-gather
 rrm_status select_conv_kernel(rrm_layer* L, int which) {
     if (which == 2 && !L->pos_ok) return fail(RRM_ERR_OPTION, "the position-gather kernel needs stride 1 and 16-byte channel runs");
@@ -539,6 +599,14 @@ int bin_cw(const rrm_layer* L) {
     return ((long long)g.n * g.tiles_y * g.tiles_x * g.groups * ((g.og + 63) / 64) >= 512) ? 16 : 8;
 }
 
+// does this step of a convolution layer take the single-launch scatter path?  ("path" = 3: always where the layer
+// is eligible; automatic: see DESIGN notes in select below)
+bool use_scatter(const rrm_layer* L) {
+    if (!L->scat_ok || L->dtype == RRM_BIN_I32) return false;
+    if (L->opt_path == 3) return true;
+    return L->opt_path == 0 && L->scat_auto;
+}
+
 int fc_splits(const rrm_layer* L) { return L->opt_fc_splits > 0 ? L->opt_fc_splits : L->fc_nsplit; }
 
 rrm_status check_ptr(const void* p, const char* what) {
@@ -617,6 +685,7 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
     else {
         st = setup_conv(L, hw);
         if (st == RRM_OK) st = setup_pos(L, hw);
+        if (st == RRM_OK) st = setup_scatter(L, hw);
     }
     if (st != RRM_OK) return bail(st);
 
@@ -683,6 +752,7 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
             if ((st = upload(ones, 16, (void**)&L->fresh)) != RRM_OK) return bail(st);
             L->cg.fresh = L->fresh;
             L->pg.fresh = L->fresh;
+            L->cg.touched_all = L->pg.touched_all = L->sc.touched_all = L->ctrl + 3;
         }
         if ((st = dalloc(256, &L->zero16)) != RRM_OK) return bail(st);
     }
@@ -732,6 +802,12 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
             if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
             RRM_HIP(launch_bin_conv(MODE_DELTA, cw, L->x_snap, L->d0, L->tileflag, L->wpack, nullptr, L->y_snap, L->bg,
                                     L->stats, s));
+        } else if (use_scatter(L)) {
+            // one launch: compare, products of the changed positions, atomic accumulation, commit
+            if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;  // (no separate scan kernel: its time is reported as 0)
+            ScatGeom sc = L->sc;
+            sc.eps = L->sg.eps;
+            RRM_HIP(launch_conv_scatter(L->dtype, L->opt_terms, x_t, L->x_snap, L->wsc, L->y_snap, sc, L->stats, s));
         } else {
             RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag, 0u, L->sg, L->stats, s));
             if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
@@ -781,6 +857,7 @@ rrm_status rrm_step_from_projection(rrm_layer* L, rrm_layer* P, int shift, int p
     src.stx = P->tshift ? P->cg.stx : wy;
     src.shift = shift; src.pool = pool ? 1 : 0;
     src.fresh = L->fresh;  // a fresh / reset layer holds no f(P) yet: everything is compared
+    src.touched_all = P->ctrl + 3;
     rrm_status rs;
     if ((rs = prof_mark(L, 0, st)) != RRM_OK) return rs;
     RRM_HIP(launch_scan_fused(src, L->x_snap, L->d0, L->bitmap, L->tileflag, L->sg, L->stats, st));
@@ -841,6 +918,8 @@ rrm_status rrm_reset(rrm_layer* L, void* hip_stream) {
         RRM_HIP(launch_fill_word(L->fresh, 16, 1u, s));
         if (L->touched) RRM_HIP(launch_fill_word(L->touched, round16(L->touched_bytes), 0x01010101u, s));
     }
+    if (L->sc_arrive)
+        RRM_HIP(launch_fill_zero(L->sc_arrive, round16((size_t)((L->sc.npos_total + L->sc.PB - 1) / L->sc.PB) * sizeof(unsigned int)), s));
     if (L->fc_arrive) RRM_HIP(launch_fill_zero(L->fc_arrive, round16((size_t)L->shape.n * sizeof(unsigned int)), s));
     L->has_snapshot = false;
     L->steps = 0;
@@ -867,7 +946,9 @@ rrm_status rrm_set_option(rrm_layer* L, const char* key, long value) {
     if (!key) return fail(RRM_ERR_NULL, "key is NULL");
     const std::string k(key);
     if (k == "path") {
-        if (value < 0 || value > 2) return fail(RRM_ERR_OPTION, "path must be 0, 1 or 2");
+        if (value < 0 || value > 3) return fail(RRM_ERR_OPTION, "path must be 0, 1, 2 or 3");
+        if (value == 3 && !L->scat_ok)
+            return fail(RRM_ERR_OPTION, "path 3 (single-launch scatter) needs an int8 / bf16 convolution with 16-byte channel runs");
         L->opt_path = (int)value;
     } else if (k == "fc_splits") {
         // the scratch of the partial sums was sized for fc_nsplit at create: only fewer are allowed
@@ -980,7 +1061,7 @@ rrm_status rrm_aux_relu_requant_pool_i8(const void* y, void* out, int n, int h, 
     if (!y || !out) return fail(RRM_ERR_NULL, "y / out is NULL");
     if (n < 1 || h < 1 || w < 1 || c < 1 || shift < 0 || shift > 31 || (pool && (h < 3 || w < 3)))
         return fail(RRM_ERR_SHAPE, "bad shape for relu_requant_pool");
-    RRM_HIP(launch_relu_requant_pool(y, out, nullptr, 0, n, h, w, c, shift, pool, static_cast<hipStream_t>(hip_stream)));
+    RRM_HIP(launch_relu_requant_pool(y, out, nullptr, nullptr, 0, n, h, w, c, shift, pool, static_cast<hipStream_t>(hip_stream)));
     return RRM_OK;
 }
 
@@ -992,7 +1073,7 @@ rrm_status rrm_aux_relu_requant_pool_changed_i8(rrm_layer* L, void* out, int shi
     const int ho = L->cg.ho, wo = L->cg.wo;
     if (shift < 0 || shift > 31 || (pool && (ho < 3 || wo < 3))) return fail(RRM_ERR_SHAPE, "bad shape for relu_requant_pool");
     if (reinterpret_cast<uintptr_t>(out) & 3) return fail(RRM_ERR_ALIGN, "out must be 4-byte aligned");
-    RRM_HIP(launch_relu_requant_pool(L->y_snap, out, L->touched, L->tshift, s.n, ho, wo, s.c_out, shift, pool,
+    RRM_HIP(launch_relu_requant_pool(L->y_snap, out, L->touched, L->ctrl + 3, L->tshift, s.n, ho, wo, s.c_out, shift, pool,
                                      static_cast<hipStream_t>(hip_stream)));
     return RRM_OK;
 }

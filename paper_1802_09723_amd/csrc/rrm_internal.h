@@ -70,6 +70,9 @@ struct FusedSrc {
     // is ignored and every unit is computed and compared.  Set by create / reset, cleared by the consumer's
     // compute kernel at the end of its first delta step (device state: a replayed graph sees it too).
     const unsigned int* fresh;
+    // device word, non-zero after a step of the producer that kept no flags (the single-launch scatter path):
+    // `touched` is ignored then as well.  Cleared by the producer's next flag-keeping step.
+    const unsigned int* touched_all;
 };
 
 constexpr int CONV_MAX_STAGE_UNITS = 12;  // 16-byte units a thread stages per slab (half for 2 terms)
@@ -118,9 +121,29 @@ struct ConvGeom {
     unsigned int magic_stx;     // d = stx
     int vec_store;       // 1: y rows allow 16-byte read-modify-write
     unsigned int* fresh;    // see FusedSrc::fresh: cleared at the end of a delta launch
+    unsigned int* touched_all;  // see FusedSrc::touched_all: cleared at the end of a delta launch
     unsigned int* touched;  // copy of the sub-tile flags of the last delta step (what it wrote in y), or nullptr
     const unsigned char* xfull;  // delta launches: the committed input in source layout (full recomputation above
     int full_pct;                //   full_pct % active sub-tiles), or nullptr: never
+};
+
+// Geometry of the single-launch scatter convolution (conv_scatter.hip).
+constexpr int SCAT_UPT = 8;  // 16-byte units of x per thread of a position block at most
+struct ScatGeom {
+    int n, h, w, c_out, kh, kw, stride, pad, groups;
+    int ho, wo, og;
+    int U;               // 16-byte units per input position (all groups)
+    int ug;              // units per group
+    int nk;              // K steps (2 units each) per group: ceil(ug / 2)
+    int ncb;             // 32-channel output blocks per group
+    int npair;           // groups * ncb: (group, channel block) pairs
+    int ntaps;           // kh * kw
+    int PB;              // input positions per block (at most 64)
+    int cs;              // output-channel splits: workgroups per position block
+    long long npos_total;  // n * h * w
+    float eps;           // bf16: truncation threshold of the difference (0 = exact)
+    unsigned int* arrive;       // one word per position block (used when cs > 1; rearmed by the kernel)
+    unsigned int* touched_all;  // device word set by every step of this path: "treat every output as written"
 };
 
 // Geometry of the binary (XNOR / popcount) convolution.
@@ -179,6 +202,11 @@ hipError_t launch_conv_pos(int dtype, int mode, int terms, const void* src0, con
                            const unsigned long long* bitmap, unsigned int* ctrl, const void* wpack, const void* bias, void* y,
                            const PosGeom& g, DevStats* stats, hipStream_t s);
 
+// one delta step of a convolution layer in a single launch (compare, products of the changed positions, atomic
+// accumulation, commit); wsc: weights in [pair][tap][K step][lane] x 16 bytes order
+hipError_t launch_conv_scatter(int dtype, int terms, const void* x_t, void* x_snap, const void* wsc, void* y,
+                               const ScatGeom& g, DevStats* stats, hipStream_t s);
+
 // one delta step of an FC layer in a single launch; `arrive`: one zeroed word per stream (rearmed by the kernel)
 hipError_t launch_fc_delta(int dtype, const void* x_t, void* x_snap, const void* wT, void* y, unsigned int* arrive,
                            const FcGeom& g, DevStats* stats, hipStream_t s);
@@ -205,8 +233,8 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_repack(int esize, const void* x, void* dst, const ScanGeom& g, hipStream_t s);
 hipError_t launch_fill_word(void* p, size_t bytes, unsigned int word, hipStream_t s);
 // touched: nullptr = every output; else byte flags per block of (1 << tshift)^2 positions of y, only outputs under
-// a set flag
-hipError_t launch_relu_requant_pool(const void* y, void* out, const void* touched, int tshift, int n, int h, int w, int c,
-                                    int shift, int pool, hipStream_t s);
+// a set flag (every output again while the device word *touched_all is non-zero)
+hipError_t launch_relu_requant_pool(const void* y, void* out, const void* touched, const unsigned int* touched_all,
+                                    int tshift, int n, int h, int w, int c, int shift, int pool, hipStream_t s);
 
 }  // namespace rrm

@@ -226,7 +226,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
         unsigned int any = 0;
         for (int sy = sy0; sy <= sy1; ++sy)
             for (int sx = sx0; sx <= sx1; ++sx) any |= t[sy * fs.stx + sx];
-        compare = fs.fresh[0] != 0u || any != 0u;
+        compare = fs.fresh[0] != 0u || fs.touched_all[0] != 0u || any != 0u;
         if (compare) {
             b_early = x_snap[v];  // in flight together with the window's loads
             int best[16];

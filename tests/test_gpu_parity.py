@@ -196,19 +196,19 @@ def _perturbed_frames(seq, seed, sigma=0.02):
     return frames
 
 
-@pytest.mark.parametrize("kind", ["conv", "conv_multi", "fc"])
+@pytest.mark.parametrize("kind", ["conv", "conv_multi", "fc", "conv_scatter"])
 @pytest.mark.parametrize("eps", [0.0, 0.03])
 def test_bf16_truncation_threshold_matches_oracle(kind, eps):
     """rrm_set_threshold: stored input bit-identical to the oracle's (same fp32 decision per entry), stored
     projection within the bf16 tolerance, same number of truncated entries (Sec. 3.4, Improving sparsity)."""
     if kind == "fc":
         seq = S.config3("fc7", S.BF16, 0.10, n=2, T=5)
-    elif kind == "conv":
+    elif kind in ("conv", "conv_scatter"):
         seq = S.config2("r28", 0.10, T=5)
     else:
         seq = S.random_layer(7007, S.conv_shape(21, 17, 24, 40, 3, 1, 1, n=3), S.BF16, T=5, frac=0.3, block=3)
     frames = _perturbed_frames(seq, 4242)
-    layer = make_layer(seq)
+    layer = make_layer(seq, **({"path": 3} if kind == "conv_scatter" else {}))
     layer.set_threshold(eps)
     st = oracle.State(seq.shape, S.BF16, seq.weights, seq.bias)
     trunc = 0
@@ -351,3 +351,102 @@ def test_many_streams_mid_size(case, dt, kern):
         frames.append(f)
     seq = S.Sequence_(shp, dt, w, None, frames, "mid")
     run_sequence(seq, check_dense=(1,), check_x=False, conv_kernel=kern)
+
+
+# ---- the single-launch scatter path ("path" = 3) ---------------------------------------------------------------------
+def _scatter_takes(shp, dt):
+    es = 1 if dt == S.I8 else 2
+    return (shp.c_in // shp.groups * es) % 16 == 0
+
+
+def _random_scatter_shapes(count, seed):
+    """Seeded random shapes the scatter path takes: any stride, kernels 1..5 (also non-square), pads 0..2, groups
+    1..3, channel runs of 16-byte multiples, any output-channel count, 1..40 streams."""
+    rng = S.rng_for(seed)
+    out = []
+    while len(out) < count:
+        dt = S.I8 if len(out) % 2 == 0 else S.BF16
+        groups = int(rng.choice([1, 1, 2, 3]))
+        cg = (16 if dt == S.I8 else 8) * int(rng.choice([1, 2, 3, 4, 6, 8]))
+        og = int(rng.choice([1, 3, 4, 8, 20, 32, 33, 64, 70]))
+        kh, kw = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        stride, pad = int(rng.integers(1, 4)), int(rng.integers(0, 3))
+        h, w = int(rng.integers(max(kh - 2 * pad, 1) + 1, 28)), int(rng.integers(max(kw - 2 * pad, 1) + 1, 28))
+        n = int(rng.choice([1, 2, 3, 7, 40]))
+        shp = S.LayerShape(S.CONV, n, h, w, cg * groups, og * groups, kh, kw, stride, pad, groups)
+        if shp.h_out < 1 or shp.w_out < 1 or n * shp.h_out * shp.w_out * cg * groups * og * kh * kw > 4e8:
+            continue
+        out.append((shp, dt))
+    return out
+
+
+@pytest.mark.parametrize("idx", range(24))
+def test_scatter_path_random_shapes(idx):
+    shp, dt = _random_scatter_shapes(24, 20260)[idx]
+    import paper_1802_09723_amd as rrm
+    seq = S.random_layer(8600 + idx, shp, dt, T=4, frac=0.2, block=2)
+    try:
+        st, _ = run_sequence(seq, check_dense=(0,), path=3)
+    except rrm.binding.RRMError as e:
+        if e.status != -2:
+            raise
+        pytest.skip("shape beyond the window-tile kernel's LDS limit (the handle needs that kernel for its dense path)")
+    assert st["delta_steps"] == 4 and st["tile_positions"] in (1, 16)
+
+
+@pytest.mark.parametrize("dt", [S.I8, S.BF16])
+def test_scatter_path_many_streams_and_shared_blocks(dt):
+    """64 streams of a 13 x 13 map (many position blocks, one workgroup each) and one stream of a 7 x 7 map with 512
+    channels (two position blocks shared by sixteen output-channel splits: the last split to compare commits)."""
+    for shp, frac in ((S.conv_shape(13, 13, 64, 128, 3, 1, 1, n=64), 0.1), (S.conv_shape(7, 7, 512, 512, 3, 1, 1), 0.3)):
+        seq = S.random_layer(8700 + shp.h, shp, dt, T=5, frac=frac, block=2)
+        run_sequence(seq, check_dense=(), path=3)
+
+
+def test_scatter_and_tile_steps_interleave():
+    """Steps of the scatter path and of the scan + tile path on one handle, in turn: each leaves the state the other
+    expects (difference buffer, change bitmap, stored input), int8 bit-exact on every frame."""
+    import paper_1802_09723_amd as rrm
+    shp = S.conv_shape(14, 14, 32, 64, 3, 1, 1, n=3)
+    seq = S.random_layer(8801, shp, S.I8, T=9, frac=0.15, block=3)
+    layer = make_layer(seq)
+    for t, x in enumerate(seq.frames):
+        layer.set_option("path", 3 if t % 3 == 1 else (1 if t % 3 == 2 else 0))
+        layer.step(to_device(x, S.I8))
+        want = oracle.dense(shp, S.I8, seq.weights, seq.bias, x)
+        assert_matches(layer.y_snapshot().cpu().numpy(), want, S.I8, f"frame {t}")
+        assert np.array_equal(layer.x_snapshot_bytes().cpu().numpy(), x.view(np.uint8).reshape(-1))
+    layer.destroy()
+
+
+def test_fused_consumer_after_a_scatter_step_of_the_producer():
+    """The scatter path keeps no flags of what it wrote; a consumer fed through rrm_step_from_projection, and the
+    incremental nonlinearity, must then look at everything."""
+    import torch
+    import paper_1802_09723_amd as rrm
+    cfg = S.config1(n=2, T=5)
+    l1, l2 = cfg["layers"][1], cfg["layers"][2]  # conv2 (5x5, groups 2) feeds conv3 through ReLU / shift / pool
+    rng = S.rng_for(8802)
+    A = rrm.Layer(l1["shape"], S.I8, l1["weights"], l1["bias"])
+    B = rrm.Layer(l2["shape"], S.I8, l2["weights"], l2["bias"])
+    frames = [S.draw_i8_relu(rng, l1["shape"].x_shape)]
+    for t in range(4):
+        f = frames[-1].copy()
+        f[:, 3 * t:3 * t + 4, 5:9, :] = S.draw_i8_relu(rng, (2, 4, 4, l1["shape"].c_in))
+        frames.append(f)
+    shift = oracle.calibrate_shift(oracle.dense(l1["shape"], S.I8, l1["weights"], l1["bias"], frames[0]))
+    ho = A.y_shape[1]
+    buf = torch.full((2, (ho - 3) // 2 + 1, (ho - 3) // 2 + 1, l1["shape"].c_out), -1, dtype=torch.int8, device="cuda")
+    for t, f in enumerate(frames):
+        A.set_option("path", 3 if t in (1, 3) else 0)
+        A.step(to_device(f, S.I8))
+        B.step_from_projection(A, shift, True)
+        A.relu_requant_pool_changed(buf, shift, True)
+        ya = oracle.dense(l1["shape"], S.I8, l1["weights"], l1["bias"], f)
+        x2 = oracle.relu_requant_pool(ya, shift, True)
+        assert_matches(A.y_snapshot().cpu().numpy(), ya, S.I8, f"frame {t} producer")
+        assert np.array_equal(buf.cpu().numpy(), x2), f"frame {t}: incremental nonlinearity"
+        assert_matches(B.y_snapshot().cpu().numpy(), oracle.dense(l2["shape"], S.I8, l2["weights"], l2["bias"], x2), S.I8,
+                       f"frame {t} consumer")
+    A.destroy()
+    B.destroy()
