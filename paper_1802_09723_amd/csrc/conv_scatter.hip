@@ -19,6 +19,7 @@
 // position block (output-channel splits) the one that finishes its compare last does it (arrival counter per block,
 // rearmed by that workgroup), because the others still read the old values until then.
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 #include "rrm_internal.h"
@@ -196,7 +197,9 @@ __global__ __launch_bounds__(ST) void conv_scatter_kernel(const uint4* __restric
         }
     }
 
-    // ---- the products: work items (channel block of a group, tap), dealt round robin to the wavefronts ------------
+    // ---- the products: work items (channel block of a group, tap, part of the K range of at most 8 steps).  A
+    // workgroup takes items blockIdx.y, + gridDim.y, ... and deals them to its wavefronts; a wavefront has an item's
+    // (at most 8) weight fragments in flight together, multiplies, and applies its columns.
     if (cnt > 0) {
         const int n = lane & 31, khalf = lane >> 5;
         const int ntile = (cnt + 31) >> 5;  // 1 or 2
@@ -214,11 +217,10 @@ __global__ __launch_bounds__(ST) void conv_scatter_kernel(const uint4* __restric
             ciy[t] = r / g.w;
             cix[t] = r - ciy[t] * g.w;
         }
-        const int npair_mine = (g.npair - (int)blockIdx.y + (int)gridDim.y - 1) / (int)gridDim.y;
-        const int nitems = npair_mine * g.ntaps;
-        for (int item = wave; item < nitems; item += ST / 64) {
-            const int pi = item / g.ntaps, tap = item - pi * g.ntaps;
-            const int pair = (int)blockIdx.y + pi * (int)gridDim.y;
+        const int nitems = g.npair * g.ntaps * g.nkp;
+        for (int item = (int)blockIdx.y + wave * (int)gridDim.y; item < nitems; item += (ST / 64) * (int)gridDim.y) {
+            const int pt = item / g.nkp, kp = item - pt * g.nkp;
+            const int pair = pt / g.ntaps, tap = pt - pair * g.ntaps;
             const int grp = pair / g.ncb, cb = pair - grp * g.ncb;
             const int ky = tap / g.kw, kx = tap - ky * g.kw;
             acc_t acc[2];
@@ -226,24 +228,23 @@ __global__ __launch_bounds__(ST) void conv_scatter_kernel(const uint4* __restric
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[t][r] = 0;
-            const uint4* wp = wsc + ((size_t)(pair * g.ntaps + tap) * g.nk) * 64 + lane;
+            const int k0 = kp * 8;
+            const uint4* wp = wsc + ((size_t)(pair * g.ntaps + tap) * g.nk + k0) * 64 + lane;
             const int ub = grp * g.ug;  // first unit of the group within a position
-            for (int k0 = 0; k0 < g.nk; k0 += 8) {
-                uint4 a[8];
+            uint4 a[8];
 #pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    if (k0 + k < g.nk) a[k] = wp[(size_t)(k0 + k) * 64];
+            for (int k = 0; k < 8; ++k)
+                if (k0 + k < g.nk) a[k] = wp[(size_t)k * 64];
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    if (k0 + k >= g.nk) break;
-                    const int chunk = 2 * (k0 + k) + khalf;
+            for (int k = 0; k < 8; ++k) {
+                if (k0 + k >= g.nk) break;
+                const int chunk = 2 * (k0 + k) + khalf;
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        if (t >= ntile) break;
-                        const uint4* bp = chunk < g.ug ? dl + (pl[t] * g.U + ub + chunk) : zero_unit;
-                        acc[t] = mma(a[k], *bp, acc[t]);
-                        if (TERMS == 2) acc[t] = mma(a[k], chunk < g.ug ? bp[plane] : *zero_unit, acc[t]);
-                    }
+                for (int t = 0; t < 2; ++t) {
+                    if (t >= ntile) break;
+                    const uint4* bp = chunk < g.ug ? dl + (pl[t] * g.U + ub + chunk) : zero_unit;
+                    acc[t] = mma(a[k], *bp, acc[t]);
+                    if (TERMS == 2) acc[t] = mma(a[k], chunk < g.ug ? bp[plane] : *zero_unit, acc[t]);
                 }
             }
             // column p of this tap's product belongs to the output position that sees input position p under the tap
@@ -287,6 +288,24 @@ hipError_t launch_conv_scatter(int dtype, int terms, const void* x_t, void* x_sn
     const uint4* xt = static_cast<const uint4*>(x_t);
     uint4* xs = static_cast<uint4*>(x_snap);
     const uint4* w = static_cast<const uint4*>(wsc);
+    if (lds > 64 * 1024) {
+        static std::mutex mu;  // shared by every handle and thread of the process
+        static bool granted = false;
+        std::lock_guard<std::mutex> lock(mu);
+        if (!granted) {
+            const int cap = 96 * 1024;
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_scatter_kernel<RRM_I8_I32, 1>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_scatter_kernel<RRM_BF16_F32, 1>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_scatter_kernel<RRM_BF16_F32, 2>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+            if (e != hipSuccess) return e;
+            granted = true;
+        }
+    }
     if (dtype == RRM_I8_I32)
         hipLaunchKernelGGL((conv_scatter_kernel<RRM_I8_I32, 1>), grid, dim3(ST), lds, s, xt, xs, w, y, g, stats);
     else if (t == 2)

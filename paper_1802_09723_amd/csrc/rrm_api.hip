@@ -91,7 +91,7 @@ struct rrm_layer {
     int prof_n = 0;
     bool prof_on = false;
     // options
-    int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0;
+    int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0, opt_conv_kernel = 0;
 
     ~rrm_layer() {
         void* ptrs[] = {wpack, wpos, wsc, sc_arrive, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, fresh, zero16, fc_arrive, fc_part, stats};
@@ -479,8 +479,12 @@ rrm_status setup_scatter(rrm_layer* L, const std::vector<unsigned char>& w) {
         }
     if (g.PB == 0) return RRM_OK;
     const long long nblk = (g.npos_total + g.PB - 1) / g.PB;
-    // few position blocks: split the output channels over more workgroups, up to about two per compute unit
-    g.cs = (int)std::max(1ll, std::min((long long)g.npair, (2ll * NUM_CU + nblk - 1) / nblk));
+    // Work items of a position block: (channel block, tap, part of the K range of at most 8 steps); a workgroup's four
+    // wavefronts take one item each per round.  Few position blocks: the items of a block are split over more
+    // workgroups (one round each at most), up to about two workgroups per compute unit in all.
+    g.nkp = (g.nk + 7) / 8;
+    const long long items = (long long)g.npair * g.ntaps * g.nkp;
+    g.cs = (int)std::max(1ll, std::min((items + 3) / 4, (2ll * NUM_CU + nblk - 1) / nblk));
     std::vector<unsigned char> pack((size_t)g.npair * g.ntaps * g.nk * 64 * 16, 0);
     const int per_vec = 16 / es;
     for (int pair = 0; pair < g.npair; ++pair)
@@ -499,6 +503,10 @@ rrm_status setup_scatter(rrm_layer* L, const std::vector<unsigned char>& w) {
     if ((st = dalloc((size_t)nblk * sizeof(unsigned int), (void**)&L->sc_arrive)) != RRM_OK) return st;
     g.arrive = L->sc_arrive;
     L->scat_ok = true;
+    // Automatic: layers with few positions in all (one stream of a small map).  Two dependent launches and the
+    // per-workgroup set-up of the tile kernels then cost more than the step's work; measured, the single launch wins
+    // there up to about a tenth of the positions changing, and on the smallest maps at any density.
+    L->scat_auto = g.npos_total <= 1024;
     return RRM_OK;
 }
 
@@ -600,11 +608,11 @@ int bin_cw(const rrm_layer* L) {
 }
 
 // does this step of a convolution layer take the single-launch scatter path?  ("path" = 3: always where the layer
-// is eligible; automatic: see DESIGN notes in select below)
+// is eligible; automatic, with the kernel choice left automatic too: layers with few positions, see setup_scatter)
 bool use_scatter(const rrm_layer* L) {
     if (!L->scat_ok || L->dtype == RRM_BIN_I32) return false;
     if (L->opt_path == 3) return true;
-    return L->opt_path == 0 && L->scat_auto;
+    return L->opt_path == 0 && L->opt_conv_kernel == 0 && L->scat_auto;
 }
 
 int fc_splits(const rrm_layer* L) { return L->opt_fc_splits > 0 ? L->opt_fc_splits : L->fc_nsplit; }
@@ -965,6 +973,7 @@ rrm_status rrm_set_option(rrm_layer* L, const char* key, long value) {
     } else if (k == "conv_kernel") {
         if (L->shape.kind != RRM_CONV || L->dtype == RRM_BIN_I32 || value < 0 || value > 2)
             return fail(RRM_ERR_OPTION, "conv_kernel is 0, 1 or 2, for int8 / bf16 convolution layers");
+        L->opt_conv_kernel = (int)value;
         return select_conv_kernel(L, (int)value);
     } else if (k == "profile") {
         if (value != 0 && value != 1) return fail(RRM_ERR_OPTION, "profile must be 0 or 1");

@@ -135,11 +135,12 @@ struct ScatGeom {
     int U;               // 16-byte units per input position (all groups)
     int ug;              // units per group
     int nk;              // K steps (2 units each) per group: ceil(ug / 2)
+    int nkp;             // parts of at most 8 K steps: ceil(nk / 8)
     int ncb;             // 32-channel output blocks per group
     int npair;           // groups * ncb: (group, channel block) pairs
     int ntaps;           // kh * kw
     int PB;              // input positions per block (at most 64)
-    int cs;              // output-channel splits: workgroups per position block
+    int cs;              // work-item splits: workgroups per position block
     long long npos_total;  // n * h * w
     float eps;           // bf16: truncation threshold of the difference (0 = exact)
     unsigned int* arrive;       // one word per position block (used when cs > 1; rearmed by the kernel)
