@@ -127,6 +127,9 @@ class Stack:
         one pass, only where that projection changed); the last layer's f, and every f with --no-fuse or on
         the dense path, is the separate kernel (bufs[i] holds the previous frame's result)."""
         last = len(self.layers) - 1
+        if self.fuse and self.path != 2:  # the library's stack call: Algorithm 1's loop over the layers
+            self.rrm.stack_step(self.layers, self.shifts, [m[4] for m in self.meta], x, self.bufs[last])
+            return
         for i, L in enumerate(self.layers):
             n, ho, wo, c, pool = self.meta[i]
             if i > 0 and self.fuse and self.path != 2:

@@ -150,9 +150,10 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
  *                 re-writing most of it); 1..100, 100 = never; defaults 62 (int8) / 40 (bf16) for the window-tile
  *                 kernel, which decides per launch, and 90 / 50 for the position-gather kernel, which decides per
  *                 work unit
- *   "conv_kernel" INT8 / BF16 conv: 0 = automatic, 1 = window-tile kernel (4x4 output blocks with their input windows
- *                 gathered into LDS; any stride), 2 = position-gather kernel (single active output positions as
- *                 columns of the product; stride 1 and channel runs of 16-byte multiples).  Set it before the
+ *   "conv_kernel" INT8 / BF16 conv: 0 = automatic (the window-tile kernel), 1 = window-tile kernel (4x4 output
+ *                 blocks with their input windows gathered into LDS; any stride), 2 = position-gather kernel
+ *                 (single active output positions as columns of the product; stride 1 and channel runs of
+ *                 16-byte multiples; faster where every stream changes sparsely and alike).  Set it before the
  *                 first rrm_step, or follow it with rrm_reset: the two kernels keep their change flags differently.
  *   "bin_cout_per_wave"  binary conv: output channels per wavefront, 8 / 16 (0 = heuristic)
  *   "profile"     1 = bracket every kernel of the following rrm_step calls with HIP events on the
@@ -177,6 +178,25 @@ rrm_status rrm_get_stats(rrm_layer* layer, rrm_stats* out);
  * Errors: RRM_ERR_NULL, RRM_ERR_DTYPE, RRM_ERR_SHAPE, RRM_ERR_STATE, RRM_ERR_ALIGN, RRM_ERR_HIP. */
 rrm_status rrm_step_from_projection(rrm_layer* layer, rrm_layer* producer, int shift, int pool, void* y_out,
                                     void* hip_stream);
+
+/* One frame through a stack of INT8 convolution layers: Algorithm 1's inner loop over the layers, with the
+ * non-linear map f between them (ReLU, right shift, clamp to 127, optional 3x3 / 2 max pooling; see
+ * rrm_step_from_projection) fused into the next layer's difference kernel, so that no layer input but the frame is
+ * ever written to memory:
+ *     layer 0                      rrm_step(entries[0].layer, x_t)
+ *     layer i > 0                  rrm_step_from_projection(entries[i].layer, entries[i-1].layer,
+ *                                                           entries[i-1].shift, entries[i-1].pool)
+ *     f_out (may be NULL)          f of the last layer's stored projection, recomputed only where its last step
+ *                                  wrote (rrm_aux_relu_requant_pool_changed_i8 with entries[n-1].shift / .pool);
+ *                                  device, int8, must hold the previous call's result
+ * The shape conditions are those of the calls above.  Everything is enqueued on hip_stream; nothing synchronises.
+ * Errors: RRM_ERR_NULL, or the first error of a constituent call. */
+typedef struct {
+    rrm_layer* layer;
+    int shift; /* right shift of f applied to this layer's projection */
+    int pool;  /* non-zero: 3x3 / stride-2 max pooling in f */
+} rrm_stack_entry;
+rrm_status rrm_stack_step(const rrm_stack_entry* entries, int n_layers, const void* x_t, void* f_out, void* hip_stream);
 
 /* Truncation threshold of a BF16 layer (Sec. 3.4, "Improving sparsity": small values of the difference are
  * truncated to zero to gain sparsity; the experiments use 1e-2).  An entry with |x_t - x_snap| < epsilon

@@ -41,6 +41,11 @@ class Stats(ctypes.Structure):
         return {k: (float if k == "truncated_sumsq" else int)(getattr(self, k)) for k, _ in self._fields_}
 
 
+class StackEntry(ctypes.Structure):
+    """``rrm_stack_entry``"""
+    _fields_ = [("layer", ctypes.c_void_p), ("shift", ctypes.c_int), ("pool", ctypes.c_int)]
+
+
 class RRMError(RuntimeError):
     def __init__(self, status: int, msg: str):
         super().__init__(f"rrm status {status}: {msg}")
@@ -84,9 +89,10 @@ def lib():
         L.rrm_aux_relu_requant_pool_changed_i8.argtypes = [P, P, I, I, P]
         L.rrm_set_threshold.argtypes = [P, ctypes.c_float]
         L.rrm_step_from_projection.argtypes = [P, P, I, I, P, P]
+        L.rrm_stack_step.argtypes = [ctypes.POINTER(StackEntry), I, P, P, P]
         for f in ("rrm_layer_create", "rrm_step", "rrm_dense", "rrm_dense_noalloc", "rrm_reset", "rrm_snapshot", "rrm_read_snapshot", "rrm_set_option",
                   "rrm_get_stats", "rrm_get_kernel_times", "rrm_aux_relu_requant_pool_i8",
-                  "rrm_aux_relu_requant_pool_changed_i8", "rrm_set_threshold", "rrm_step_from_projection"):
+                  "rrm_aux_relu_requant_pool_changed_i8", "rrm_set_threshold", "rrm_step_from_projection", "rrm_stack_step"):
             getattr(L, f).restype = I
         _lib = L
     return _lib
@@ -231,6 +237,12 @@ class Layer:
         _check(lib().rrm_read_snapshot(self._h, out.data_ptr(), None, _stream_ptr(None)))
         torch.cuda.synchronize()
         return out
+
+
+def stack_step(layers, shifts, pools, x_t, f_out=None, stream=None) -> None:
+    """``rrm_stack_step``: one frame through a stack of int8 conv layers with the fused nonlinearity."""
+    arr = (StackEntry * len(layers))(*[StackEntry(L._h, int(s), int(bool(p))) for L, s, p in zip(layers, shifts, pools)])
+    _check(lib().rrm_stack_step(arr, len(layers), _dptr(x_t), _dptr(f_out), _stream_ptr(stream)))
 
 
 def relu_requant_pool_i8(y, out, n, h, w, c, shift, pool, stream=None) -> None:

@@ -513,12 +513,11 @@ rrm_status setup_scatter(rrm_layer* L, const std::vector<unsigned char>& w) {
 // choose the convolution kernel of an int8 / bf16 layer: 0 = automatic, 1 = window-tile, 2 = position-gather
 rrm_status select_conv_kernel(rrm_layer* L, int which) {
     if (which == 2 && !L->pos_ok) return fail(RRM_ERR_OPTION, "the position-gather kernel needs stride 1 and 16-byte channel runs");
-    // Automatic: the position-gather kernel where it measured faster, int8 layers on small maps with enough streams
-    // to give every compute unit several work units; elsewhere (large maps, whose 4x4 blocks waste little; bf16,
-    // whose second difference term doubles its staging; few streams, where its per-unit set-up is not amortised)
-    // the window-tile kernel.
-    const bool pos_pays = L->pos_ok && L->dtype == RRM_I8_I32 && L->pg.ho * L->pg.wo <= 256 && L->pg.total_units >= 2 * NUM_CU;
-    L->use_pos = which == 2 || (which == 0 && pos_pays);
+    // Automatic is the window-tile kernel.  The position-gather kernel measured 8-10 % faster on small int8 maps
+    // when every stream changes in the same scattered way, and 15-25 % slower on the video recipe, whose streams
+    // differ widely (its fixed set-up per (stream, band) unit is paid by the static streams too, and once a
+    // third of the positions change the gather saves little over whole windows): it is the caller's choice.
+    L->use_pos = which == 2;
     L->tshift = L->use_pos ? 0 : 2;
     ScanGeom& sg = L->sg;
     sg.sty = L->use_pos ? 0 : L->cg.sty;  // (no sub-tile flags for the position-gather kernel: it reads the bitmap)
@@ -881,6 +880,20 @@ rrm_status rrm_step_from_projection(rrm_layer* L, rrm_layer* P, int shift, int p
     ++L->steps;
     if (y_out) RRM_HIP(launch_copy(y_out, L->y_snap, L->y_bytes, st));
     return RRM_OK;
+}
+
+rrm_status rrm_stack_step(const rrm_stack_entry* entries, int n_layers, const void* x_t, void* f_out, void* hip_stream) {
+    if (!entries || n_layers < 1) return fail(RRM_ERR_NULL, "entries is NULL or empty");
+    for (int i = 0; i < n_layers; ++i)
+        if (!entries[i].layer) return fail(RRM_ERR_NULL, "a stack entry has no layer");
+    rrm_status st = rrm_step(entries[0].layer, x_t, nullptr, hip_stream);
+    for (int i = 1; i < n_layers && st == RRM_OK; ++i)
+        st = rrm_step_from_projection(entries[i].layer, entries[i - 1].layer, entries[i - 1].shift, entries[i - 1].pool, nullptr,
+                                      hip_stream);
+    if (st == RRM_OK && f_out)
+        st = rrm_aux_relu_requant_pool_changed_i8(entries[n_layers - 1].layer, f_out, entries[n_layers - 1].shift,
+                                                  entries[n_layers - 1].pool, hip_stream);
+    return st;
 }
 
 rrm_status rrm_dense(rrm_layer* L, const void* x, void* y, void* hip_stream) {

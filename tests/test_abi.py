@@ -23,7 +23,8 @@ def test_library_exports_every_declared_symbol():
     names = _declared()
     assert {"rrm_layer_create", "rrm_step", "rrm_dense", "rrm_reset", "rrm_snapshot", "rrm_read_snapshot",
             "rrm_set_option", "rrm_get_stats", "rrm_layer_destroy", "rrm_status_string", "rrm_last_error",
-            "rrm_aux_relu_requant_pool_i8", "rrm_aux_relu_requant_pool_changed_i8", "rrm_set_threshold", "rrm_step_from_projection"} <= set(names)
+            "rrm_aux_relu_requant_pool_i8", "rrm_aux_relu_requant_pool_changed_i8", "rrm_set_threshold", "rrm_step_from_projection",
+            "rrm_stack_step", "rrm_dense_noalloc"} <= set(names)
     L = ctypes.CDLL(rrm.lib_path())
     for n in names:
         assert hasattr(L, n), f"{n} is declared in rrm.h but not exported"

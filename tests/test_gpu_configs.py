@@ -201,3 +201,33 @@ def test_fused_step_after_reset_compares_everything():
         assert_matches(B.y_snapshot().cpu().numpy(), want, S.I8, f"frame {t}")
     A.destroy()
     B.destroy()
+
+
+def test_config1_stack_call():
+    """rrm_stack_step (Algorithm 1's loop over the layers in one call, f fused into the next layer's difference
+    kernel) against the oracle: every layer's stored projection and f of the last one, on every frame."""
+    import torch
+    import paper_1802_09723_amd as rrm
+    n, T = 2, 5
+    cfg = S.config1(n=n, T=T)
+    layers = [rrm.Layer(l["shape"], S.I8, l["weights"], l["bias"]) for l in cfg["layers"]]
+    pools = [l["pool"] for l in cfg["layers"]]
+    shifts = None
+    last = cfg["layers"][-1]
+    ho = layers[-1].y_shape[1]
+    po = (ho - 3) // 2 + 1 if last["pool"] else ho
+    f_out = torch.full((n, po, po, last["shape"].c_out), -1, dtype=torch.int8, device="cuda")
+    for t, frame in enumerate(cfg["frames"]):
+        ys, x = [], frame
+        for i, l in enumerate(cfg["layers"]):
+            y = oracle.dense(l["shape"], S.I8, l["weights"], l["bias"], x)
+            ys.append(y)
+            if shifts is None or len(shifts) <= i:
+                shifts = (shifts or []) + [oracle.calibrate_shift(y)]
+            x = oracle.relu_requant_pool(y, shifts[i], l["pool"])
+        rrm.stack_step(layers, shifts, pools, to_device(frame, S.I8), f_out)
+        for i, (l, L) in enumerate(zip(cfg["layers"], layers)):
+            assert_matches(L.y_snapshot().cpu().numpy(), ys[i], S.I8, f"frame {t} {l['name']}")
+        assert np.array_equal(f_out.cpu().numpy(), x), f"frame {t}: f of the last layer"
+    for L in layers:
+        L.destroy()
