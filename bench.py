@@ -2,18 +2,24 @@
 """Benchmark of the MI355X Recurrent Residual Module library.
 
 Default run: the headline workload, an AlexNet-shaped int8 conv stack -- five conv layers with
-ReLU / requantisation / max-pool between them -- over synthetic 32-frame moving-patch sequences for `--streams` independent video streams (chunks
-processed in parallel, Sec. 3.2 of the paper).  One "step" is one frame of every stream through
-the whole stack: per layer one rrm_step (delta + change map, then the tile kernel on changed
-tiles) followed by the harness nonlinearity.  Every 32nd step starts a new sequence, i.e. a frame
-in which everything changes.  Inputs are resident in HBM before the timed region.  Prints ONE
-JSON line; everything else goes to stderr.
+ReLU / requantisation / max-pool between them -- over synthetic 32-frame moving-patch sequences for `--streams`
+independent video streams (chunks processed in parallel, Sec. 3.2 of the paper).  One "step" is one frame of
+every stream through the whole stack (rrm_stack_step: per layer the difference and change map, then the
+convolution of the changed part, with the nonlinearity fused into the next layer's difference kernel).  The
+steps walk cyclically through two different 32-frame sequences (64 frames); steps W .. W+K-1 are timed, so a
+sequence start (a frame in which everything changes) lies in the timed region whenever that range crosses a
+multiple of 32; the JSON line says how many did.  Inputs are resident in HBM before the timed region.  After
+the timed loops, outside them, sampled streams of every layer's stored projection are compared with the CPU
+oracle ("verified").  Then every layer of the other configurations (single int8 conv, ResNet-shaped bf16
+convs, FC sparse-delta, binary conv) is timed at 5 / 10 / 25 % change, at one stream and at `--config-streams`
+streams ("configs"), the device's sustained copy and matrix-core rates are measured ("peaks"), and the CPU
+oracle is timed on a bounded sample.  Prints ONE JSON line; everything else goes to stderr.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--streams S] [--sweep]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--streams S] [--no-configs] [--sweep] [--lean | --lean-case C]
 
---sweep additionally times every layer of configs 2-4 (ResNet bf16, FC sparse-delta, binary) over
-their density grids, at one stream (the configs' batch 1: launch-latency bound) and at --sweep-streams
-streams (throughput), and writes sweep.jsonl into the output folder plus a table on stderr.
+--sweep times the full density grids of configs 2-4 and writes sweep.jsonl into the output folder plus a
+table on stderr.  --lean runs only eager steps of the headline stack (delta path, then dense path) after the
+calibration copy: the run a profiler wraps.
 """
 from __future__ import annotations
 
@@ -172,6 +178,25 @@ class Stack:
             self.run_steps(W, K, use_graph)
         return t.ms / K
 
+    def verify(self, frame_index: int, streams):
+        """Compare, for the given streams, every layer's stored projection with the CPU oracle's dense
+        projection of frame `frame_index` through the stack (Sec. 3.2: the recurrence yields what a normal
+        layer computes from the frame itself).  Returns the number of differing entries (int8 stack: exact)."""
+        import oracle
+        S = self.S
+        self.torch.cuda.synchronize()
+        got = [L.y_snapshot() for L in self.layers]
+        bad = 0
+        for b in streams:
+            x = np.ascontiguousarray(self.host_frames[frame_index][b:b + 1])
+            for i, l in enumerate(self.cfg["layers"]):
+                y = oracle.dense(l["shape"].with_n(1), S.I8, l["weights"], l["bias"], x)
+                bad += int(np.count_nonzero(got[i][b:b + 1].cpu().numpy() != y))
+                x = oracle.relu_requant_pool(y, self.shifts[i], l["pool"])
+            # f of the last layer (the stack call's output buffer)
+            bad += int(np.count_nonzero(self.bufs[-1][b:b + 1].cpu().numpy() != x))
+        return bad
+
     def profile_layers(self, K: int, W: int):
         """Eager pass with every kernel of rrm_step bracketed by HIP events (the library's
         "profile" option): per-layer average scan / compute kernel time and change statistics."""
@@ -220,18 +245,51 @@ def active_positions(shape, stats_row, tiles_per_step):
 
 
 COPY_BYTES = 64 << 20
+_CAL = []  # the calibration copy's two buffers
 
 
 def calibration_copy(reps: int = 4):
-    """A plain copy of known size (COPY_BYTES read, COPY_BYTES written per launch, one torch
-    elementwise kernel), so that a rocprofv3 --pmc run of this script holds the reading of
-    FETCH_SIZE / WRITE_SIZE for a known number of HBM bytes next to the library's kernels."""
+    """A plain copy of known size (COPY_BYTES read, COPY_BYTES written per launch: the library's copy probe), so
+    that a rocprofv3 --pmc run of this script holds the reading of FETCH_SIZE / WRITE_SIZE for a known number
+    of HBM bytes next to the library's kernels.  In the --lean modes it also marks, in the list of dispatches,
+    where the counted steps begin and end."""
     import torch
-    src = torch.arange(COPY_BYTES // 4, dtype=torch.int32, device="cuda")
-    dst = torch.empty_like(src)
+    import paper_1802_09723_amd as rrm
+    if not _CAL:
+        _CAL.append(torch.arange(COPY_BYTES // 4, dtype=torch.int32, device="cuda"))
+        _CAL.append(torch.empty_like(_CAL[0]))
+    src, dst = _CAL
     for _ in range(reps):
-        torch.mul(src, 1, out=dst)
+        rrm.probe_copy(dst, src, COPY_BYTES)
     torch.cuda.synchronize()
+
+
+def measure_peaks():
+    """What this device sustains on the library's two probes: a streaming copy of 1 GiB (bytes read + written
+    per second) and a register-resident matrix-core loop on every compute unit (int8 and bf16)."""
+    import torch
+    import paper_1802_09723_amd as rrm
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    src.zero_()
+    rrm.probe_copy(dst, src, nbytes)
+    with Timer() as t:
+        for _ in range(5):
+            rrm.probe_copy(dst, src, nbytes)
+    copy = 2 * nbytes * 5 / (t.ms * 1e-3)
+    del src, dst
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    out = {"copy_GBps": round(copy / 1e9, 1), "copy_frac_of_8TBps": round(copy / HBM_PEAK, 3)}
+    wgs, iters = 256 * 8, 4096
+    for name, dt, per in (("mfma_i8_TOPs", rrm.I8, 65536), ("mfma_bf16_TFLOPs", rrm.BF16, 32768)):
+        rrm.probe_mfma(dt, sink, 64, wgs)
+        with Timer() as t:
+            rrm.probe_mfma(dt, sink, iters, wgs)
+        rate = wgs * 4 * 4 * iters * per / (t.ms * 1e-3)
+        out[name] = round(rate / 1e12, 1)
+        out[name.split("_T")[0] + "_frac_of_published"] = round(rate / MFMA_PEAK[0 if dt == rrm.I8 else 1], 3)
+    return out
 
 
 def measured_traffic(kernel: str, streams: int):
@@ -270,9 +328,23 @@ def run_stack(args):
     # ---- headline: K steps of the delta path (graph replay unless --no-graph) --------------------
     st.set_path(0)
     ms_delta = st.timed(args.steps, args.warmup, not args.no_graph)
+    # ---- outside the timed region: what the timed steps left behind, against the CPU oracle -----------
+    nf, last = len(st.frames), args.warmup + args.steps - 1
+    sample = sorted({0, B // 2, B - 1})
+    verified = {"streams": sample, "what": "every layer's stored projection and f of the last layer, element by element, "
+                "against the CPU oracle's dense projection of the same frame"}
+    verified["after_timed_loop"] = st.verify(last % nf, sample) == 0
+    # ... and on across the boundary between the two sequences, to the second frame of the next sequence
+    more = (st.T + 1 - last) % st.T or st.T
+    st.run_steps(last + 1, more, not args.no_graph)
+    verified["after_sequence_boundary"] = st.verify((last + more) % nf, sample) == 0
+    starts = sum(1 for k in range(args.warmup, args.warmup + args.steps) if k % st.T == 0)
     # ---- same steps with every layer recomputed densely (the library's own dense path) -----------
     st.set_path(2)
     ms_dense = st.timed(args.steps, args.warmup, not args.no_graph)
+    verified["dense_path"] = st.verify(last % nf, sample) == 0
+    verified["ok"] = bool(verified["after_timed_loop"] and verified["after_sequence_boundary"] and verified["dense_path"])
+    log("[verified]", json.dumps(verified))
     st.set_path(0)
     # ---- per-kernel times and change statistics (eager, event-bracketed) -------------------------
     prof = st.profile_layers(args.steps, args.warmup)
@@ -343,7 +415,9 @@ def run_stack(args):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_delta, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "cfg1_alexnet_conv_stack_int8", "streams": B, "frames_per_sequence": st.T,
-                   "graph_replay": not args.no_graph, "fused_f": not args.no_fuse},
+                   "graph_replay": not args.no_graph, "fused_f": not args.no_fuse,
+                   "sequence_starts_in_timed_region": starts},
+        "verified": verified,
         "dense_equiv_gops": round(2 * total_macs / (ms_delta * 1e-3) * 1e-9, 1),
         "ms_per_step_dense_path": round(ms_dense, 5),
         "speedup_vs_dense_path": round(ms_dense / ms_delta, 3),
@@ -373,41 +447,81 @@ def launch_floor(st) -> float:
     return t.ms * 1e3 / 1000
 
 
-def cpu_baseline_stack(st, budget_s: float = 12.0):
+def cpu_baseline_stack(st, budget_s: float = 8.0):
     """The CPU oracle (dense projection of every layer, its own nonlinearity in between) on this host's
-    cores: whole 32-frame sequences, one stream after the other, until about `budget_s` seconds of work."""
+    cores: whole 32-frame sequences, one stream after the other, until about `budget_s` seconds of work.
+    Beside it, on shorter samples: the same on one thread, and the oracle's own recurrence (Algorithm 1 on the
+    CPU: work proportional to the changed inputs) on all threads and on one."""
     import oracle
     S = st.S
     cfg = st.cfg
-    frames_done, streams_done, t0 = 0, 0, time.perf_counter()
     layers1 = [(l["shape"].with_n(1), l) for l in cfg["layers"]]
-    while streams_done < st.B and (time.perf_counter() - t0) < budget_s:
+    nthreads = oracle.threads()
+
+    def dense_frames(budget, max_streams):
+        frames_done, streams_done, t0 = 0, 0, time.perf_counter()
+        while streams_done < max_streams and (time.perf_counter() - t0) < budget:
+            for f in range(st.T):
+                x = np.ascontiguousarray(st.host_frames[f][streams_done:streams_done + 1])
+                for i, (sh, l) in enumerate(layers1):
+                    y = oracle.dense(sh, S.I8, l["weights"], l["bias"], x)
+                    x = oracle.relu_requant_pool(y, st.shifts[i], l["pool"])
+                frames_done += 1
+                if (time.perf_counter() - t0) > 2 * budget:
+                    break
+            streams_done += 1
+        return frames_done, streams_done, time.perf_counter() - t0
+
+    def recurrence_frames(budget):
+        states = [oracle.State(sh, S.I8, l["weights"], l["bias"]) for sh, l in layers1]
+        frames_done, t0, t_first = 0, time.perf_counter(), 0.0
         for f in range(st.T):
-            x = np.ascontiguousarray(st.host_frames[f][streams_done:streams_done + 1])
+            x = np.ascontiguousarray(st.host_frames[f][0:1])
             for i, (sh, l) in enumerate(layers1):
-                y = oracle.dense(sh, S.I8, l["weights"], l["bias"], x)
-                x = oracle.relu_requant_pool(y, st.shifts[i], l["pool"])
-            frames_done += 1
-        streams_done += 1
-    dt = time.perf_counter() - t0
-    return {"value": round(frames_done / dt, 3), "unit": "frames/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"{frames_done} frames ({streams_done} streams x {st.T} frames) through the 5-layer stack "
-                      f"(dense oracle per layer), {dt:.1f} s"}
+                x = oracle.relu_requant_pool(states[i].step(x), st.shifts[i], l["pool"])
+            if f == 0:
+                t_first = time.perf_counter() - t0  # (the first frame changes everything: not a delta step)
+            else:
+                frames_done += 1
+            if (time.perf_counter() - t0) > budget and frames_done >= 2:
+                break
+        return frames_done, time.perf_counter() - t0 - t_first
+
+    frames_done, streams_done, dt = dense_frames(budget_s, st.B)
+    out = {"value": round(frames_done / dt, 3), "unit": "frames/s", "cores": nthreads, "kind": "oracle",
+           "sample": f"{frames_done} frames ({streams_done} streams x {st.T} frames) through the 5-layer stack "
+                     f"(dense oracle per layer), {dt:.1f} s"}
+    k, dt = recurrence_frames(4.0)
+    out["oracle_step"] = {"value": round(k / dt, 3), "unit": "frames/s", "cores": nthreads,
+                          "sample": f"{k} delta frames of stream 0 through the oracle's recurrence, {dt:.1f} s"}
+    oracle.set_threads(1)
+    try:
+        k, _, dt = dense_frames(2.0, 1)
+        out["single_thread"] = {"value": round(k / dt, 3), "unit": "frames/s", "cores": 1,
+                                "sample": f"{k} frames of stream 0, dense oracle, {dt:.1f} s"}
+        k, dt = recurrence_frames(3.0)
+        out["oracle_step_single_thread"] = {"value": round(k / dt, 3), "unit": "frames/s", "cores": 1,
+                                            "sample": f"{k} delta frames of stream 0, {dt:.1f} s"}
+    finally:
+        oracle.set_threads(nthreads)
+    return out
 
 
 # ------------------------------------------------------------------------------------------------
-# sweep over configs 2-4 (one layer at a time)
+# configs 0, 2, 3, 4 (one layer at a time)
 # ------------------------------------------------------------------------------------------------
-def time_layer(seq, to_dev, weights, reps: int = 5, eps: float = 0.0):
+def time_layer(seq, to_dev, weights, reps: int = 5, eps: float = 0.0, drift: bool = False, cold: bool = False):
     """Per-step wall time (graph of one whole sequence, delta and dense path) and event-bracketed
-    kernel times of one layer over its frame sequence.  eps: truncation threshold (bf16 layers)."""
+    kernel times of one layer over its frame sequence.  eps: truncation threshold (bf16 layers).
+    drift (bf16 conv): after the whole sequence on the delta path, max |stored projection - dense projection of
+    the last frame| / max |dense projection|, with the difference carried as two bf16 terms and as one.
+    cold: the delta and the dense step again with the caches flushed before each step (a 1 GiB copy)."""
     import torch
     import paper_1802_09723_amd as rrm
     L = rrm.Layer(seq.shape, seq.dtype, weights, seq.bias)
     if eps:
         L.set_threshold(eps)
     xs = [to_dev(f) for f in seq.frames]
-    T = len(xs)
     res = {}
     for tag, path in (("delta", 0), ("dense", 2)):
         L.set_option("path", path)
@@ -439,14 +553,43 @@ def time_layer(seq, to_dev, weights, reps: int = 5, eps: float = 0.0):
         if path == 0:
             res["stats"] = {k: (s1[k] - s0[k]) / max(n, 1)
                             for k in ("changed_elems", "changed_units", "active_tiles", "total_tiles", "truncated_elems")}
+            res["stats"]["tile_positions"] = s1["tile_positions"]
+        if cold:
+            big_a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+            big_b = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in order[:12]]
+            for x, (e0, e1) in zip(order, ev):
+                rrm.probe_copy(big_b, big_a, 1 << 30)
+                e0.record()
+                L.step(x)
+                e1.record()
+            torch.cuda.synchronize()
+            res[f"{tag}_cold_us"] = float(np.median([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e3
+            del big_a, big_b
+    if drift:
+        y_ref = torch.empty(L.y_shape, dtype=torch.float32, device="cuda")
+        L.dense(xs[-1], y_ref)
+        for terms in (2, 1):
+            L.set_option("path", 1)  # (never the in-kernel switch to recomputation, which would hide the drift)
+            L.set_option("bf16_terms", terms)
+            L.reset()
+            for x in xs:
+                L.step(x)
+            y = L.y_snapshot()
+            res[f"drift_terms{terms}"] = float((y - y_ref).abs().max() / y_ref.abs().max())
+        L.set_option("bf16_terms", 2)
     L.destroy()
     return res
 
 
-def run_sweep(args):
+CONFIG_GRID = {2: (0.05, 0.10, 0.25), 3: (0.05, 0.10, 0.25), 4: (0.05, 0.10, 0.20)}
+
+
+def config_rows(stream_counts, full: bool):
+    """Every layer of configurations 0, 2, 3, 4 over a density grid (full: the configurations' whole grids and
+    the truncation-threshold cases; else 5 / 10 / 25 %), at each of `stream_counts` streams."""
     import torch
     import rrm_synth as S
-    from paper_1802_09723_amd import binding  # noqa: F401
     rows = []
 
     def dev_i8(f):
@@ -458,112 +601,217 @@ def run_sweep(args):
     def dev_bin(f):
         return torch.from_numpy(S.pack_pm1(f).view(np.int32)).cuda()
 
-    for ns in sorted({1, max(1, args.sweep_streams)}):
+    def conv_row(config, seq, r, ns, esize, terms, peak, sfx, extra=None):
+        sh, stt = seq.shape, r["stats"]
+        pos = active_positions(sh, stt, stt["active_tiles"])
+        scan_b, tile_b = conv_alg_bytes(sh, esize, stt["changed_units"], pos, terms=terms)
+        rho_elem = stt["changed_elems"] / (sh.n * sh.h * sh.w * sh.c_in)
+        ops = 2 * rho_elem * macs(sh)
+        kt = r["delta_scan_us"] + r["delta_compute_us"]
+        t_hbm, t_mfma = (scan_b + tile_b) / HBM_PEAK * 1e6, ops / peak * 1e6
+        roof = max(t_hbm, t_mfma)
+        row = {"config": config, "case": seq.name + sfx, "streams": ns, "rho_elem": rho_elem,
+               "rho_tile": stt["active_tiles"] / max(stt["total_tiles"], 1),
+               "step_us": r["delta_us"], "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"],
+               "compute_us": r["delta_compute_us"], "dense_kernel_us": r["dense_compute_us"],
+               "frames_per_s": ns * 1e6 / r["delta_us"], "dense_equiv_gops": 2 * macs(sh) / r["delta_us"] * 1e-3,
+               "speedup_vs_dense": r["dense_us"] / r["delta_us"], "alg_bytes": scan_b + tile_b, "roof_us": roof,
+               "roof_bound": "hbm" if t_hbm >= t_mfma else "mfma",
+               "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]}
+        for k in ("drift_terms1", "drift_terms2"):
+            if k in r:
+                row[k] = r[k]
+        row.update(extra or {})
+        rows.append(row)
+        log("[config]", json.dumps(row))
+
+    for ns in stream_counts:
         # many streams: shorter sequences keep the synthetic data small; one stream: the configs' lengths
         Tc, Tf, Tb = (16, 64, 32) if ns == 1 else (6, 8, 6)
         sfx = "" if ns == 1 else f"_s{ns}"
+        # config 0: one small int8 conv
+        seq = S.config0(n=ns, T=8)
+        conv_row(0, seq, time_layer(seq, dev_i8, seq.weights), ns, 1, 1, MFMA_PEAK[0], sfx)
         # config 2: ResNet-18-shaped bf16 3x3 convs
         for layer, hw, c in S.RESNET_LAYERS:
-            for frac in S.RESNET_DENSITIES:
+            for frac in (S.RESNET_DENSITIES if full else CONFIG_GRID[2]):
                 seq = S.config2(layer, frac, n=ns, T=Tc)
-                r = time_layer(seq, dev_bf16, seq.weights)
-                sh, stt = seq.shape, r["stats"]
-                scan_b, tile_b = conv_alg_bytes(sh, 2, stt["changed_units"], stt["active_tiles"], terms=2)
-                rho_elem = stt["changed_elems"] / (ns * hw * hw * c)
-                ops = 2 * rho_elem * macs(sh)
-                kt = r["delta_scan_us"] + r["delta_compute_us"]
-                roof = max((scan_b + tile_b) / HBM_PEAK, ops / MFMA_PEAK[1]) * 1e6
-                rows.append({"config": 2, "case": seq.name + sfx, "streams": ns, "rho_elem": rho_elem,
-                             "rho_tile": stt["active_tiles"] / max(stt["total_tiles"], 1),
-                             "step_us": r["delta_us"], "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"],
-                             "compute_us": r["delta_compute_us"], "dense_kernel_us": r["dense_compute_us"],
-                             "frames_per_s": ns * 1e6 / r["delta_us"], "dense_equiv_gops": 2 * macs(sh) / r["delta_us"] * 1e-3,
-                             "speedup_vs_dense": r["dense_us"] / r["delta_us"], "alg_bytes": scan_b + tile_b, "roof_us": roof,
-                             "roof_bound": "hbm" if (scan_b + tile_b) / HBM_PEAK >= ops / MFMA_PEAK[1] else "mfma",
-                             "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]})
-                log("[sweep]", json.dumps(rows[-1]))
+                conv_row(2, seq, time_layer(seq, dev_bf16, seq.weights, drift=(ns == 1)), ns, 2, 2, MFMA_PEAK[1], sfx)
         # The truncation threshold (Sec. 3.4, "Improving sparsity"; the paper's experiments use 1e-2): the same
         # block-redraw sequences with a little noise on every entry, as a camera would add; without a
         # threshold every entry changes, with it the noise is truncated.
-        if ns > 1:
+        if full and ns > 1:
             for layer, hw, c in S.RESNET_LAYERS[:2]:
                 base = S.config2(layer, 0.05, n=ns, T=Tc)
                 rng = S.rng_for(S.seed_for(2, 900) + hw)
                 noisy = [base.frames[0]] + [
                     S.f32_to_bf16_bits(np.maximum(S.bf16_bits_to_f32(f) + rng.normal(0, 0.0015, size=f.shape).astype(np.float32), 0))
                     for f in base.frames[1:]]
-                seq = S.Sequence_(base.shape, base.dtype, base.weights, base.bias, noisy, base.name)
                 for eps in (0.0, 1e-2):
+                    seq = S.Sequence_(base.shape, base.dtype, base.weights, base.bias, noisy, f"{base.name}_noise_eps{eps:g}")
                     r = time_layer(seq, dev_bf16, seq.weights, eps=eps)
-                    sh, stt = seq.shape, r["stats"]
-                    scan_b, tile_b = conv_alg_bytes(sh, 2, stt["changed_units"], stt["active_tiles"], terms=2)
-                    rho_elem = stt["changed_elems"] / (ns * hw * hw * c)
-                    ops = 2 * rho_elem * macs(sh)
-                    kt = r["delta_scan_us"] + r["delta_compute_us"]
-                    roof = max((scan_b + tile_b) / HBM_PEAK, ops / MFMA_PEAK[1]) * 1e6
-                    rows.append({"config": 2, "case": f"{seq.name}_noise_eps{eps:g}{sfx}", "streams": ns, "rho_elem": rho_elem,
-                                 "rho_tile": stt["active_tiles"] / max(stt["total_tiles"], 1), "epsilon": eps,
-                                 "truncated_frac": stt["truncated_elems"] / (ns * hw * hw * c),
-                                 "step_us": r["delta_us"], "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"],
-                                 "compute_us": r["delta_compute_us"], "dense_kernel_us": r["dense_compute_us"],
-                                 "frames_per_s": ns * 1e6 / r["delta_us"], "dense_equiv_gops": 2 * macs(sh) / r["delta_us"] * 1e-3,
-                                 "speedup_vs_dense": r["dense_us"] / r["delta_us"], "alg_bytes": scan_b + tile_b, "roof_us": roof,
-                                 "roof_bound": "hbm" if (scan_b + tile_b) / HBM_PEAK >= ops / MFMA_PEAK[1] else "mfma",
-                                 "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]})
-                    log("[sweep]", json.dumps(rows[-1]))
+                    conv_row(2, seq, r, ns, 2, 2, MFMA_PEAK[1], sfx,
+                             {"epsilon": eps, "truncated_frac": r["stats"]["truncated_elems"] / (ns * hw * hw * c)})
         # config 3: FC sparse-delta mat-vec
         for layer, ci, co in S.FC_LAYERS:
             for dt, es in ((S.I8, 1), (S.BF16, 2)):
-                for frac in S.FC_DENSITIES:
+                for frac in (S.FC_DENSITIES if full else CONFIG_GRID[3]):
                     seq = S.config3(layer, dt, frac, n=ns, T=Tf)
-                    r = time_layer(seq, dev_i8 if dt == S.I8 else dev_bf16, seq.weights)
+                    r = time_layer(seq, dev_i8 if dt == S.I8 else dev_bf16, seq.weights, cold=(ns == 1))
                     nnz = r["stats"]["changed_elems"]  # over all streams
-                    # a column of W is read once however many streams need it
+                    # a column of W is priced once however many streams need it (at most all of W)
                     byts = min(nnz, ci) * co * es + ns * (2 * ci * es + 2 * co * 4)
                     kt = r["delta_scan_us"] + r["delta_compute_us"]
                     roof = byts / HBM_PEAK * 1e6
-                    rows.append({"config": 3, "case": seq.name + sfx, "streams": ns, "rho_elem": nnz / (ns * ci),
-                                 "step_us": r["delta_us"], "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"],
-                                 "compute_us": r["delta_compute_us"], "dense_kernel_us": r["dense_compute_us"],
-                                 "frames_per_s": ns * 1e6 / r["delta_us"],
-                                 "dense_equiv_gops": 2 * ns * ci * co / r["delta_us"] * 1e-3,
-                                 "speedup_vs_dense": r["dense_us"] / r["delta_us"],
-                                 "alg_bytes": byts, "roof_us": roof, "roof_bound": "hbm",
-                                 "scatter_GBps": nnz * co * es / (r["delta_compute_us"] * 1e-6) / 1e9,
-                                 "dense_GBps": ns * ci * co * es / (r["dense_compute_us"] * 1e-6) / 1e9,
-                                 "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]})
-                    log("[sweep]", json.dumps(rows[-1]))
+                    row = {"config": 3, "case": seq.name + sfx, "streams": ns, "rho_elem": nnz / (ns * ci),
+                           "step_us": r["delta_us"], "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"],
+                           "compute_us": r["delta_compute_us"], "dense_kernel_us": r["dense_compute_us"],
+                           "frames_per_s": ns * 1e6 / r["delta_us"],
+                           "dense_equiv_gops": 2 * ns * ci * co / r["delta_us"] * 1e-3,
+                           "speedup_vs_dense": r["dense_us"] / r["delta_us"],
+                           "alg_bytes": byts, "roof_us": roof, "roof_bound": "hbm",
+                           "columns_GBps": nnz * co * es / (kt * 1e-6) / 1e9,
+                           "dense_GBps": ns * ci * co * es / (r["dense_compute_us"] * 1e-6) / 1e9,
+                           "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]}
+                    if "delta_cold_us" in r:
+                        row["cold_step_us"], row["cold_dense_step_us"] = r["delta_cold_us"], r["dense_cold_us"]
+                    rows.append(row)
+                    log("[config]", json.dumps(row))
         # config 4: binary conv
         for layer, hw, c in S.XNOR_LAYERS:
-            for frac in S.XNOR_FLIPS:
+            for frac in (S.XNOR_FLIPS if full else CONFIG_GRID[4]):
                 seq = S.config4(layer, frac, n=ns, T=Tb)
                 r = time_layer(seq, dev_bin, S.pack_pm1(seq.weights))
                 sh, stt = seq.shape, r["stats"]
                 words = stt["changed_units"] * 4  # upper bound on 32-bit words holding a flipped bit
                 lane_instr = 2 * words * c * 9
                 roof = max(lane_instr / VALU_LANE_PEAK,
-                           (2 * ns * hw * hw * c / 8 + 2 * stt["active_tiles"] * 64 * c * 4) / HBM_PEAK) * 1e6
+                           (2 * ns * hw * hw * c / 8 + 2 * active_positions(sh, stt, stt["active_tiles"]) * c * 4) / HBM_PEAK) * 1e6
                 kt = r["delta_scan_us"] + r["delta_compute_us"]
-                rows.append({"config": 4, "case": seq.name + sfx, "streams": ns,
-                             "rho_elem": stt["changed_elems"] / (ns * hw * hw * c),
-                             "rho_tile": stt["active_tiles"] / max(stt["total_tiles"], 1), "step_us": r["delta_us"],
-                             "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"], "compute_us": r["delta_compute_us"],
-                             "dense_kernel_us": r["dense_compute_us"], "frames_per_s": ns * 1e6 / r["delta_us"],
-                             "dense_equiv_gops": 2 * macs(sh) / r["delta_us"] * 1e-3,
-                             "speedup_vs_dense": r["dense_us"] / r["delta_us"],
-                             "roof_us": roof, "roof_bound": "alu", "roof_frac_kernels": roof / kt,
-                             "roof_frac_wall": roof / r["delta_us"]})
-                log("[sweep]", json.dumps(rows[-1]))
+                row = {"config": 4, "case": seq.name + sfx, "streams": ns,
+                       "rho_elem": stt["changed_elems"] / (ns * hw * hw * c),
+                       "rho_tile": stt["active_tiles"] / max(stt["total_tiles"], 1), "step_us": r["delta_us"],
+                       "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"], "compute_us": r["delta_compute_us"],
+                       "dense_kernel_us": r["dense_compute_us"], "frames_per_s": ns * 1e6 / r["delta_us"],
+                       "dense_equiv_gops": 2 * macs(sh) / r["delta_us"] * 1e-3,
+                       "speedup_vs_dense": r["dense_us"] / r["delta_us"],
+                       "roof_us": roof, "roof_bound": "alu", "roof_frac_kernels": roof / kt,
+                       "roof_frac_wall": roof / r["delta_us"]}
+                rows.append(row)
+                log("[config]", json.dumps(row))
+    return rows
+
+
+def compact(rows):
+    """The per-configuration array of the JSON line: case, streams, change density, wall time of a delta step and
+    of a dense step (graph replay), roofline time and the fraction of it reached on wall time (and on the
+    kernels' own time, which leaves out launch gaps)."""
+    out = []
+    for r in rows:
+        c = {"cfg": r["config"], "case": r["case"], "n": r["streams"], "rho": round(r["rho_elem"], 4),
+             "us": round(r["step_us"], 2), "dense_us": round(r["dense_step_us"], 2), "roof_us": round(r["roof_us"], 3),
+             "bound": r["roof_bound"], "frac": round(r["roof_frac_wall"], 4), "frac_kernels": round(r["roof_frac_kernels"], 4)}
+        for k, name in (("cold_step_us", "cold_us"), ("cold_dense_step_us", "cold_dense_us"),
+                        ("drift_terms1", "drift_terms1"), ("drift_terms2", "drift_terms2")):
+            if k in r:
+                c[name] = float(f"{r[k]:.3g}")
+        out.append(c)
+    return out
+
+
+def write_sweep(rows):
     os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
     with open(os.path.join(ROOT, "gpurun_out", "sweep.jsonl"), "w") as f:
         for r in rows:
             f.write(json.dumps(r) + "\n")
-    log("| case | rho_elem | step us | dense us | speedup | scan us | compute us | roof us | frac (kernels) |")
-    log("|---|---|---|---|---|---|---|---|---|")
+    log("| case | rho_elem | step us | dense us | speedup | scan us | compute us | roof us | frac (kernels) | frac (wall) |")
+    log("|---|---|---|---|---|---|---|---|---|---|")
     for r in rows:
         log(f"| {r['case']} | {r['rho_elem']:.3f} | {r['step_us']:.2f} | {r['dense_step_us']:.2f} | {r['speedup_vs_dense']:.2f} | "
-            f"{r['scan_us']:.2f} | {r['compute_us']:.2f} | {r['roof_us']:.3f} | {r['roof_frac_kernels']:.3f} |")
-    return rows
+            f"{r['scan_us']:.2f} | {r['compute_us']:.2f} | {r['roof_us']:.3f} | {r['roof_frac_kernels']:.3f} | {r['roof_frac_wall']:.3f} |")
+
+
+def run_lean_case(args):
+    """Eager steps of one layer of configurations 0, 2, 3, 4 and nothing else, for a profiler.  --lean-case is
+    "<cfg>:<layer>:<density>:<streams>[:<dtype i8|bf16>][:path=<p>]", e.g. "3:fc6:0.25:1:i8" or "2:r14:0.05:1:path=3".
+    Dispatch order: warm-up pass, copy, the counted delta steps (per step the layer's kernels in launch order),
+    copy, dense warm-up pass, copy, the counted dense steps, copy."""
+    import torch
+    import rrm_synth as S
+    import paper_1802_09723_amd as rrm
+    f = args.lean_case.split(":")
+    cfg, layer, frac, ns = int(f[0]), f[1], float(f[2]), int(f[3])
+    opts = [x for x in f[4:] if "=" in x]
+    dts = [x for x in f[4:] if "=" not in x]
+    if cfg == 0:
+        seq, w = S.config0(n=ns, T=8), None
+    elif cfg == 2:
+        seq, w = S.config2(layer, frac, n=ns, T=16 if ns == 1 else 6), None
+    elif cfg == 3:
+        seq, w = S.config3(layer, S.BF16 if dts and dts[0] == "bf16" else S.I8, frac, n=ns, T=64 if ns == 1 else 8), None
+    elif cfg == 4:
+        seq = S.config4(layer, frac, n=ns, T=32 if ns == 1 else 6)
+        w = S.pack_pm1(seq.weights)
+    else:
+        raise SystemExit("--lean-case: configuration 0, 2, 3 or 4")
+    w = seq.weights if w is None else w
+
+    def dev(fr):
+        if seq.dtype == S.BIN:
+            return torch.from_numpy(S.pack_pm1(fr).view(np.int32)).cuda()
+        a = np.ascontiguousarray(fr)
+        return torch.from_numpy(a if seq.dtype == S.I8 else a.view(np.int16)).cuda()
+
+    L = rrm.Layer(seq.shape, seq.dtype, w, seq.bias)
+    for o in opts:
+        k, v = o.split("=")
+        if k != "path":
+            L.set_option(k, int(v))
+    xs = [dev(fr) for fr in seq.frames]
+    order = xs[-2::-1] + xs[1:]
+    path = int(dict(o.split("=") for o in opts).get("path", 0))
+    calibration_copy(0)  # (allocates the markers' buffers)
+    for p in (path, 2):
+        L.set_option("path", p)
+        for x in xs:
+            L.step(x)
+        torch.cuda.synchronize()
+        calibration_copy(1)
+        for x in order[:args.steps]:
+            L.step(x)
+        torch.cuda.synchronize()
+        calibration_copy(1)
+    st = L.stats()
+    L.destroy()
+    return {"lean_case": args.lean_case, "name": seq.name, "counted_steps": min(args.steps, len(order)),
+            "changed_elems": int(st["changed_elems"]), "changed_units": int(st["changed_units"])}
+
+
+def run_lean(args):
+    """Eager steps of the headline stack and nothing else, for a profiler: `--steps` delta steps (frames
+    warmup .. warmup+steps-1 of the cyclic pair of sequences), then as many dense-path steps, each counted run
+    between two copies of known size (COPY_BYTES read and written: the counters' calibration and the markers).
+    Per step the dispatches come in a fixed order: per layer its difference kernel then its convolution kernel,
+    and last the nonlinearity of conv5 (dense path: the nonlinearity after every layer)."""
+    import torch
+    st = Stack(args.streams, fuse=not args.no_fuse)
+    if args.conv_kernel:
+        for L in st.layers:
+            try:
+                L.set_option("conv_kernel", args.conv_kernel)
+            except Exception:
+                pass
+            L.reset()
+    calibration_copy(0)  # (allocates the markers' buffers)
+    for path in (0, 2):
+        st.set_path(path)
+        st.run_steps(0, args.warmup, False)
+        torch.cuda.synchronize()
+        calibration_copy(1)  # (marks the boundary between warm-up and counted steps in the dispatch list)
+        st.run_steps(args.warmup, args.steps, False)
+        torch.cuda.synchronize()
+        calibration_copy(1)
+    return {"lean": True, "steps": args.steps, "warmup": args.warmup, "streams": args.streams}
 
 
 def main():
@@ -577,9 +825,13 @@ def main():
     ap.add_argument("--no-fuse", action="store_true",
                     help="delta path: write every layer's input to memory (separate f kernel) instead of rrm_step_from_projection")
     ap.add_argument("--conv-kernel", type=int, default=0, help="0 automatic, 1 window-tile, 2 position-gather (where eligible)")
-    ap.add_argument("--sweep", action="store_true")
-    ap.add_argument("--sweep-streams", type=int, default=64,
-                    help="--sweep times every layer at 1 stream (the configs' batch) and at this many streams")
+    ap.add_argument("--sweep", action="store_true", help="full density grids of configs 2-4 into sweep.jsonl and a table")
+    ap.add_argument("--no-configs", action="store_true", help="leave out the per-configuration array")
+    ap.add_argument("--config-streams", type=int, default=64,
+                    help="the per-configuration array times every layer at 1 stream (the configs' batch) and at this many")
+    ap.add_argument("--lean", action="store_true", help="only eager steps of the headline stack (for a profiler)")
+    ap.add_argument("--lean-case", default="", help="only eager steps of one layer of configs 0/2/3/4 (for a profiler), "
+                    "cfg:layer:density:streams[:i8|bf16][:path=P]")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (video streams are independent and would shard without any "
@@ -590,9 +842,23 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.lean_case:
+        print(json.dumps(run_lean_case(args)), flush=True)
+        return
+    if args.lean:
+        print(json.dumps(run_lean(args)), flush=True)
+        return
     out = run_stack(args)
-    if args.sweep:
-        run_sweep(args)
+    out["peaks"] = measure_peaks()
+    log("[peaks]", json.dumps(out["peaks"]))
+    r = out["roofline"]
+    meas = out["peaks"]["copy_GBps"] if r["bound"] == "hbm" else out["peaks"]["mfma_i8_TOPs"]
+    r["frac_of_measured_peak"] = round(r["achieved"] / meas, 4)
+    if not args.no_configs or args.sweep:
+        rows = config_rows(sorted({1, max(1, args.config_streams)}), full=args.sweep)
+        out["configs"] = compact(rows)
+        if args.sweep:
+            write_sweep(rows)
     print(json.dumps(out), flush=True)
 
 

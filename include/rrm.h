@@ -83,8 +83,9 @@ typedef struct {
     uint64_t changed_elems;   /* input elements (binary: bits) that differed from the snapshot */
     uint64_t changed_units;   /* 16-byte input units with any difference (FC: = changed_elems) */
     uint64_t active_tiles;    /* int8 / bf16 conv: output blocks recomputed (4x4 positions for the window-tile
-                                 kernel, single positions for the position-gather kernel); binary conv: 8x8 output
-                                 tiles recomputed; FC: columns streamed */
+                                 kernel, single positions for the position-gather kernel); binary conv: output
+                                 positions updated (8x8 tiles where a layer's bands do not fit LDS); FC: columns
+                                 streamed */
     uint64_t total_tiles;     /* the same unit, counted as a dense step would, summed over delta steps
                                  (FC: c_in per step) */
     int32_t range_error;      /* non-zero once an int8 difference overflowed */
@@ -233,6 +234,18 @@ rrm_status rrm_aux_relu_requant_pool_i8(const void* y, void* out, int n, int h, 
  * Errors: RRM_ERR_NULL, RRM_ERR_SHAPE (not an int8 conv layer, c_out % 4 != 0, bad shift / pool),
  * RRM_ERR_ALIGN, RRM_ERR_HIP. */
 rrm_status rrm_aux_relu_requant_pool_changed_i8(rrm_layer* layer, void* out, int shift, int pool, void* hip_stream);
+
+/* Measurement probes for the benchmark, NOT part of the method: what the device sustains, to price the
+ * library's kernels against measured as well as published peaks.
+ * rrm_aux_probe_mfma: `workgroups` workgroups of four wavefronts, each wavefront issuing 4 * iters
+ *   matrix-core products of register-resident operands (dtype RRM_I8_I32: 32x32x32 int8 tiles, 65536
+ *   operations each; RRM_BF16_F32: 32x32x16 bf16 tiles, 32768 each).  `sink` is a device word that the
+ *   kernel practically never writes.  1 <= iters <= 1 << 20, 1 <= workgroups <= 1 << 16.
+ * rrm_aux_probe_copy: copies bytes / 16 sixteen-byte vectors from src to dst (device pointers, 16-byte
+ *   aligned, not overlapping): `bytes` read and `bytes` written.
+ * Errors: RRM_ERR_NULL, RRM_ERR_DTYPE, RRM_ERR_SHAPE (counts out of range), RRM_ERR_ALIGN, RRM_ERR_HIP. */
+rrm_status rrm_aux_probe_mfma(int dtype, void* sink, int iters, int workgroups, void* hip_stream);
+rrm_status rrm_aux_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -6,5 +6,5 @@ PyTorch fallback: if the built library is missing, importing :mod:`.binding` sym
 it raises.
 """
 from .binding import (  # noqa: F401
-    BF16, BIN, CONV, FC, I8, Layer, RRMError, Shape, StackEntry, Stats, lib, lib_path, relu_requant_pool_i8, stack_step,
+    BF16, BIN, CONV, FC, I8, Layer, RRMError, Shape, StackEntry, Stats, lib, lib_path, probe_copy, probe_mfma, relu_requant_pool_i8, stack_step,
 )

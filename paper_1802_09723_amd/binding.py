@@ -90,6 +90,9 @@ def lib():
         L.rrm_set_threshold.argtypes = [P, ctypes.c_float]
         L.rrm_step_from_projection.argtypes = [P, P, I, I, P, P]
         L.rrm_stack_step.argtypes = [ctypes.POINTER(StackEntry), I, P, P, P]
+        L.rrm_aux_probe_mfma.argtypes = [I, P, I, I, P]
+        L.rrm_aux_probe_copy.argtypes = [P, P, ctypes.c_size_t, P]
+        L.rrm_aux_probe_mfma.restype = L.rrm_aux_probe_copy.restype = I
         for f in ("rrm_layer_create", "rrm_step", "rrm_dense", "rrm_dense_noalloc", "rrm_reset", "rrm_snapshot", "rrm_read_snapshot", "rrm_set_option",
                   "rrm_get_stats", "rrm_get_kernel_times", "rrm_aux_relu_requant_pool_i8",
                   "rrm_aux_relu_requant_pool_changed_i8", "rrm_set_threshold", "rrm_step_from_projection", "rrm_stack_step"):
@@ -243,6 +246,16 @@ def stack_step(layers, shifts, pools, x_t, f_out=None, stream=None) -> None:
     """``rrm_stack_step``: one frame through a stack of int8 conv layers with the fused nonlinearity."""
     arr = (StackEntry * len(layers))(*[StackEntry(L._h, int(s), int(bool(p))) for L, s, p in zip(layers, shifts, pools)])
     _check(lib().rrm_stack_step(arr, len(layers), _dptr(x_t), _dptr(f_out), _stream_ptr(stream)))
+
+
+def probe_mfma(dtype: int, sink, iters: int, workgroups: int, stream=None) -> None:
+    """``rrm_aux_probe_mfma``: register-resident matrix-core loop (a measurement probe)."""
+    _check(lib().rrm_aux_probe_mfma(int(dtype), _dptr(sink), int(iters), int(workgroups), _stream_ptr(stream)))
+
+
+def probe_copy(dst, src, nbytes: int, stream=None) -> None:
+    """``rrm_aux_probe_copy``: streaming copy of `nbytes` bytes (a measurement probe)."""
+    _check(lib().rrm_aux_probe_copy(_dptr(dst), _dptr(src), int(nbytes), _stream_ptr(stream)))
 
 
 def relu_requant_pool_i8(y, out, n, h, w, c, shift, pool, stream=None) -> None:

@@ -9,15 +9,30 @@
 // Per lane and 32 inputs this is one v_bfi_b32 ((w & B) | (~w & A) with A = m & x, B = m & ~x, which
 // equals m & (w XOR x)) and one v_bcnt_u32_b32 with accumulate: plain vector ALU work, no matrix core.
 //
-// Mapping: one workgroup = one 8x8 output tile (lane = output position) x 4*CW output channels
-// (wavefront w owns CW of them); the filter words of an output channel are wave-uniform and come
-// through scalar loads.  A/B words of the tile's input window are staged in LDS once; (slab, tap)
-// pairs in which no lane of the wavefront has a flipped bit are skipped.
+// Mapping of the tile kernel (the dense layer, and the delta step of layers whose band does not fit LDS): one
+// workgroup = one 8x8 output tile (lane = output position) x 4*CW output channels (wavefront w owns CW of
+// them); the filter words of an output channel are wave-uniform and come through scalar loads.  A/B words of
+// the tile's input window are staged in LDS once; (slab, tap) pairs in which no lane of the wavefront has a
+// flipped bit are skipped.
+//
+// Mapping of the band kernel (the delta step): one workgroup = a band of output rows of one stream x 4*CW
+// output channels.  It stages the band's input window as above, notes which input positions hold a flip, lists
+// the output positions whose window sees one (ballot compaction into LDS) and deals that list to the lanes 64
+// at a time: a wavefront's lanes are all output positions with work to do, wherever in the band they lie, so
+// the work follows the changed positions instead of the 8x8 tiles they fall into.
 #include "rrm_internal.h"
 
 namespace rrm {
 
 namespace {
+
+// t + popcount(v) in one instruction (v_bcnt_u32_b32 adds its second operand; the compiler otherwise counts
+// into a fresh register and adds pairs of counts with a third instruction)
+__device__ __forceinline__ int popc_acc(unsigned int v, int t) {
+    int r;
+    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(v), "v"(t));
+    return r;
+}
 
 template <int MODE, int CW>
 __global__ __launch_bounds__(256) void bin_conv_kernel(const unsigned int* __restrict__ xsrc,
@@ -101,10 +116,10 @@ __global__ __launch_bounds__(256) void bin_conv_kernel(const unsigned int* __res
                 for (int o = 0; o < 8; ++o) {
                     const uint4 w = wp[o];
                     int t = tot[o8 * 8 + o];
-                    t += __popc((w.x & bb.x) | (~w.x & a.x));
-                    t += __popc((w.y & bb.y) | (~w.y & a.y));
-                    t += __popc((w.z & bb.z) | (~w.z & a.z));
-                    t += __popc((w.w & bb.w) | (~w.w & a.w));
+                    t = popc_acc((w.x & bb.x) | (~w.x & a.x), t);
+                    t = popc_acc((w.y & bb.y) | (~w.y & a.y), t);
+                    t = popc_acc((w.z & bb.z) | (~w.z & a.z), t);
+                    t = popc_acc((w.w & bb.w) | (~w.w & a.w), t);
                     tot[o8 * 8 + o] = t;
                 }
             }
@@ -151,6 +166,189 @@ __global__ __launch_bounds__(256) void bin_conv_kernel(const unsigned int* __res
     }
 }
 
+// the band kernel's inner part: NP x 64 listed output positions (lane l takes entries first + l, first + 64 + l)
+// against the CW output channels of this wavefront; the filter words of a (slab, tap) are loaded once for all NP
+template <int CW, int NP>
+__device__ __forceinline__ void band_items(const unsigned int* A, const unsigned int* B, const unsigned short* list,
+                                           int first, int cnt, const uint4* __restrict__ wpack, int* y,
+                                           const BinGeom& g, int b, int oy0, int grp, int co_w, int lane) {
+    const int ntaps = g.kh * g.kw;
+    const long long ob8 = (long long)grp * g.nob8 + co_w / 8;
+    const bool vec = (g.c_out & 3) == 0 && (g.og & 3) == 0;
+    bool valid[NP];
+    int oyl[NP], ox[NP], lbase[NP], popm[NP];
+    int tot[NP][CW];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int e = first + p * 64 + lane;
+        valid[p] = e < cnt;
+        const int q = list[valid[p] ? e : 0];
+        oyl[p] = q / g.wo;
+        ox[p] = q - oyl[p] * g.wo;
+        lbase[p] = ((oyl[p] * g.stride) * g.btw_in + ox[p] * g.stride) * g.pitch;
+        popm[p] = 0;
+#pragma unroll
+        for (int o = 0; o < CW; ++o) tot[p][o] = 0;
+    }
+    for (int slab = 0; slab < g.nslab; ++slab) {
+        for (int tap = 0; tap < ntaps; ++tap) {
+            const int ky = tap / g.kw, kx = tap - ky * g.kw;
+            const int toff = (ky * g.btw_in + kx) * g.pitch + slab * 4;
+            uint4 a[NP], bb[NP];
+            unsigned int any = 0;
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                a[p] = *reinterpret_cast<const uint4*>(A + lbase[p] + toff);
+                bb[p] = *reinterpret_cast<const uint4*>(B + lbase[p] + toff);
+                any |= a[p].x | a[p].y | a[p].z | a[p].w | bb[p].x | bb[p].y | bb[p].z | bb[p].w;
+            }
+            if (__ballot(any != 0u) == 0ull) continue;  // wave-uniform: nothing flipped under this tap
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+                popm[p] = popc_acc(a[p].w | bb[p].w, popc_acc(a[p].z | bb[p].z, popc_acc(a[p].y | bb[p].y, popc_acc(a[p].x | bb[p].x, popm[p]))));
+#pragma unroll
+            for (int o8 = 0; o8 < CW / 8; ++o8) {
+                const uint4* wp = wpack + (((ob8 + o8) * g.nslab + slab) * ntaps + tap) * 8;
+#pragma unroll
+                for (int o = 0; o < 8; ++o) {
+                    const uint4 w = wp[o];
+#pragma unroll
+                    for (int p = 0; p < NP; ++p) {
+                        int t = tot[p][o8 * 8 + o];
+                        t = popc_acc((w.x & bb[p].x) | (~w.x & a[p].x), t);
+                        t = popc_acc((w.y & bb[p].y) | (~w.y & a[p].y), t);
+                        t = popc_acc((w.z & bb[p].z) | (~w.z & a[p].z), t);
+                        t = popc_acc((w.w & bb[p].w) | (~w.w & a[p].w), t);
+                        tot[p][o8 * 8 + o] = t;
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        if (!valid[p] || popm[p] == 0) continue;
+        const long long ybase = (((long long)b * g.ho + oy0 + oyl[p]) * g.wo + ox[p]) * g.c_out + (long long)grp * g.og + co_w;
+#pragma unroll
+        for (int o4 = 0; o4 < CW / 4; ++o4) {
+            const int co = co_w + o4 * 4;
+            if (co >= g.og) break;
+            int r[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) r[k] = 2 * (popm[p] - 2 * tot[p][o4 * 4 + k]);
+            if (vec && co + 3 < g.og) {
+                int4* yp = reinterpret_cast<int4*>(y + ybase + o4 * 4);
+                int4 o = *yp;
+                o.x += r[0]; o.y += r[1]; o.z += r[2]; o.w += r[3];
+                *yp = o;
+            } else {
+                for (int k = 0; k < 4 && co + k < g.og; ++k) y[ybase + o4 * 4 + k] += r[k];
+            }
+        }
+    }
+}
+
+template <int CW>
+__global__ __launch_bounds__(256) void bin_band_kernel(const unsigned int* __restrict__ xsrc,
+                                                       const unsigned int* __restrict__ flip,
+                                                       const uint4* __restrict__ wpack, int* y, BinGeom g,
+                                                       DevStats* __restrict__ stats) {
+    extern __shared__ uint4 smem[];
+    const int npos = g.bth_in * g.btw_in;
+    unsigned int* A = reinterpret_cast<unsigned int*>(smem);
+    unsigned int* B = A + npos * g.pitch;
+    unsigned char* posany = reinterpret_cast<unsigned char*>(B + npos * g.pitch);     // input position holds a flip
+    unsigned short* list = reinterpret_cast<unsigned short*>(posany + ((npos + 3) & ~3));  // active output positions
+    __shared__ unsigned int s_wc[4];
+
+    const int b = (int)blockIdx.x / g.nbands, band = (int)blockIdx.x - b * g.nbands;
+    const int nblk = (g.og + 4 * CW - 1) / (4 * CW);
+    const int grp = blockIdx.y / nblk;
+    const int blk = blockIdx.y - grp * nblk;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int oy0 = band * g.band_rows;
+    const int rows = min(g.band_rows, g.ho - oy0);
+    const int iy0 = oy0 * g.stride - g.pad, ix0 = -g.pad;
+    const int wg4 = g.nslab * 4;
+
+    for (int i = tid; i < npos; i += 256) posany[i] = 0;
+    __syncthreads();
+    // ---- stage A = m & x and B = m & ~x of the band's input window ------------------------------
+    if (g.vec4) {
+        // four words at a time, both loads issued whatever the mask holds (independent loads, several in flight)
+        const int units = npos * g.nslab;
+#pragma unroll 4
+        for (int u = tid; u < units; u += 256) {
+            const int hp = (int)(g.magic_nslab ? __umulhi((unsigned int)u, g.magic_nslab) : (unsigned int)u), sl = u - hp * g.nslab;
+            const int hy = (int)(g.magic_btw ? __umulhi((unsigned int)hp, g.magic_btw) : (unsigned int)hp), hx = hp - hy * g.btw_in;
+            const int iy = iy0 + hy, ix = ix0 + hx;
+            uint4 m = make_uint4(0, 0, 0, 0), xv = make_uint4(0, 0, 0, 0);
+            if (iy >= 0 && iy < g.h && ix >= 0 && ix < g.w) {
+                const long long wi = (((long long)b * g.h + iy) * g.w + ix) * g.wpp + (long long)grp * g.wg + sl * 4;
+                m = *reinterpret_cast<const uint4*>(flip + wi);  // the flip buffer is zero where nothing changed
+                xv = *reinterpret_cast<const uint4*>(xsrc + wi);
+            }
+            if (m.x | m.y | m.z | m.w) posany[hp] = 1;
+            *reinterpret_cast<uint4*>(A + hp * g.pitch + sl * 4) = make_uint4(m.x & xv.x, m.y & xv.y, m.z & xv.z, m.w & xv.w);
+            *reinterpret_cast<uint4*>(B + hp * g.pitch + sl * 4) = make_uint4(m.x & ~xv.x, m.y & ~xv.y, m.z & ~xv.z, m.w & ~xv.w);
+        }
+    } else {
+        const int units = npos * wg4;
+        for (int u = tid; u < units; u += 256) {
+            const int hp = (int)(g.magic_wg4 ? __umulhi((unsigned int)u, g.magic_wg4) : (unsigned int)u), wd = u - hp * wg4;
+            const int hy = (int)(g.magic_btw ? __umulhi((unsigned int)hp, g.magic_btw) : (unsigned int)hp), hx = hp - hy * g.btw_in;
+            const int iy = iy0 + hy, ix = ix0 + hx;
+            unsigned int m = 0, xv = 0;
+            if (wd < g.wg && iy >= 0 && iy < g.h && ix >= 0 && ix < g.w) {
+                const long long wi = (((long long)b * g.h + iy) * g.w + ix) * g.wpp + (long long)grp * g.wg + wd;
+                m = flip[wi];  // the flip buffer is zero where nothing changed
+                if (m) {
+                    xv = xsrc[wi];
+                    posany[hp] = 1;
+                }
+            }
+            A[hp * g.pitch + wd] = m & xv;
+            B[hp * g.pitch + wd] = m & ~xv;
+        }
+    }
+    __syncthreads();
+    // ---- list the output positions of the band whose window holds a flip ------------------------
+    const int nout = rows * g.wo;
+    int cnt = 0;
+    for (int base = 0; base < nout; base += 256) {
+        const int q = base + tid;
+        bool act = false;
+        if (q < nout) {
+            const int oyl = q / g.wo, ox = q - oyl * g.wo;
+            const unsigned char* pa = posany + (oyl * g.stride) * g.btw_in + ox * g.stride;
+            for (int ky = 0; ky < g.kh; ++ky)
+                for (int kx = 0; kx < g.kw; ++kx) act |= pa[ky * g.btw_in + kx] != 0;
+        }
+        // (the same order in every workgroup of the band: the workgroups of a list split deal its chunks among them)
+        const unsigned long long mask = __ballot(act);
+        if (lane == 0) s_wc[wave] = (unsigned int)__popcll(mask);
+        __syncthreads();
+        const unsigned int c0 = s_wc[0], c1 = s_wc[1], c2 = s_wc[2], c3 = s_wc[3];
+        const unsigned int wbase = (unsigned int)cnt + (wave > 0 ? c0 : 0u) + (wave > 1 ? c1 : 0u) + (wave > 2 ? c2 : 0u);
+        if (act) list[wbase + __popcll(mask & ((1ull << lane) - 1ull))] = (unsigned short)q;
+        cnt += (int)(c0 + c1 + c2 + c3);
+        __syncthreads();  // (the counts are overwritten in the next round; after the last one: the list is complete)
+    }
+    if (cnt == 0) return;
+    if (blockIdx.y == 0 && blockIdx.z == 0 && tid == 0)
+        atomicAdd(&stats[blockIdx.x & (STAT_SLOTS - 1)].active_tiles, (unsigned long long)cnt);
+
+    const int co_w = blk * 4 * CW + wave * CW;  // first output channel of this wavefront in the group
+    if (co_w >= g.og) return;
+    for (int first = (int)blockIdx.z * 128; first < cnt; first += (int)gridDim.z * 128) {
+        if (cnt - first > 64)
+            band_items<CW, 2>(A, B, list, first, cnt, wpack, y, g, b, oy0, grp, co_w, lane);
+        else
+            band_items<CW, 1>(A, B, list, first, cnt, wpack, y, g, b, oy0, grp, co_w, lane);
+    }
+}
+
 template <int MODE, int CW>
 hipError_t launch_one(const void* xsrc, const void* flip, unsigned int* tileflag, const void* wpack,
                       const void* bias, void* y, const BinGeom& g, DevStats* stats, hipStream_t s) {
@@ -167,6 +365,34 @@ hipError_t launch_one(const void* xsrc, const void* flip, unsigned int* tileflag
 }  // namespace
 
 int bin_consumers(int cw, const BinGeom& g) { return g.groups * ((g.og + 4 * cw - 1) / (4 * cw)); }
+
+size_t bin_band_lds_bytes(const BinGeom& g, int band_rows) {
+    const size_t npos = (size_t)((band_rows - 1) * g.stride + g.kh) * (size_t)((g.wo - 1) * g.stride + g.kw);
+    return 2 * npos * g.pitch * 4 + ((npos + 3) & ~(size_t)3) + (((size_t)band_rows * g.wo * 2 + 15) & ~(size_t)15);
+}
+
+template <int CW>
+hipError_t launch_band(const void* xsrc, const void* flip, const void* wpack, void* y, const BinGeom& g, DevStats* stats,
+                       hipStream_t s) {
+    const int nblk = (g.og + 4 * CW - 1) / (4 * CW);
+    // few streams: deal the band's list over several workgroups (each stages the window again: it is small)
+    const long long wgs = (long long)g.n * g.nbands * g.groups * nblk;
+    const int chunks = (g.band_rows * g.wo + 127) / 128;  // (a workgroup takes the list 128 entries at a time)
+    int z = (int)((2 * NUM_CU + wgs - 1) / wgs);
+    z = z < 1 ? 1 : (z > chunks ? chunks : z);
+    dim3 grid((unsigned int)(g.n * g.nbands), (unsigned int)(g.groups * nblk), (unsigned int)z);
+    hipLaunchKernelGGL((bin_band_kernel<CW>), grid, dim3(256), bin_band_lds_bytes(g, g.band_rows), s,
+                       static_cast<const unsigned int*>(xsrc), static_cast<const unsigned int*>(flip),
+                       static_cast<const uint4*>(wpack), static_cast<int*>(y), g, stats);
+    return hipGetLastError();
+}
+
+hipError_t launch_bin_band(int cw, const void* xsrc, const void* flip, const void* wpack, void* y, const BinGeom& g,
+                           DevStats* stats, hipStream_t s) {
+    if (g.band_rows < 1 || g.band_rows * g.wo > 65535) return hipErrorInvalidValue;  // (list entries are 16 bits)
+    if (cw == 16) return launch_band<16>(xsrc, flip, wpack, y, g, stats, s);
+    return launch_band<8>(xsrc, flip, wpack, y, g, stats, s);
+}
 
 hipError_t launch_bin_conv(int mode, int cw, const void* xsrc, const void* flip, unsigned int* tileflag,
                            const void* wpack, const void* bias, void* y, const BinGeom& g, DevStats* stats,

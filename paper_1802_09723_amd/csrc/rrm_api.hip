@@ -548,6 +548,29 @@ rrm_status setup_bin(rrm_layer* L, const std::vector<unsigned char>& w) {
     g.magic_tw = magic_for(g.tw_in);
     if ((long long)2 * g.th_in * g.tw_in * g.pitch * 4 > 64 * 1024)
         return fail(RRM_ERR_SHAPE, "input window of one output tile does not fit LDS");
+    // delta step: bands of output rows whose window, flags and list fit 64 KB of LDS (two workgroups per compute
+    // unit); as tall as fits when the streams alone fill the chip (a tall band wastes least on its halo rows and
+    // fills its 64-lane chunks best), shorter -- down to 4 rows -- while there are fewer than two workgroups per
+    // compute unit; no band at all = the tile kernel
+    g.band_rows = 0;
+    for (int r = g.ho; r >= 1; --r)
+        if (bin_band_lds_bytes(g, r) <= 64 * 1024 - 64 && (long long)r * g.wo <= 65535) {
+            g.band_rows = r;
+            break;
+        }
+    g.nbands = 1;
+    if (g.band_rows > 0) {
+        g.nbands = (g.ho + g.band_rows - 1) / g.band_rows;
+        const long long per_band = (long long)g.n * g.groups * ((g.og + 63) / 64);
+        while (per_band * g.nbands < 2 * NUM_CU && (g.ho + g.nbands) / (g.nbands + 1) >= 4) ++g.nbands;
+        g.band_rows = (g.ho + g.nbands - 1) / g.nbands;
+        g.nbands = (g.ho + g.band_rows - 1) / g.band_rows;
+    }
+    g.vec4 = (g.wg % 4 == 0 && g.wpp % 4 == 0) ? 1 : 0;
+    g.magic_nslab = magic_for(g.nslab);
+    g.bth_in = (std::max(g.band_rows, 1) - 1) * s.stride + s.kh;
+    g.btw_in = (g.wo - 1) * s.stride + s.kw;
+    g.magic_btw = magic_for(g.btw_in);
     const int ntaps = s.kh * s.kw;
     // filter words: [group][co/8][slab][tap][co%8][4 words]
     std::vector<unsigned int> pack((size_t)s.groups * g.nob8 * g.nslab * ntaps * 8 * 4, 0u);
@@ -730,7 +753,8 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
         if ((st = dalloc(((nvec + 63) / 64) * 8, (void**)&L->bitmap)) != RRM_OK) return bail(st);
         sg.sty = (int)((ho + 3) / 4);
         sg.stx = (int)((wo + 3) / 4);
-        sg.tiles_per_step = dtype == RRM_BIN_I32 ? (unsigned long long)s.n * sg.tiles_y * sg.tiles_x
+        sg.tiles_per_step = dtype == RRM_BIN_I32 ? (L->bg.band_rows > 0 ? (unsigned long long)s.n * ho * wo
+                                                                        : (unsigned long long)s.n * sg.tiles_y * sg.tiles_x)
                                                  : (unsigned long long)s.n * sg.sty * sg.stx;
         // binary: one stamp per 8x8 tile; int8 / bf16: one byte flag per 4x4 sub-tile
         L->marks_bytes = dtype == RRM_BIN_I32 ? (size_t)s.n * sg.tiles_y * sg.tiles_x * 4
@@ -804,11 +828,15 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
         if ((st = prof_mark(L, 0, s)) != RRM_OK) return st;
         if (L->dtype == RRM_BIN_I32) {
             const int cw = bin_cw(L);
+            const bool band = L->bg.band_rows > 0;  // (the band kernel reads the flip words itself: no tile stamps)
             RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag,
-                                (unsigned int)bin_consumers(cw, L->bg), L->sg, L->stats, s));
+                                band ? 0u : (unsigned int)bin_consumers(cw, L->bg), L->sg, L->stats, s));
             if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
-            RRM_HIP(launch_bin_conv(MODE_DELTA, cw, L->x_snap, L->d0, L->tileflag, L->wpack, nullptr, L->y_snap, L->bg,
-                                    L->stats, s));
+            if (band)
+                RRM_HIP(launch_bin_band(cw, L->x_snap, L->d0, L->wpack, L->y_snap, L->bg, L->stats, s));
+            else
+                RRM_HIP(launch_bin_conv(MODE_DELTA, cw, L->x_snap, L->d0, L->tileflag, L->wpack, nullptr, L->y_snap, L->bg,
+                                        L->stats, s));
         } else if (use_scatter(L)) {
             // one launch: compare, products of the changed positions, atomic accumulation, commit
             if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;  // (no separate scan kernel: its time is reported as 0)
@@ -1033,7 +1061,7 @@ rrm_status rrm_get_stats(rrm_layer* L, rrm_stats* out) {
     out->active_tiles = d.active_tiles;
     out->total_tiles = d.total_tiles;
     out->range_error = (int32_t)d.range_error;
-    out->tile_positions = L->shape.kind == RRM_FC ? 0 : (L->dtype == RRM_BIN_I32 ? TILE * TILE : (L->use_pos ? 1 : 16));
+    out->tile_positions = L->shape.kind == RRM_FC ? 0 : (L->dtype == RRM_BIN_I32 ? (L->bg.band_rows > 0 ? 1 : TILE * TILE) : (L->use_pos ? 1 : 16));
     out->truncated_elems = d.truncated_elems;
     out->truncated_sumsq = d.truncated_sumsq;
     if (d.range_error) return fail(RRM_ERR_RANGE, "an int8 input difference did not fit int8");
@@ -1084,6 +1112,23 @@ rrm_status rrm_aux_relu_requant_pool_i8(const void* y, void* out, int n, int h, 
     if (n < 1 || h < 1 || w < 1 || c < 1 || shift < 0 || shift > 31 || (pool && (h < 3 || w < 3)))
         return fail(RRM_ERR_SHAPE, "bad shape for relu_requant_pool");
     RRM_HIP(launch_relu_requant_pool(y, out, nullptr, nullptr, 0, n, h, w, c, shift, pool, static_cast<hipStream_t>(hip_stream)));
+    return RRM_OK;
+}
+
+rrm_status rrm_aux_probe_mfma(int dtype, void* sink, int iters, int workgroups, void* hip_stream) {
+    if (!sink) return fail(RRM_ERR_NULL, "sink is NULL");
+    if (dtype != RRM_I8_I32 && dtype != RRM_BF16_F32) return fail(RRM_ERR_DTYPE, "the matrix-core probe runs int8 or bf16 tiles");
+    if (iters < 1 || iters > (1 << 20) || workgroups < 1 || workgroups > (1 << 16))
+        return fail(RRM_ERR_SHAPE, "probe: iters in [1, 2^20], workgroups in [1, 2^16]");
+    RRM_HIP(launch_probe_mfma(dtype == RRM_BF16_F32, sink, iters, workgroups, static_cast<hipStream_t>(hip_stream)));
+    return RRM_OK;
+}
+
+rrm_status rrm_aux_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+    if (!dst || !src) return fail(RRM_ERR_NULL, "dst / src is NULL");
+    if (((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15) != 0)
+        return fail(RRM_ERR_ALIGN, "probe copy: pointers must be 16-byte aligned");
+    RRM_HIP(launch_probe_copy(dst, src, bytes, static_cast<hipStream_t>(hip_stream)));
     return RRM_OK;
 }
 

@@ -160,6 +160,12 @@ struct BinGeom {
     int nob8;            // packed 8-channel filter blocks per group (og padded to 16)
     unsigned int magic_wg4;    // floor(2^32/d)+1 for d = 4*nslab
     unsigned int magic_tw;     // same for d = tw_in
+    // band kernel (delta step): bands of band_rows output rows over the full width; 0 rows = the layer's bands
+    // do not fit LDS and the delta step runs the tile kernel
+    int band_rows, nbands, bth_in, btw_in;
+    unsigned int magic_btw;    // same for d = btw_in
+    unsigned int magic_nslab;  // same for d = nslab
+    int vec4;                  // 1: a group's words per position are whole 16-byte vectors (wg % 4 == 0, wpp % 4 == 0)
 };
 
 struct FcGeom {
@@ -226,6 +232,9 @@ hipError_t launch_bin_conv(int mode, int cw, const void* xsrc, const void* flip,
                            const void* wpack, const void* bias, void* y, const BinGeom& g, DevStats* stats,
                            hipStream_t s);
 int bin_consumers(int cw, const BinGeom& g);     // workgroups per tile of the binary kernel
+size_t bin_band_lds_bytes(const BinGeom& g, int band_rows);
+hipError_t launch_bin_band(int cw, const void* xsrc, const void* flip, const void* wpack, void* y, const BinGeom& g,
+                           DevStats* stats, hipStream_t s);
 
 hipError_t launch_fill_bias(int is_float, void* y, const void* bias, long long rows, int c_out, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
@@ -235,6 +244,8 @@ hipError_t launch_repack(int esize, const void* x, void* dst, const ScanGeom& g,
 hipError_t launch_fill_word(void* p, size_t bytes, unsigned int word, hipStream_t s);
 // touched: nullptr = every output; else byte flags per block of (1 << tshift)^2 positions of y, only outputs under
 // a set flag (every output again while the device word *touched_all is non-zero)
+hipError_t launch_probe_mfma(int is_bf16, void* sink, int iters, int workgroups, hipStream_t s);
+hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_relu_requant_pool(const void* y, void* out, const void* touched, const unsigned int* touched_all,
                                     int tshift, int n, int h, int w, int c, int shift, int pool, hipStream_t s);
 

@@ -357,7 +357,8 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
     }
     // mark the output blocks that see the changed positions
     if (DT == RRM_BIN_I32) {
-        for (int p = p0; p <= p1; ++p) mark_tiles(g, p, tileflag, stamp);
+        if (stamp)  // (stamp 0: the layer's delta kernel reads the flip words itself)
+            for (int p = p0; p <= p1; ++p) mark_tiles(g, p, tileflag, stamp);
     } else if (g.sty > 0) {  // (layers on the position-gather kernel read the bitmap instead: no flags)
         for (int p = p0; p <= p1; ++p) mark_subtiles(g, (unsigned int)p, reinterpret_cast<unsigned char*>(tileflag));
     }

@@ -317,6 +317,22 @@ def test_random_binary_shapes(idx):
     run_sequence(seq, check_dense=(0, 3))
 
 
+def test_binary_band_list_longer_than_one_pass_and_wide_layer_on_the_tile_kernel():
+    """The binary delta step's band kernel with several 128-entry passes over a band's list, dealt over several
+    workgroups (one stream, half of the positions changing), with three streams, and a layer so wide that no
+    band of it fits LDS, which takes the tile kernel."""
+    big = S.conv_shape(40, 40, 64, 32, 3, 1, 1, 1)
+    seq = S.random_layer(8501, big, S.BIN, T=4, frac=0.5, block=3)
+    run_sequence(seq, check_dense=(0, 3))
+    seq = S.random_layer(8502, S.conv_shape(30, 26, 128, 48, 3, 1, 1, 1, n=3), S.BIN, T=4, frac=0.2, block=4)
+    st, _ = run_sequence(seq, check_dense=(0, 3))
+    assert st["tile_positions"] == 1
+    wide = S.conv_shape(6, 300, 256, 16, 3, 1, 1, 1)
+    seq = S.random_layer(8503, wide, S.BIN, T=3, frac=0.05, block=4)
+    st, _ = run_sequence(seq, check_dense=(0, 2))
+    assert st["tile_positions"] == 64
+
+
 @pytest.mark.parametrize("idx", range(8))
 def test_random_fc_shapes(idx):
     rng = S.rng_for(900 + idx)
