@@ -510,7 +510,7 @@ def cpu_baseline_stack(st, budget_s: float = 8.0):
 # ------------------------------------------------------------------------------------------------
 # configs 0, 2, 3, 4 (one layer at a time)
 # ------------------------------------------------------------------------------------------------
-def time_layer(seq, to_dev, weights, reps: int = 5, eps: float = 0.0, drift: bool = False, cold: bool = False):
+def time_layer(seq, to_dev, weights, reps: int = 5, eps: float = 0.0, drift: bool = False, cold: bool = False, opts=None):
     """Per-step wall time (graph of one whole sequence, delta and dense path) and event-bracketed
     kernel times of one layer over its frame sequence.  eps: truncation threshold (bf16 layers).
     drift (bf16 conv): after the whole sequence on the delta path, max |stored projection - dense projection of
@@ -521,6 +521,8 @@ def time_layer(seq, to_dev, weights, reps: int = 5, eps: float = 0.0, drift: boo
     L = rrm.Layer(seq.shape, seq.dtype, weights, seq.bias)
     if eps:
         L.set_threshold(eps)
+    for k, v in (opts or {}).items():
+        L.set_option(k, v)
     xs = [to_dev(f) for f in seq.frames]
     res = {}
     for tag, path in (("delta", 0), ("dense", 2)):
@@ -675,6 +677,28 @@ def config_rows(stream_counts, full: bool):
                            "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]}
                     if "delta_cold_us" in r:
                         row["cold_step_us"], row["cold_dense_step_us"] = r["delta_cold_us"], r["dense_cold_us"]
+                    rows.append(row)
+                    log("[config]", json.dumps(row))
+        # config 3 with pruned weights (Sec. 4.3: compressed models keep about a tenth of their FC weights): a seeded
+        # random tenth of fc6's weights survives; the delta step walks the non-zeros of the changed columns
+        if ns == 1:
+            for dt, es in ((S.I8, 1), (S.BF16, 2)):
+                for frac in (0.05, 0.25):
+                    seq = S.pruned(S.config3("fc6", dt, frac, n=ns, T=Tf), 0.10, S.seed_for(3, 77))
+                    r = time_layer(seq, dev_i8 if dt == S.I8 else dev_bf16, seq.weights, opts={"fc_sparse_weights": 1})
+                    ci, co = 9216, 4096
+                    nnz = r["stats"]["changed_elems"]
+                    nzw = float(np.count_nonzero(seq.weights)) / seq.weights.size
+                    # per changed column its non-zeros (value + 2-byte row) and two offsets; x twice; y read and written
+                    byts = nnz * (co * nzw * (es + 2) + 8) + ns * (2 * ci * es + 2 * co * 4)
+                    kt = r["delta_scan_us"] + r["delta_compute_us"]
+                    roof = byts / HBM_PEAK * 1e6
+                    row = {"config": 3, "case": seq.name, "streams": ns, "rho_elem": nnz / (ns * ci), "weight_density": nzw,
+                           "step_us": r["delta_us"], "dense_step_us": r["dense_us"], "scan_us": r["delta_scan_us"],
+                           "compute_us": r["delta_compute_us"], "dense_kernel_us": r["dense_compute_us"],
+                           "frames_per_s": ns * 1e6 / r["delta_us"], "dense_equiv_gops": 2 * ns * ci * co / r["delta_us"] * 1e-3,
+                           "speedup_vs_dense": r["dense_us"] / r["delta_us"], "alg_bytes": byts, "roof_us": roof,
+                           "roof_bound": "hbm", "roof_frac_kernels": roof / kt, "roof_frac_wall": roof / r["delta_us"]}
                     rows.append(row)
                     log("[config]", json.dumps(row))
         # config 4: binary conv

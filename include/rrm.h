@@ -145,6 +145,10 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
  *                 positions in all (one stream of a small map), where two dependent launches cost more than the work.
  *   "fc_splits"   FC, dense path: number of row splits of the weight matrix, in [1, the default chosen at
  *                 create] (the partial-sum scratch is sized for the default)
+ *   "fc_sparse_weights"  FC, delta step: 1 = walk the non-zero weights of the changed columns only (pruned
+ *                 models, Sec. 4.3; the (row, value) lists exist when at most half of W is non-zero at create,
+ *                 else RRM_ERR_OPTION), 0 = walk whole columns (default).  fp32 sums of the sparse walk
+ *                 depend on the order of its atomic adds, within the layer's tolerance; integers are exact.
  *   "bf16_terms"  BF16 conv: 2 = difference carried as hi+lo bf16 pair (default), 1 = hi only
  *   "dense_switch_pct"  INT8 / BF16 conv: a delta step whose changes touch more than this percentage of the
  *                 4x4 output blocks recomputes the whole projection (same result; cheaper than reading and

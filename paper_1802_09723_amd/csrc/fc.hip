@@ -33,7 +33,13 @@ __device__ __forceinline__ float bf16_to_f32(unsigned int h) { return __uint_as_
 // atomics on y, the same summation order in every run.  The stored input is committed by whichever workgroup of
 // the stream finishes its compare last (an arrival counter tells it that nobody reads the old values any more);
 // it also rearms the counter, so a step leaves no host-visible state behind (graph replay safe).
-template <int DT>
+//
+// CSC = true (pruned weights, Sec. 4.3: the compressed model keeps its non-zero weights only): the columns of W
+// are stored as (row, value) lists.  Workgroup (r, b) takes every gridDim.x-th block of eight listed columns, one
+// column per wavefront with the lanes over its non-zeros, and adds the products into a private copy of the
+// projection's update in LDS (all c_out rows); at the end it adds the rows it touched into the stored projection
+// with atomic adds (exact for integers; fp32 sums then depend on the order within the layer's tolerance).
+template <int DT, bool CSC>
 __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned char* __restrict__ x_t,
                                                                unsigned char* x_snap,
                                                                const unsigned char* __restrict__ wT, void* y_v,
@@ -48,7 +54,11 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
     __shared__ val_t red[FCD_THREADS / 64][4][PV];
     __shared__ int wave_tot[FCD_THREADS / 64];
     __shared__ unsigned int s_prev;
+    extern __shared__ uint4 fc_dyn[];  // CSC: one update accumulator per output row
+    val_t* ly = reinterpret_cast<val_t*>(fc_dyn);
     const int r = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (CSC)
+        for (int o = tid; o < g.c_out; o += FCD_THREADS) ly[o] = 0;  // (the first round's barriers order this)
     // integer layers split long lists over gridDim.z workgroups, pass by pass (pass p of NCG * FCD_UN columns goes
     // to workgroup p % gridDim.z), and add with integer atomics: exact in any order
     const int ks = blockIdx.z, nks = gridDim.z;
@@ -159,7 +169,7 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
     // this workgroup's channels of the stored projection, fetched now and needed at the end
     const int co_y = r * (FCD_SEG / ESIZE) + tid;
     val_t y_old = 0;
-    if (nks == 1 && tid < 4 * PV && co_y < g.c_out) y_old = static_cast<const val_t*>(y_v)[(long long)b * g.c_out + co_y];
+    if (!CSC && nks == 1 && tid < 4 * PV && co_y < g.c_out) y_old = static_cast<const val_t*>(y_v)[(long long)b * g.c_out + co_y];
     uint4 cur_a = make_uint4(0, 0, 0, 0), cur_s = cur_a;
     if (tid * PV < min(CHU, g.c_in)) load_unit(tid * PV, cur_a, cur_s);
     for (int ch = 0; ch < nchunk; ++ch) {
@@ -215,8 +225,39 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
         total += (unsigned int)cnt;
         // every read of the stored input by this workgroup is done: tell the stream's other workgroups
         if (ch == nchunk - 1 && tid == 0) s_prev = atomicAdd(&arrive[b], 1u);
-        // ---- this workgroup's 64 bytes of every listed column ------------------------------------------------
-        if (live) {
+        if (CSC) {
+            // ---- this workgroup's blocks of eight listed columns, one column per wavefront ---------------------
+            const unsigned int* cptr = g.csc_ptr;
+            constexpr int NW = FCD_THREADS / 64, PRE = 4;  // (PRE columns' offsets in flight per wavefront)
+            const int kstep = (int)gridDim.x * NW;
+            for (int k0 = (int)blockIdx.x * NW + wave; k0 < cnt; k0 += PRE * kstep) {
+                unsigned int p0[PRE], p1[PRE];
+                val_t d[PRE];
+#pragma unroll
+                for (int i = 0; i < PRE; ++i) {
+                    const int k = k0 + i * kstep;
+                    const bool ok = k < cnt;
+                    const int j = ok ? base + l_idx[k] : 0;
+                    d[i] = ok ? l_val[k] : (val_t)0;
+                    p0[i] = ok ? cptr[j] : 0u;
+                    p1[i] = ok ? cptr[j + 1] : 0u;
+                }
+#pragma unroll
+                for (int i = 0; i < PRE; ++i) {
+#pragma unroll 8
+                    for (unsigned int e = p0[i] + lane; e < p1[i]; e += 64) {
+                        const int o = g.csc_row[e];
+                        val_t w;
+                        if (DT == RRM_I8_I32)
+                            w = (val_t)(int)static_cast<const signed char*>(g.csc_val)[e];
+                        else
+                            w = (val_t)bf16_to_f32(static_cast<const unsigned short*>(g.csc_val)[e]);
+                        atomicAdd(&ly[o], d[i] * w);  // (LDS: rows of one column are distinct, wavefronts may share a row)
+                    }
+                }
+            }
+        } else if (live) {
+            // ---- this workgroup's 64 bytes of every listed column ------------------------------------------------
             for (int k0 = ks * (FCD_UN * NCG); k0 < cnt; k0 += nks * (FCD_UN * NCG)) {
                 const int k = k0 + cgid;
                 int j[FCD_UN];
@@ -250,7 +291,16 @@ __global__ __launch_bounds__(FCD_THREADS) void fc_delta_kernel(const unsigned ch
 
     // ---- column groups -> one sum per channel: butterfly inside the wavefront (lanes with the same `sub`), then
     // the wavefronts in order through LDS.  The order is fixed, so fp32 results repeat from run to run.
-    if (total) {  // (the same in every thread: the list lengths)
+    if (CSC) {
+        __syncthreads();  // every wavefront's LDS adds are done
+        if (total) {
+            val_t* yb = static_cast<val_t*>(y_v) + (long long)b * g.c_out;
+            for (int o = tid; o < g.c_out; o += FCD_THREADS) {
+                const val_t v = ly[o];
+                if (v != (val_t)0) atomicAdd(yb + o, v);
+            }
+        }
+    } else if (total) {  // (the same in every thread: the list lengths)
 #pragma unroll
         for (int e = 0; e < PV; ++e) {
             val_t v = acc[e];
@@ -471,17 +521,42 @@ __global__ __launch_bounds__(FC_MAX_SPLITS * 16) void fc_reduce_kernel(const voi
 hipError_t launch_fc_delta(int dtype, const void* x_t, void* x_snap, const void* wT, void* y, unsigned int* arrive,
                            const FcGeom& g, DevStats* stats, hipStream_t s) {
     const int esize = dtype == RRM_I8_I32 ? 1 : 2;
+    dim3 block(FCD_THREADS);
+    if (g.csc_ptr) {
+        // pruned weights: up to 64 workgroups per stream share the list (each pays c_out atomic adds at the end)
+        const int nw = std::max(1, std::min(64, NUM_CU / g.n));
+        const size_t lds = ((size_t)g.c_out * 4 + 15) & ~(size_t)15;
+        static std::once_flag once;
+        static hipError_t attr = hipSuccess;
+        std::call_once(once, [] {
+            attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&fc_delta_kernel<RRM_I8_I32, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, FC_CSC_MAX_LDS);
+            if (attr == hipSuccess)
+                attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&fc_delta_kernel<RRM_BF16_F32, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, FC_CSC_MAX_LDS);
+        });
+        if (attr != hipSuccess) return attr;
+        if (lds > (size_t)FC_CSC_MAX_LDS) return hipErrorInvalidValue;
+        dim3 grid((unsigned int)nw, (unsigned int)g.n, 1u);
+        if (dtype == RRM_I8_I32)
+            hipLaunchKernelGGL((fc_delta_kernel<RRM_I8_I32, true>), grid, block, lds, s, (const unsigned char*)x_t,
+                               (unsigned char*)x_snap, (const unsigned char*)wT, y, arrive, g, stats);
+        else
+            hipLaunchKernelGGL((fc_delta_kernel<RRM_BF16_F32, true>), grid, block, lds, s, (const unsigned char*)x_t,
+                               (unsigned char*)x_snap, (const unsigned char*)wT, y, arrive, g, stats);
+        return hipGetLastError();
+    }
     const int ranges = (g.c_out_p * esize + FCD_SEG - 1) / FCD_SEG;
     // integer layers with long input vectors: up to four list splits while that fills more of the chip's 256
     // compute units (measured: pays off from about a thousand changed columns; short vectors lose to the extra
     // workgroups' compare)
     const int nks = dtype == RRM_I8_I32 && g.c_in >= 8192 ? std::max(1, std::min(4, 256 / (ranges * g.n))) : 1;
-    dim3 grid((unsigned int)ranges, (unsigned int)g.n, (unsigned int)nks), block(FCD_THREADS);
+    dim3 grid((unsigned int)ranges, (unsigned int)g.n, (unsigned int)nks);
     if (dtype == RRM_I8_I32)
-        hipLaunchKernelGGL(fc_delta_kernel<RRM_I8_I32>, grid, block, 0, s, (const unsigned char*)x_t,
+        hipLaunchKernelGGL((fc_delta_kernel<RRM_I8_I32, false>), grid, block, 0, s, (const unsigned char*)x_t,
                            (unsigned char*)x_snap, (const unsigned char*)wT, y, arrive, g, stats);
     else
-        hipLaunchKernelGGL(fc_delta_kernel<RRM_BF16_F32>, grid, block, 0, s, (const unsigned char*)x_t,
+        hipLaunchKernelGGL((fc_delta_kernel<RRM_BF16_F32, false>), grid, block, 0, s, (const unsigned char*)x_t,
                            (unsigned char*)x_snap, (const unsigned char*)wT, y, arrive, g, stats);
     return hipGetLastError();
 }

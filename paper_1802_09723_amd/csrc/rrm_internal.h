@@ -174,7 +174,13 @@ struct FcGeom {
     int per_vec;         // output channels per lane per 16-byte load: 16 / 8
     int vec_ok;          // 1: x rows are 16-byte aligned multiples
     float eps;           // bf16: truncation threshold of the difference (0 = exact)
+    // pruned weights (delta step only): column j of W holds the non-zeros csc_ptr[j] .. csc_ptr[j + 1] - 1, each a
+    // row index and a value (int8 / bf16 bits); csc_ptr == nullptr = the dense columns are walked
+    const unsigned int* csc_ptr;
+    const unsigned short* csc_row;
+    const void* csc_val;
 };
+constexpr int FC_CSC_MAX_LDS = 96 * 1024;   // the pruned-weight kernel's update accumulators: c_out <= 24576
 
 // floor(u / d) through the reciprocal magic = floor(2^32 / d) + 1 (0 encodes d == 1).  The product's high word is
 // the quotient or one more than it for every u < 2^32 - d (the reciprocal is rounded up), so one

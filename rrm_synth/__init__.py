@@ -469,3 +469,13 @@ def random_layer(seed: int, shape: LayerShape, dtype: int, T: int = 4, frac: flo
         else:
             streams.append(block_redraw_frames(rng, shape.h, shape.w, shape.c_in, T, min(block, shape.h, shape.w), frac, draw))
     return Sequence_(shape, dtype, wts, bias, _stack_streams(streams), "random")
+
+
+def pruned(seq: Sequence_, keep: float, seed: int) -> Sequence_:
+    """The same sequence with a pruned copy of the weights: a seeded random subset of `keep` of them survives,
+    the rest are zero (a stand-in for a compressed model's weights, Sec. 4.3: the paper's own pruned models
+    are not available)."""
+    rng = rng_for(seed)
+    mask = rng.random(seq.weights.shape) < keep
+    w = np.where(mask, seq.weights, np.zeros_like(seq.weights))
+    return Sequence_(seq.shape, seq.dtype, w, seq.bias, seq.frames, f"{seq.name}_w{int(round(keep * 100))}", dict(seq.meta))

@@ -467,3 +467,25 @@ def test_fused_consumer_after_a_scatter_step_of_the_producer():
                        f"frame {t} consumer")
     A.destroy()
     B.destroy()
+
+
+@pytest.mark.parametrize("dtype", [S.I8, S.BF16])
+def test_fc_pruned_weights_walk_nonzeros_only(dtype):
+    """FC layers whose weights are mostly zero (pruned models, Sec. 4.3): the delta step walks the (row, value)
+    lists of the changed columns.  Several streams, a ragged shape, a full-size layer, the list longer than one
+    compare round (c_in above 8192), an all-zero column; and the dense-column walk forced on the same handle."""
+    import paper_1802_09723_amd as rrm
+    cases = [(S.fc_shape(700, 300, n=3), 0.10, 0.2), (S.fc_shape(4096, 4096), 0.10, 0.05), (S.fc_shape(9216, 1000, n=2), 0.25, 0.5),
+             (S.fc_shape(33, 17), 0.3, 0.5)]
+    for i, (shp, keep, frac) in enumerate(cases):
+        seq = S.pruned(S.random_layer(8600 + i, shp, dtype, T=4, frac=frac), keep, 8700 + i)
+        seq.weights[:, min(5, shp.c_in - 1)] = 0  # a column without any non-zero
+        st, _ = run_sequence(seq, check_dense=(0, 3), rel=1e-4, fc_sparse_weights=1)
+        assert st["delta_steps"] == 4
+        st2, _ = run_sequence(seq, check_dense=(), rel=1e-4)
+        assert st2["changed_elems"] == st["changed_elems"]
+    dense_w = S.random_layer(8650, S.fc_shape(64, 64), dtype, T=2, frac=0.5)
+    L = make_layer(dense_w)
+    with pytest.raises(rrm.binding.RRMError):
+        L.set_option("fc_sparse_weights", 1)
+    L.destroy()
