@@ -140,10 +140,35 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool producer = wave < 4;
     const int cw = wave - 4;  // consumer index
+    // Workgroup coordinates: BX of GX unit lanes (a lane takes work units BX, BX + GX, ...), BY of GY channel-block
+    // groups.  With g.xcd_gy set the grid is one-dimensional and the coordinates are dealt so that the GY
+    // workgroups of a lane, which gather the same input windows, sit on the same XCD (workgroups go to the
+    // eight XCDs round-robin by their linear index) and find each other's windows in that XCD's L2.
+    int BX, BY, GX, GY;
+    if (g.xcd_gy) {
+        const int lin = (int)blockIdx.x;
+        GY = g.xcd_gy;
+        GX = (int)gridDim.x / GY;
+        const int dealt = (GX >> 3) * 8 * GY;  // workgroups of the lanes that are dealt XCD by XCD
+        if (lin < dealt) {
+            const int slot = lin >> 3;
+            BY = slot % GY;
+            BX = (slot / GY) * 8 + (lin & 7);
+        } else {  // (the few lanes beyond a multiple of eight: wherever they fall)
+            const int rem = lin - dealt;
+            BY = rem % GY;
+            BX = (GX >> 3) * 8 + rem / GY;
+        }
+    } else {
+        BX = (int)blockIdx.x;
+        BY = (int)blockIdx.y;
+        GX = (int)gridDim.x;
+        GY = (int)gridDim.y;
+    }
 
     const int ncbg = (g.ncb + NCB - 1) / NCB;  // channel-block groups per filter group
-    const int grp = blockIdx.y / ncbg;
-    const int cbg = blockIdx.y - grp * ncbg;
+    const int grp = BY / ncbg;
+    const int cbg = BY - grp * ncbg;
     // packed weights: [group][32-channel block (padded to ncbg*NCB)][MFMA step][lane]; a slab is MFMA steps
     // slab*nq2 .. slab*nq2 + nq2 - 1 of each of this workgroup's NCB blocks
     const int kall = g.nslab * nq2;
@@ -229,10 +254,10 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     // Few sub-tiles in all (one stream of a small map: at most 256, and every group of nt consecutive sub-tiles
     // has a workgroup of its own in the grid): the launch is latency bound, so there is no global list.  A workgroup reads
     // the flags of its own group only, compacts them with one ballot, and is done after one barrier.
-    const bool own_group = MODE == MODE_DELTA && g.n_sub <= (int)gridDim.x * g.nt && g.n_sub <= CONV_THREADS;
+    const bool own_group = MODE == MODE_DELTA && g.n_sub <= GX * g.nt && g.n_sub <= CONV_THREADS;
     if (own_group) {
         if (wave == 0) {
-            const int id = (int)blockIdx.x * g.nt + lane;
+            const int id = BX * g.nt + lane;
             const bool f = lane < g.nt && id < g.n_sub && (reinterpret_cast<const unsigned char*>(flags)[id] & 1u);
             const unsigned long long m = __ballot(f);
             if (f) s_list[__popcll(m & ((1ull << lane) - 1ull))] = id;
@@ -281,8 +306,8 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     // The active sub-tiles are cut into work units of `per` sub-tiles: few sub-tiles are spread thinly (a
     // unit's latency grows with its size), many are packed NT per unit (operand reuse).
     // (a workgroup with a sub-tile group of its own: one unit, the group's active sub-tiles)
-    const int gx = own_group ? 1 : (int)gridDim.x;
-    const int bx = own_group ? 0 : (int)blockIdx.x;
+    const int gx = own_group ? 1 : GX;
+    const int bx = own_group ? 0 : BX;
     // (several units per workgroup: as many as full-size units would need, but of equal size, so that the
     // last pass over the grid is not a nearly empty one of full-size units)
     const int passes = max(1, (count + gx * g.nt - 1) / (gx * g.nt));
@@ -303,7 +328,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
     // the arrival counter) for the next step, at its own end, off everybody's critical path.
     auto retire = [&]() {
         if (MODE != MODE_DELTA) return;
-        if (tid == 0) s_last = (arrived_before == gridDim.x * gridDim.y - 1u) ? 1 : 0;
+        if (tid == 0) s_last = (arrived_before == (unsigned int)(GX * GY) - 1u) ? 1 : 0;
         __syncthreads();
         if (s_last) {
             for (int w = tid; w < g.n_words; w += WG_THREADS) {
@@ -318,8 +343,8 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
             }
         }
         // (each workgroup counted only its own group's flags)
-        if (own_group && tid == 0 && n_flagged && blockIdx.y == 0)
-            atomicAdd(&stats[blockIdx.x & (STAT_SLOTS - 1)].active_tiles, (unsigned long long)n_flagged);
+        if (own_group && tid == 0 && n_flagged && BY == 0)
+            atomicAdd(&stats[(unsigned int)BX & (STAT_SLOTS - 1)].active_tiles, (unsigned long long)n_flagged);
     };
     if (bx >= nunits) {
         __builtin_amdgcn_s_waitcnt(0);  // let the early weight copy land before the LDS is released
@@ -327,7 +352,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         retire();
         return;
     }
-    // this workgroup's units: blockIdx.x + i*gx, i = 0 .. my_nunits-1, ranked in rounds of `ur` units
+    // this workgroup's units: BX + i*gx, i = 0 .. my_nunits-1, ranked in rounds of `ur` units
     const int my_nunits = (nunits - bx + gx - 1) / gx;
     const int ur = LIST_CAP / per;
 
@@ -356,7 +381,7 @@ __global__ __launch_bounds__(WG_THREADS) void conv_gather_kernel(
         if (r0 > 0) __syncthreads();  // the previous round's list is no longer in use
         if (listed && !own_group) {  // (own_group: the list was made with the count)
             // The rank of a set flag is the number of set flags before it; this workgroup owns the ranks
-            // unit*per .. unit*per + per - 1 of its units blockIdx.x + i*gx, i = r0 .. r1-1.  Every producer
+            // unit*per .. unit*per + per - 1 of its units BX + i*gx, i = r0 .. r1-1.  Every producer
             // thread looks its share of those ranks up: which thread's flags hold the rank (binary search in
             // the prefix counts), then which of that thread's set bits it is.  Nobody walks a long run of bits.
             const int n_owned = (r1 - r0) * per;
@@ -766,8 +791,16 @@ hipError_t launch_one(const void* src0, const void* src1, const void* zero16, un
     // no more workgroups than are resident at once (the kernel loops over its work units)
     const int gy = g.groups * ncbg;
     const int resident = NUM_CU;  // eight wavefronts with up to 256 registers each fill a compute unit
-    const int gx = std::min((g.n_sub + g.nt - 1) / g.nt, std::max(1, resident / gy));
+    int gx = std::min((g.n_sub + g.nt - 1) / g.nt, std::max(1, resident / gy));
     dim3 grid((unsigned int)gx, (unsigned int)gy);
+    // A full grid (more units than lanes): one-dimensional, with the channel-block groups of a lane on one XCD
+    // (see the kernel).
+    ConvGeom gg = g;
+    gg.xcd_gy = 0;
+    if (gx >= 8 && gx == resident / gy) {
+        grid = dim3((unsigned int)(gx * gy), 1u);
+        gg.xcd_gy = gy;
+    }
     auto kern = conv_gather_kernel<DT, MODE, NCB, NT, TERMS>;
     if (lds > 64 * 1024) {
         // one per instantiation, shared by every handle and thread of the process: guarded, so that
@@ -784,7 +817,7 @@ hipError_t launch_one(const void* src0, const void* src1, const void* zero16, un
     }
     hipLaunchKernelGGL(kern, grid, dim3(WG_THREADS), lds, s, static_cast<const unsigned char*>(src0),
                        static_cast<const unsigned char*>(src1), static_cast<const unsigned char*>(zero16), flags, ctrl,
-                       static_cast<const uint4*>(wpack), offtab, bias, y, g, stats);
+                       static_cast<const uint4*>(wpack), offtab, bias, y, gg, stats);
     return hipGetLastError();
 }
 

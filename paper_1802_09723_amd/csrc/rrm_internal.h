@@ -125,6 +125,8 @@ struct ConvGeom {
     unsigned int* touched;  // copy of the sub-tile flags of the last delta step (what it wrote in y), or nullptr
     const unsigned char* xfull;  // delta launches: the committed input in source layout (full recomputation above
     int full_pct;                //   full_pct % active sub-tiles), or nullptr: never
+    int xcd_gy;          // set by the launcher: 0 = two-dimensional grid, else the channel-block groups of a
+                         // one-dimensional grid dealt XCD by XCD
 };
 
 // Geometry of the single-launch scatter convolution (conv_scatter.hip).
