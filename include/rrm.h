@@ -136,7 +136,8 @@ rrm_status rrm_snapshot(rrm_layer* layer, const void** x_snap, const void** y_sn
  * n*h_out*w_out*c_out values of y_snap. */
 rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* hip_stream);
 
-/* Options (value semantics per key):
+/* Options: how a step is carried out, never what it computes (every setting yields the P_t of Eq. 5 / Algorithm 1,
+ * within the layer's tolerance).  Value semantics per key:
  *   "path"        0 auto, 1 sparse delta path always (scan + tile kernel, no switch to recomputation), 2 recompute
  *                 densely every step, 3 INT8 / BF16 conv: the single-launch scatter path always (one kernel compares,
  *                 multiplies the changed input positions and adds the products into the stored projection with
@@ -165,7 +166,9 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
  *                 caller's stream (see rrm_get_kernel_times; not for use under graph capture), 0 = off */
 rrm_status rrm_set_option(rrm_layer* layer, const char* key, long value);
 
-/* Read the counters.  Synchronises with the device (copies a small block back); call it after
+/* Read the counters: how many inputs changed and how much of the projection a step touched, the measured
+ * counterpart of the density rho in the cost model of Sec. 3.3 (Table 1, Eq. 6), and the truncated differences
+ * of Sec. 3.4 (Eq. 7).  Synchronises with the device (copies a small block back); call it after
  * the stream has been synchronised, outside timed regions.  Returns RRM_ERR_RANGE (with *out
  * filled) if the sticky range flag is set. */
 rrm_status rrm_get_stats(rrm_layer* layer, rrm_stats* out);

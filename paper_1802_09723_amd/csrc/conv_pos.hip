@@ -77,25 +77,6 @@ __device__ __forceinline__ void sched_interleave() {
     }
 }
 
-// Wait until at most n of this wavefront's vector-memory operations are outstanding (they complete in order, so
-// everything but the n youngest has landed).  The count is an immediate of the instruction, hence the switch; LDS
-// and scalar counters are not waited for.
-__device__ __forceinline__ void wait_vmcnt(int n) {
-#define RRM_VM(N) \
-    case N:       \
-        __builtin_amdgcn_s_waitcnt(((N) & 15) | (((N) >> 4) << 14) | (7 << 4) | (15 << 8)); \
-        break;
-    switch (n) {
-        RRM_VM(0) RRM_VM(1) RRM_VM(2) RRM_VM(3) RRM_VM(4) RRM_VM(5) RRM_VM(6) RRM_VM(7) RRM_VM(8) RRM_VM(9) RRM_VM(10)
-        RRM_VM(11) RRM_VM(12) RRM_VM(13) RRM_VM(14) RRM_VM(15) RRM_VM(16) RRM_VM(17) RRM_VM(18) RRM_VM(19) RRM_VM(20)
-        RRM_VM(21) RRM_VM(22) RRM_VM(23) RRM_VM(24)
-        default:
-            __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8));
-            break;
-    }
-#undef RRM_VM
-}
-
 typedef const void __attribute__((address_space(1))) * gptr_t;
 typedef void __attribute__((address_space(3))) * lptr_t;
 

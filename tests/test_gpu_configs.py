@@ -71,9 +71,12 @@ def test_config2_resnet_bf16_16_frames(layer, frac):
     print(f"{seq.name}: worst |err|/max|y| = {worst:.2e}")
 
 
+@pytest.mark.parametrize("layer", [k for k, _, _ in S.RESNET_LAYERS])
 @pytest.mark.parametrize("frac", [0.02, 0.10, 0.25])
-def test_config2_resnet_bf16_other_densities(frac):
-    run_sequence(S.config2("r28", frac), check_frames=(0,), check_dense=(), check_x=False)
+def test_config2_resnet_bf16_other_densities(layer, frac):
+    """Full size, the remaining densities of the configuration's grid, every layer; the whole 16 frames run, the
+    first, a middle and the last frame are compared."""
+    run_sequence(S.config2(layer, frac), check_frames=(0, 8), check_dense=(), check_x=False)
 
 
 @pytest.mark.parametrize("layer", ["fc6", "fc7"])
