@@ -161,6 +161,10 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
  *                 (single active output positions as columns of the product; stride 1 and channel runs of
  *                 16-byte multiples; faster where every stream changes sparsely and alike).  Set it before the
  *                 first rrm_step, or follow it with rrm_reset: the two kernels keep their change flags differently.
+ *   "bin_single_launch"  binary conv, delta step: 1 (default) = the whole step in one launch where the layer allows
+ *                 it (compare, popcount products of the changed positions and commit in the band kernel), 0 = a
+ *                 difference kernel followed by the band kernel.  Change it only right after create or rrm_reset
+ *                 (the two forms keep the flip buffer differently).
  *   "bin_cout_per_wave"  binary conv: output channels per wavefront, 8 / 16 (0 = heuristic)
  *   "profile"     1 = bracket every kernel of the following rrm_step calls with HIP events on the
  *                 caller's stream (see rrm_get_kernel_times; not for use under graph capture), 0 = off */

@@ -248,9 +248,14 @@ __device__ __forceinline__ void band_items(const unsigned int* A, const unsigned
     }
 }
 
-template <int CW>
+// FUSED: the whole step in this one launch.  `xsrc` is the new frame x_t and `flip` the stored input: the flip
+// mask is their XOR, formed while the window is staged (no difference kernel, no flip buffer); the change counts
+// are taken over the input rows a band owns; and the workgroup of a stream that finishes staging last (arrival
+// counter) copies the frame into the stored input, when nobody reads the old one any more, and rearms the counter.
+template <int CW, bool FUSED>
 __global__ __launch_bounds__(256) void bin_band_kernel(const unsigned int* __restrict__ xsrc,
-                                                       const unsigned int* __restrict__ flip,
+                                                       const unsigned int* flip, unsigned int* snap,
+                                                       unsigned int* arrive,
                                                        const uint4* __restrict__ wpack, int* y, BinGeom g,
                                                        DevStats* __restrict__ stats) {
     extern __shared__ uint4 smem[];
@@ -259,7 +264,7 @@ __global__ __launch_bounds__(256) void bin_band_kernel(const unsigned int* __res
     unsigned int* B = A + npos * g.pitch;
     unsigned char* posany = reinterpret_cast<unsigned char*>(B + npos * g.pitch);     // input position holds a flip
     unsigned short* list = reinterpret_cast<unsigned short*>(posany + ((npos + 3) & ~3));  // active output positions
-    __shared__ unsigned int s_wc[4];
+    __shared__ unsigned int s_wc[4], s_prev;
 
     const int b = (int)blockIdx.x / g.nbands, band = (int)blockIdx.x - b * g.nbands;
     const int nblk = (g.og + 4 * CW - 1) / (4 * CW);
@@ -274,6 +279,10 @@ __global__ __launch_bounds__(256) void bin_band_kernel(const unsigned int* __res
 
     for (int i = tid; i < npos; i += 256) posany[i] = 0;
     __syncthreads();
+    // (FUSED) input rows whose changes this band counts, by the workgroup of the band's first channel block
+    const int own_lo = oy0 * g.stride, own_hi = band == g.nbands - 1 ? g.h : (oy0 + g.band_rows) * g.stride;
+    const bool count_here = FUSED && blk == 0 && blockIdx.z == 0;
+    unsigned int nbits = 0, nunits = 0;
     // ---- stage A = m & x and B = m & ~x of the band's input window ------------------------------
     if (g.vec4) {
         // four words at a time, both loads issued whatever the mask holds (independent loads, several in flight)
@@ -288,6 +297,13 @@ __global__ __launch_bounds__(256) void bin_band_kernel(const unsigned int* __res
                 const long long wi = (((long long)b * g.h + iy) * g.w + ix) * g.wpp + (long long)grp * g.wg + sl * 4;
                 m = *reinterpret_cast<const uint4*>(flip + wi);  // the flip buffer is zero where nothing changed
                 xv = *reinterpret_cast<const uint4*>(xsrc + wi);
+                if (FUSED) {
+                    m = make_uint4(m.x ^ xv.x, m.y ^ xv.y, m.z ^ xv.z, m.w ^ xv.w);
+                    if (count_here && iy >= own_lo && iy < own_hi && (m.x | m.y | m.z | m.w)) {
+                        nbits += __popc(m.x) + __popc(m.y) + __popc(m.z) + __popc(m.w);
+                        ++nunits;
+                    }
+                }
             }
             if (m.x | m.y | m.z | m.w) posany[hp] = 1;
             *reinterpret_cast<uint4*>(A + hp * g.pitch + sl * 4) = make_uint4(m.x & xv.x, m.y & xv.y, m.z & xv.z, m.w & xv.w);
@@ -313,6 +329,25 @@ __global__ __launch_bounds__(256) void bin_band_kernel(const unsigned int* __res
         }
     }
     __syncthreads();
+    if (FUSED) {
+        // this workgroup has read the stored input for the last time
+        if (tid == 0) s_prev = atomicAdd(&arrive[b], 1u);
+        if (count_here) {
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                nbits += __shfl_xor(nbits, o);
+                nunits += __shfl_xor(nunits, o);
+            }
+            if (lane == 0 && nunits) {
+                atomicAdd(&stats[blockIdx.x & (STAT_SLOTS - 1)].changed_elems, (unsigned long long)nbits);
+                atomicAdd(&stats[blockIdx.x & (STAT_SLOTS - 1)].changed_units, (unsigned long long)nunits);
+            }
+        }
+        if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {  // one launch = one delta step
+            atomicAdd(&stats[0].delta_steps, 1ull);
+            atomicAdd(&stats[0].total_tiles, (unsigned long long)g.n * g.ho * g.wo);
+        }
+    }
     // ---- list the output positions of the band whose window holds a flip ------------------------
     const int nout = rows * g.wo;
     int cnt = 0;
@@ -335,17 +370,27 @@ __global__ __launch_bounds__(256) void bin_band_kernel(const unsigned int* __res
         cnt += (int)(c0 + c1 + c2 + c3);
         __syncthreads();  // (the counts are overwritten in the next round; after the last one: the list is complete)
     }
-    if (cnt == 0) return;
-    if (blockIdx.y == 0 && blockIdx.z == 0 && tid == 0)
+    if (cnt > 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0)
         atomicAdd(&stats[blockIdx.x & (STAT_SLOTS - 1)].active_tiles, (unsigned long long)cnt);
 
     const int co_w = blk * 4 * CW + wave * CW;  // first output channel of this wavefront in the group
-    if (co_w >= g.og) return;
-    for (int first = (int)blockIdx.z * 128; first < cnt; first += (int)gridDim.z * 128) {
-        if (cnt - first > 64)
-            band_items<CW, 2>(A, B, list, first, cnt, wpack, y, g, b, oy0, grp, co_w, lane);
-        else
-            band_items<CW, 1>(A, B, list, first, cnt, wpack, y, g, b, oy0, grp, co_w, lane);
+    if (co_w < g.og) {
+        for (int first = (int)blockIdx.z * 128; first < cnt; first += (int)gridDim.z * 128) {
+            if (cnt - first > 64)
+                band_items<CW, 2>(A, B, list, first, cnt, wpack, y, g, b, oy0, grp, co_w, lane);
+            else
+                band_items<CW, 1>(A, B, list, first, cnt, wpack, y, g, b, oy0, grp, co_w, lane);
+        }
+    }
+    if (FUSED) {
+        // commit: the stream's last workgroup to finish staging (s_prev was published by the list's barriers)
+        if (s_prev == (unsigned int)g.nbands * gridDim.y * gridDim.z - 1u) {
+            const long long words = (long long)g.h * g.w * g.wpp;  // (a multiple of four: whole 16-byte vectors)
+            const uint4* src = reinterpret_cast<const uint4*>(xsrc + (long long)b * words);
+            uint4* dst = reinterpret_cast<uint4*>(snap + (long long)b * words);
+            for (long long i = tid; i < words / 4; i += 256) dst[i] = src[i];
+            if (tid == 0) arrive[b] = 0u;
+        }
     }
 }
 
@@ -371,9 +416,9 @@ size_t bin_band_lds_bytes(const BinGeom& g, int band_rows) {
     return 2 * npos * g.pitch * 4 + ((npos + 3) & ~(size_t)3) + (((size_t)band_rows * g.wo * 2 + 15) & ~(size_t)15);
 }
 
-template <int CW>
-hipError_t launch_band(const void* xsrc, const void* flip, const void* wpack, void* y, const BinGeom& g, DevStats* stats,
-                       hipStream_t s) {
+template <int CW, bool FUSED>
+hipError_t launch_band(const void* xsrc, const void* flip, void* snap, unsigned int* arrive, const void* wpack, void* y,
+                       const BinGeom& g, DevStats* stats, hipStream_t s) {
     const int nblk = (g.og + 4 * CW - 1) / (4 * CW);
     // few streams: deal the band's list over several workgroups (each stages the window again: it is small)
     const long long wgs = (long long)g.n * g.nbands * g.groups * nblk;
@@ -381,17 +426,28 @@ hipError_t launch_band(const void* xsrc, const void* flip, const void* wpack, vo
     int z = (int)((2 * NUM_CU + wgs - 1) / wgs);
     z = z < 1 ? 1 : (z > chunks ? chunks : z);
     dim3 grid((unsigned int)(g.n * g.nbands), (unsigned int)(g.groups * nblk), (unsigned int)z);
-    hipLaunchKernelGGL((bin_band_kernel<CW>), grid, dim3(256), bin_band_lds_bytes(g, g.band_rows), s,
+    hipLaunchKernelGGL((bin_band_kernel<CW, FUSED>), grid, dim3(256), bin_band_lds_bytes(g, g.band_rows), s,
                        static_cast<const unsigned int*>(xsrc), static_cast<const unsigned int*>(flip),
-                       static_cast<const uint4*>(wpack), static_cast<int*>(y), g, stats);
+                       static_cast<unsigned int*>(snap), arrive, static_cast<const uint4*>(wpack), static_cast<int*>(y),
+                       g, stats);
     return hipGetLastError();
 }
 
+// two launches: xsrc = the stored input after the difference kernel, flip = its flip buffer
 hipError_t launch_bin_band(int cw, const void* xsrc, const void* flip, const void* wpack, void* y, const BinGeom& g,
                            DevStats* stats, hipStream_t s) {
     if (g.band_rows < 1 || g.band_rows * g.wo > 65535) return hipErrorInvalidValue;  // (list entries are 16 bits)
-    if (cw == 16) return launch_band<16>(xsrc, flip, wpack, y, g, stats, s);
-    return launch_band<8>(xsrc, flip, wpack, y, g, stats, s);
+    if (cw == 16) return launch_band<16, false>(xsrc, flip, nullptr, nullptr, wpack, y, g, stats, s);
+    return launch_band<8, false>(xsrc, flip, nullptr, nullptr, wpack, y, g, stats, s);
+}
+
+// one launch: the whole step (needs g.fused_ok: every input position lies in the window of the band that owns it,
+// and a group's words per position are whole 16-byte vectors)
+hipError_t launch_bin_band_fused(int cw, const void* x_t, void* x_snap, unsigned int* arrive, const void* wpack, void* y,
+                                 const BinGeom& g, DevStats* stats, hipStream_t s) {
+    if (g.band_rows < 1 || g.band_rows * g.wo > 65535 || !g.fused_ok || !arrive) return hipErrorInvalidValue;
+    if (cw == 16) return launch_band<16, true>(x_t, x_snap, x_snap, arrive, wpack, y, g, stats, s);
+    return launch_band<8, true>(x_t, x_snap, x_snap, arrive, wpack, y, g, stats, s);
 }
 
 hipError_t launch_bin_conv(int mode, int cw, const void* xsrc, const void* flip, unsigned int* tileflag,

@@ -60,6 +60,7 @@ struct rrm_layer {
     bool scat_auto = false; // ... and does when "path" is automatic
     void* wsc = nullptr;    // weights packed for it
     unsigned int* sc_arrive = nullptr;  // its arrival counters (one per position block)
+    unsigned int* bin_arrive = nullptr;  // binary single-launch step: arrival counter per stream
     size_t touched_bytes = 0;
     BinGeom bg{};
     FcGeom fg{};
@@ -94,10 +95,10 @@ struct rrm_layer {
     int prof_n = 0;
     bool prof_on = false;
     // options
-    int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0, opt_conv_kernel = 0;
+    int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0, opt_conv_kernel = 0, opt_bin_fused = 1;
 
     ~rrm_layer() {
-        void* ptrs[] = {wpack, wpos, wsc, sc_arrive, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, fresh, zero16, fc_arrive, fc_part, csc_ptr, csc_row, csc_val, stats};
+        void* ptrs[] = {wpack, wpos, wsc, sc_arrive, bin_arrive, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, fresh, zero16, fc_arrive, fc_part, csc_ptr, csc_row, csc_val, stats};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
         for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
@@ -574,6 +575,20 @@ rrm_status setup_bin(rrm_layer* L, const std::vector<unsigned char>& w) {
     g.bth_in = (std::max(g.band_rows, 1) - 1) * s.stride + s.kh;
     g.btw_in = (g.wo - 1) * s.stride + s.kw;
     g.magic_btw = magic_for(g.btw_in);
+    // The band kernel can run the whole step in one launch when every input position lies inside the window of
+    // the band that owns its row (band k owns input rows k*R*stride .. (k+1)*R*stride - 1, the last band the rest):
+    // then each position is compared and counted exactly once, and whole 16-byte vectors are compared.
+    g.fused_ok = 0;
+    if (g.band_rows > 0 && g.vec4) {
+        const bool cols = g.btw_in - s.pad >= s.w;
+        const bool rows_mid = g.nbands == 1 || s.stride <= s.kh - s.pad;
+        const bool rows_last = (g.nbands - 1) * g.band_rows * s.stride - s.pad + g.bth_in >= s.h;
+        g.fused_ok = (cols && rows_mid && rows_last) ? 1 : 0;
+    }
+    if (g.fused_ok) {
+        rrm_status st2 = dalloc((size_t)s.n * sizeof(unsigned int), (void**)&L->bin_arrive);
+        if (st2 != RRM_OK) return st2;
+    }
     const int ntaps = s.kh * s.kw;
     // filter words: [group][co/8][slab][tap][co%8][4 words]
     std::vector<unsigned int> pack((size_t)s.groups * g.nob8 * g.nslab * ntaps * 8 * 4, 0u);
@@ -877,6 +892,11 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
         if ((st = prof_mark(L, 0, s)) != RRM_OK) return st;
         if (L->dtype == RRM_BIN_I32) {
             const int cw = bin_cw(L);
+            if (L->bg.fused_ok && L->opt_bin_fused) {
+                // one launch: compare, popcount products of the changed positions, commit
+                if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;  // (no separate difference kernel: its time is reported as 0)
+                RRM_HIP(launch_bin_band_fused(cw, x_t, L->x_snap, L->bin_arrive, L->wpack, L->y_snap, L->bg, L->stats, s));
+            } else {
             const bool band = L->bg.band_rows > 0;  // (the band kernel reads the flip words itself: no tile stamps)
             RRM_HIP(launch_scan(L->dtype, x_t, L->x_snap, L->d0, L->d1, L->bitmap, L->tileflag,
                                 band ? 0u : (unsigned int)bin_consumers(cw, L->bg), L->sg, L->stats, s));
@@ -886,6 +906,7 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
             else
                 RRM_HIP(launch_bin_conv(MODE_DELTA, cw, L->x_snap, L->d0, L->tileflag, L->wpack, nullptr, L->y_snap, L->bg,
                                         L->stats, s));
+            }
         } else if (use_scatter(L)) {
             // one launch: compare, products of the changed positions, atomic accumulation, commit
             if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;  // (no separate scan kernel: its time is reported as 0)
@@ -1016,6 +1037,7 @@ rrm_status rrm_reset(rrm_layer* L, void* hip_stream) {
         RRM_HIP(launch_fill_word(L->fresh, 16, 1u, s));
         if (L->touched) RRM_HIP(launch_fill_word(L->touched, round16(L->touched_bytes), 0x01010101u, s));
     }
+    if (L->bin_arrive) RRM_HIP(launch_fill_zero(L->bin_arrive, round16((size_t)L->shape.n * sizeof(unsigned int)), s));
     if (L->sc_arrive)
         RRM_HIP(launch_fill_zero(L->sc_arrive, round16((size_t)((L->sc.npos_total + L->sc.PB - 1) / L->sc.PB) * sizeof(unsigned int)), s));
     if (L->fc_arrive) RRM_HIP(launch_fill_zero(L->fc_arrive, round16((size_t)L->shape.n * sizeof(unsigned int)), s));
@@ -1075,6 +1097,9 @@ rrm_status rrm_set_option(rrm_layer* L, const char* key, long value) {
             return fail(RRM_ERR_OPTION, "fc_sparse_weights: the layer holds no non-zero lists (more than half of its weights "
                                          "are non-zero, or c_out is above 24576)");
         L->use_csc = value == 1;
+    } else if (k == "bin_single_launch") {
+        if (L->dtype != RRM_BIN_I32 || (value != 0 && value != 1)) return fail(RRM_ERR_OPTION, "bin_single_launch is 0 or 1, for binary layers");
+        L->opt_bin_fused = (int)value;
     } else if (k == "bin_cout_per_wave") {
         if (value != 0 && value != 8 && value != 16) return fail(RRM_ERR_OPTION, "bin_cout_per_wave must be 0, 8 or 16");
         L->opt_bin_cw = (int)value;

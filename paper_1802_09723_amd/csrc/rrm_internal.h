@@ -168,6 +168,7 @@ struct BinGeom {
     unsigned int magic_btw;    // same for d = btw_in
     unsigned int magic_nslab;  // same for d = nslab
     int vec4;                  // 1: a group's words per position are whole 16-byte vectors (wg % 4 == 0, wpp % 4 == 0)
+    int fused_ok;              // 1: the band kernel can run the whole step (compare and commit included)
 };
 
 struct FcGeom {
@@ -243,6 +244,8 @@ int bin_consumers(int cw, const BinGeom& g);     // workgroups per tile of the b
 size_t bin_band_lds_bytes(const BinGeom& g, int band_rows);
 hipError_t launch_bin_band(int cw, const void* xsrc, const void* flip, const void* wpack, void* y, const BinGeom& g,
                            DevStats* stats, hipStream_t s);
+hipError_t launch_bin_band_fused(int cw, const void* x_t, void* x_snap, unsigned int* arrive, const void* wpack, void* y,
+                                 const BinGeom& g, DevStats* stats, hipStream_t s);
 
 hipError_t launch_fill_bias(int is_float, void* y, const void* bias, long long rows, int c_out, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);

@@ -314,7 +314,11 @@ def _random_bin_shapes(count, seed):
 def test_random_binary_shapes(idx):
     shp = _random_bin_shapes(10, 777)[idx]
     seq = S.random_layer(8300 + idx, shp, S.BIN, T=4, frac=0.1, block=2)
-    run_sequence(seq, check_dense=(0, 3))
+    st, _ = run_sequence(seq, check_dense=(0, 3))
+    # the same with a difference kernel in front of the band kernel: same results, same change counts
+    st2, _ = run_sequence(seq, check_dense=(), bin_single_launch=0)
+    assert (st2["changed_elems"], st2["changed_units"], st2["active_tiles"]) == \
+        (st["changed_elems"], st["changed_units"], st["active_tiles"])
 
 
 def test_binary_band_list_longer_than_one_pass_and_wide_layer_on_the_tile_kernel():
@@ -327,6 +331,9 @@ def test_binary_band_list_longer_than_one_pass_and_wide_layer_on_the_tile_kernel
     seq = S.random_layer(8502, S.conv_shape(30, 26, 128, 48, 3, 1, 1, 1, n=3), S.BIN, T=4, frac=0.2, block=4)
     st, _ = run_sequence(seq, check_dense=(0, 3))
     assert st["tile_positions"] == 1
+    st2, _ = run_sequence(seq, check_dense=(), bin_single_launch=0)
+    assert (st2["changed_elems"], st2["changed_units"], st2["active_tiles"]) == \
+        (st["changed_elems"], st["changed_units"], st["active_tiles"])
     wide = S.conv_shape(6, 300, 256, 16, 3, 1, 1, 1)
     seq = S.random_layer(8503, wide, S.BIN, T=3, frac=0.05, block=4)
     st, _ = run_sequence(seq, check_dense=(0, 2))
