@@ -153,7 +153,7 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
  *   "bf16_terms"  BF16 conv: 2 = difference carried as hi+lo bf16 pair (default), 1 = hi only
  *   "dense_switch_pct"  INT8 / BF16 conv: a delta step whose changes touch more than this percentage of the
  *                 4x4 output blocks recomputes the whole projection (same result; cheaper than reading and
- *                 re-writing most of it); 1..100, 100 = never; defaults 62 (int8) / 40 (bf16) for the window-tile
+ *                 re-writing most of it); 1..100, 100 = never; defaults 75 (int8) / 40 (bf16) for the window-tile
  *                 kernel, which decides per launch, and 90 / 50 for the position-gather kernel, which decides per
  *                 work unit
  *   "conv_kernel" INT8 / BF16 conv: 0 = automatic (the window-tile kernel), 1 = window-tile kernel (4x4 output

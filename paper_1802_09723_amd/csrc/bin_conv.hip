@@ -20,11 +20,16 @@
 // the output positions whose window sees one (ballot compaction into LDS) and deals that list to the lanes 64
 // at a time: a wavefront's lanes are all output positions with work to do, wherever in the band they lie, so
 // the work follows the changed positions instead of the 8x8 tiles they fall into.
+#include <algorithm>
+#include <mutex>
+
 #include "rrm_internal.h"
 
 namespace rrm {
 
 namespace {
+
+constexpr int BAND_THREADS = 512;  // the band kernel's workgroup: eight wavefronts
 
 // t + popcount(v) in one instruction (v_bcnt_u32_b32 adds its second operand; the compiler otherwise counts
 // into a fresh register and adds pairs of counts with a third instruction)
@@ -166,12 +171,12 @@ __global__ __launch_bounds__(256) void bin_conv_kernel(const unsigned int* __res
     }
 }
 
-// the band kernel's inner part: NP x 64 listed output positions (lane l takes entries first + l, first + 64 + l)
+// the band kernel's inner part: NP x 64 listed output positions (lane l takes entries first + l, first + 128 + l)
 // against the CW output channels of this wavefront; the filter words of a (slab, tap) are loaded once for all NP
-template <int CW, int NP>
+template <int CW, int NP, bool WL>
 __device__ __forceinline__ void band_items(const unsigned int* A, const unsigned int* B, const unsigned short* list,
-                                           int first, int cnt, const uint4* __restrict__ wpack, int* y,
-                                           const BinGeom& g, int b, int oy0, int grp, int co_w, int lane) {
+                                           int first, int cnt, const uint4* __restrict__ wpack, const uint4* wl, int* y,
+                                           const BinGeom& g, int b, int oy0, int grp, int co_w, int lane, int wave) {
     const int ntaps = g.kh * g.kw;
     const long long ob8 = (long long)grp * g.nob8 + co_w / 8;
     const bool vec = (g.c_out & 3) == 0 && (g.og & 3) == 0;
@@ -180,7 +185,7 @@ __device__ __forceinline__ void band_items(const unsigned int* A, const unsigned
     int tot[NP][CW];
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
-        const int e = first + p * 64 + lane;
+        const int e = first + p * 128 + lane;
         valid[p] = e < cnt;
         const int q = list[valid[p] ? e : 0];
         oyl[p] = q / g.wo;
@@ -208,10 +213,17 @@ __device__ __forceinline__ void band_items(const unsigned int* A, const unsigned
                 popm[p] = popc_acc(a[p].w | bb[p].w, popc_acc(a[p].z | bb[p].z, popc_acc(a[p].y | bb[p].y, popc_acc(a[p].x | bb[p].x, popm[p]))));
 #pragma unroll
             for (int o8 = 0; o8 < CW / 8; ++o8) {
-                const uint4* wp = wpack + (((ob8 + o8) * g.nslab + slab) * ntaps + tap) * 8;
+                // filter words of eight output channels: from the workgroup's copy in LDS (every lane reads the same
+                // address: a broadcast, and plain LDS reads pipeline where scalar loads make the wavefront wait), or
+                // through scalar loads
+                const uint4* wp = WL ? wl + ((slab * ntaps + tap) * 4 + wave) * CW + o8 * 8
+                                     : wpack + (((ob8 + o8) * g.nslab + slab) * ntaps + tap) * 8;
+                uint4 wq[8];  // all eight reads in flight before the first is used
+#pragma unroll
+                for (int o = 0; o < 8; ++o) wq[o] = wp[o];
 #pragma unroll
                 for (int o = 0; o < 8; ++o) {
-                    const uint4 w = wp[o];
+                    const uint4 w = wq[o];
 #pragma unroll
                     for (int p = 0; p < NP; ++p) {
                         int t = tot[p][o8 * 8 + o];
@@ -252,8 +264,8 @@ __device__ __forceinline__ void band_items(const unsigned int* A, const unsigned
 // mask is their XOR, formed while the window is staged (no difference kernel, no flip buffer); the change counts
 // are taken over the input rows a band owns; and the workgroup of a stream that finishes staging last (arrival
 // counter) copies the frame into the stored input, when nobody reads the old one any more, and rearms the counter.
-template <int CW, bool FUSED>
-__global__ __launch_bounds__(256) void bin_band_kernel(const unsigned int* __restrict__ xsrc,
+template <int CW, bool FUSED, bool WL>
+__global__ __launch_bounds__(BAND_THREADS) void bin_band_kernel(const unsigned int* __restrict__ xsrc,
                                                        const unsigned int* flip, unsigned int* snap,
                                                        unsigned int* arrive,
                                                        const uint4* __restrict__ wpack, int* y, BinGeom g,
@@ -263,32 +275,49 @@ __global__ __launch_bounds__(256) void bin_band_kernel(const unsigned int* __res
     unsigned int* A = reinterpret_cast<unsigned int*>(smem);
     unsigned int* B = A + npos * g.pitch;
     unsigned char* posany = reinterpret_cast<unsigned char*>(B + npos * g.pitch);     // input position holds a flip
-    unsigned short* list = reinterpret_cast<unsigned short*>(posany + ((npos + 3) & ~3));  // active output positions
-    __shared__ unsigned int s_wc[4], s_prev;
+    unsigned short* list = reinterpret_cast<unsigned short*>(posany + ((npos + 15) & ~15));  // active output positions
+    // (WL) the workgroup's filter words, [slab][tap][4 * CW channels], behind the list (16-byte aligned)
+    uint4* wl = reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(list) + (((size_t)g.band_rows * g.wo * 2 + 15) & ~(size_t)15));
+    __shared__ unsigned int s_wc[BAND_THREADS / 64], s_prev;
 
-    const int b = (int)blockIdx.x / g.nbands, band = (int)blockIdx.x - b * g.nbands;
+    // grid: x = list split (fastest, so the workgroups that share a band start together), y = channel block,
+    // z = stream x band
+    const int sb = (int)blockIdx.z, zsplit = (int)blockIdx.x, nsplit = (int)gridDim.x;
+    const int b = sb / g.nbands, band = sb - b * g.nbands;
     const int nblk = (g.og + 4 * CW - 1) / (4 * CW);
     const int grp = blockIdx.y / nblk;
     const int blk = blockIdx.y - grp * nblk;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // eight wavefronts: four channel sub-blocks (cwave) times two halves of the list (phalf)
+    const int cwave = wave & 3, phalf = wave >> 2;
     const int oy0 = band * g.band_rows;
     const int rows = min(g.band_rows, g.ho - oy0);
     const int iy0 = oy0 * g.stride - g.pad, ix0 = -g.pad;
     const int wg4 = g.nslab * 4;
 
-    for (int i = tid; i < npos; i += 256) posany[i] = 0;
+    for (int i = tid; i < npos; i += BAND_THREADS) posany[i] = 0;
+    if (WL) {
+        const int nit = g.nslab * g.kh * g.kw;
+        for (int i = tid; i < nit * 4 * CW; i += BAND_THREADS) {
+            const int it = i / (4 * CW), c = i - it * (4 * CW);
+            const int co = blk * 4 * CW + c;  // channel within the group
+            uint4 w = make_uint4(0, 0, 0, 0);
+            if (co < g.nob8 * 8) w = wpack[(((long long)grp * g.nob8 + co / 8) * nit + it) * 8 + (co & 7)];
+            wl[i] = w;
+        }
+    }
     __syncthreads();
     // (FUSED) input rows whose changes this band counts, by the workgroup of the band's first channel block
     const int own_lo = oy0 * g.stride, own_hi = band == g.nbands - 1 ? g.h : (oy0 + g.band_rows) * g.stride;
-    const bool count_here = FUSED && blk == 0 && blockIdx.z == 0;
+    const bool count_here = FUSED && blk == 0 && zsplit == 0;
     unsigned int nbits = 0, nunits = 0;
     // ---- stage A = m & x and B = m & ~x of the band's input window ------------------------------
     if (g.vec4) {
         // four words at a time, both loads issued whatever the mask holds (independent loads, several in flight)
         const int units = npos * g.nslab;
 #pragma unroll 4
-        for (int u = tid; u < units; u += 256) {
+        for (int u = tid; u < units; u += BAND_THREADS) {
             const int hp = (int)(g.magic_nslab ? __umulhi((unsigned int)u, g.magic_nslab) : (unsigned int)u), sl = u - hp * g.nslab;
             const int hy = (int)(g.magic_btw ? __umulhi((unsigned int)hp, g.magic_btw) : (unsigned int)hp), hx = hp - hy * g.btw_in;
             const int iy = iy0 + hy, ix = ix0 + hx;
@@ -311,7 +340,7 @@ __global__ __launch_bounds__(256) void bin_band_kernel(const unsigned int* __res
         }
     } else {
         const int units = npos * wg4;
-        for (int u = tid; u < units; u += 256) {
+        for (int u = tid; u < units; u += BAND_THREADS) {
             const int hp = (int)(g.magic_wg4 ? __umulhi((unsigned int)u, g.magic_wg4) : (unsigned int)u), wd = u - hp * wg4;
             const int hy = (int)(g.magic_btw ? __umulhi((unsigned int)hp, g.magic_btw) : (unsigned int)hp), hx = hp - hy * g.btw_in;
             const int iy = iy0 + hy, ix = ix0 + hx;
@@ -339,11 +368,11 @@ __global__ __launch_bounds__(256) void bin_band_kernel(const unsigned int* __res
                 nunits += __shfl_xor(nunits, o);
             }
             if (lane == 0 && nunits) {
-                atomicAdd(&stats[blockIdx.x & (STAT_SLOTS - 1)].changed_elems, (unsigned long long)nbits);
-                atomicAdd(&stats[blockIdx.x & (STAT_SLOTS - 1)].changed_units, (unsigned long long)nunits);
+                atomicAdd(&stats[sb & (STAT_SLOTS - 1)].changed_elems, (unsigned long long)nbits);
+                atomicAdd(&stats[sb & (STAT_SLOTS - 1)].changed_units, (unsigned long long)nunits);
             }
         }
-        if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {  // one launch = one delta step
+        if (sb == 0 && blockIdx.y == 0 && zsplit == 0 && tid == 0) {  // one launch = one delta step
             atomicAdd(&stats[0].delta_steps, 1ull);
             atomicAdd(&stats[0].total_tiles, (unsigned long long)g.n * g.ho * g.wo);
         }
@@ -351,7 +380,7 @@ __global__ __launch_bounds__(256) void bin_band_kernel(const unsigned int* __res
     // ---- list the output positions of the band whose window holds a flip ------------------------
     const int nout = rows * g.wo;
     int cnt = 0;
-    for (int base = 0; base < nout; base += 256) {
+    for (int base = 0; base < nout; base += BAND_THREADS) {
         const int q = base + tid;
         bool act = false;
         if (q < nout) {
@@ -364,31 +393,39 @@ __global__ __launch_bounds__(256) void bin_band_kernel(const unsigned int* __res
         const unsigned long long mask = __ballot(act);
         if (lane == 0) s_wc[wave] = (unsigned int)__popcll(mask);
         __syncthreads();
-        const unsigned int c0 = s_wc[0], c1 = s_wc[1], c2 = s_wc[2], c3 = s_wc[3];
-        const unsigned int wbase = (unsigned int)cnt + (wave > 0 ? c0 : 0u) + (wave > 1 ? c1 : 0u) + (wave > 2 ? c2 : 0u);
+        unsigned int wbase = (unsigned int)cnt, all = 0;
+#pragma unroll
+        for (int w = 0; w < BAND_THREADS / 64; ++w) {
+            const unsigned int c = s_wc[w];
+            if (w < wave) wbase += c;
+            all += c;
+        }
         if (act) list[wbase + __popcll(mask & ((1ull << lane) - 1ull))] = (unsigned short)q;
-        cnt += (int)(c0 + c1 + c2 + c3);
+        cnt += (int)all;
         __syncthreads();  // (the counts are overwritten in the next round; after the last one: the list is complete)
     }
-    if (cnt > 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0)
-        atomicAdd(&stats[blockIdx.x & (STAT_SLOTS - 1)].active_tiles, (unsigned long long)cnt);
+    if (cnt > 0 && blockIdx.y == 0 && zsplit == 0 && tid == 0)
+        atomicAdd(&stats[sb & (STAT_SLOTS - 1)].active_tiles, (unsigned long long)cnt);
 
-    const int co_w = blk * 4 * CW + wave * CW;  // first output channel of this wavefront in the group
+    // The list is dealt in 64-entry chunks: of every four consecutive chunks the first half of the wavefronts takes
+    // the even ones and the second half the odd ones (so a list of up to 128 entries is one chunk each, not two
+    // for one half), two chunks per pass where a half has two (they share the filter words).
+    const int co_w = blk * 4 * CW + cwave * CW;  // first output channel of this wavefront in the group
     if (co_w < g.og) {
-        for (int first = (int)blockIdx.z * 128; first < cnt; first += (int)gridDim.z * 128) {
-            if (cnt - first > 64)
-                band_items<CW, 2>(A, B, list, first, cnt, wpack, y, g, b, oy0, grp, co_w, lane);
+        for (int first = zsplit * 256 + phalf * 64; first < cnt; first += nsplit * 256) {
+            if (first + 128 < cnt)
+                band_items<CW, 2, WL>(A, B, list, first, cnt, wpack, wl, y, g, b, oy0, grp, co_w, lane, cwave);
             else
-                band_items<CW, 1>(A, B, list, first, cnt, wpack, y, g, b, oy0, grp, co_w, lane);
+                band_items<CW, 1, WL>(A, B, list, first, cnt, wpack, wl, y, g, b, oy0, grp, co_w, lane, cwave);
         }
     }
     if (FUSED) {
         // commit: the stream's last workgroup to finish staging (s_prev was published by the list's barriers)
-        if (s_prev == (unsigned int)g.nbands * gridDim.y * gridDim.z - 1u) {
+        if (s_prev == (unsigned int)g.nbands * gridDim.y * (unsigned int)nsplit - 1u) {
             const long long words = (long long)g.h * g.w * g.wpp;  // (a multiple of four: whole 16-byte vectors)
             const uint4* src = reinterpret_cast<const uint4*>(xsrc + (long long)b * words);
             uint4* dst = reinterpret_cast<uint4*>(snap + (long long)b * words);
-            for (long long i = tid; i < words / 4; i += 256) dst[i] = src[i];
+            for (long long i = tid; i < words / 4; i += BAND_THREADS) dst[i] = src[i];
             if (tid == 0) arrive[b] = 0u;
         }
     }
@@ -413,24 +450,43 @@ int bin_consumers(int cw, const BinGeom& g) { return g.groups * ((g.og + 4 * cw 
 
 size_t bin_band_lds_bytes(const BinGeom& g, int band_rows) {
     const size_t npos = (size_t)((band_rows - 1) * g.stride + g.kh) * (size_t)((g.wo - 1) * g.stride + g.kw);
-    return 2 * npos * g.pitch * 4 + ((npos + 3) & ~(size_t)3) + (((size_t)band_rows * g.wo * 2 + 15) & ~(size_t)15);
+    const size_t wl = g.wlds ? (size_t)g.nslab * g.kh * g.kw * 64 * 16 : 0;  // filter words of 64 channels
+    return 2 * npos * g.pitch * 4 + ((npos + 15) & ~(size_t)15) + (((size_t)band_rows * g.wo * 2 + 15) & ~(size_t)15) + wl;
+}
+
+template <int CW, bool FUSED, bool WL>
+hipError_t launch_band_k(const void* xsrc, const void* flip, void* snap, unsigned int* arrive, const void* wpack, void* y,
+                         const BinGeom& g, DevStats* stats, hipStream_t s) {
+    const int nblk = (g.og + 4 * CW - 1) / (4 * CW);
+    // few streams: deal the band's list over several workgroups (each stages the window again: it is small)
+    const long long wgs = (long long)g.n * g.nbands * g.groups * nblk;
+    const int chunks = (g.band_rows * g.wo + 255) / 256;  // (a workgroup takes the list 256 entries at a time)
+    int z = (int)((2 * NUM_CU + wgs - 1) / wgs);
+    z = z < 1 ? 1 : (z > chunks ? chunks : z);
+    dim3 grid((unsigned int)z, (unsigned int)(g.groups * nblk), (unsigned int)(g.n * g.nbands));
+    const size_t lds = bin_band_lds_bytes(g, g.band_rows);
+    auto kern = bin_band_kernel<CW, FUSED, WL>;
+    if (lds > 64 * 1024) {
+        static std::mutex mu;
+        static size_t granted = 0;
+        std::lock_guard<std::mutex> lock(mu);
+        if (lds > granted) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            granted = lds;
+        }
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(BAND_THREADS), lds, s, static_cast<const unsigned int*>(xsrc),
+                       static_cast<const unsigned int*>(flip), static_cast<unsigned int*>(snap), arrive,
+                       static_cast<const uint4*>(wpack), static_cast<int*>(y), g, stats);
+    return hipGetLastError();
 }
 
 template <int CW, bool FUSED>
 hipError_t launch_band(const void* xsrc, const void* flip, void* snap, unsigned int* arrive, const void* wpack, void* y,
                        const BinGeom& g, DevStats* stats, hipStream_t s) {
-    const int nblk = (g.og + 4 * CW - 1) / (4 * CW);
-    // few streams: deal the band's list over several workgroups (each stages the window again: it is small)
-    const long long wgs = (long long)g.n * g.nbands * g.groups * nblk;
-    const int chunks = (g.band_rows * g.wo + 127) / 128;  // (a workgroup takes the list 128 entries at a time)
-    int z = (int)((2 * NUM_CU + wgs - 1) / wgs);
-    z = z < 1 ? 1 : (z > chunks ? chunks : z);
-    dim3 grid((unsigned int)(g.n * g.nbands), (unsigned int)(g.groups * nblk), (unsigned int)z);
-    hipLaunchKernelGGL((bin_band_kernel<CW, FUSED>), grid, dim3(256), bin_band_lds_bytes(g, g.band_rows), s,
-                       static_cast<const unsigned int*>(xsrc), static_cast<const unsigned int*>(flip),
-                       static_cast<unsigned int*>(snap), arrive, static_cast<const uint4*>(wpack), static_cast<int*>(y),
-                       g, stats);
-    return hipGetLastError();
+    if (g.wlds) return launch_band_k<CW, FUSED, true>(xsrc, flip, snap, arrive, wpack, y, g, stats, s);
+    return launch_band_k<CW, FUSED, false>(xsrc, flip, snap, arrive, wpack, y, g, stats, s);
 }
 
 // two launches: xsrc = the stored input after the difference kernel, flip = its flip buffer

@@ -556,9 +556,13 @@ rrm_status setup_bin(rrm_layer* L, const std::vector<unsigned char>& w) {
     // unit); as tall as fits when the streams alone fill the chip (a tall band wastes least on its halo rows and
     // fills its 64-lane chunks best), shorter -- down to 4 rows -- while there are fewer than two workgroups per
     // compute unit; no band at all = the tile kernel
+    // (the filter words of a workgroup's 64 channels go to LDS too when they take at most 40 KB; the budget is then
+    // 79 KB per workgroup, still two per compute unit)
+    g.wlds = (long long)g.nslab * s.kh * s.kw * 1024 <= 40 * 1024 ? 1 : 0;
+    const long long band_budget = g.wlds ? 79 * 1024 : 64 * 1024 - 64;
     g.band_rows = 0;
     for (int r = g.ho; r >= 1; --r)
-        if (bin_band_lds_bytes(g, r) <= 64 * 1024 - 64 && (long long)r * g.wo <= 65535) {
+        if ((long long)bin_band_lds_bytes(g, r) <= band_budget && (long long)r * g.wo <= 65535) {
             g.band_rows = r;
             break;
         }
@@ -570,6 +574,7 @@ rrm_status setup_bin(rrm_layer* L, const std::vector<unsigned char>& w) {
         g.band_rows = (g.ho + g.nbands - 1) / g.nbands;
         g.nbands = (g.ho + g.band_rows - 1) / g.band_rows;
     }
+    if ((long long)g.n * g.nbands > 65535) g.band_rows = 0;  // (stream x band is the grid's z dimension)
     g.vec4 = (g.wg % 4 == 0 && g.wpp % 4 == 0) ? 1 : 0;
     g.magic_nslab = magic_for(g.nslab);
     g.bth_in = (std::max(g.band_rows, 1) - 1) * s.stride + s.kh;
@@ -830,7 +835,7 @@ rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_sha
             // input, equal to x_t after the scan, is the source: only layers whose x layout is the kernel's)
             L->cg.xfull = L->cg.aligned ? static_cast<const unsigned char*>(L->x_snap) : nullptr;
             // (a bf16 delta multiplies two terms, a recomputation one: it pays off earlier)
-            L->cg.full_pct = dtype == RRM_BF16_F32 ? 40 : 62;
+            L->cg.full_pct = dtype == RRM_BF16_F32 ? 40 : 75;
             L->pg.xfull = static_cast<const unsigned char*>(L->x_snap);  // (its layers are always in x's layout)
             L->pg.full_pct = dtype == RRM_BF16_F32 ? 50 : 90;
             if ((st = select_conv_kernel(L, 0)) != RRM_OK) return bail(st);

@@ -169,6 +169,7 @@ struct BinGeom {
     unsigned int magic_nslab;  // same for d = nslab
     int vec4;                  // 1: a group's words per position are whole 16-byte vectors (wg % 4 == 0, wpp % 4 == 0)
     int fused_ok;              // 1: the band kernel can run the whole step (compare and commit included)
+    int wlds;                  // 1: the band kernel keeps its workgroup's filter words in LDS
 };
 
 struct FcGeom {
