@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIBDIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIBDIR, "librrm_hip.so")
-SOURCES = ["rrm_api.hip", "scan.hip", "conv_gather.hip", "conv_pos.hip", "conv_scatter.hip", "fc.hip", "bin_conv.hip", "aux.hip", "probe.hip"]
+SOURCES = ["rrm_api.hip", "scan.hip", "conv_gather.hip", "conv_pos.hip", "conv_scatter.hip", "fc.hip", "fc_batched.hip", "bin_conv.hip", "aux.hip", "probe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared", "-fvisibility=hidden",

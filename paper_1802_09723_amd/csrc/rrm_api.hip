@@ -83,6 +83,8 @@ struct rrm_layer {
     unsigned int* fc_arrive = nullptr;  // FC delta step: arrival counter per stream
     void* fc_part = nullptr;  // FC dense path: per-split partial sums [n][fc_nsplit][c_out_p]
     void *csc_ptr = nullptr, *csc_row = nullptr, *csc_val = nullptr;  // FC, pruned weights: non-zeros by column
+    void* w_rm = nullptr;     // FC with many streams: W in its own row-major layout, for the batched product
+    int opt_fc_batched = 1;
     bool csc_ok = false, use_csc = false;
     double w_density = 1.0;  // FC: share of non-zero weights
     int fc_nsplit = 0;
@@ -98,7 +100,7 @@ struct rrm_layer {
     int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0, opt_conv_kernel = 0, opt_bin_fused = 1;
 
     ~rrm_layer() {
-        void* ptrs[] = {wpack, wpos, wsc, sc_arrive, bin_arrive, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, fresh, zero16, fc_arrive, fc_part, csc_ptr, csc_row, csc_val, stats};
+        void* ptrs[] = {wpack, wpos, wsc, sc_arrive, bin_arrive, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, fresh, zero16, fc_arrive, fc_part, csc_ptr, csc_row, csc_val, w_rm, stats};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
         for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
@@ -664,6 +666,14 @@ rrm_status setup_fc(rrm_layer* L, const std::vector<unsigned char>& w) {
             L->csc_ok = true;
         }
     }
+    // many streams: the layer runs as one product on the matrix cores, from W in its own layout, with the
+    // difference of all streams in d0 (d1: the low bf16 term)
+    if (fc_batched_ok(L->dtype, g)) {
+        if ((st = upload(w.data(), (size_t)s.c_in * s.c_out * es, &L->w_rm)) != RRM_OK) return st;
+        const size_t xb = (size_t)s.n * s.c_in * es;
+        if ((st = dalloc(xb, &L->d0)) != RRM_OK) return st;
+        if (L->dtype == RRM_BF16_F32 && (st = dalloc(xb, &L->d1)) != RRM_OK) return st;
+    }
     // dense path: enough workgroups to keep memory busy (about 256 in total, at most 64 row splits per stream)
     L->fc_nsplit = std::max(1, std::min(64, 256 / (fc_dense_slices(L->dtype, g) * s.n)));
     if ((st = dalloc((size_t)s.n * L->fc_nsplit * g.c_out_p * 4, &L->fc_part)) != RRM_OK) return st;
@@ -711,7 +721,10 @@ rrm_status check_ptr(const void* p, const char* what) {
 // dense layer of Eq. 3 from x into y
 rrm_status enqueue_dense(rrm_layer* L, const void* x, void* y, hipStream_t st) {
     if (L->shape.kind == RRM_FC) {
-        RRM_HIP(launch_fc_dense(L->dtype, fc_splits(L), L->wpack, x, L->fc_part, L->bias, y, L->fg, st));
+        if (L->w_rm && L->opt_fc_batched)
+            RRM_HIP(launch_fc_batched_dense(L->dtype, L->w_rm, x, L->bias, y, L->fg, st));
+        else
+            RRM_HIP(launch_fc_dense(L->dtype, fc_splits(L), L->wpack, x, L->fc_part, L->bias, y, L->fg, st));
     } else if (L->dtype == RRM_BIN_I32) {
         RRM_HIP(launch_bin_conv(MODE_DENSE, bin_cw(L), x, nullptr, nullptr, L->wpack, L->bias, y, L->bg, L->stats, st));
     } else {
@@ -884,6 +897,12 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
         if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
     } else if (L->shape.kind == RRM_FC) {
         if ((st = prof_mark(L, 0, s)) != RRM_OK) return st;
+        if (L->w_rm && L->opt_fc_batched && !L->use_csc && L->fg.eps == 0.0f) {
+            // many streams: difference of all streams, then one product over W (two launches; the events bracket both)
+            if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
+            RRM_HIP(launch_fc_batched_delta(L->dtype, L->w_rm, x_t, L->x_snap, L->d0, L->d1, L->y_snap, L->fg, L->stats, s));
+            if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
+        } else {
         if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;  // (no separate scan kernel: its time is reported as 0)
         FcGeom fg = L->fg;
         if (L->use_csc) {
@@ -893,6 +912,7 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
         }
         RRM_HIP(launch_fc_delta(L->dtype, x_t, L->x_snap, L->wpack, L->y_snap, L->fc_arrive, fg, L->stats, s));
         if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
+        }
     } else {
         if ((st = prof_mark(L, 0, s)) != RRM_OK) return st;
         if (L->dtype == RRM_BIN_I32) {
@@ -1096,6 +1116,9 @@ rrm_status rrm_set_option(rrm_layer* L, const char* key, long value) {
         if (value != 0 && value != 1) return fail(RRM_ERR_OPTION, "profile must be 0 or 1");
         L->prof_on = value != 0;
         L->prof_n = 0;
+    } else if (k == "fc_batched") {
+        if (L->shape.kind != RRM_FC || (value != 0 && value != 1)) return fail(RRM_ERR_OPTION, "fc_batched is 0 or 1, for FC layers");
+        L->opt_fc_batched = (int)value;
     } else if (k == "fc_sparse_weights") {
         if (L->shape.kind != RRM_FC || (value != 0 && value != 1)) return fail(RRM_ERR_OPTION, "fc_sparse_weights is 0 or 1, for FC layers");
         if (value == 1 && !L->csc_ok)

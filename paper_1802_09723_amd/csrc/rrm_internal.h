@@ -184,6 +184,8 @@ struct FcGeom {
     const unsigned short* csc_row;
     const void* csc_val;
 };
+constexpr int FC_BATCH_MIN_STREAMS = 16;    // from this many streams on an FC layer runs as one product on the matrix cores
+constexpr int FC_BATCH_MAX_STREAMS = 256;   // (16 stream tiles of accumulators per wavefront)
 constexpr int FC_CSC_MAX_LDS = 96 * 1024;   // the pruned-weight kernel's update accumulators: c_out <= 24576
 
 // floor(u / d) through the reciprocal magic = floor(2^32 / d) + 1 (0 encodes d == 1).  The product's high word is
@@ -230,6 +232,11 @@ hipError_t launch_fc_delta(int dtype, const void* x_t, void* x_snap, const void*
 
 // dense FC layer: row/slice split into per-split partial sums (scratch `part`: [n][splits][c_out_p] 4-byte
 // values), then y = bias + the sum of the splits in a fixed order
+bool fc_batched_ok(int dtype, const FcGeom& g);
+hipError_t launch_fc_batched_dense(int dtype, const void* w_rm, const void* x, const void* bias, void* y, const FcGeom& g,
+                                   hipStream_t s);
+hipError_t launch_fc_batched_delta(int dtype, const void* w_rm, const void* x_t, void* x_snap, void* d0, void* d1, void* y,
+                                   const FcGeom& g, DevStats* stats, hipStream_t s);
 int fc_dense_slices(int dtype, const FcGeom& g);
 hipError_t launch_fc_dense(int dtype, int splits, const void* wT, const void* x, void* part, const void* bias, void* y,
                            const FcGeom& g, hipStream_t s);

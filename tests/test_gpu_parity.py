@@ -496,3 +496,18 @@ def test_fc_pruned_weights_walk_nonzeros_only(dtype):
     with pytest.raises(rrm.binding.RRMError):
         L.set_option("fc_sparse_weights", 1)
     L.destroy()
+
+
+@pytest.mark.parametrize("dtype", [S.I8, S.BF16])
+def test_fc_many_streams_as_one_product(dtype):
+    """FC layers with 16 or more streams run as one product on the matrix cores (dense layer and delta step): a
+    ragged stream count, one tile exactly, several tiles, the full-size fc7 at 64 streams; and the same handles on
+    the per-stream column walk."""
+    cases = [(S.fc_shape(192, 48, n=16), 0.3), (S.fc_shape(640, 272, n=37), 0.1), (S.fc_shape(4096, 4096, n=64), 0.05),
+             (S.fc_shape(128, 16, n=200), 0.5)]
+    for i, (shp, frac) in enumerate(cases):
+        seq = S.random_layer(8800 + i, shp, dtype, T=4, frac=frac)
+        st, _ = run_sequence(seq, check_dense=(0, 3), rel=1e-4)
+        assert st["delta_steps"] == 4
+        st2, _ = run_sequence(seq, check_dense=(3,), rel=1e-4, fc_batched=0)
+        assert st2["changed_elems"] == st["changed_elems"]
