@@ -73,6 +73,10 @@ def test_argument_errors_come_back_as_status_codes():
     assert L.rrm_step(None, None, None, None) == -1
     assert L.rrm_dense(None, None, None, None) == -1
     assert L.rrm_reset(None, None) == -1
+    assert L.rrm_stack_step(None, 0, None, None, None) == -1
+    assert L.rrm_dense_noalloc(None, None, None, None) == -1
+    assert L.rrm_aux_probe_copy(None, None, 0, None) == -1
+    assert L.rrm_aux_probe_mfma(0, None, 1, 1, None) == -1
     assert L.rrm_set_option(None, b"path", 0) == -1
     assert L.rrm_get_stats(None, None) == -1
     assert L.rrm_status_string(-9) == b"misaligned pointer"
