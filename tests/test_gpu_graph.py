@@ -152,3 +152,60 @@ def test_many_subtiles_power_of_two_grid():
     for s, want in ((0, want0), (15, want0), (16, want1), (17, want0), (255, want0), (256, want1)):
         assert_matches(got[s:s + 1].cpu().numpy(), want, S.I8, f"frame 1 stream {s}")
     L.destroy()
+
+
+def _replay_case(seq, **opts):
+    """A whole-sequence graph (ping-pong through the frames, so that it ends where it starts) of one layer, replayed
+    three times with eager steps and a reset in between; after every replay and eager step the stored projection is the
+    oracle's dense projection of the frame last stepped."""
+    import torch
+    from gpu_util import make_layer
+    L = make_layer(seq, **opts)
+    xs = [to_device(f, seq.dtype) for f in seq.frames]
+    want = [oracle.dense(seq.shape, seq.dtype, seq.weights, seq.bias, f) for f in seq.frames]
+    for x in xs:  # eager pass: the snapshot is at the last frame
+        L.step(x)
+    torch.cuda.synchronize()
+    T = len(xs)
+    order = list(range(T - 2, -1, -1)) + list(range(1, T))  # T-2 .. 0 .. T-1
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for k in order:
+            L.step(xs[k])
+    def check(k, what):
+        assert_matches(L.y_snapshot().cpu().numpy(), want[k], seq.dtype, f"{seq.name} {what}", 1e-3)
+    s0 = L.stats()["delta_steps"]
+    g.replay(); check(T - 1, "replay 1")
+    L.step(xs[0]); check(0, "eager step after replay 1")
+    L.step(xs[T - 1])
+    g.replay(); check(T - 1, "replay 2")
+    L.reset()
+    L.step(xs[T - 1]); check(T - 1, "first step after reset")
+    g.replay(); check(T - 1, "replay 3")
+    if seq.dtype != S.BIN:  # (a binary layer's first step after a reset is a dense one)
+        assert L.stats()["delta_steps"] == len(order) + 1  # (the reset cleared the counters; replays advance them)
+    L.destroy()
+
+
+@pytest.mark.parametrize("case", ["scatter_bf16", "scatter_i8", "binary_one_launch", "binary_two_launches", "fc_walk",
+                                  "fc_pruned", "fc_batched_i8", "fc_batched_bf16"])
+def test_single_layer_graphs_of_the_newer_paths_replay_correctly(case):
+    """The paths whose step keeps state on the device between launches (arrival counters that the last workgroup
+    rearms, stored inputs committed by whoever finishes last, difference buffers): captured once, replayed several
+    times, mixed with eager steps and a reset."""
+    if case == "scatter_bf16":
+        _replay_case(S.config2("r14", 0.10, T=5))
+    elif case == "scatter_i8":
+        _replay_case(S.config0(T=5), path=3)
+    elif case == "binary_one_launch":
+        _replay_case(S.config4("b14", 0.10, n=3, T=5))
+    elif case == "binary_two_launches":
+        _replay_case(S.config4("b14", 0.10, n=3, T=5), bin_single_launch=0)
+    elif case == "fc_walk":
+        _replay_case(S.config3("fc7", S.I8, 0.10, T=5))
+    elif case == "fc_pruned":
+        _replay_case(S.pruned(S.config3("fc7", S.BF16, 0.10, T=5), 0.1, 4242), fc_sparse_weights=1)
+    elif case == "fc_batched_i8":
+        _replay_case(S.random_layer(9101, S.fc_shape(1024, 512, n=40), S.I8, T=5, frac=0.1))
+    else:
+        _replay_case(S.random_layer(9102, S.fc_shape(512, 256, n=24), S.BF16, T=5, frac=0.1))
