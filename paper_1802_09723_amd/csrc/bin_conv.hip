@@ -448,12 +448,6 @@ hipError_t launch_one(const void* xsrc, const void* flip, unsigned int* tileflag
 
 int bin_consumers(int cw, const BinGeom& g) { return g.groups * ((g.og + 4 * cw - 1) / (4 * cw)); }
 
-size_t bin_band_lds_bytes(const BinGeom& g, int band_rows) {
-    const size_t npos = (size_t)((band_rows - 1) * g.stride + g.kh) * (size_t)((g.wo - 1) * g.stride + g.kw);
-    const size_t wl = g.wlds ? (size_t)g.nslab * g.kh * g.kw * 64 * 16 : 0;  // filter words of 64 channels
-    return 2 * npos * g.pitch * 4 + ((npos + 15) & ~(size_t)15) + (((size_t)band_rows * g.wo * 2 + 15) & ~(size_t)15) + wl;
-}
-
 template <int CW, bool FUSED, bool WL>
 hipError_t launch_band_k(const void* xsrc, const void* flip, void* snap, unsigned int* arrive, const void* wpack, void* y,
                          const BinGeom& g, DevStats* stats, hipStream_t s) {

@@ -536,62 +536,7 @@ rrm_status select_conv_kernel(rrm_layer* L, int which) {
 rrm_status setup_bin(rrm_layer* L, const std::vector<unsigned char>& w) {
     const rrm_shape& s = L->shape;
     BinGeom& g = L->bg;
-    g.n = s.n; g.h = s.h; g.w = s.w; g.c_out = s.c_out; g.kh = s.kh; g.kw = s.kw;
-    g.stride = s.stride; g.pad = s.pad; g.groups = s.groups;
-    g.wpp = s.c_in / 32;
-    g.wg = g.wpp / s.groups;
-    g.og = s.c_out / s.groups;
-    g.ho = (s.h + 2 * s.pad - s.kh) / s.stride + 1;
-    g.wo = (s.w + 2 * s.pad - s.kw) / s.stride + 1;
-    g.tiles_y = (g.ho + TILE - 1) / TILE;
-    g.tiles_x = (g.wo + TILE - 1) / TILE;
-    g.th_in = (TILE - 1) * s.stride + s.kh;
-    g.tw_in = (TILE - 1) * s.stride + s.kw;
-    g.nslab = (g.wg + 3) / 4;
-    g.pitch = g.nslab * 4 + 4;
-    g.nob8 = 2 * ((g.og + 15) / 16);
-    g.magic_wg4 = magic_for(g.nslab * 4);
-    g.magic_tw = magic_for(g.tw_in);
-    if ((long long)2 * g.th_in * g.tw_in * g.pitch * 4 > 64 * 1024)
-        return fail(RRM_ERR_SHAPE, "input window of one output tile does not fit LDS");
-    // delta step: bands of output rows whose window, flags and list fit 64 KB of LDS (two workgroups per compute
-    // unit); as tall as fits when the streams alone fill the chip (a tall band wastes least on its halo rows and
-    // fills its 64-lane chunks best), shorter -- down to 4 rows -- while there are fewer than two workgroups per
-    // compute unit; no band at all = the tile kernel
-    // (the filter words of a workgroup's 64 channels go to LDS too when they take at most 40 KB; the budget is then
-    // 79 KB per workgroup, still two per compute unit)
-    g.wlds = (long long)g.nslab * s.kh * s.kw * 1024 <= 40 * 1024 ? 1 : 0;
-    const long long band_budget = g.wlds ? 79 * 1024 : 64 * 1024 - 64;
-    g.band_rows = 0;
-    for (int r = g.ho; r >= 1; --r)
-        if ((long long)bin_band_lds_bytes(g, r) <= band_budget && (long long)r * g.wo <= 65535) {
-            g.band_rows = r;
-            break;
-        }
-    g.nbands = 1;
-    if (g.band_rows > 0) {
-        g.nbands = (g.ho + g.band_rows - 1) / g.band_rows;
-        const long long per_band = (long long)g.n * g.groups * ((g.og + 63) / 64);
-        while (per_band * g.nbands < 2 * NUM_CU && (g.ho + g.nbands) / (g.nbands + 1) >= 4) ++g.nbands;
-        g.band_rows = (g.ho + g.nbands - 1) / g.nbands;
-        g.nbands = (g.ho + g.band_rows - 1) / g.band_rows;
-    }
-    if ((long long)g.n * g.nbands > 65535) g.band_rows = 0;  // (stream x band is the grid's z dimension)
-    g.vec4 = (g.wg % 4 == 0 && g.wpp % 4 == 0) ? 1 : 0;
-    g.magic_nslab = magic_for(g.nslab);
-    g.bth_in = (std::max(g.band_rows, 1) - 1) * s.stride + s.kh;
-    g.btw_in = (g.wo - 1) * s.stride + s.kw;
-    g.magic_btw = magic_for(g.btw_in);
-    // The band kernel can run the whole step in one launch when every input position lies inside the window of
-    // the band that owns its row (band k owns input rows k*R*stride .. (k+1)*R*stride - 1, the last band the rest):
-    // then each position is compared and counted exactly once, and whole 16-byte vectors are compared.
-    g.fused_ok = 0;
-    if (g.band_rows > 0 && g.vec4) {
-        const bool cols = g.btw_in - s.pad >= s.w;
-        const bool rows_mid = g.nbands == 1 || s.stride <= s.kh - s.pad;
-        const bool rows_last = (g.nbands - 1) * g.band_rows * s.stride - s.pad + g.bth_in >= s.h;
-        g.fused_ok = (cols && rows_mid && rows_last) ? 1 : 0;
-    }
+    if (!bin_choose_shape(s, g)) return fail(RRM_ERR_SHAPE, "input window of one output tile does not fit LDS");
     if (g.fused_ok) {
         rrm_status st2 = dalloc((size_t)s.n * sizeof(unsigned int), (void**)&L->bin_arrive);
         if (st2 != RRM_OK) return st2;

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "rrm.h"
+#include "bin_shape.h"
 #include "pos_shape.h"
 
 namespace rrm {
@@ -149,29 +150,6 @@ struct ScatGeom {
     unsigned int* touched_all;  // device word set by every step of this path: "treat every output as written"
 };
 
-// Geometry of the binary (XNOR / popcount) convolution.
-struct BinGeom {
-    int n, h, w, c_out, kh, kw, stride, pad, groups;
-    int wpp;             // 32-bit words per input position (all groups)
-    int wg;              // words per position per group
-    int og;              // output channels per group
-    int ho, wo, tiles_y, tiles_x;
-    int th_in, tw_in;
-    int pitch;           // LDS words per staged position
-    int nslab;           // word slabs of 4 per group
-    int nob8;            // packed 8-channel filter blocks per group (og padded to 16)
-    unsigned int magic_wg4;    // floor(2^32/d)+1 for d = 4*nslab
-    unsigned int magic_tw;     // same for d = tw_in
-    // band kernel (delta step): bands of band_rows output rows over the full width; 0 rows = the layer's bands
-    // do not fit LDS and the delta step runs the tile kernel
-    int band_rows, nbands, bth_in, btw_in;
-    unsigned int magic_btw;    // same for d = btw_in
-    unsigned int magic_nslab;  // same for d = nslab
-    int vec4;                  // 1: a group's words per position are whole 16-byte vectors (wg % 4 == 0, wpp % 4 == 0)
-    int fused_ok;              // 1: the band kernel can run the whole step (compare and commit included)
-    int wlds;                  // 1: the band kernel keeps its workgroup's filter words in LDS
-};
-
 struct FcGeom {
     int n, c_in, c_out;
     int c_out_p;         // row pitch of the transposed weights (elements), multiple of per_vec
@@ -249,7 +227,6 @@ hipError_t launch_bin_conv(int mode, int cw, const void* xsrc, const void* flip,
                            const void* wpack, const void* bias, void* y, const BinGeom& g, DevStats* stats,
                            hipStream_t s);
 int bin_consumers(int cw, const BinGeom& g);     // workgroups per tile of the binary kernel
-size_t bin_band_lds_bytes(const BinGeom& g, int band_rows);
 hipError_t launch_bin_band(int cw, const void* xsrc, const void* flip, const void* wpack, void* y, const BinGeom& g,
                            DevStats* stats, hipStream_t s);
 hipError_t launch_bin_band_fused(int cw, const void* x_t, void* x_snap, unsigned int* arrive, const void* wpack, void* y,
