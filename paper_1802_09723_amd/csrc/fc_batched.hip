@@ -153,29 +153,45 @@ __global__ __launch_bounds__(WAVES * 64) void fc_batched_kernel(const unsigned c
         else
             return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
     };
-    for (int st0 = wave; st0 < nsteps; st0 += WAVES * U) {
+    // two register sets: the loads of the next U steps are issued before the current U steps are multiplied
+    struct Ops {
         uint4 a[U], bh[U][TMAX], bl[U][TERMS == 2 ? TMAX : 1];
+    };
+    auto load = [&](int st0, Ops& o) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int st = st0 + u * WAVES;
-            const long long off = (long long)(st < nsteps ? st : st0) * 64;  // (a step beyond the end re-reads the first: not used)
-            a[u] = *reinterpret_cast<const uint4*>(wp + off);
+            const long long off = (long long)(st < nsteps ? st : wave) * 64;  // (a step beyond the end re-reads the first: not used)
+            o.a[u] = *reinterpret_cast<const uint4*>(wp + off);
 #pragma unroll
             for (int t = 0; t < TMAX; ++t)
                 if (t < ntiles) {
-                    bh[u][t] = *reinterpret_cast<const uint4*>(bp0[t] + off);
-                    if (TERMS == 2) bl[u][t] = *reinterpret_cast<const uint4*>(bp1[t] + off);
+                    o.bh[u][t] = *reinterpret_cast<const uint4*>(bp0[t] + off);
+                    if (TERMS == 2) o.bl[u][t] = *reinterpret_cast<const uint4*>(bp1[t] + off);
                 }
         }
+    };
+    auto multiply = [&](int st0, const Ops& o) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (st0 + u * WAVES >= nsteps) break;
 #pragma unroll
             for (int t = 0; t < TMAX; ++t)
                 if (t < ntiles) {
-                    acc[t] = mma(a[u], bh[u][t], acc[t]);
-                    if (TERMS == 2) acc[t] = mma(a[u], bl[u][t], acc[t]);
+                    acc[t] = mma(o.a[u], o.bh[u][t], acc[t]);
+                    if (TERMS == 2) acc[t] = mma(o.a[u], o.bl[u][t], acc[t]);
                 }
+        }
+    };
+    Ops ra, rb;
+    constexpr int STRIDE = WAVES * U;
+    load(wave, ra);
+    for (int st0 = wave; st0 < nsteps; st0 += 2 * STRIDE) {
+        if (st0 + STRIDE < nsteps) load(st0 + STRIDE, rb);
+        multiply(st0, ra);
+        if (st0 + STRIDE < nsteps) {
+            if (st0 + 2 * STRIDE < nsteps) load(st0 + 2 * STRIDE, ra);
+            multiply(st0 + STRIDE, rb);
         }
     }
     // ---- the wavefronts' sums, added in a fixed order ---------------------------------------------------------
@@ -226,9 +242,9 @@ void launch_batched(const void* w_rm, const void* b0, const void* b1, const void
     const unsigned char* p1 = static_cast<const unsigned char*>(b1);
     // (two-term products hold twice the operands: half the steps in flight)
     if (ntiles <= 4)
-        hipLaunchKernelGGL((fc_batched_kernel<DT, DELTA, TERMS, 4, 8, TERMS == 2 ? 2 : 4>), grid, dim3(512), 0, s, w, p0, p1, bias, y, g, ntiles);
+        hipLaunchKernelGGL((fc_batched_kernel<DT, DELTA, TERMS, 4, 8, TERMS == 2 ? 1 : 2>), grid, dim3(512), 0, s, w, p0, p1, bias, y, g, ntiles);
     else if (ntiles <= 8)
-        hipLaunchKernelGGL((fc_batched_kernel<DT, DELTA, TERMS, 8, 8, TERMS == 2 ? 1 : 2>), grid, dim3(512), 0, s, w, p0, p1, bias, y, g, ntiles);
+        hipLaunchKernelGGL((fc_batched_kernel<DT, DELTA, TERMS, 8, 8, 1>), grid, dim3(512), 0, s, w, p0, p1, bias, y, g, ntiles);
     else
         hipLaunchKernelGGL((fc_batched_kernel<DT, DELTA, TERMS, 16, 4, 1>), grid, dim3(256), 0, s, w, p0, p1, bias, y, g, ntiles);
 }
