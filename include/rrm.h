@@ -97,7 +97,12 @@ typedef struct {
 /* Create a layer handle (Eq. 3 defines the layer; Sec. 3.2 the state it keeps).
  *   weights  layout and element type as above; host or device; copied and repacked.
  *   bias     c_out values (int32 or float32), host or device, may be NULL (= 0); copied.
- *   shape    validated; unsupported combinations give RRM_ERR_SHAPE.
+ *   shape    validated; unsupported combinations give RRM_ERR_SHAPE.  A convolution keeps the input window of
+ *            a 4 x 4 output sub-tile (3*stride + kh rows, 3*stride + kw columns, one 16-byte channel chunk or
+ *            more) and that chunk's weights of every filter tap in on-chip memory.  Of the windows up to
+ *            11 x 11 at strides up to 4, all fit except BF16 11 x 11 at stride 4 with 16 or more channels per
+ *            group; a layer that does not fit is refused here, with a message.  BIN layers keep the window of
+ *            an 8 x 8 output tile (7*stride + kh rows) twice: 152 KB bounds it.
  *   out      receives the handle.  The initial state is I_0 = 0 (Algorithm 1, first line) and
  *            P_0 = b, so the first rrm_step yields the dense result of its frame. */
 rrm_status rrm_layer_create(const void* weights, const void* bias, const rrm_shape* shape, int dtype,

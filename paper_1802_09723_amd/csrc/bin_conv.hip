@@ -437,7 +437,18 @@ hipError_t launch_one(const void* xsrc, const void* flip, unsigned int* tileflag
     const int nblk = (g.og + 4 * CW - 1) / (4 * CW);
     dim3 grid((unsigned int)(g.n * g.tiles_y * g.tiles_x), (unsigned int)(g.groups * nblk));
     const size_t lds = (size_t)2 * g.th_in * g.tw_in * g.pitch * sizeof(unsigned int);
-    hipLaunchKernelGGL((bin_conv_kernel<MODE, CW>), grid, dim3(256), lds, s, static_cast<const unsigned int*>(xsrc),
+    auto kern = bin_conv_kernel<MODE, CW>;
+    if (lds > 64 * 1024) {  // (large strided windows; at most BIN_TILE_MAX_LDS, checked at create)
+        static std::mutex mu;
+        static size_t granted = 0;
+        std::lock_guard<std::mutex> lock(mu);
+        if (lds > granted) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            granted = lds;
+        }
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, static_cast<const unsigned int*>(xsrc),
                        static_cast<const unsigned int*>(flip), tileflag,
                        static_cast<const uint4*>(wpack), static_cast<const int*>(bias), static_cast<int*>(y), g,
                        stats);

@@ -8,6 +8,7 @@
 namespace rrm {
 
 constexpr int BIN_TILE = 8;        // output tile edge of the tile kernel
+constexpr long long BIN_TILE_MAX_LDS = 152 * 1024;  // both window copies of one tile (160 KB per workgroup, less static use)
 constexpr int BIN_NUM_CU = 256;    // compute units of the MI355X
 
 struct BinGeom {
@@ -63,7 +64,7 @@ inline bool bin_choose_shape(const rrm_shape& s, BinGeom& g) {
     g.nob8 = 2 * ((g.og + 15) / 16);
     g.magic_wg4 = bin_magic_for(g.nslab * 4);
     g.magic_tw = bin_magic_for(g.tw_in);
-    if ((long long)2 * g.th_in * g.tw_in * g.pitch * 4 > 64 * 1024) return false;
+    if ((long long)2 * g.th_in * g.tw_in * g.pitch * 4 > BIN_TILE_MAX_LDS) return false;
     // delta step: bands of output rows whose window, flags and list fit the LDS budget (two workgroups per compute
     // unit); as tall as fits when the streams alone fill the chip (a tall band wastes least on its halo rows and
     // fills its 64-lane chunks best), shorter -- down to 4 rows -- while there are fewer than two workgroups per

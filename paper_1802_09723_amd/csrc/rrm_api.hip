@@ -301,12 +301,12 @@ void choose_rotation(ConvGeom& t, int ntaps) {
 }
 
 // Fill the slab-dependent fields for (blocks, sub-tiles) per workgroup with the largest slab that fits
-// the LDS budget; false if none does.
-bool conv_try_shape(ConvGeom& g, int terms, int wg_cb, int nt, int ntaps, long long budget) {
+// the LDS budget; false if none does.  Several slabs: a slab is a whole number of K steps (4 pairs
+// each) unless `padded`, which lets every slab end in up to 3 zero-weight pairs.
+bool conv_try_shape(ConvGeom& g, int terms, int wg_cb, int nt, int ntaps, long long budget, bool padded = false) {
     const int max_units = CONV_MAX_STAGE_UNITS * CONV_THREADS;
     for (int sc = g.chunks; sc >= 1; --sc) {
-        // several slabs: a slab must be a whole number of K steps (4 pairs each)
-        if (sc < g.chunks && (sc * ntaps) % 4 != 0) continue;
+        if (!padded && sc < g.chunks && (sc * ntaps) % 4 != 0) continue;
         ConvGeom t = g;
         t.wg_cb = wg_cb;
         t.nt = nt;
@@ -415,6 +415,9 @@ rrm_status setup_conv(rrm_layer* L, const std::vector<unsigned char>& w) {
     if (!ok)
         for (const Cand& c : cands)
             if (!ok) ok = conv_try_shape(g, terms, c.cb, c.nt, ntaps, 153 * 1024);
+    if (!ok)  // large filter windows: slabs of any chunk count, down to one sub-tile per workgroup
+        for (const Cand& c : {Cand{1, 8}, Cand{1, 4}, Cand{1, 2}, Cand{1, 1}})
+            if (!ok) ok = conv_try_shape(g, terms, c.cb, c.nt, ntaps, 153 * 1024, true);
     if (!ok) return fail(RRM_ERR_SHAPE, "input window of one output sub-tile does not fit LDS");
     return pack_conv(L, w);
 }

@@ -265,6 +265,44 @@ def test_random_conv_shapes(idx):
     run_sequence(seq, check_dense=(0, 3), conv_kernel=1)
 
 
+# Large filter windows and many channels: the weights of one slab of chunks and the input windows no longer fit
+# LDS together with slabs of whole K steps, so the layer runs with padded slabs and fewer sub-tiles per workgroup
+# (down to one for the 11 x 11 windows).  (kernel, stride, channels per group, groups, streams, height)
+LARGE_WINDOWS = [(5, 1, 64, 1, 2, 14), (5, 2, 96, 2, 1, 17), (7, 1, 96, 1, 1, 12), (7, 2, 64, 1, 3, 19),
+                 (3, 4, 64, 1, 2, 21), (3, 3, 128, 2, 1, 20), (11, 1, 32, 1, 1, 13), (11, 2, 16, 1, 2, 23),
+                 (11, 1, 64, 1, 1, 12), (7, 4, 512, 1, 1, 23)]
+
+
+@pytest.mark.parametrize("case", LARGE_WINDOWS, ids=lambda c: "k%ds%dc%dg%dn%dh%d" % c)
+@pytest.mark.parametrize("dt", [S.I8, S.BF16])
+def test_large_windows_with_many_channels(case, dt):
+    k, stride, cg, groups, n, h = case
+    shp = S.LayerShape(S.CONV, n, h, h + 3, cg * groups, 40 * groups, k, k, stride, k // 2, groups)
+    for frac in (0.05, 0.6):
+        seq = S.random_layer(7000 + k * stride + cg, shp, dt, T=3, frac=frac, block=2)
+        run_sequence(seq, check_dense=(0, 2))
+
+
+@pytest.mark.parametrize("case", [(5, 4, 96, 1, 1, 31), (11, 4, 128, 1, 1, 33), (7, 4, 384, 4, 1, 24), (9, 4, 192, 2, 5, 17),
+                                  (11, 3, 256, 1, 2, 30)], ids=lambda c: "k%ds%dc%dg%dn%dh%d" % c)
+def test_binary_large_strided_windows(case):
+    """the 8 x 8 tile's window takes more than 64 KB of LDS (both copies): the tile kernel runs with the large
+    allocation, for the dense pass and, where no band fits, for the delta steps"""
+    k, stride, c_in, groups, n, h = case
+    shp = S.LayerShape(S.CONV, n, h, h + 5, c_in, 13 * groups, k, k, stride, k // 2, groups)
+    for frac in (0.02, 0.5):
+        seq = S.random_layer(7200 + k + stride, shp, S.BIN, T=3, frac=frac, block=2)
+        run_sequence(seq, check_dense=(0, 2))
+
+
+def test_window_too_large_for_lds_is_refused_with_a_message():
+    import paper_1802_09723_amd as rrm
+    shp = S.LayerShape(S.CONV, 1, 35, 38, 32, 40, 11, 11, 4, 5, 1)
+    seq = S.random_layer(7100, shp, S.BF16, T=1, frac=1.0)
+    with pytest.raises(rrm.binding.RRMError, match="does not fit LDS"):
+        make_layer(seq)
+
+
 def _random_pos_shapes(count, seed):
     """Seeded random shapes the position-gather kernel takes: stride 1, kernels 1..5 (also non-square), pads 0..2,
     groups 1..2, channel runs of 16-byte multiples (odd chunk counts too), outputs in fours, 1..40 streams."""
