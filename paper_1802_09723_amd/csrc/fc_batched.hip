@@ -2,13 +2,15 @@
 // streams' vectors [c_in x n], and it runs on the matrix cores with W read once for all streams.
 //
 // Dense layer (Eq. 3, FC form):      Y = b + W X^T
-// Delta step (Algorithm 1, FC branch): Y += W D^T with D = X_t - X_{t-1} for all streams, in two launches:
-//   fc_diff_kernel     writes D (int8: the byte differences; bf16: the fp32 difference split in two bf16 terms, hi
-//                      and lo), commits the stored input and counts the changes;
+// Delta step (Algorithm 1, FC branch), int8: Y += W D^T with D = X_t - X_{t-1} for all streams, in two launches:
+//   fc_diff_kernel     writes D (the byte differences), commits the stored input and counts the changes;
 //   fc_batched_kernel  multiplies.  With tens of streams the union of the changed columns is most of the matrix
 //                      (64 streams at 1 % each already touch half of the columns), so the product runs over all of
 //                      W: its cost is one pass over W whatever the density, a tenth of what n separate column walks
 //                      cost at 64 streams.
+// bf16: the fp32 difference of two bf16 values needs two bf16 terms (hi and lo), so the delta product would be two
+// passes of matrix instructions for the same pass over W that the layer itself takes; the step therefore commits,
+// counts and recomputes Y = b + W X_t^T (which is also free of the step-to-step rounding of an accumulated sum).
 // Shapes: v_mfma_i32_16x16x64_i8 / v_mfma_f32_16x16x32_bf16.  Lane l of a wavefront supplies 16 bytes of A (row
 // l % 16 of a 16-row block of W, k-group l / 16: contiguous in W's own row-major layout) and 16 bytes of B (stream
 // l % 16 of a 16-stream tile, same k-group: contiguous in a stream's vector), and receives rows 4 (l / 16) .. + 3
@@ -29,8 +31,9 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 
-// D = x_t - x_snap for every stream, x_snap <- x_t, change counts.  One thread per 16-byte unit.
-template <int DT>
+// D = x_t - x_snap for every stream, x_snap <- x_t, change counts.  One thread per 16-byte unit.  !WRITE_D: the commit
+// and the counts only (the step recomputes the layer from x_t).
+template <int DT, bool WRITE_D>
 __global__ __launch_bounds__(256) void fc_diff_kernel(const uint4* __restrict__ x_t, uint4* __restrict__ x_snap,
                                                       uint4* __restrict__ d0, uint4* __restrict__ d1, long long nvec,
                                                       unsigned long long n_cin, DevStats* __restrict__ stats) {
@@ -64,6 +67,7 @@ __global__ __launch_bounds__(256) void fc_diff_kernel(const uint4* __restrict__ 
                         const unsigned int xa = (aw[i] >> (16 * k)) & 0xFFFFu, xb = (sw[i] >> (16 * k)) & 0xFFFFu;
                         if (xa == xb) continue;
                         ++nchanged;
+                        if (!WRITE_D) continue;
                         const float d = __uint_as_float(xa << 16) - __uint_as_float(xb << 16);
                         // round-to-nearest-even bf16 of d, and of what is left
                         auto to_bf16 = [](float f) {
@@ -83,8 +87,10 @@ __global__ __launch_bounds__(256) void fc_diff_kernel(const uint4* __restrict__ 
             lo = make_uint4(lw[0], lw[1], lw[2], lw[3]);
             x_snap[v] = a;
         }
-        d0[v] = hi;
-        if (DT == RRM_BF16_F32) d1[v] = lo;
+        if (WRITE_D) {
+            d0[v] = hi;
+            if (DT == RRM_BF16_F32) d1[v] = lo;
+        }
     }
     // counts: wavefront, then workgroup, then one set of atomics
     __shared__ unsigned int s_n[4];
@@ -266,21 +272,23 @@ hipError_t launch_fc_batched_dense(int dtype, const void* w_rm, const void* x, c
     return hipGetLastError();
 }
 
-hipError_t launch_fc_batched_delta(int dtype, const void* w_rm, const void* x_t, void* x_snap, void* d0, void* d1, void* y,
-                                   const FcGeom& g, DevStats* stats, hipStream_t s) {
+hipError_t launch_fc_batched_delta(int dtype, const void* w_rm, const void* x_t, void* x_snap, void* d0, void* d1,
+                                   const void* bias, void* y, const FcGeom& g, DevStats* stats, hipStream_t s) {
     if (!fc_batched_ok(dtype, g) || g.eps != 0.0f) return hipErrorInvalidValue;
     const int esize = dtype == RRM_I8_I32 ? 1 : 2;
     const long long nvec = (long long)g.n * g.c_in * esize / 16;
     const unsigned long long n_cin = (unsigned long long)g.n * (unsigned long long)g.c_in;
     dim3 dgrid((unsigned int)((nvec + 255) / 256)), dblock(256);
     if (dtype == RRM_I8_I32) {
-        hipLaunchKernelGGL(fc_diff_kernel<RRM_I8_I32>, dgrid, dblock, 0, s, (const uint4*)x_t, (uint4*)x_snap, (uint4*)d0,
+        hipLaunchKernelGGL((fc_diff_kernel<RRM_I8_I32, true>), dgrid, dblock, 0, s, (const uint4*)x_t, (uint4*)x_snap, (uint4*)d0,
                            (uint4*)d1, nvec, n_cin, stats);
         launch_batched<RRM_I8_I32, true, 1>(w_rm, d0, nullptr, nullptr, y, g, s);
     } else {
-        hipLaunchKernelGGL(fc_diff_kernel<RRM_BF16_F32>, dgrid, dblock, 0, s, (const uint4*)x_t, (uint4*)x_snap, (uint4*)d0,
-                           (uint4*)d1, nvec, n_cin, stats);
-        launch_batched<RRM_BF16_F32, true, 2>(w_rm, d0, d1, nullptr, y, g, s);
+        // bf16: the difference needs two bf16 terms, i.e. two products over all of W, while the layer itself (Eq. 3)
+        // is one -- and it does not accumulate rounding from step to step.  The step commits, counts and recomputes.
+        hipLaunchKernelGGL((fc_diff_kernel<RRM_BF16_F32, false>), dgrid, dblock, 0, s, (const uint4*)x_t, (uint4*)x_snap,
+                           (uint4*)nullptr, (uint4*)nullptr, nvec, n_cin, stats);
+        launch_batched<RRM_BF16_F32, false, 1>(w_rm, x_t, nullptr, bias, y, g, s);
     }
     return hipGetLastError();
 }

@@ -614,13 +614,11 @@ rrm_status setup_fc(rrm_layer* L, const std::vector<unsigned char>& w) {
             L->csc_ok = true;
         }
     }
-    // many streams: the layer runs as one product on the matrix cores, from W in its own layout, with the
-    // difference of all streams in d0 (d1: the low bf16 term)
+    // many streams: the layer runs as one product on the matrix cores, from W in its own layout; int8 steps
+    // multiply the difference of all streams (d0), bf16 steps recompute from x_t
     if (fc_batched_ok(L->dtype, g)) {
         if ((st = upload(w.data(), (size_t)s.c_in * s.c_out * es, &L->w_rm)) != RRM_OK) return st;
-        const size_t xb = (size_t)s.n * s.c_in * es;
-        if ((st = dalloc(xb, &L->d0)) != RRM_OK) return st;
-        if (L->dtype == RRM_BF16_F32 && (st = dalloc(xb, &L->d1)) != RRM_OK) return st;
+        if (L->dtype == RRM_I8_I32 && (st = dalloc((size_t)s.n * s.c_in * es, &L->d0)) != RRM_OK) return st;
     }
     // dense path: enough workgroups to keep memory busy (about 256 in total, at most 64 row splits per stream)
     L->fc_nsplit = std::max(1, std::min(64, 256 / (fc_dense_slices(L->dtype, g) * s.n)));
@@ -846,9 +844,10 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
     } else if (L->shape.kind == RRM_FC) {
         if ((st = prof_mark(L, 0, s)) != RRM_OK) return st;
         if (L->w_rm && L->opt_fc_batched && !L->use_csc && L->fg.eps == 0.0f) {
-            // many streams: difference of all streams, then one product over W (two launches; the events bracket both)
+            // many streams: difference (or commit) of all streams, then one product over W (two launches; the events
+            // bracket both)
             if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
-            RRM_HIP(launch_fc_batched_delta(L->dtype, L->w_rm, x_t, L->x_snap, L->d0, L->d1, L->y_snap, L->fg, L->stats, s));
+            RRM_HIP(launch_fc_batched_delta(L->dtype, L->w_rm, x_t, L->x_snap, L->d0, L->d1, L->bias, L->y_snap, L->fg, L->stats, s));
             if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
         } else {
         if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;  // (no separate scan kernel: its time is reported as 0)

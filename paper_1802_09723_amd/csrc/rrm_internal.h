@@ -213,8 +213,8 @@ hipError_t launch_fc_delta(int dtype, const void* x_t, void* x_snap, const void*
 bool fc_batched_ok(int dtype, const FcGeom& g);
 hipError_t launch_fc_batched_dense(int dtype, const void* w_rm, const void* x, const void* bias, void* y, const FcGeom& g,
                                    hipStream_t s);
-hipError_t launch_fc_batched_delta(int dtype, const void* w_rm, const void* x_t, void* x_snap, void* d0, void* d1, void* y,
-                                   const FcGeom& g, DevStats* stats, hipStream_t s);
+hipError_t launch_fc_batched_delta(int dtype, const void* w_rm, const void* x_t, void* x_snap, void* d0, void* d1,
+                                   const void* bias, void* y, const FcGeom& g, DevStats* stats, hipStream_t s);
 int fc_dense_slices(int dtype, const FcGeom& g);
 hipError_t launch_fc_dense(int dtype, int splits, const void* wT, const void* x, void* part, const void* bias, void* y,
                            const FcGeom& g, hipStream_t s);
