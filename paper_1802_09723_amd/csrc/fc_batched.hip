@@ -4,7 +4,7 @@
 // Dense layer (Eq. 3, FC form):      Y = b + W X^T
 // Delta step (Algorithm 1, FC branch), int8: Y += W D^T with D = X_t - X_{t-1} for all streams, in two launches:
 //   fc_diff_kernel     writes D (the byte differences), commits the stored input and counts the changes;
-//   fc_batched_kernel  multiplies.  With tens of streams the union of the changed columns is most of the matrix
+//   fc_bt_kernel       multiplies.  With tens of streams the union of the changed columns is most of the matrix
 //                      (64 streams at 1 % each already touch half of the columns), so the product runs over all of
 //                      W: its cost is one pass over W whatever the density, a tenth of what n separate column walks
 //                      cost at 64 streams.
@@ -15,9 +15,9 @@
 // l % 16 of a 16-row block of W, k-group l / 16: contiguous in W's own row-major layout) and 16 bytes of B (stream
 // l % 16 of a 16-stream tile, same k-group: contiguous in a stream's vector), and receives rows 4 (l / 16) .. + 3
 // of column l % 16: four consecutive output channels of one stream, one 16-byte store.
-// Workgroup = one 16-row block of W, eight (four) wavefronts on interleaved 64-byte k-steps; their sums are added through
-// LDS in a fixed order (bit-reproducible fp32), so c_out / 16 workgroups each read their rows of W exactly once and
-// the streams' vectors (a few hundred KB, resident in L2) once each.
+// The k range is split over workgroups (fc_bt_kernel, partial sums per split) and a second launch adds the splits
+// in a fixed order (fc_bt_reduce_kernel: bit-reproducible fp32).
+#include <algorithm>
 #include <type_traits>
 
 #include "rrm_internal.h"
@@ -101,9 +101,10 @@ __global__ __launch_bounds__(256) void fc_diff_kernel(const uint4* __restrict__ 
     if (threadIdx.x == 0) {
         const unsigned int tot = s_n[0] + s_n[1] + s_n[2] + s_n[3];
         if (tot) {
-            atomicAdd(&stats->changed_elems, (unsigned long long)tot);
-            atomicAdd(&stats->changed_units, (unsigned long long)tot);
-            atomicAdd(&stats->active_tiles, (unsigned long long)tot);
+            DevStats* slot = stats + (blockIdx.x & (STAT_SLOTS - 1));
+            atomicAdd(&slot->changed_elems, (unsigned long long)tot);
+            atomicAdd(&slot->changed_units, (unsigned long long)tot);
+            atomicAdd(&slot->active_tiles, (unsigned long long)tot);
         }
         if (blockIdx.x == 0) {  // one launch = one delta step
             atomicAdd(&stats->delta_steps, 1ull);
@@ -112,167 +113,231 @@ __global__ __launch_bounds__(256) void fc_diff_kernel(const uint4* __restrict__ 
     }
 }
 
-// Y (+)= W B^T.  w: [c_out][c_in] row-major; b0 (b1): [n][c_in] (the streams' vectors, or the difference's terms);
-// y: [n][c_out].  DELTA: y is read and added to (TERMS planes of B); else y = bias + product.
-// TMAX bounds the 16-stream tiles (accumulators), WAVES wavefronts share the k-steps of the rows, and every
-// wavefront issues the loads of U steps before it multiplies the first: the loop is bound by memory latency otherwise
-// (a step is one 64-byte piece of a row and of every stream's vector).
-template <int DT, bool DELTA, int TERMS, int TMAX, int WAVES, int U>
-__global__ __launch_bounds__(WAVES * 64) void fc_batched_kernel(const unsigned char* __restrict__ w,
-                                                                const unsigned char* __restrict__ b0,
-                                                                const unsigned char* __restrict__ b1,
-                                                                const void* __restrict__ bias_v, void* y_v, FcGeom g,
-                                                                int ntiles) {
+// Partial products P[split] = W[:, k range of the split] B[:, k range]^T.  w: [c_out][c_in] row-major; b: [n][c_in]
+// (the streams' vectors, or their differences); part: [splits][n][c_out] 4-byte sums.
+// Workgroup (blockIdx.x, blockIdx.y) = (64-row group of W, split of the k range); wavefront v of its four takes the
+// 16-row block v of the group.  The k range is walked in chunks of CK steps (a step = 64 bytes of a row and of every
+// stream's vector).  Per chunk the workgroup copies the streams' bytes into LDS once -- all four wavefronts multiply
+// the same streams, and read from memory they would cost four times the bytes of W -- while every lane reads its own
+// 16 bytes of W per step straight into registers.  Loads run two chunks ahead of the matrix instructions, LDS is
+// double-buffered, one barrier per chunk.
+// LDS layout: (step of the chunk, stream) -> 80 bytes (64 used): the 16 streams that a group of 16 lanes reads for
+// one k-group start 20 banks apart and fall on 16 different 4-bank groups.
+template <int DT, int TMAX, int CK>
+__global__ __launch_bounds__(256) void fc_bt_kernel(const unsigned char* __restrict__ w, const unsigned char* __restrict__ b,
+                                                    void* __restrict__ part_v, FcGeom g, int cps) {
     constexpr int ESIZE = DT == RRM_I8_I32 ? 1 : 2;
-    constexpr int KSTEP = 64 / ESIZE;  // elements per MFMA step: 64 int8 / 32 bf16 (64 bytes of a row)
+    constexpr int KSTEP = 64 / ESIZE;  // elements per step: 64 int8 / 32 bf16
+    constexpr int NS = 16 * TMAX;      // stream slots of the LDS layout
+    constexpr int UPT = (NS * CK * 4 + 255) / 256;  // 16-byte units of the streams' chunk per thread
+    constexpr int SPP = 256 / (CK * 4);             // streams covered by one pass of the 256 threads
+    static_assert(256 % (CK * 4) == 0, "a pass of the threads covers whole streams");
     typedef typename std::conditional<DT == RRM_I8_I32, int, float>::type val_t;
     typedef typename std::conditional<DT == RRM_I8_I32, v4i, v4f>::type acc_t;
-    __shared__ acc_t red[WAVES - 1][TMAX][64];
+    __shared__ uint4 xs[2][CK * NS * 5];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int o0 = (int)blockIdx.x * 16;
-    const int row = o0 + (lane & 15);  // (c_out is a multiple of 16: every row exists)
-    const int kg = lane >> 4;          // k-group: bytes 16 kg .. 16 kg + 15 of a 64-byte step
+    const int kg = lane >> 4;  // k-group: bytes 16 kg .. 16 kg + 15 of a step
     const long long row_bytes = (long long)g.c_in * ESIZE;
-    const unsigned char* wp = w + (long long)row * row_bytes + kg * 16;
     const int nsteps = g.c_in / KSTEP;
-    // this lane's stream in tile t is 16 t + lane % 16; streams beyond n read stream n - 1 (their columns are not stored)
-    const unsigned char* bp0[TMAX];
-    const unsigned char* bp1[TMAX];
+    const int kbeg = (int)blockIdx.y * cps * CK;
+    const int kend = min(kbeg + cps * CK, nsteps);
+    const int nch = (kend - kbeg + CK - 1) / CK;  // (>= 1: the host launches no empty split)
+    // W: row of this lane (blocks beyond c_out read the last row; their sums are not stored)
+    const int o0 = (int)blockIdx.x * 64 + wave * 16;
+    const int row = min(o0 + (lane & 15), g.c_out - 1);
+    // (byte offsets in 32 bits from the uniform bases: W and the streams' vectors are below 4 GB, checked at create)
+    const unsigned int aoff = (unsigned int)row * (unsigned int)row_bytes + kg * 16;
+    // streams' chunk: unit tid + 256 i = (stream tid / (4 CK) + SPP i, step (tid / 4) % CK, k-group tid % 4)
+    const int xc = (tid >> 2) % CK;
+    unsigned int xp[UPT], xm[UPT];
+    int xoff[UPT];
 #pragma unroll
-    for (int t = 0; t < TMAX; ++t) {
-        int s = 16 * t + (lane & 15);
-        s = s < g.n ? s : g.n - 1;
-        bp0[t] = b0 + (long long)s * row_bytes + kg * 16;
-        bp1[t] = TERMS == 2 ? b1 + (long long)s * row_bytes + kg * 16 : nullptr;
+    for (int i = 0; i < UPT; ++i) {
+        const int s = tid / (CK * 4) + i * SPP;
+        xm[i] = (unsigned int)-(int)(s < g.n);  // (a stream beyond n reads offset 0: never stored)
+        xp[i] = (unsigned int)min(s, g.n - 1) * (unsigned int)row_bytes + (tid & 3) * 16;  // (streams beyond n: the last one's bytes, unused)
+        xoff[i] = (xc * NS + s) * 5 + (tid & 3);
     }
-
     acc_t acc[TMAX];
 #pragma unroll
     for (int t = 0; t < TMAX; ++t)
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc[t][i] = 0;
-
-    auto mma = [&](const uint4& a, const uint4& b, acc_t c) {
+    auto mma = [&](const uint4& a, const uint4& bb, acc_t c) {
         if constexpr (DT == RRM_I8_I32)
-            return __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, a), __builtin_bit_cast(v4i, b), c, 0, 0, 0);
+            return __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, a), __builtin_bit_cast(v4i, bb), c, 0, 0, 0);
         else
-            return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+            return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, bb), c, 0, 0, 0);
     };
-    // two register sets: the loads of the next U steps are issued before the current U steps are multiplied
-    struct Ops {
-        uint4 a[U], bh[U][TMAX], bl[U][TERMS == 2 ? TMAX : 1];
+    struct Set {
+        uint4 a[CK], x[UPT];
     };
-    auto load = [&](int st0, Ops& o) __attribute__((always_inline)) {
+    // Loads and LDS stores are unconditional and free of branches, so that the counted waits stay exact (a wait
+    // placed after a branch would be for all outstanding loads, the newest included, and the prefetch would be
+    // worth nothing): a chunk beyond the split, or a stream slot beyond the tiles in use, reads offset 0 -- one
+    // cached line for the whole wavefront -- and the bytes it stores to LDS are never multiplied.  A step beyond
+    // the range re-reads the last step: loaded, never multiplied.
+    auto issue = [&](int chunk, Set& s) __attribute__((always_inline)) {
+        const int k0 = kbeg + chunk * CK;
+        const unsigned int lm = (unsigned int)-(int)(chunk < nch);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int st = st0 + u * WAVES;
-            const long long off = (long long)(st < nsteps ? st : wave) * 64;  // (a step beyond the end re-reads the first: not used)
-            o.a[u] = *reinterpret_cast<const uint4*>(wp + off);
+        for (int c = 0; c < CK; ++c)
+            s.a[c] = *reinterpret_cast<const uint4*>(w + (size_t)((aoff + (unsigned int)min(k0 + c, nsteps - 1) * 64u) & lm));
 #pragma unroll
-            for (int t = 0; t < TMAX; ++t)
-                if (t < ntiles) {
-                    o.bh[u][t] = *reinterpret_cast<const uint4*>(bp0[t] + off);
-                    if (TERMS == 2) o.bl[u][t] = *reinterpret_cast<const uint4*>(bp1[t] + off);
-                }
+        for (int i = 0; i < UPT; ++i)
+            s.x[i] = *reinterpret_cast<const uint4*>(b + (size_t)((xp[i] + (unsigned int)min(k0 + xc, nsteps - 1) * 64u) & lm & xm[i]));
+    };
+    auto stage = [&](const Set& s, int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < UPT; ++i) xs[buf][xoff[i]] = s.x[i];
+    };
+    const int boff = (lane & 15) * 5 + kg;
+    // (TMAX is the number of 16-stream tiles in use or the next instantiated count: a tile beyond the streams
+    // multiplies the bytes that the masked loads brought -- its sums are not stored -- so the products of a chunk
+    // are one straight line of LDS reads and matrix instructions)
+    auto compute = [&](const uint4(&a)[CK], int buf, int chunk) __attribute__((always_inline)) {
+        const int k0 = kbeg + chunk * CK;
+        if (k0 + CK <= kend) {
+#pragma unroll
+            for (int c = 0; c < CK; ++c)
+#pragma unroll
+                for (int t = 0; t < TMAX; ++t) acc[t] = mma(a[c], xs[buf][(c * NS + 16 * t) * 5 + boff], acc[t]);
+        } else {  // the ragged last chunk of the range
+#pragma unroll
+            for (int c = 0; c < CK; ++c) {
+                if (k0 + c >= kend) break;
+#pragma unroll
+                for (int t = 0; t < TMAX; ++t) acc[t] = mma(a[c], xs[buf][(c * NS + 16 * t) * 5 + boff], acc[t]);
+            }
         }
     };
-    auto multiply = [&](int st0, const Ops& o) __attribute__((always_inline)) {
+    // Two register sets: while chunk j is multiplied, chunks j + 1 and j + 2 are in flight.  Per chunk: multiply;
+    // the next chunk's streams go to the other LDS buffer (every wavefront finished reading it before the last
+    // barrier) and its rows of W to `acur`; the freed set is refilled; one barrier.
+    Set s0, s1;
+    uint4 acur[CK];
+    auto take = [&](const Set& s) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (st0 + u * WAVES >= nsteps) break;
-#pragma unroll
-            for (int t = 0; t < TMAX; ++t)
-                if (t < ntiles) {
-                    acc[t] = mma(o.a[u], o.bh[u][t], acc[t]);
-                    if (TERMS == 2) acc[t] = mma(o.a[u], o.bl[u][t], acc[t]);
-                }
-        }
+        for (int c = 0; c < CK; ++c) acur[c] = s.a[c];
     };
-    Ops ra, rb;
-    constexpr int STRIDE = WAVES * U;
-    load(wave, ra);
-    for (int st0 = wave; st0 < nsteps; st0 += 2 * STRIDE) {
-        if (st0 + STRIDE < nsteps) load(st0 + STRIDE, rb);
-        multiply(st0, ra);
-        if (st0 + STRIDE < nsteps) {
-            if (st0 + 2 * STRIDE < nsteps) load(st0 + 2 * STRIDE, ra);
-            multiply(st0 + STRIDE, rb);
-        }
-    }
-    // ---- the wavefronts' sums, added in a fixed order ---------------------------------------------------------
-    if (wave > 0) {
-#pragma unroll
-        for (int t = 0; t < TMAX; ++t)
-            if (t < ntiles) red[wave - 1][t][lane] = acc[t];
-    }
+    issue(0, s0);
+    issue(1, s1);
+    stage(s0, 0);
+    take(s0);
+    issue(2, s0);
     __syncthreads();
-    if (wave == 0) {
-        val_t* y = static_cast<val_t*>(y_v);
-        const val_t* bias = static_cast<const val_t*>(bias_v);
-        const int oc = o0 + 4 * (lane >> 4);  // this lane's four consecutive output channels
+    for (int j = 0; j < nch; j += 2) {
+        compute(acur, 0, j);
+        stage(s1, 1);
+        take(s1);
+        issue(j + 3, s1);
+        __syncthreads();
+        if (j + 1 < nch) compute(acur, 1, j + 1);
+        stage(s0, 0);
+        take(s0);
+        issue(j + 4, s0);
+        __syncthreads();
+    }
+    // this split's sums: rows 4 (lane / 16) .. + 3 of the block for stream lane % 16 of every tile
+    if (o0 < g.c_out) {
+        val_t* part = static_cast<val_t*>(part_v) + (long long)blockIdx.y * g.n * g.c_out;
+        const int oc = o0 + 4 * kg;
 #pragma unroll
         for (int t = 0; t < TMAX; ++t) {
-            if (t >= ntiles) continue;
-            acc_t sum = acc[t];
-#pragma unroll
-            for (int q = 0; q < WAVES - 1; ++q) {
-                const acc_t o = red[q][t][lane];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) sum[i] += o[i];
-            }
             const int s = 16 * t + (lane & 15);
-            if (s >= g.n) continue;
-            acc_t* yp = reinterpret_cast<acc_t*>(y + (long long)s * g.c_out + oc);  // (c_out % 16 == 0: 16-byte aligned)
-            acc_t base;
-            if (DELTA) {
-                base = *yp;
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) base[i] = bias ? bias[oc + i] : (val_t)0;
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) base[i] += sum[i];
-            *yp = base;
+            if (s < g.n) *reinterpret_cast<acc_t*>(part + (long long)s * g.c_out + oc) = acc[t];
         }
     }
 }
 
-template <int DT, bool DELTA, int TERMS>
-void launch_batched(const void* w_rm, const void* b0, const void* b1, const void* bias, void* y, const FcGeom& g,
-                    hipStream_t s) {
+// y = base + the splits' sums, added in the order of the splits (bit-reproducible fp32); base: y itself (delta step)
+// or the bias.  One thread per four consecutive output channels of one stream.
+template <int DT, bool DELTA>
+__global__ __launch_bounds__(256) void fc_bt_reduce_kernel(const void* __restrict__ part_v, const void* __restrict__ bias_v,
+                                                           void* y_v, long long nvec, int c_out4, int splits) {
+    typedef typename std::conditional<DT == RRM_I8_I32, v4i, v4f>::type acc_t;
+    const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= nvec) return;
+    const acc_t* part = static_cast<const acc_t*>(part_v);
+    acc_t sum = part[v];
+    for (int sp = 1; sp < splits; ++sp) {
+        const acc_t o = part[(long long)sp * nvec + v];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sum[i] += o[i];
+    }
+    acc_t* y = static_cast<acc_t*>(y_v);
+    acc_t base;
+    if (DELTA) {
+        base = y[v];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) base[i] = 0;
+        if (bias_v) base = static_cast<const acc_t*>(bias_v)[v % c_out4];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) base[i] += sum[i];
+    y[v] = base;
+}
+
+int bt_chunk(int ntiles) { return ntiles <= 4 ? 4 : ntiles <= 8 ? 2 : 1; }
+
+template <int DT, bool DELTA>
+void launch_batched(const void* w_rm, const void* b0, void* part, const void* bias, void* y, const FcGeom& g, hipStream_t s) {
     const int ntiles = (g.n + 15) / 16;
-    dim3 grid((unsigned int)(g.c_out / 16));
+    const int esize = DT == RRM_I8_I32 ? 1 : 2;
+    const int nsteps = g.c_in * esize / 64;
+    const int ck = bt_chunk(ntiles);
+    const int chunks = (nsteps + ck - 1) / ck;
+    const int cps = (chunks + fc_batched_splits(DT, g) - 1) / fc_batched_splits(DT, g);
+    const int splits = (chunks + cps - 1) / cps;  // (no empty split)
+    dim3 grid((unsigned int)((g.c_out + 63) / 64), (unsigned int)splits);
     const unsigned char* w = static_cast<const unsigned char*>(w_rm);
     const unsigned char* p0 = static_cast<const unsigned char*>(b0);
-    const unsigned char* p1 = static_cast<const unsigned char*>(b1);
-    // (two-term products hold twice the operands: half the steps in flight)
-    if (ntiles <= 4)
-        hipLaunchKernelGGL((fc_batched_kernel<DT, DELTA, TERMS, 4, 8, TERMS == 2 ? 1 : 2>), grid, dim3(512), 0, s, w, p0, p1, bias, y, g, ntiles);
-    else if (ntiles <= 8)
-        hipLaunchKernelGGL((fc_batched_kernel<DT, DELTA, TERMS, 8, 8, 1>), grid, dim3(512), 0, s, w, p0, p1, bias, y, g, ntiles);
-    else
-        hipLaunchKernelGGL((fc_batched_kernel<DT, DELTA, TERMS, 16, 4, 1>), grid, dim3(256), 0, s, w, p0, p1, bias, y, g, ntiles);
+#define RRM_BT(T, C)                                                                                                  \
+    if (ntiles <= T) {                                                                                                \
+        hipLaunchKernelGGL((fc_bt_kernel<DT, T, C>), grid, dim3(256), 0, s, w, p0, part, g, cps);                     \
+    } else
+    RRM_BT(1, 4) RRM_BT(2, 4) RRM_BT(3, 4) RRM_BT(4, 4) RRM_BT(6, 2) RRM_BT(8, 2) RRM_BT(12, 1) RRM_BT(16, 1) {}
+#undef RRM_BT
+    const long long nvec = (long long)g.n * g.c_out / 4;
+    hipLaunchKernelGGL((fc_bt_reduce_kernel<DT, DELTA>), dim3((unsigned int)((nvec + 255) / 256)), dim3(256), 0, s, part, bias, y,
+                       nvec, g.c_out / 4, splits);
 }
 
 }  // namespace
 
-bool fc_batched_ok(int dtype, const FcGeom& g) {
+// Splits of the k range: about one workgroup per compute unit, at least three chunks per split, and partial sums
+// (written and read once per split) of at most half the bytes of W.
+int fc_batched_splits(int dtype, const FcGeom& g) {
     const int esize = dtype == RRM_I8_I32 ? 1 : 2;
-    return g.n >= FC_BATCH_MIN_STREAMS && g.n <= FC_BATCH_MAX_STREAMS && g.c_out % 16 == 0 && (g.c_in * esize) % 64 == 0;
+    const int ck = bt_chunk((g.n + 15) / 16);
+    const int chunks = (g.c_in * esize / 64 + ck - 1) / ck;
+    const int groups = (g.c_out + 63) / 64;
+    int s = (NUM_CU + groups - 1) / groups;
+    s = std::min(s, chunks / 3);
+    s = std::min(s, g.c_in * esize / (16 * g.n));
+    return std::max(s, 1);
 }
 
-hipError_t launch_fc_batched_dense(int dtype, const void* w_rm, const void* x, const void* bias, void* y, const FcGeom& g,
-                                   hipStream_t s) {
+bool fc_batched_ok(int dtype, const FcGeom& g) {
+    const int esize = dtype == RRM_I8_I32 ? 1 : 2;
+    // (whole 16-row blocks and 64-byte steps; byte offsets into W in 32 bits)
+    return g.n >= FC_BATCH_MIN_STREAMS && g.n <= FC_BATCH_MAX_STREAMS && g.c_out % 16 == 0 && (g.c_in * esize) % 64 == 0 &&
+           (long long)g.c_in * esize * g.c_out <= 0xFFFFFFFFll;
+}
+
+hipError_t launch_fc_batched_dense(int dtype, const void* w_rm, const void* x, void* part, const void* bias, void* y,
+                                   const FcGeom& g, hipStream_t s) {
     if (!fc_batched_ok(dtype, g)) return hipErrorInvalidValue;
     if (dtype == RRM_I8_I32)
-        launch_batched<RRM_I8_I32, false, 1>(w_rm, x, nullptr, bias, y, g, s);
+        launch_batched<RRM_I8_I32, false>(w_rm, x, part, bias, y, g, s);
     else
-        launch_batched<RRM_BF16_F32, false, 1>(w_rm, x, nullptr, bias, y, g, s);
+        launch_batched<RRM_BF16_F32, false>(w_rm, x, part, bias, y, g, s);
     return hipGetLastError();
 }
 
-hipError_t launch_fc_batched_delta(int dtype, const void* w_rm, const void* x_t, void* x_snap, void* d0, void* d1,
+hipError_t launch_fc_batched_delta(int dtype, const void* w_rm, const void* x_t, void* x_snap, void* d0, void* part,
                                    const void* bias, void* y, const FcGeom& g, DevStats* stats, hipStream_t s) {
     if (!fc_batched_ok(dtype, g) || g.eps != 0.0f) return hipErrorInvalidValue;
     const int esize = dtype == RRM_I8_I32 ? 1 : 2;
@@ -281,14 +346,14 @@ hipError_t launch_fc_batched_delta(int dtype, const void* w_rm, const void* x_t,
     dim3 dgrid((unsigned int)((nvec + 255) / 256)), dblock(256);
     if (dtype == RRM_I8_I32) {
         hipLaunchKernelGGL((fc_diff_kernel<RRM_I8_I32, true>), dgrid, dblock, 0, s, (const uint4*)x_t, (uint4*)x_snap, (uint4*)d0,
-                           (uint4*)d1, nvec, n_cin, stats);
-        launch_batched<RRM_I8_I32, true, 1>(w_rm, d0, nullptr, nullptr, y, g, s);
+                           (uint4*)nullptr, nvec, n_cin, stats);
+        launch_batched<RRM_I8_I32, true>(w_rm, d0, part, nullptr, y, g, s);
     } else {
         // bf16: the difference needs two bf16 terms, i.e. two products over all of W, while the layer itself (Eq. 3)
         // is one -- and it does not accumulate rounding from step to step.  The step commits, counts and recomputes.
         hipLaunchKernelGGL((fc_diff_kernel<RRM_BF16_F32, false>), dgrid, dblock, 0, s, (const uint4*)x_t, (uint4*)x_snap,
                            (uint4*)nullptr, (uint4*)nullptr, nvec, n_cin, stats);
-        launch_batched<RRM_BF16_F32, false, 1>(w_rm, x_t, nullptr, bias, y, g, s);
+        launch_batched<RRM_BF16_F32, false>(w_rm, x_t, part, bias, y, g, s);
     }
     return hipGetLastError();
 }

@@ -81,6 +81,7 @@ struct rrm_layer {
     unsigned int* fresh = nullptr;     // conv: device word, non-zero until the first delta step has run (see FusedSrc)
     void* zero16 = nullptr;            // a block of zeros: source of staged units outside the image
     unsigned int* fc_arrive = nullptr;  // FC delta step: arrival counter per stream
+    void* fc_bpart = nullptr; // FC as one product (many streams): the k splits' partial sums [splits][n][c_out]
     void* fc_part = nullptr;  // FC dense path: per-split partial sums [n][fc_nsplit][c_out_p]
     void *csc_ptr = nullptr, *csc_row = nullptr, *csc_val = nullptr;  // FC, pruned weights: non-zeros by column
     void* w_rm = nullptr;     // FC with many streams: W in its own row-major layout, for the batched product
@@ -100,7 +101,7 @@ struct rrm_layer {
     int opt_path = 0, opt_wm = 0, opt_fc_splits = 0, opt_terms = 2, opt_bin_cw = 0, opt_conv_kernel = 0, opt_bin_fused = 1;
 
     ~rrm_layer() {
-        void* ptrs[] = {wpack, wpos, wsc, sc_arrive, bin_arrive, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, fresh, zero16, fc_arrive, fc_part, csc_ptr, csc_row, csc_val, w_rm, stats};
+        void* ptrs[] = {wpack, wpos, wsc, sc_arrive, bin_arrive, offtab, bias, x_snap, y_snap, d0, d1, xpad, bitmap, tileflag, touched, ctrl, fresh, zero16, fc_arrive, fc_part, fc_bpart, csc_ptr, csc_row, csc_val, w_rm, stats};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
         for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
@@ -619,6 +620,7 @@ rrm_status setup_fc(rrm_layer* L, const std::vector<unsigned char>& w) {
     if (fc_batched_ok(L->dtype, g)) {
         if ((st = upload(w.data(), (size_t)s.c_in * s.c_out * es, &L->w_rm)) != RRM_OK) return st;
         if (L->dtype == RRM_I8_I32 && (st = dalloc((size_t)s.n * s.c_in * es, &L->d0)) != RRM_OK) return st;
+        if ((st = dalloc((size_t)fc_batched_splits(L->dtype, g) * s.n * s.c_out * 4, &L->fc_bpart)) != RRM_OK) return st;
     }
     // dense path: enough workgroups to keep memory busy (about 256 in total, at most 64 row splits per stream)
     L->fc_nsplit = std::max(1, std::min(64, 256 / (fc_dense_slices(L->dtype, g) * s.n)));
@@ -668,7 +670,7 @@ rrm_status check_ptr(const void* p, const char* what) {
 rrm_status enqueue_dense(rrm_layer* L, const void* x, void* y, hipStream_t st) {
     if (L->shape.kind == RRM_FC) {
         if (L->w_rm && L->opt_fc_batched)
-            RRM_HIP(launch_fc_batched_dense(L->dtype, L->w_rm, x, L->bias, y, L->fg, st));
+            RRM_HIP(launch_fc_batched_dense(L->dtype, L->w_rm, x, L->fc_bpart, L->bias, y, L->fg, st));
         else
             RRM_HIP(launch_fc_dense(L->dtype, fc_splits(L), L->wpack, x, L->fc_part, L->bias, y, L->fg, st));
     } else if (L->dtype == RRM_BIN_I32) {
@@ -847,7 +849,7 @@ rrm_status rrm_step(rrm_layer* L, const void* x_t, void* y_out, void* hip_stream
             // many streams: difference (or commit) of all streams, then one product over W (two launches; the events
             // bracket both)
             if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;
-            RRM_HIP(launch_fc_batched_delta(L->dtype, L->w_rm, x_t, L->x_snap, L->d0, L->d1, L->bias, L->y_snap, L->fg, L->stats, s));
+            RRM_HIP(launch_fc_batched_delta(L->dtype, L->w_rm, x_t, L->x_snap, L->d0, L->fc_bpart, L->bias, L->y_snap, L->fg, L->stats, s));
             if ((st = prof_mark(L, 2, s)) != RRM_OK) return st;
         } else {
         if ((st = prof_mark(L, 1, s)) != RRM_OK) return st;  // (no separate scan kernel: its time is reported as 0)

@@ -211,9 +211,10 @@ hipError_t launch_fc_delta(int dtype, const void* x_t, void* x_snap, const void*
 // dense FC layer: row/slice split into per-split partial sums (scratch `part`: [n][splits][c_out_p] 4-byte
 // values), then y = bias + the sum of the splits in a fixed order
 bool fc_batched_ok(int dtype, const FcGeom& g);
-hipError_t launch_fc_batched_dense(int dtype, const void* w_rm, const void* x, const void* bias, void* y, const FcGeom& g,
-                                   hipStream_t s);
-hipError_t launch_fc_batched_delta(int dtype, const void* w_rm, const void* x_t, void* x_snap, void* d0, void* d1,
+int fc_batched_splits(int dtype, const FcGeom& g);  // splits of the k range; part: [splits][n][c_out] 4-byte sums
+hipError_t launch_fc_batched_dense(int dtype, const void* w_rm, const void* x, void* part, const void* bias, void* y,
+                                   const FcGeom& g, hipStream_t s);
+hipError_t launch_fc_batched_delta(int dtype, const void* w_rm, const void* x_t, void* x_snap, void* d0, void* part,
                                    const void* bias, void* y, const FcGeom& g, DevStats* stats, hipStream_t s);
 int fc_dense_slices(int dtype, const FcGeom& g);
 hipError_t launch_fc_dense(int dtype, int splits, const void* wT, const void* x, void* part, const void* bias, void* y,

@@ -549,3 +549,27 @@ def test_fc_many_streams_as_one_product(dtype):
         assert st["delta_steps"] == 4
         st2, _ = run_sequence(seq, check_dense=(3,), rel=1e-4, fc_batched=0)
         assert st2["changed_elems"] == st["changed_elems"]
+
+
+def _batched_fc_shapes():
+    """every stream-tile count the product kernel is built for (1, 2, 3, 4, 6, 8, 12, 16 tiles of 16 streams, and
+    ragged counts between them), row counts that are not multiples of the 64-row group, k ranges that leave a ragged
+    last chunk, one split and several"""
+    rng = S.rng_for(9100)
+    out = []
+    for n in (16, 17, 32, 33, 48, 64, 65, 90, 96, 100, 128, 129, 190, 200, 256):
+        for dt in (S.I8, S.BF16):
+            es = 1 if dt == S.I8 else 2
+            steps = int(rng.choice([1, 2, 3, 5, 7, 13, 24, 37, 50]))
+            c_out = 16 * int(rng.choice([1, 2, 3, 4, 5, 9, 17]))
+            out.append((S.fc_shape(steps * 64 // es, c_out, n=n), dt))
+    return out
+
+
+@pytest.mark.parametrize("idx", range(30))
+def test_fc_product_kernel_shapes(idx):
+    shp, dt = _batched_fc_shapes()[idx]
+    seq = S.random_layer(9100 + idx, shp, dt, T=3, frac=0.3)
+    st, _ = run_sequence(seq, check_dense=(0, 2), rel=1e-4)
+    assert st["delta_steps"] == 3
+
