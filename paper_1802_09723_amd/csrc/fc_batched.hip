@@ -16,7 +16,9 @@
 // l % 16 of a 16-stream tile, same k-group: contiguous in a stream's vector), and receives rows 4 (l / 16) .. + 3
 // of column l % 16: four consecutive output channels of one stream, one 16-byte store.
 // The k range is split over workgroups (fc_bt_kernel, partial sums per split) and a second launch adds the splits
-// in a fixed order (fc_bt_reduce_kernel: bit-reproducible fp32).
+// in a fixed order (fc_bt_reduce_kernel: bit-reproducible fp32).  (Adding them in the product kernel, by the last
+// split to arrive, needs device-scope fences around the arrival count; with those the kernel measured 28 us
+// slower on the 9216 x 4096 layer -- the second launch costs 4.)
 #include <algorithm>
 #include <type_traits>
 
@@ -119,7 +121,7 @@ __global__ __launch_bounds__(256) void fc_diff_kernel(const uint4* __restrict__ 
 // 16-row block v of the group.  The k range is walked in chunks of CK steps (a step = 64 bytes of a row and of every
 // stream's vector).  Per chunk the workgroup copies the streams' bytes into LDS once -- all four wavefronts multiply
 // the same streams, and read from memory they would cost four times the bytes of W -- while every lane reads its own
-// 16 bytes of W per step straight into registers.  Loads run two chunks ahead of the matrix instructions, LDS is
+// 16 bytes of W per step straight into registers.  Loads run four chunks ahead of the matrix instructions, LDS is
 // double-buffered, one barrier per chunk.
 // LDS layout: (step of the chunk, stream) -> 80 bytes (64 used): the 16 streams that a group of 16 lanes reads for
 // one k-group start 20 banks apart and fall on 16 different 4-bank groups.
@@ -203,6 +205,15 @@ __global__ __launch_bounds__(256) void fc_bt_kernel(const unsigned char* __restr
             for (int c = 0; c < CK; ++c)
 #pragma unroll
                 for (int t = 0; t < TMAX; ++t) acc[t] = mma(a[c], xs[buf][(c * NS + 16 * t) * 5 + boff], acc[t]);
+            // issue order: the LDS reads of a step ahead of the matrix instructions of the step before it (one
+            // wavefront per SIMD: nothing else hides the LDS latency)
+            __builtin_amdgcn_sched_group_barrier(0x100, TMAX, 0);
+#pragma unroll
+            for (int c = 0; c + 1 < CK; ++c) {
+                __builtin_amdgcn_sched_group_barrier(0x100, TMAX, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, TMAX, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, TMAX, 0);
         } else {  // the ragged last chunk of the range
 #pragma unroll
             for (int c = 0; c < CK; ++c) {
@@ -212,32 +223,36 @@ __global__ __launch_bounds__(256) void fc_bt_kernel(const unsigned char* __restr
             }
         }
     };
-    // Two register sets: while chunk j is multiplied, chunks j + 1 and j + 2 are in flight.  Per chunk: multiply;
-    // the next chunk's streams go to the other LDS buffer (every wavefront finished reading it before the last
-    // barrier) and its rows of W to `acur`; the freed set is refilled; one barrier.
-    Set s0, s1;
+    // Four register sets in a ring: while chunk j is multiplied, chunks j + 1 .. j + 4 are in flight (one workgroup
+    // per compute unit: the depth in registers is what keeps enough bytes in flight).  Per chunk: multiply; the next
+    // chunk's streams go to the other LDS buffer (every wavefront finished reading it before the last barrier) and
+    // its rows of W to `acur`; the freed set is refilled with the chunk four further on; one barrier.
+    Set s0, s1, s2, s3;
     uint4 acur[CK];
     auto take = [&](const Set& s) __attribute__((always_inline)) {
 #pragma unroll
         for (int c = 0; c < CK; ++c) acur[c] = s.a[c];
     };
+    auto phase = [&](int j, int buf, Set& nxt) __attribute__((always_inline)) {
+        if (j < nch) compute(acur, buf, j);
+        stage(nxt, buf ^ 1);
+        take(nxt);
+        issue(j + 5, nxt);
+        __syncthreads();
+    };
     issue(0, s0);
     issue(1, s1);
+    issue(2, s2);
+    issue(3, s3);
     stage(s0, 0);
     take(s0);
-    issue(2, s0);
+    issue(4, s0);
     __syncthreads();
-    for (int j = 0; j < nch; j += 2) {
-        compute(acur, 0, j);
-        stage(s1, 1);
-        take(s1);
-        issue(j + 3, s1);
-        __syncthreads();
-        if (j + 1 < nch) compute(acur, 1, j + 1);
-        stage(s0, 0);
-        take(s0);
-        issue(j + 4, s0);
-        __syncthreads();
+    for (int j = 0; j < nch; j += 4) {
+        phase(j, 0, s1);
+        phase(j + 1, 1, s2);
+        phase(j + 2, 0, s3);
+        phase(j + 3, 1, s0);
     }
     // this split's sums: rows 4 (lane / 16) .. + 3 of the block for stream lane % 16 of every tile
     if (o0 < g.c_out) {
