@@ -152,9 +152,11 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
  *   "fc_splits"   FC, dense path: number of row splits of the weight matrix, in [1, the default chosen at
  *                 create] (the partial-sum scratch is sized for the default)
  *   "fc_batched"  FC with 16 to 256 streams (c_out a multiple of 16, rows of whole 64-byte steps): 1 (default) =
- *                 dense layer and delta step run as one product on the matrix cores with W read once for all
- *                 streams (the delta step then costs one pass over W whatever the density), 0 = one column walk
- *                 per stream as at batch 1.  Layers with a truncation threshold or "fc_sparse_weights" take the walk.
+ *                 dense layer and step run as one product on the matrix cores with W read once for all streams:
+ *                 an I8 step multiplies the difference of all streams (one pass over W whatever the density), a
+ *                 BF16 step commits x_t and recomputes b + W x_t (its difference would need two bf16 terms, two
+ *                 products); 0 = one column walk per stream as at batch 1.  Layers with a truncation threshold
+ *                 or "fc_sparse_weights" take the walk.
  *   "fc_sparse_weights"  FC, delta step: 1 = walk the non-zero weights of the changed columns only (pruned
  *                 models, Sec. 4.3; the (row, value) lists exist when at most half of W is non-zero at create,
  *                 else RRM_ERR_OPTION), 0 = walk whole columns (default).  fp32 sums of the sparse walk
