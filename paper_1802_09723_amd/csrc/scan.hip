@@ -193,13 +193,12 @@ __global__ void repack_word_kernel(const unsigned char* __restrict__ x, unsigned
 
 // FUSED: the unit's input is computed from the producer's projection (see FusedSrc); a unit none of whose
 // source blocks was written by the producer's last step cannot have changed and is not even loaded.
-template <int DT, bool SCATTER, bool FUSED>
-__global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restrict__ x_t, uint4* __restrict__ x_snap,
-                                                   uint4* __restrict__ d0, uint4* __restrict__ d1,
-                                                   unsigned long long* __restrict__ bitmap,
-                                                   unsigned int* __restrict__ tileflag, unsigned int stamp,
-                                                   ScanGeom g, long long nvec, long long total_bytes,
-                                                   DevStats* __restrict__ stats_base, FusedSrc fs) {
+template <int DT, bool SCATTER, bool FUSED, bool POOL>
+__device__ __forceinline__ void scan_body(const unsigned char* __restrict__ x_t, uint4* __restrict__ x_snap,
+                                          uint4* __restrict__ d0, uint4* __restrict__ d1,
+                                          unsigned long long* __restrict__ bitmap, unsigned int* __restrict__ tileflag,
+                                          unsigned int stamp, const ScanGeom& g, long long nvec, long long total_bytes,
+                                          DevStats* __restrict__ stats_base, const FusedSrc& fs) {
     // FUSED: neighbouring workgroups read overlapping rows of the producer's projection (pooling windows), and
     // consecutive workgroup ids go to different XCDs, each with an L2 of its own: the grid is a multiple of 8
     // and workgroup id i works on block (i % 8) * (grid / 8) + i / 8, so that an XCD gets a contiguous range.
@@ -220,7 +219,10 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
         const unsigned int p = udiv_big(e0, g.r_c), c0 = e0 - p * (unsigned int)g.c;
         const unsigned int bb = udiv_big(p, g.r_hw), r = p - bb * (unsigned int)(g.h * g.w);
         const int iy = (int)udiv_big(r, g.r_w), ix = (int)r - iy * g.w;
-        const int y0 = fs.pool ? 2 * iy : iy, x0 = fs.pool ? 2 * ix : ix, span = fs.pool ? 2 : 0;
+        // (POOL is a template parameter: the unpooled form keeps no window in registers and runs at twice the
+        // occupancy)
+        constexpr int span = POOL ? 2 : 0;
+        const int y0 = POOL ? 2 * iy : iy, x0 = POOL ? 2 * ix : ix;
         const unsigned char* t = fs.touched + (size_t)bb * fs.sty * fs.stx;
         const int sy0 = y0 >> fs.tshift, sy1 = (y0 + span) >> fs.tshift, sx0 = x0 >> fs.tshift, sx1 = (x0 + span) >> fs.tshift;
         unsigned int any = 0;
@@ -402,6 +404,27 @@ __global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restri
     }
 }
 
+// The entry points.  The pooled fused form keeps a row of its 3x3 window in flight (12 loads of 16 bytes) and is
+// fastest with about 100 registers at four wavefronts per SIMD (measured on the 27 x 27 and 13 x 13 consumers: 47 us
+// against 53 us at 64 registers); every other form needs 32 to 52 registers and runs at the occupancy that allows.
+template <int DT, bool SCATTER, bool FUSED>
+__global__ __launch_bounds__(256) void scan_kernel(const unsigned char* __restrict__ x_t, uint4* __restrict__ x_snap,
+                                                   uint4* __restrict__ d0, uint4* __restrict__ d1,
+                                                   unsigned long long* __restrict__ bitmap,
+                                                   unsigned int* __restrict__ tileflag, unsigned int stamp,
+                                                   ScanGeom g, long long nvec, long long total_bytes,
+                                                   DevStats* __restrict__ stats_base, FusedSrc fs) {
+    scan_body<DT, SCATTER, FUSED, false>(x_t, x_snap, d0, d1, bitmap, tileflag, stamp, g, nvec, total_bytes, stats_base, fs);
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void scan_pooled_kernel(
+    uint4* __restrict__ x_snap, uint4* __restrict__ d0, unsigned long long* __restrict__ bitmap,
+    unsigned int* __restrict__ tileflag, ScanGeom g, long long nvec, long long total_bytes,
+    DevStats* __restrict__ stats_base, FusedSrc fs) {
+    scan_body<RRM_I8_I32, false, true, true>(nullptr, x_snap, d0, nullptr, bitmap, tileflag, 0u, g, nvec, total_bytes,
+                                             stats_base, fs);
+}
+
 }  // namespace
 
 hipError_t launch_repack(int esize, const void* x, void* dst, const ScanGeom& g, hipStream_t s) {
@@ -454,9 +477,13 @@ hipError_t launch_scan_fused(const FusedSrc& src, void* x_snap, void* d0, unsign
     const long long nvec = total_bytes / 16;
     const long long blocks = ((nvec + 255) / 256 + 7) / 8 * 8;  // a multiple of the 8 XCDs (see the kernel)
     if (blocks <= 0) return hipSuccess;
-    hipLaunchKernelGGL((scan_kernel<RRM_I8_I32, false, true>), dim3((unsigned int)blocks), dim3(256), 0, s,
-                       (const unsigned char*)nullptr, (uint4*)x_snap, (uint4*)d0, (uint4*)nullptr, bitmap, marks, 0u, g, nvec,
-                       total_bytes, stats, src);
+    if (src.pool)
+        hipLaunchKernelGGL(scan_pooled_kernel, dim3((unsigned int)blocks), dim3(256), 0, s, (uint4*)x_snap, (uint4*)d0, bitmap,
+                           marks, g, nvec, total_bytes, stats, src);
+    else
+        hipLaunchKernelGGL((scan_kernel<RRM_I8_I32, false, true>), dim3((unsigned int)blocks), dim3(256), 0, s,
+                           (const unsigned char*)nullptr, (uint4*)x_snap, (uint4*)d0, (uint4*)nullptr, bitmap, marks, 0u, g, nvec,
+                           total_bytes, stats, src);
     return hipGetLastError();
 }
 
