@@ -295,29 +295,45 @@ __global__ __launch_bounds__(256) void fc_bt_reduce_kernel(const void* __restric
     y[v] = base;
 }
 
-int bt_chunk(int ntiles) { return ntiles <= 4 ? 4 : ntiles <= 8 ? 2 : 1; }
+int bt_chunk(int ntiles) { return ntiles <= 4 ? 4 : 2; }
+
+// streams per launch of the product kernel: more than 128 go in equal groups (a launch for 256 streams would walk the
+// k range in single steps with a barrier each and far fewer splits: two launches of 128 take half its time, W is read
+// twice)
+constexpr int BT_MAX_STREAMS = 128;
+int bt_group(int n) {
+    const int ngroups = (n + BT_MAX_STREAMS - 1) / BT_MAX_STREAMS;
+    return std::min(n, ((n + ngroups - 1) / ngroups + 15) / 16 * 16);
+}
 
 template <int DT, bool DELTA>
 void launch_batched(const void* w_rm, const void* b0, void* part, const void* bias, void* y, const FcGeom& g, hipStream_t s) {
-    const int ntiles = (g.n + 15) / 16;
     const int esize = DT == RRM_I8_I32 ? 1 : 2;
     const int nsteps = g.c_in * esize / 64;
-    const int ck = bt_chunk(ntiles);
-    const int chunks = (nsteps + ck - 1) / ck;
-    const int cps = (chunks + fc_batched_splits(DT, g) - 1) / fc_batched_splits(DT, g);
-    const int splits = (chunks + cps - 1) / cps;  // (no empty split)
-    dim3 grid((unsigned int)((g.c_out + 63) / 64), (unsigned int)splits);
+    const int per = bt_group(g.n);
     const unsigned char* w = static_cast<const unsigned char*>(w_rm);
-    const unsigned char* p0 = static_cast<const unsigned char*>(b0);
+    for (int s0 = 0; s0 < g.n; s0 += per) {
+        FcGeom gg = g;
+        gg.n = std::min(per, g.n - s0);
+        const int ntiles = (gg.n + 15) / 16;
+        const int ck = bt_chunk(ntiles);
+        const int chunks = (nsteps + ck - 1) / ck;
+        const int want = fc_batched_splits(DT, gg);
+        const int cps = (chunks + want - 1) / want;
+        const int splits = (chunks + cps - 1) / cps;  // (no empty split)
+        dim3 grid((unsigned int)((g.c_out + 63) / 64), (unsigned int)splits);
+        const unsigned char* p0 = static_cast<const unsigned char*>(b0) + (size_t)s0 * g.c_in * esize;
+        unsigned char* yg = static_cast<unsigned char*>(y) + (size_t)s0 * g.c_out * 4;
 #define RRM_BT(T, C)                                                                                                  \
     if (ntiles <= T) {                                                                                                \
-        hipLaunchKernelGGL((fc_bt_kernel<DT, T, C>), grid, dim3(256), 0, s, w, p0, part, g, cps);                     \
+        hipLaunchKernelGGL((fc_bt_kernel<DT, T, C>), grid, dim3(256), 0, s, w, p0, part, gg, cps);                    \
     } else
-    RRM_BT(1, 4) RRM_BT(2, 4) RRM_BT(3, 4) RRM_BT(4, 4) RRM_BT(6, 2) RRM_BT(8, 2) RRM_BT(12, 1) RRM_BT(16, 1) {}
+        RRM_BT(1, 4) RRM_BT(2, 4) RRM_BT(3, 4) RRM_BT(4, 4) RRM_BT(6, 2) RRM_BT(8, 2) {}
 #undef RRM_BT
-    const long long nvec = (long long)g.n * g.c_out / 4;
-    hipLaunchKernelGGL((fc_bt_reduce_kernel<DT, DELTA>), dim3((unsigned int)((nvec + 255) / 256)), dim3(256), 0, s, part, bias, y,
-                       nvec, g.c_out / 4, splits);
+        const long long nvec = (long long)gg.n * g.c_out / 4;
+        hipLaunchKernelGGL((fc_bt_reduce_kernel<DT, DELTA>), dim3((unsigned int)((nvec + 255) / 256)), dim3(256), 0, s, part, bias,
+                           yg, nvec, g.c_out / 4, splits);
+    }
 }
 
 }  // namespace
@@ -326,12 +342,13 @@ void launch_batched(const void* w_rm, const void* b0, void* part, const void* bi
 // (written and read once per split) of at most half the bytes of W.
 int fc_batched_splits(int dtype, const FcGeom& g) {
     const int esize = dtype == RRM_I8_I32 ? 1 : 2;
-    const int ck = bt_chunk((g.n + 15) / 16);
+    const int n = bt_group(g.n);  // (streams of one launch)
+    const int ck = bt_chunk((n + 15) / 16);
     const int chunks = (g.c_in * esize / 64 + ck - 1) / ck;
     const int groups = (g.c_out + 63) / 64;
     int s = (NUM_CU + groups - 1) / groups;
     s = std::min(s, chunks / 3);
-    s = std::min(s, g.c_in * esize / (16 * g.n));
+    s = std::min(s, g.c_in * esize / (16 * n));
     return std::max(s, 1);
 }
 
