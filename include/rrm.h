@@ -151,7 +151,7 @@ rrm_status rrm_read_snapshot(rrm_layer* layer, void* x_dst, void* y_dst, void* h
  *                 positions in all (one stream of a small map), where two dependent launches cost more than the work.
  *   "fc_splits"   FC, dense path: number of row splits of the weight matrix, in [1, the default chosen at
  *                 create] (the partial-sum scratch is sized for the default)
- *   "fc_batched"  FC with 16 to 256 streams (c_out a multiple of 16, rows of whole 64-byte steps): 1 (default) =
+ *   "fc_batched"  FC with 16 to 4096 streams (c_out a multiple of 16, rows of whole 64-byte steps): 1 (default) =
  *                 dense layer and step run as one product on the matrix cores with W read once for all streams:
  *                 an I8 step multiplies the difference of all streams (one pass over W whatever the density), a
  *                 BF16 step commits x_t and recomputes b + W x_t (its difference would need two bf16 terms, two

@@ -163,7 +163,7 @@ struct FcGeom {
     const void* csc_val;
 };
 constexpr int FC_BATCH_MIN_STREAMS = 16;    // from this many streams on an FC layer runs as one product on the matrix cores
-constexpr int FC_BATCH_MAX_STREAMS = 256;   // (16 stream tiles of accumulators per wavefront)
+constexpr int FC_BATCH_MAX_STREAMS = 4096;  // (launched in groups of at most 128 streams)
 constexpr int FC_CSC_MAX_LDS = 96 * 1024;   // the pruned-weight kernel's update accumulators: c_out <= 24576
 
 // floor(u / d) through the reciprocal magic = floor(2^32 / d) + 1 (0 encodes d == 1).  The product's high word is

@@ -557,7 +557,7 @@ def _batched_fc_shapes():
     last chunk, one split and several"""
     rng = S.rng_for(9100)
     out = []
-    for n in (16, 17, 32, 33, 48, 64, 65, 90, 96, 100, 128, 129, 190, 200, 256):
+    for n in (16, 17, 32, 33, 48, 64, 65, 90, 96, 100, 128, 129, 190, 200, 256, 300, 512):
         for dt in (S.I8, S.BF16):
             es = 1 if dt == S.I8 else 2
             steps = int(rng.choice([1, 2, 3, 5, 7, 13, 24, 37, 50]))
@@ -566,7 +566,7 @@ def _batched_fc_shapes():
     return out
 
 
-@pytest.mark.parametrize("idx", range(30))
+@pytest.mark.parametrize("idx", range(34))
 def test_fc_product_kernel_shapes(idx):
     shp, dt = _batched_fc_shapes()[idx]
     seq = S.random_layer(9100 + idx, shp, dt, T=3, frac=0.3)
